@@ -1,0 +1,142 @@
+/*
+ * lutq — fused lookup-table dequantise + small-batch matmul for AMD MI355X (gfx950).
+ *
+ * C ABI of liblutq.so.  Plain pointers and sizes only; every buffer is owned by
+ * the caller.  The library never allocates device memory, never synchronises the
+ * device and never aborts: arguments are validated on the host and a status code
+ * is returned BEFORE anything is launched, so on error no output is touched.
+ *
+ * Problem (Section 3 of "Fast Matrix Multiplications for Lookup Table-Quantized
+ * LLMs", arXiv 2407.10960): an index matrix Q with entries in {0..2^b-1}, a table
+ * T = [v_0 .. v_{2^b-1}] of 16-bit floats, dequantised weights W^ = T[Q], and the
+ * product Y = X * W^ with a small number of activation rows.  With the group
+ * scales of Section 4.1 ("LUT quantization method") / Section 4.2 the weight is
+ *
+ *        W^[n, k] = round16( T[Q[n, k]] * S[n, k / group_size] )
+ *        Y[m, n]  = sum_k X[m, k] * W^[n, k]          (fp32 accumulation)
+ *
+ * Orientation: the paper writes Q and W as k-by-n; this library stores their
+ * transposes, [N, K] row-major (one row per output channel, as a linear layer
+ * does).  A group is `group_size` consecutive elements along K inside one row.
+ * round16 is one round-to-nearest-even to the 16-bit type `dtype`.
+ *
+ * Supported domain: bits in {2,3,4}; group_size in {32,64,128}; 1 <= M <= 32;
+ * N a multiple of 16; K a multiple of the K-tile of the bit width (128 for
+ * 4-bit, 256 for 2- and 3-bit) and of group_size; device pointers 16-byte aligned.
+ */
+#ifndef LUTQ_H
+#define LUTQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LUTQ_OK = 0,
+    LUTQ_ERR_NULL = 1,         /* a required pointer is NULL */
+    LUTQ_ERR_BITS = 2,         /* bits not in {2,3,4} */
+    LUTQ_ERR_GROUP = 3,        /* group_size not in {32,64,128} or does not divide K */
+    LUTQ_ERR_SHAPE = 4,        /* M, N or K outside the supported domain */
+    LUTQ_ERR_ALIGN = 5,        /* a device pointer is not 16-byte aligned */
+    LUTQ_ERR_INDEX_RANGE = 6,  /* lutq_pack: an index is >= 2^bits */
+    LUTQ_ERR_WORKSPACE = 7,    /* workspace missing or smaller than lutq_workspace_bytes() */
+    LUTQ_ERR_DTYPE = 8,        /* dtype not LUTQ_F16 / LUTQ_BF16 */
+    LUTQ_ERR_DEVICE = 9,       /* a HIP runtime call failed (launch, device query) */
+    LUTQ_ERR_PLAN = 10         /* lutq_plan fields outside their documented ranges */
+} lutq_status;
+
+typedef enum { LUTQ_F16 = 0, LUTQ_BF16 = 1 } lutq_dtype;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* lutq_status_string(lutq_status s);
+
+/* ---------------------------------------------------------------------------
+ * Offline restructuring (Section 3.1 "Offline Matrix Restructuring"; first line of
+ * Algorithm 1, reorder_and_split).  Host code, run once per weight matrix.
+ *
+ * The packed form orders indices so that a wavefront's 128-bit loads deliver them
+ * already in the operand order of the gfx950 16x16x32 matrix instruction, and
+ * splits 3-bit indices into a 2-bit slice and a 1-bit slice so that every load is
+ * a power-of-two number of bits.  The byte layout is spelled out at the top of csrc/lutq_pack.cpp; it
+ * does not depend on group_size (the argument is validated and otherwise unused).
+ * ------------------------------------------------------------------------- */
+
+/* Size in bytes of the packed form (N*K*bits/8); 0 if the arguments are unsupported. */
+size_t lutq_packed_bytes(int64_t N, int64_t K, int bits, int group_size);
+
+/* indices: host, [N, K] row-major, one index per byte, each < 2^bits.
+ * packed_out: host, caller-owned, lutq_packed_bytes() bytes, fully overwritten.
+ * Errors: NULL, BITS, GROUP, SHAPE, INDEX_RANGE (packed_out contents then unspecified). */
+lutq_status lutq_pack(const uint8_t* indices, int64_t N, int64_t K, int bits, int group_size,
+                      void* packed_out);
+
+/* Inverse of lutq_pack (host to host). indices_out: [N, K] row-major, one index per byte. */
+lutq_status lutq_unpack(const void* packed, int64_t N, int64_t K, int bits, int group_size,
+                        uint8_t* indices_out);
+
+/* ---------------------------------------------------------------------------
+ * The fused kernel (Algorithm 1 / Algorithm 2: copy table to on-chip memory, stream
+ * packed weights, combine bit-slices, vectorised table lookup + group scale, matrix
+ * instruction, Stream-K style partial-sum fix-up through global scratch).
+ * ------------------------------------------------------------------------- */
+
+/* Bytes of device scratch lutq_matmul may need for any M <= 32 with these arguments
+ * (the semaphore and partial-sum areas of Algorithm 2).  0 if unsupported. */
+size_t lutq_workspace_bytes(int64_t N, int64_t K, int bits, int group_size);
+
+/* Work-decomposition knobs (Section 3.3 Stream-K partitioning; Section 4.1: tile
+ * shape and number of table duplicates are chosen per shape).  All fields 0 = let
+ * the library choose. */
+typedef struct {
+    int row_blocks_per_wave;  /* 16-row blocks each wavefront streams together: 0,1,2,4; must divide N/16 */
+    int grid;                 /* number of 256-thread workgroups: 0 or 1..2048 */
+    int lut_copies;           /* copies of the vectorised table in LDS: 0 or a power of two
+                                 <= 32 (<= 16 for 2-bit); one copy per bank column removes conflicts */
+    int waves_split_k;        /* reserved, must be 0 */
+} lutq_plan;
+
+/* Fills *plan with the library's choice for this problem. */
+lutq_status lutq_plan_default(int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                              lutq_dtype dtype, lutq_plan* plan);
+
+/* Y = X * W^T-dequantised, asynchronous on `stream`.
+ *   X       device, [M, K] row-major, dtype
+ *   packed  device, bytes produced by lutq_pack for (N, K, bits)
+ *   scales  device, [N, K / group_size] row-major, dtype
+ *   lut     device, 2^bits entries, dtype (any finite values, any order)
+ *   Y       device, [M, N] row-major, dtype; fully overwritten
+ *   workspace  device, >= lutq_workspace_bytes(); must be zero-filled once before its
+ *              first use.  Its first 64 KiB hold the arrival counters, which every successful
+ *              call returns to zero; the rest holds partial sums that the next call simply
+ *              overwrites.  The same workspace can therefore be reused by any later call on
+ *              the same stream without clearing it.  Calls that may run concurrently
+ *              (different streams) need separate workspaces.
+ *   stream  a hipStream_t (NULL = the default stream)
+ * Errors: NULL, BITS, GROUP, SHAPE, ALIGN, WORKSPACE, DTYPE, DEVICE; Y untouched on error. */
+lutq_status lutq_matmul(const void* X, const void* packed, const void* scales, const void* lut,
+                        int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                        lutq_dtype dtype, void* Y,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same, with an explicit work decomposition (additionally returns LUTQ_ERR_PLAN).
+ * The result does not depend on the plan beyond fp32 summation order. */
+lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scales, const void* lut,
+                             int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                             lutq_dtype dtype, void* Y,
+                             void* workspace, size_t workspace_bytes, void* stream,
+                             const lutq_plan* plan);
+
+/* The separate-kernel path of Section 3 (dequantise to memory): writes
+ * W_out[n, k] = round16(T[Q[n,k]] * S[n, k/group_size]), device [N, K] row-major, dtype,
+ * using the same on-chip lookup + scale routine as lutq_matmul.  Asynchronous on `stream`. */
+lutq_status lutq_dequant(const void* packed, const void* scales, const void* lut,
+                         int bits, int group_size, int64_t N, int64_t K, lutq_dtype dtype,
+                         void* W_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LUTQ_H */

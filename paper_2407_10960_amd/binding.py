@@ -1,0 +1,220 @@
+"""ctypes binding for liblutq.so.  Names and argument order follow include/lutq.h."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTED_SYMBOLS = (
+    "lutq_status_string", "lutq_packed_bytes", "lutq_pack", "lutq_unpack", "lutq_workspace_bytes",
+    "lutq_plan_default", "lutq_matmul", "lutq_matmul_plan", "lutq_dequant",
+    "lutq_calib_stream_read", "lutq_calib_copy",
+)
+
+LUTQ_F16, LUTQ_BF16 = 0, 1
+
+
+class LutqError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: lutq status {code} ({_status_string(code)})")
+        self.code = code
+
+
+class _CPlan(ctypes.Structure):
+    _fields_ = [("row_blocks_per_wave", ctypes.c_int), ("grid", ctypes.c_int),
+                ("lut_copies", ctypes.c_int), ("waves_split_k", ctypes.c_int)]
+
+
+@dataclass
+class Plan:
+    """Work decomposition knobs of lutq_matmul_plan; 0 = library default."""
+    row_blocks_per_wave: int = 0
+    grid: int = 0
+    lut_copies: int = 0
+
+    def _c(self) -> _CPlan:
+        return _CPlan(self.row_blocks_per_wave, self.grid, self.lut_copies, 0)
+
+
+def lib_path() -> str:
+    return os.path.join(_PKG_DIR, "liblutq.so")
+
+
+def load_library():
+    """Loads liblutq.so; raises if it has not been built (there is no other code path)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2407_10960_amd.build` "
+                           "(there is no CPU or PyTorch fallback)")
+    lib = ctypes.CDLL(path)
+    vp, i64, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    lib.lutq_status_string.restype = ctypes.c_char_p
+    lib.lutq_status_string.argtypes = [ci]
+    lib.lutq_packed_bytes.restype = sz
+    lib.lutq_packed_bytes.argtypes = [i64, i64, ci, ci]
+    lib.lutq_pack.restype = ci
+    lib.lutq_pack.argtypes = [vp, i64, i64, ci, ci, vp]
+    lib.lutq_unpack.restype = ci
+    lib.lutq_unpack.argtypes = [vp, i64, i64, ci, ci, vp]
+    lib.lutq_workspace_bytes.restype = sz
+    lib.lutq_workspace_bytes.argtypes = [i64, i64, ci, ci]
+    lib.lutq_plan_default.restype = ci
+    lib.lutq_plan_default.argtypes = [ci, ci, i64, i64, i64, ci, ctypes.POINTER(_CPlan)]
+    lib.lutq_matmul.restype = ci
+    lib.lutq_matmul.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp]
+    lib.lutq_matmul_plan.restype = ci
+    lib.lutq_matmul_plan.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp,
+                                     ctypes.POINTER(_CPlan)]
+    lib.lutq_dequant.restype = ci
+    lib.lutq_dequant.argtypes = [vp, vp, vp, ci, ci, i64, i64, ci, vp, vp]
+    lib.lutq_calib_stream_read.restype = ci
+    lib.lutq_calib_stream_read.argtypes = [vp, sz, ci, vp, vp]
+    lib.lutq_calib_copy.restype = ci
+    lib.lutq_calib_copy.argtypes = [vp, vp, sz, ci, vp]
+    _LIB = lib
+    return lib
+
+
+def _status_string(code: int) -> str:
+    try:
+        return load_library().lutq_status_string(code).decode()
+    except Exception:  # pragma: no cover
+        return "?"
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        raise LutqError(code, what)
+
+
+# ------------------------------------------------------------------ host side (offline packer)
+def lutq_packed_bytes(N: int, K: int, bits: int, group_size: int) -> int:
+    return int(load_library().lutq_packed_bytes(N, K, bits, group_size))
+
+
+def lutq_pack(indices, bits: int, group_size: int) -> np.ndarray:
+    """indices: [N, K] uint8 (numpy, or anything np.asarray accepts) -> packed bytes (numpy uint8, 1-D)."""
+    lib = load_library()
+    idx = np.ascontiguousarray(np.asarray(indices, dtype=np.uint8))
+    if idx.ndim != 2:
+        raise ValueError("indices must be [N, K]")
+    N, K = idx.shape
+    nbytes = lib.lutq_packed_bytes(N, K, bits, group_size)
+    out = np.empty(max(int(nbytes), 1), dtype=np.uint8)
+    _check(lib.lutq_pack(idx.ctypes.data, N, K, bits, group_size, out.ctypes.data), "lutq_pack")
+    return out[:nbytes]
+
+
+def lutq_unpack(packed, N: int, K: int, bits: int, group_size: int) -> np.ndarray:
+    lib = load_library()
+    buf = np.ascontiguousarray(np.asarray(packed, dtype=np.uint8)).reshape(-1)
+    if buf.size != lib.lutq_packed_bytes(N, K, bits, group_size):
+        raise ValueError("packed buffer has the wrong size for (N, K, bits)")
+    out = np.empty((N, K), dtype=np.uint8)
+    _check(lib.lutq_unpack(buf.ctypes.data, N, K, bits, group_size, out.ctypes.data), "lutq_unpack")
+    return out
+
+
+# ------------------------------------------------------------------ device side
+def lutq_workspace_bytes(N: int, K: int, bits: int, group_size: int) -> int:
+    return int(load_library().lutq_workspace_bytes(N, K, bits, group_size))
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float16:
+        return LUTQ_F16
+    if t.dtype == torch.bfloat16:
+        return LUTQ_BF16
+    raise TypeError("X, scales, lut and Y must be float16 or bfloat16")
+
+
+def _stream_ptr(stream) -> int:
+    torch = _torch()
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def new_workspace(N: int, K: int, bits: int, group_size: int, device="cuda"):
+    """A zero-filled device workspace for lutq_matmul (reusable across calls on one stream)."""
+    torch = _torch()
+    n = lutq_workspace_bytes(N, K, bits, group_size)
+    if n == 0:
+        raise ValueError("unsupported problem")
+    return torch.zeros(n, dtype=torch.uint8, device=device)
+
+
+def lutq_plan_default(bits: int, group_size: int, M: int, N: int, K: int, dtype_code: int = LUTQ_F16) -> Plan:
+    cp = _CPlan()
+    _check(load_library().lutq_plan_default(bits, group_size, M, N, K, dtype_code, ctypes.byref(cp)),
+           "lutq_plan_default")
+    return Plan(cp.row_blocks_per_wave, cp.grid, cp.lut_copies)
+
+
+def lutq_matmul(X, packed, scales, lut, bits: int, group_size: int, Y, workspace, stream=None,
+                plan: Plan | None = None):
+    """Y[M,N] = X[M,K] @ dequant(packed, scales, lut)^T on the GPU.  All tensors are caller-owned
+    torch CUDA tensors (X/scales/lut/Y float16 or bfloat16, packed/workspace uint8)."""
+    lib = load_library()
+    if not (X.is_cuda and packed.is_cuda and scales.is_cuda and lut.is_cuda and Y.is_cuda and workspace.is_cuda):
+        raise ValueError("lutq_matmul needs CUDA (HIP) tensors")
+    for t in (X, packed, scales, lut, Y, workspace):
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+    code = _dtype_code(X)
+    if not (_dtype_code(scales) == code and _dtype_code(lut) == code and _dtype_code(Y) == code):
+        raise TypeError("X, scales, lut and Y must share one dtype")
+    M, K = X.shape
+    N = scales.shape[0]
+    if scales.shape[1] * group_size != K or tuple(Y.shape) != (M, N) or lut.numel() != (1 << bits):
+        raise ValueError("inconsistent shapes")
+    if packed.numel() != lib.lutq_packed_bytes(N, K, bits, group_size):
+        raise ValueError("packed buffer has the wrong size for (N, K, bits)")
+    args = [X.data_ptr(), packed.data_ptr(), scales.data_ptr(), lut.data_ptr(), bits, group_size, M, N, K, code,
+            Y.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(stream)]
+    if plan is None:
+        _check(lib.lutq_matmul(*args), "lutq_matmul")
+    else:
+        cp = plan._c()
+        _check(lib.lutq_matmul_plan(*args, ctypes.byref(cp)), "lutq_matmul_plan")
+    return Y
+
+
+def lutq_dequant(packed, scales, lut, bits: int, group_size: int, W_out, stream=None):
+    """W_out[N,K] = round16(lut[Q] * scales) on the GPU (same lookup + scale routine as lutq_matmul)."""
+    lib = load_library()
+    code = _dtype_code(W_out)
+    N, K = W_out.shape
+    if not (packed.is_cuda and scales.is_cuda and lut.is_cuda and W_out.is_cuda):
+        raise ValueError("lutq_dequant needs CUDA (HIP) tensors")
+    if scales.shape[0] != N or scales.shape[1] * group_size != K or lut.numel() != (1 << bits):
+        raise ValueError("inconsistent shapes")
+    if packed.numel() != lib.lutq_packed_bytes(N, K, bits, group_size):
+        raise ValueError("packed buffer has the wrong size for (N, K, bits)")
+    _check(lib.lutq_dequant(packed.data_ptr(), scales.data_ptr(), lut.data_ptr(), bits, group_size, N, K, code,
+                            W_out.data_ptr(), _stream_ptr(stream)), "lutq_dequant")
+    return W_out
+
+
+# ------------------------------------------------------------------ measurement helpers
+def calib_stream_read(src, grid: int, sink, stream=None):
+    _check(load_library().lutq_calib_stream_read(src.data_ptr(), src.numel() * src.element_size(), grid,
+                                                 sink.data_ptr(), _stream_ptr(stream)), "lutq_calib_stream_read")
+
+
+def calib_copy(src, dst, grid: int, stream=None):
+    _check(load_library().lutq_calib_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), grid,
+                                          _stream_ptr(stream)), "lutq_calib_copy")

@@ -1,0 +1,233 @@
+// Device-side building blocks shared by the fused matmul kernel and the dequantise
+// kernel: tile geometry per bit width, the vectorised lookup table in LDS
+// (Section 3.2 of the paper: a table over all index pairs, duplicated to avoid bank
+// conflicts), bit-slice combination for 3-bit (Section 3.1), and group scaling.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lutq {
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct F16 {};
+struct BF16 {};
+
+// Tile geometry of the packed layout (see lutq_pack.cpp).
+template <int BITS> struct Geo;
+template <> struct Geo<4> {
+    static constexpr int TK = 128, STEPS = 4, TILE_BYTES = 1024;
+    static constexpr int ENTRIES = 256, ENTRY_BYTES = 4, MAX_LOG2_COPIES = 5;   // pair table
+};
+template <> struct Geo<3> {
+    static constexpr int TK = 256, STEPS = 8, TILE_BYTES = 1536;
+    static constexpr int ENTRIES = 64, ENTRY_BYTES = 4, MAX_LOG2_COPIES = 5;    // pair table, 6-bit address
+};
+template <> struct Geo<2> {
+    static constexpr int TK = 256, STEPS = 8, TILE_BYTES = 1024;
+    static constexpr int ENTRIES = 256, ENTRY_BYTES = 8, MAX_LOG2_COPIES = 4;   // quad table
+};
+
+// Packed words of one tile as held by one lane.
+template <int BITS> struct WFrag { u32x4 w; };
+template <> struct WFrag<3> { u32x4 w; u32x2 hi; };
+
+template <int BITS>
+__device__ __forceinline__ void load_wfrag(WFrag<BITS>& f, const uint8_t* tile, int lane) {
+    f.w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 16 * lane));
+    if constexpr (BITS == 3)
+        f.hi = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(tile + 1024 + 8 * lane));
+}
+
+// ---------------------------------------------------------------------------------------
+// Vectorised table in LDS.  Entry e of copy c lives at byte (e << (log2c + log2 ENTRY_BYTES))
+// + c * ENTRY_BYTES, and lane l reads copy l mod copies: with 32 copies of a 4-byte entry every
+// lane of a half-wave stays in its own bank whatever the indices are.
+//   4-bit: e = 8-bit pair  (q0 | q1 << 4)            -> {T[q0], T[q1]}
+//   3-bit: e = 6-bit pair  (lo2(q0) | lo2(q1) << 2 | bit2(q0) << 4 | bit2(q1) << 5)
+//   2-bit: e = 8-bit quad  (q0 | q1 << 2 | q2 << 4 | q3 << 6) -> {T[q0], T[q1], T[q2], T[q3]}
+// Called by all 256 threads of the workgroup; caller synchronises afterwards.
+// ---------------------------------------------------------------------------------------
+template <int BITS>
+__device__ __forceinline__ void build_lut(char* lds, const uint16_t* __restrict__ T, int log2c, int tid) {
+    const int copies = 1 << log2c;
+    if constexpr (BITS == 4) {
+        const uint32_t e = (uint32_t)T[tid & 15] | ((uint32_t)T[tid >> 4] << 16);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(lds) + ((size_t)tid << log2c);
+        for (int c = 0; c < copies; ++c) dst[c] = e;
+    } else if constexpr (BITS == 3) {
+        const int e6 = tid & 63;
+        const int q0 = (e6 & 3) | (((e6 >> 4) & 1) << 2);
+        const int q1 = ((e6 >> 2) & 3) | (((e6 >> 5) & 1) << 2);
+        const uint32_t e = (uint32_t)T[q0] | ((uint32_t)T[q1] << 16);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(lds) + ((size_t)e6 << log2c);
+        for (int c = tid >> 6; c < copies; c += 4) dst[c] = e;
+    } else {
+        u32x2 e;
+        e.x = (uint32_t)T[tid & 3] | ((uint32_t)T[(tid >> 2) & 3] << 16);
+        e.y = (uint32_t)T[(tid >> 4) & 3] | ((uint32_t)T[tid >> 6] << 16);
+        u32x2* dst = reinterpret_cast<u32x2*>(lds) + ((size_t)tid << log2c);
+        for (int c = 0; c < copies; ++c) dst[c] = e;
+    }
+}
+
+template <int BITS>
+__host__ __device__ constexpr int lut_lds_bytes(int log2c) {
+    return (Geo<BITS>::ENTRIES * Geo<BITS>::ENTRY_BYTES) << log2c;
+}
+
+// Per-lane constants of the lookup: the shift that turns an entry number into a byte offset, and
+// the LDS byte address of entry 0 of this lane's private copy (table base included).
+typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
+typedef __attribute__((address_space(3))) const u32x2 lds_cu64;
+
+struct LutAddr {
+    int sh;
+    uint32_t lane_base;
+};
+template <int BITS>
+__device__ __forceinline__ LutAddr make_lut_addr(const char* lut_lds, int log2c, int lane) {
+    LutAddr a;
+    a.sh = log2c + (Geo<BITS>::ENTRY_BYTES == 8 ? 3 : 2);
+    const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lut_lds;
+    a.lane_base = base + (uint32_t)(lane & ((1 << log2c) - 1)) * Geo<BITS>::ENTRY_BYTES;
+    return a;
+}
+
+__device__ __forceinline__ uint32_t lds_u32(uint32_t idx, LutAddr la) {
+    return *reinterpret_cast<lds_cu32*>((uintptr_t)((idx << la.sh) + la.lane_base));
+}
+__device__ __forceinline__ u32x2 lds_u64(uint32_t idx, LutAddr la) {
+    return *reinterpret_cast<lds_cu64*>((uintptr_t)((idx << la.sh) + la.lane_base));
+}
+
+// ---------------------------------------------------------------------------------------
+// Group scale.  fp16: one packed half multiply per pair.  bf16: widen both halves to fp32 (exact),
+// multiply (exact: 8 x 8 significand bits), round once to bf16 (round-to-nearest-even).
+// Both give round16(T[q] * s) with a single rounding.
+// ---------------------------------------------------------------------------------------
+template <typename DT> struct ScaleReg;
+template <> struct ScaleReg<F16> { uint32_t s2; };    // scale in both halves
+template <> struct ScaleReg<BF16> { float s; };
+
+template <typename DT> __device__ __forceinline__ ScaleReg<DT> make_scale(uint32_t bits16);
+template <> __device__ __forceinline__ ScaleReg<F16> make_scale<F16>(uint32_t b) {
+    ScaleReg<F16> r; r.s2 = (b & 0xffffu) | (b << 16); return r;
+}
+template <> __device__ __forceinline__ ScaleReg<BF16> make_scale<BF16>(uint32_t b) {
+    ScaleReg<BF16> r; r.s = __builtin_bit_cast(float, b << 16); return r;
+}
+
+__device__ __forceinline__ uint32_t scale_pair(uint32_t pair, ScaleReg<F16> s) {
+    f16x2 v = __builtin_bit_cast(f16x2, pair) * __builtin_bit_cast(f16x2, s.s2);
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint32_t scale_pair(uint32_t pair, ScaleReg<BF16> s) {
+    f32x2 v;
+    v.x = __builtin_bit_cast(float, pair << 16) * s.s;
+    v.y = __builtin_bit_cast(float, pair & 0xffff0000u) * s.s;
+    bf16x2 r = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// ---------------------------------------------------------------------------------------
+// One 32-wide K step of one 16-row block.  lookup_step issues the table reads for this lane's 8
+// weights (unscaled, four 32-bit registers in A-operand order); scale4 applies the group scale.
+// They are separate so that the caller can issue the LDS reads of the next step before it consumes
+// the current one.
+// ---------------------------------------------------------------------------------------
+template <int BITS>
+__device__ __forceinline__ u32x4 lookup_step(const WFrag<BITS>& f, int step, LutAddr la) {
+    u32x4 a;
+    if constexpr (BITS == 4) {
+        const uint32_t w = f.w[step];
+        a.x = lds_u32(w & 0xffu, la);
+        a.y = lds_u32((w >> 8) & 0xffu, la);
+        a.z = lds_u32((w >> 16) & 0xffu, la);
+        a.w = lds_u32(w >> 24, la);
+    } else if constexpr (BITS == 3) {
+        // combine the two bit-slices: bits 0..3 of each byte from the low slice, bits 4..5 from the
+        // high slice; bits 6..7 are don't-care and dropped by the 6-bit field extract.
+        const uint32_t lo = (step & 1) ? (f.w[step >> 1] >> 4) : f.w[step >> 1];
+        const int u = step & 3;
+        const uint32_t h = f.hi[step >> 2];
+        const uint32_t hs = (u == 0) ? (h << 4) : (u == 1) ? (h << 2) : (u == 2) ? h : (h >> 2);
+        const uint32_t c = (hs & 0x30303030u) | (lo & ~0x30303030u);
+        a.x = lds_u32(c & 0x3fu, la);
+        a.y = lds_u32((c >> 8) & 0x3fu, la);
+        a.z = lds_u32((c >> 16) & 0x3fu, la);
+        a.w = lds_u32((c >> 24) & 0x3fu, la);
+    } else {
+        const uint32_t w = f.w[step >> 1] >> (16 * (step & 1));
+        const u32x2 q0 = lds_u64(w & 0xffu, la);
+        const u32x2 q1 = lds_u64((w >> 8) & 0xffu, la);
+        a.x = q0.x; a.y = q0.y; a.z = q1.x; a.w = q1.y;
+    }
+    return a;
+}
+
+template <typename DT>
+__device__ __forceinline__ u32x4 scale4(u32x4 raw, ScaleReg<DT> sc) {
+    u32x4 a;
+    a.x = scale_pair(raw.x, sc);
+    a.y = scale_pair(raw.y, sc);
+    a.z = scale_pair(raw.z, sc);
+    a.w = scale_pair(raw.w, sc);
+    return a;
+}
+
+// v_mfma_f32_16x16x32: D(16x16, fp32) += A(16x32) * B(32x16).  Lane l = 16*o + i supplies A[i][8o..8o+7]
+// and B[8o..8o+7][i]; it receives D[4o..4o+3][i].
+template <typename DT>
+__device__ __forceinline__ f32x4 mfma16x16x32(u32x4 a, u32x4 b, f32x4 c);
+template <>
+__device__ __forceinline__ f32x4 mfma16x16x32<F16>(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ f32x4 mfma16x16x32<BF16>(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// fp32 -> 16-bit, round-to-nearest-even, four values packed into 8 bytes.
+template <typename DT> __device__ __forceinline__ u32x2 pack4(f32x4 v);
+template <> __device__ __forceinline__ u32x2 pack4<F16>(f32x4 v) {
+    f16x4 h = __builtin_convertvector(v, f16x4);
+    return __builtin_bit_cast(u32x2, h);
+}
+template <> __device__ __forceinline__ u32x2 pack4<BF16>(f32x4 v) {
+    bf16x4 h = __builtin_convertvector(v, bf16x4);
+    return __builtin_bit_cast(u32x2, h);
+}
+
+// Scales of one tile for one row: NS = TK / GROUP consecutive 16-bit values, loaded as one access.
+template <int NS> struct ScaleWords { uint32_t w[(NS + 1) / 2]; };
+
+template <int NS>
+__device__ __forceinline__ void load_scales(ScaleWords<NS>& s, const uint16_t* p) {
+    if constexpr (NS == 1) s.w[0] = *p;
+    else if constexpr (NS == 2) s.w[0] = *reinterpret_cast<const uint32_t*>(p);
+    else if constexpr (NS == 4) {
+        u32x2 v = *reinterpret_cast<const u32x2*>(p);
+        s.w[0] = v.x; s.w[1] = v.y;
+    } else {
+        u32x4 v = *reinterpret_cast<const u32x4*>(p);
+        s.w[0] = v.x; s.w[1] = v.y; s.w[2] = v.z; s.w[3] = v.w;
+    }
+}
+template <int NS>
+__device__ __forceinline__ uint32_t scale_bits(const ScaleWords<NS>& s, int g) {
+    return (g & 1) ? (s.w[g >> 1] >> 16) : (s.w[g >> 1] & 0xffffu);
+}
+
+}  // namespace lutq

@@ -1,0 +1,206 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on identical seeded inputs.
+
+Bars: packed bytes and dequantised weights bit-exact; Y within 2e-3 relative Frobenius error of the
+fp64 oracle (the stated target), and additionally every element within half a 16-bit ulp plus a small
+fp32-accumulation allowance of the oracle value.
+"""
+import numpy as np
+import pytest
+
+import lutq_inputs as gen
+from oracle import lutq_oracle as orc
+from gpu_util import DeviceCase, to_bits, to_dev, torch_dtype, ulp16
+
+pytestmark = pytest.mark.gpu
+
+# Stated target: 2e-3 relative Frobenius error for fp16 output.  A bf16 output that is the correctly
+# rounded fp64 result already has a relative error of up to 2^-8 per element (8 significant bits), so
+# for bf16 the Frobenius bar is that bound; the per-element half-ulp check below is the tight one.
+TOL = {"f16": 2e-3, "bf16": 2.0 ** -8}
+BITS = (2, 3, 4)
+GROUPS = (32, 64, 128)
+DTYPES = ("f16", "bf16")
+
+
+def tk(bits):
+    return 128 if bits == 4 else 256
+
+
+def check_y(Y_bits, case, what=""):
+    What = orc.dequant(case.Q, case.T, case.S, case.group_size, case.dtype)
+    Yref = orc.matmul_f64(case.X, What, case.dtype)
+    Y = orc.to_f64(Y_bits, case.dtype)
+    assert np.isfinite(Y).all(), what
+    err = orc.rel_fro_err(Y, Yref)
+    assert err <= TOL[case.dtype], f"{what}: rel fro err {err:.3e}"
+    mag = np.abs(orc.to_f64(case.X, case.dtype)) @ np.abs(orc.to_f64(What, case.dtype)).T
+    bound = 0.5 * ulp16(Yref, case.dtype) * (1 + 1e-9) + 1e-5 * mag
+    worst = np.max(np.abs(Y - Yref) - bound)
+    assert worst <= 0, f"{what}: element outside half-ulp + accumulation allowance by {worst:.3e}"
+    return err
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("group", GROUPS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_dequant_bit_exact(lutq, bits, group, dtype):
+    import torch
+    N, K = 80, 3 * tk(bits)
+    for lut in ("nf", "learned", "random_index"):
+        c = gen.make_case(3, 1, N, K, bits, group, dtype, lut)
+        d = DeviceCase(lutq, c)
+        assert np.array_equal(d.packed_host, orc.pack(c.Q, bits))
+        W = torch.empty((N, K), dtype=torch_dtype(dtype), device="cuda")
+        lutq.lutq_dequant(d.packed, d.S, d.T, bits, group, W)
+        torch.cuda.synchronize()
+        ref = orc.dequant(c.Q, c.T, c.S, group, dtype)
+        got = to_bits(W)
+        assert np.array_equal(got, ref), f"{np.count_nonzero(got != ref)} of {ref.size} differ ({lut})"
+
+
+def test_dequant_subnormal_and_signed_zero_products(lutq):
+    """fp16 products in the subnormal range and -0.0 entries must round exactly as the oracle does."""
+    import torch
+    bits, group, dtype, N, K = 4, 32, "f16", 16, 128
+    c = gen.make_case(5, 1, N, K, bits, group, dtype, "random_index")
+    c.T = gen.encode16(np.array([-1, -0.5, -0.25, -0.0, 0.0, 1e-3, 3e-3, 0.01, 0.03, 0.1, 0.3, 0.5, 0.7, 0.9, 1.0, 1.5]), dtype)
+    c.S = gen.encode16(np.full((N, K // group), 6.1e-5) * np.linspace(0.01, 1.0, N)[:, None], dtype)
+    d = DeviceCase(lutq, c)
+    W = torch.empty((N, K), dtype=torch.float16, device="cuda")
+    lutq.lutq_dequant(d.packed, d.S, d.T, bits, group, W)
+    torch.cuda.synchronize()
+    ref = orc.dequant(c.Q, c.T, c.S, group, dtype)
+    assert ((ref & 0x7C00) == 0).mean() > 0.5          # most products are subnormal or zero
+    assert np.array_equal(to_bits(W), ref)
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dtype,group", [("f16", 128), ("f16", 32), ("bf16", 64)])
+def test_one_hot_x_reads_weights_back_bit_exact(lutq, bits, dtype, group):
+    """X[m] = e_k  =>  Y[m, n] = W^[n, k] exactly: proves layout and scale indexing through the real matmul."""
+    N, K = 64, 2 * tk(bits)
+    c = gen.make_case(9, 32, N, K, bits, group, dtype, "learned")
+    d = DeviceCase(lutq, c)
+    ref = orc.dequant(c.Q, c.T, c.S, group, dtype)                # [N, K] bits
+    one = gen.encode16(np.array([1.0]), dtype)[0]
+    for k0 in range(0, K, 32):
+        Xh = np.zeros((32, K), dtype=np.uint16)
+        Xh[np.arange(32), k0 + np.arange(32)] = one
+        Y = to_bits(d.matmul(lutq, X=to_dev(Xh, dtype)))          # [32, N]
+        want = ref[:, k0:k0 + 32].T
+        # +0 and -0 compare equal as numbers; an fp32 sum of one product and zeros keeps the value
+        assert np.array_equal(orc.to_f64(Y, dtype), orc.to_f64(want, dtype)), (bits, dtype, group, k0)
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("group", GROUPS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_matmul_matches_oracle(lutq, bits, group, dtype):
+    # 17 row blocks (one block per wave), 5 K tiles: several tiles and a ragged split over workgroups
+    for (N, K, Ms, lut) in [(272, 5 * tk(bits), (1, 3, 16, 17, 32), "nf"),
+                            (192, 4 * tk(bits), (2, 8, 31), "learned"),
+                            (160, 3 * tk(bits), (5, 24), "random_index")]:
+        for M in Ms:
+            c = gen.make_case(M, M, N, K, bits, group, dtype, lut)
+            d = DeviceCase(lutq, c)
+            check_y(to_bits(d.matmul(lutq)), c, f"b{bits} g{group} {dtype} M{M} N{N} K{K}")
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_every_batch_size_1_to_32(lutq, bits):
+    N, K, group, dtype = 128, 4 * tk(bits), 64, "f16"
+    base = gen.make_case(0, 32, N, K, bits, group, dtype, "nf")
+    d = DeviceCase(lutq, base)
+    for M in range(1, 33):
+        c = gen.Case(M, N, K, bits, group, dtype, base.X[:M].copy(), base.Q, base.S, base.T)
+        Y = to_bits(d.matmul(lutq, X=to_dev(c.X, dtype)))
+        assert Y.shape == (M, N)
+        check_y(Y, c, f"b{bits} M{M}")
+
+
+@pytest.mark.parametrize("bits,dtype", [(4, "f16"), (3, "f16"), (2, "bf16"), (4, "bf16")])
+def test_result_independent_of_work_decomposition(lutq, bits, dtype):
+    """Any grid / rows-per-wave / table-copies plan gives the same Y up to fp32 summation order, is
+    bit-reproducible call after call, and returns the arrival counters to zero (no clearing between calls)."""
+    import torch
+    N, K, group = 256, 8 * tk(bits), 128
+    for M in (1, 16, 32):
+        c = gen.make_case(40 + M, M, N, K, bits, group, dtype, "nf")
+        d = DeviceCase(lutq, c)
+        results = []
+        max_copies = 16 if bits == 2 else 32
+        for plan in [lutq.Plan(4, 1, 0), lutq.Plan(4, 2, 0), lutq.Plan(4, 3, 1), lutq.Plan(4, 7, 4), lutq.Plan(4, 31, 0),
+                     lutq.Plan(2, 5, 0), lutq.Plan(2, 64, 8), lutq.Plan(1, 16, 0), lutq.Plan(1, 33, 2),
+                     lutq.Plan(1, 128, max_copies), lutq.Plan(1, 2048, 0), lutq.Plan(0, 0, 0)]:
+            Y1 = to_bits(d.matmul(lutq, plan=plan))
+            assert not d.ws[:65536].any().item(), f"arrival counters not left zero by plan {plan}"
+            Y2 = to_bits(d.matmul(lutq, plan=plan))
+            assert np.array_equal(Y1, Y2), f"plan {plan} is not reproducible"
+            check_y(Y1, c, f"b{bits} {dtype} M{M} {plan}")
+            results.append(orc.to_f64(Y1, dtype))
+        spread = max(orc.rel_fro_err(r, results[0]) for r in results)
+        assert spread <= TOL[dtype]
+
+
+def test_edge_cases(lutq):
+    import torch
+    # smallest legal problem for each bit width; zero scales; unsorted table with duplicates
+    for bits in BITS:
+        c = gen.make_case(1, 1, 16, tk(bits), bits, 32, "f16", "learned")
+        c.T = c.T[::-1].copy()
+        c.T[1] = c.T[0]
+        c.S[3, :] = 0
+        d = DeviceCase(lutq, c)
+        Y = to_bits(d.matmul(lutq))
+        check_y(Y, c, f"minimal b{bits}")
+        assert orc.to_f64(Y, "f16")[0, 3] == 0.0
+    # all indices equal (every lane reads the same table entry)
+    c = gen.make_case(2, 4, 64, 512, 4, 128, "bf16", "nf")
+    c.Q[:] = 15
+    d = DeviceCase(lutq, c)
+    check_y(to_bits(d.matmul(lutq)), c, "constant index")
+    # X = 0 gives exact zeros
+    Y = d.matmul(lutq, X=torch.zeros_like(d.X))
+    assert not Y.any().item()
+
+
+def test_bad_plan_is_rejected_and_y_untouched(lutq):
+    import torch
+    c = gen.make_case(3, 2, 48, 256, 4, 64, "f16", "nf")            # 3 row blocks: R = 2, 4 do not divide
+    d = DeviceCase(lutq, c)
+    Y = torch.full((2, 48), 7.0, dtype=torch.float16, device="cuda")
+    for plan in (lutq.Plan(2, 0, 0), lutq.Plan(3, 0, 0), lutq.Plan(0, 4096, 0), lutq.Plan(0, 0, 3), lutq.Plan(0, 0, 64)):
+        with pytest.raises(lutq.LutqError) as e:
+            lutq.lutq_matmul(d.X, d.packed, d.S, d.T, 4, 64, Y, d.ws, plan=plan)
+        assert e.value.code == 10
+    small_ws = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(lutq.LutqError) as e:
+        lutq.lutq_matmul(d.X, d.packed, d.S, d.T, 4, 64, Y, small_ws)
+    assert e.value.code == 7
+    torch.cuda.synchronize()
+    assert (Y == 7.0).all().item()
+
+
+FULL_SIZE = [
+    # (name, N, K, bits, group, dtype, M) -- BASELINE configs at full size, default launch configuration
+    ("8B gate_up W4 g128", 28672, 4096, 4, 128, "f16", 1),
+    ("8B down W4 g128", 4096, 14336, 4, 128, "f16", 16),
+    ("8B qkv W3 g64", 6144, 4096, 3, 64, "f16", 32),
+    ("70B o W3 g64 bf16", 8192, 8192, 3, 64, "bf16", 16),
+    ("8192^2 W2 g32", 8192, 8192, 2, 32, "f16", 4),
+]
+
+
+@pytest.mark.parametrize("name,N,K,bits,group,dtype,M", FULL_SIZE)
+def test_full_size_sampled_rows(lutq, name, N, K, bits, group, dtype, M):
+    """Full BASELINE sizes in the launch configuration the benchmark times; the oracle recomputes a
+    sample of output columns (all M rows of 192 sampled weight rows, first/last row blocks included)."""
+    c = gen.make_case(17, M, N, K, bits, group, dtype, "random_index")
+    d = DeviceCase(lutq, c)
+    Y = to_bits(d.matmul(lutq))
+    assert not d.ws[:65536].any().item()
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([np.arange(16), np.arange(N - 16, N), rng.choice(N, 160, replace=False)]))
+    sub = gen.Case(M, len(rows), K, bits, group, dtype, c.X, c.Q[rows], c.S[rows], c.T)
+    check_y(Y[:, rows], sub, name)
+    assert np.isfinite(orc.to_f64(Y, dtype)).all()
