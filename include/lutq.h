@@ -87,15 +87,15 @@ lutq_status lutq_unpack(const void* packed, int64_t N, int64_t K, int bits, int 
  * (the semaphore and partial-sum areas of Algorithm 2).  0 if unsupported. */
 size_t lutq_workspace_bytes(int64_t N, int64_t K, int bits, int group_size);
 
-/* Work-decomposition knobs (Section 3.3 Stream-K partitioning; Section 4.1: tile
- * shape and number of table duplicates are chosen per shape).  All fields 0 = let
- * the library choose. */
+/* Work-decomposition knobs (Section 3.3 Stream-K partitioning; Section 4.1: the kernel instance is
+ * chosen per shape).  All fields 0 = let the library choose.  The number of table duplicates, a
+ * tuning knob in the paper, is fixed here: one copy per lane (64 copies of a 4-byte entry, 32 of an
+ * 8-byte entry), which is conflict-free by construction and makes the entry stride 256 bytes. */
 typedef struct {
     int row_blocks_per_wave;  /* 16-row blocks each wavefront streams together: 0,1,2,4; must divide N/16 */
-    int grid;                 /* number of 256-thread workgroups: 0 or 1..2048 */
-    int lut_copies;           /* copies of the vectorised table in LDS: 0 or a power of two
-                                 <= 32 (<= 16 for 2-bit); one copy per bank column removes conflicts */
-    int waves_split_k;        /* reserved, must be 0 */
+    int grid;                 /* number of workgroups: 0 or 1..2048 */
+    int waves_per_workgroup;  /* wavefronts that share one table and split a K range: 0, 4 or 8 */
+    int reserved;             /* must be 0 */
 } lutq_plan;
 
 /* Fills *plan with the library's choice for this problem. */

@@ -27,7 +27,7 @@ class LutqError(RuntimeError):
 
 class _CPlan(ctypes.Structure):
     _fields_ = [("row_blocks_per_wave", ctypes.c_int), ("grid", ctypes.c_int),
-                ("lut_copies", ctypes.c_int), ("waves_split_k", ctypes.c_int)]
+                ("waves_per_workgroup", ctypes.c_int), ("reserved", ctypes.c_int)]
 
 
 @dataclass
@@ -35,10 +35,10 @@ class Plan:
     """Work decomposition knobs of lutq_matmul_plan; 0 = library default."""
     row_blocks_per_wave: int = 0
     grid: int = 0
-    lut_copies: int = 0
+    waves_per_workgroup: int = 0
 
     def _c(self) -> _CPlan:
-        return _CPlan(self.row_blocks_per_wave, self.grid, self.lut_copies, 0)
+        return _CPlan(self.row_blocks_per_wave, self.grid, self.waves_per_workgroup, 0)
 
 
 def lib_path() -> str:
@@ -161,7 +161,7 @@ def lutq_plan_default(bits: int, group_size: int, M: int, N: int, K: int, dtype_
     cp = _CPlan()
     _check(load_library().lutq_plan_default(bits, group_size, M, N, K, dtype_code, ctypes.byref(cp)),
            "lutq_plan_default")
-    return Plan(cp.row_blocks_per_wave, cp.grid, cp.lut_copies)
+    return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup)
 
 
 def lutq_matmul(X, packed, scales, lut, bits: int, group_size: int, Y, workspace, stream=None,

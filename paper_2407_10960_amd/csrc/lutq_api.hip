@@ -2,6 +2,7 @@
 // decomposition (host part of Algorithm 1: tile scheduler and number of blocks), kernel launch.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstdlib>
 #include <mutex>
 
@@ -24,6 +25,9 @@ lutq_status check_problem(int bits, int group_size, int64_t N, int64_t K) {
     if (group_size != 32 && group_size != 64 && group_size != 128) return LUTQ_ERR_GROUP;
     if (N <= 0 || K <= 0 || N % 16 != 0 || K % tile_k(bits) != 0) return LUTQ_ERR_SHAPE;
     if (N / 16 > (int64_t)(kCounterBytes / 4) || N > (1 << 24) || K > (1 << 24)) return LUTQ_ERR_SHAPE;
+    // the kernels address every buffer with 32-bit offsets and use offsets >= 2 GiB as "out of range"
+    if (N * K * bits / 8 >= (int64_t)1 << 31 || N * (K / 32) * 2 >= (int64_t)1 << 31 || 32 * K * 2 >= (int64_t)1 << 31)
+        return LUTQ_ERR_SHAPE;
     if (K % group_size != 0) return LUTQ_ERR_GROUP;
     return LUTQ_OK;
 }
@@ -52,7 +56,8 @@ DeviceInfo device_info() {
     return cache[dev];
 }
 
-int max_log2_copies(int bits) { return bits == 2 ? 4 : 5; }
+// bytes of the replicated table in LDS: 256-byte entry stride in the fused kernel, 8 copies in lutq_dequant
+int lut_bytes_matmul(int bits) { return (bits == 3 ? 64 : 256) * 256; }
 int lut_bytes(int bits, int log2c) { return (bits == 3 ? 64 * 4 : bits == 4 ? 256 * 4 : 256 * 8) << log2c; }
 
 int ilog2(int v) {
@@ -78,7 +83,7 @@ lutq_status default_plan(int bits, int group_size, int64_t M, int64_t N, int64_t
     int64_t grid = 2 * (int64_t)cus;
     const char* env_wgs = std::getenv("LUTQ_WGS_PER_CU");
     if (env_wgs) { int v = std::atoi(env_wgs); if (v >= 1 && v <= 8) grid = (int64_t)v * cus; }
-    if (grid > tiles / 4) grid = tiles / 4;                 // at least one tile per wavefront
+    if (grid > tiles / 4) grid = tiles / 4;                 // about one tile per wavefront at least
     if (M > 8) {
         // keep whole output tiles in one workgroup when there are enough of them to fill the chip
         const int64_t groups = nb / r;
@@ -89,17 +94,17 @@ lutq_status default_plan(int bits, int group_size, int64_t M, int64_t N, int64_t
     const char* env_g = std::getenv("LUTQ_GRID");
     if (env_g) { int v = std::atoi(env_g); if (v >= 1 && v <= kMaxGrid) grid = v; }
     if (grid > tiles) grid = tiles;
-    int copies = 1 << max_log2_copies(bits);
-    const char* env_c = std::getenv("LUTQ_COPIES");
-    if (env_c) { int v = std::atoi(env_c); if (v >= 1 && v <= copies && (v & (v - 1)) == 0) copies = v; }
+    int nw = 4;
+    const char* env_nw = std::getenv("LUTQ_NW");
+    if (env_nw) { int v = std::atoi(env_nw); if (v == 4 || v == 8) nw = v; }
     plan->row_blocks_per_wave = r;
     plan->grid = (int)grid;
-    plan->lut_copies = copies;
-    plan->waves_split_k = 0;
+    plan->waves_per_workgroup = nw;
+    plan->reserved = 0;
     return LUTQ_OK;
 }
 
-typedef hipError_t (*matmul_launcher)(int, int, int, const MatmulParams&, int, hipStream_t);
+typedef hipError_t (*matmul_launcher)(int, int, int, int, bool, const MatmulParams&, int, hipStream_t);
 typedef hipError_t (*dequant_launcher)(int, const DequantParams&, int, int, hipStream_t);
 
 matmul_launcher pick_matmul(int bits, lutq_dtype dt) {
@@ -166,7 +171,8 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     int force_r = 0;
     if (user_plan) {
-        if (user_plan->waves_split_k != 0) return LUTQ_ERR_PLAN;
+        const int w = user_plan->waves_per_workgroup;
+        if ((w != 0 && w != 4 && w != 8) || user_plan->reserved != 0) return LUTQ_ERR_PLAN;
         force_r = user_plan->row_blocks_per_wave;
         if (force_r != 0 && ((force_r != 1 && force_r != 2 && force_r != 4) || nb % force_r != 0)) return LUTQ_ERR_PLAN;
     }
@@ -177,11 +183,7 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
             if (user_plan->grid < 1 || user_plan->grid > kMaxGrid) return LUTQ_ERR_PLAN;
             plan.grid = user_plan->grid;
         }
-        const int c = user_plan->lut_copies;
-        if (c != 0) {
-            if (c < 1 || (c & (c - 1)) != 0 || c > (1 << max_log2_copies(bits))) return LUTQ_ERR_PLAN;
-            plan.lut_copies = c;
-        }
+        if (user_plan->waves_per_workgroup != 0) plan.waves_per_workgroup = user_plan->waves_per_workgroup;
     }
     const int r = plan.row_blocks_per_wave;
     const int64_t tiles = (nb / r) * kt;
@@ -195,15 +197,21 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     p.Y = static_cast<uint16_t*>(Y);
     p.counters = static_cast<uint32_t*>(workspace);
     p.slots = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
+    p.packed_bytes = (uint32_t)(N * K * bits / 8);
     p.M = (int)M; p.N = (int)N; p.K = (int)K;
     p.KT = (int)kt;
     p.NRG = (int)(nb / r);
     p.G = plan.grid;
-    p.log2c = ilog2(plan.lut_copies);
     p.SG = (int)(K / group_size);
     const int mb = M > 16 ? 2 : 1;
-    const int lds = lut_bytes(bits, p.log2c) + 3 * (r * mb * 4) * 64 * (int)sizeof(float);
-    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, p, lds, static_cast<hipStream_t>(stream));
+    const int nw = plan.waves_per_workgroup;
+    const bool sch = (K / group_size) % 8 == 0;            // scale rows are 16-byte aligned: chunked scale path
+    const int slot = r * mb * 4 * 64 * (int)sizeof(float);
+    const int lds = lut_bytes_matmul(bits) + (slot > 2048 ? slot : 2048) + (sch ? nw * 1024 : 0);
+    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, nw, sch, p, lds, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess && std::getenv("LUTQ_VERBOSE"))
+        std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d, lds %d)\n", hipGetErrorString(e), p.G,
+                     nw * 64, lds);
     return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
 }
 
@@ -230,6 +238,7 @@ extern "C" lutq_status lutq_dequant(const void* packed, const void* scales, cons
     p.scales = static_cast<const uint16_t*>(scales);
     p.lut = static_cast<const uint16_t*>(lut);
     p.W = static_cast<uint16_t*>(W_out);
+    p.packed_bytes = (uint32_t)(N * K * bits / 8);
     p.N = (int)N; p.K = (int)K;
     p.KT = (int)(K / tile_k(bits));
     p.SG = (int)(K / group_size);
@@ -238,7 +247,7 @@ extern "C" lutq_status lutq_dequant(const void* packed, const void* scales, cons
     int64_t grid = (p.tiles + 3) / 4;
     const int64_t cap = (int64_t)di.cus * 8;
     if (grid > cap) grid = cap;
-    hipError_t e = pick_dequant(bits, dtype)(group_size, p, (int)grid, lut_bytes(bits, p.log2c),
+    hipError_t e = pick_dequant(bits, dtype)(group_size, p, (int)grid, lut_bytes(bits, p.log2c) + 2048,
                                              static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
 }

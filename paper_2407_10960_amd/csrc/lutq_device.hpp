@@ -42,42 +42,75 @@ template <> struct Geo<2> {
 template <int BITS> struct WFrag { u32x4 w; };
 template <> struct WFrag<3> { u32x4 w; u32x2 hi; };
 
+// ---------------------------------------------------------------------------------------
+// Global loads go through buffer instructions: an offset at or beyond the buffer size returns zeros
+// and touches no memory.  That gives (a) the zero padding of the activation rows m >= M for free and
+// (b) branch-free software pipelining: a prefetch past the end of a wave's K range is issued with an
+// out-of-range offset instead of being skipped, so the instruction stream (and with it the
+// compiler's wait counts) is the same on every path.
+// ---------------------------------------------------------------------------------------
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr uint32_t kOutOfRange = 0x80000000u;      // every buffer is smaller than 2 GiB (checked on the host)
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+
+constexpr int kAuxNone = 0;
+constexpr int kAuxStream = 2;   // non-temporal: data that is read exactly once
+
 template <int BITS>
-__device__ __forceinline__ void load_wfrag(WFrag<BITS>& f, const uint8_t* tile, int lane) {
-    f.w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 16 * lane));
+__device__ __forceinline__ void load_wfrag(WFrag<BITS>& f, rsrc_t packed, uint32_t tile_off, int lane) {
+    f.w = __builtin_amdgcn_raw_buffer_load_b128(packed, tile_off + 16u * lane, 0, kAuxStream);
     if constexpr (BITS == 3)
-        f.hi = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(tile + 1024 + 8 * lane));
+        f.hi = __builtin_amdgcn_raw_buffer_load_b64(packed, tile_off + 1024u + 8u * lane, 0, kAuxStream);
 }
 
 // ---------------------------------------------------------------------------------------
-// Vectorised table in LDS.  Entry e of copy c lives at byte (e << (log2c + log2 ENTRY_BYTES))
-// + c * ENTRY_BYTES, and lane l reads copy l mod copies: with 32 copies of a 4-byte entry every
-// lane of a half-wave stays in its own bank whatever the indices are.
+// Vectorised table in LDS (Section 3.2).  Entry e of copy c lives at byte
+// (e << (log2c + log2 ENTRY_BYTES)) + c * ENTRY_BYTES, and lane l reads copy l mod copies, so the
+// bank a lane touches depends on the lane only, never on the index: no bank conflicts.
 //   4-bit: e = 8-bit pair  (q0 | q1 << 4)            -> {T[q0], T[q1]}
 //   3-bit: e = 6-bit pair  (lo2(q0) | lo2(q1) << 2 | bit2(q0) << 4 | bit2(q1) << 5)
 //   2-bit: e = 8-bit quad  (q0 | q1 << 2 | q2 << 4 | q3 << 6) -> {T[q0], T[q1], T[q2], T[q3]}
-// Called by all 256 threads of the workgroup; caller synchronises afterwards.
+// With an entry stride of exactly 256 bytes (64 copies of 4 bytes, 32 copies of 8 bytes) the byte
+// address is "index byte in bits 8..15, lane offset in bits 0..7", which one v_perm_b32 assembles
+// straight from a packed word: one VALU instruction per lookup instead of extract + shift-add.
+//
+// Built in two phases so that the LDS writes are conflict-free 128-bit stores: first one copy of
+// the table into `stage`, then every thread expands consecutive 16-byte chunks of the replicated
+// table.  Called by all `nthreads` threads; contains one barrier; the caller synchronises after it.
 // ---------------------------------------------------------------------------------------
 template <int BITS>
-__device__ __forceinline__ void build_lut(char* lds, const uint16_t* __restrict__ T, int log2c, int tid) {
-    const int copies = 1 << log2c;
-    if constexpr (BITS == 4) {
-        const uint32_t e = (uint32_t)T[tid & 15] | ((uint32_t)T[tid >> 4] << 16);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(lds) + ((size_t)tid << log2c);
-        for (int c = 0; c < copies; ++c) dst[c] = e;
-    } else if constexpr (BITS == 3) {
-        const int e6 = tid & 63;
-        const int q0 = (e6 & 3) | (((e6 >> 4) & 1) << 2);
-        const int q1 = ((e6 >> 2) & 3) | (((e6 >> 5) & 1) << 2);
-        const uint32_t e = (uint32_t)T[q0] | ((uint32_t)T[q1] << 16);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(lds) + ((size_t)e6 << log2c);
-        for (int c = tid >> 6; c < copies; c += 4) dst[c] = e;
-    } else {
-        u32x2 e;
-        e.x = (uint32_t)T[tid & 3] | ((uint32_t)T[(tid >> 2) & 3] << 16);
-        e.y = (uint32_t)T[(tid >> 4) & 3] | ((uint32_t)T[tid >> 6] << 16);
-        u32x2* dst = reinterpret_cast<u32x2*>(lds) + ((size_t)tid << log2c);
-        for (int c = 0; c < copies; ++c) dst[c] = e;
+__device__ __forceinline__ void build_lut(char* lds, char* stage, const uint16_t* __restrict__ T, int log2c,
+                                          int tid, int nthreads) {
+    using Gm = Geo<BITS>;
+    uint32_t* st32 = reinterpret_cast<uint32_t*>(stage);
+    if (tid < Gm::ENTRIES) {
+        if constexpr (BITS == 4) {
+            st32[tid] = (uint32_t)T[tid & 15] | ((uint32_t)T[tid >> 4] << 16);
+        } else if constexpr (BITS == 3) {
+            const int q0 = (tid & 3) | (((tid >> 4) & 1) << 2);
+            const int q1 = ((tid >> 2) & 3) | (((tid >> 5) & 1) << 2);
+            st32[tid] = (uint32_t)T[q0] | ((uint32_t)T[q1] << 16);
+        } else {
+            st32[2 * tid] = (uint32_t)T[tid & 3] | ((uint32_t)T[(tid >> 2) & 3] << 16);
+            st32[2 * tid + 1] = (uint32_t)T[(tid >> 4) & 3] | ((uint32_t)T[tid >> 6] << 16);
+        }
+    }
+    __syncthreads();
+    constexpr int ESH = Gm::ENTRY_BYTES == 8 ? 3 : 2;
+    const int sh = log2c + ESH;                                   // log2 of the entry stride in bytes
+    const int chunks = (Gm::ENTRIES << sh) >> 4;
+    for (int ch = tid; ch < chunks; ch += nthreads) {
+        u32x4 v;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t byte = (uint32_t)ch * 16u + 4u * d;
+            const uint32_t idx = byte >> sh;
+            v[d] = (Gm::ENTRY_BYTES == 8) ? st32[2 * idx + ((byte >> 2) & 1)] : st32[idx];
+        }
+        *reinterpret_cast<u32x4*>(lds + (size_t)ch * 16) = v;
     }
 }
 
@@ -85,12 +118,22 @@ template <int BITS>
 __host__ __device__ constexpr int lut_lds_bytes(int log2c) {
     return (Geo<BITS>::ENTRIES * Geo<BITS>::ENTRY_BYTES) << log2c;
 }
+template <int BITS>
+__host__ __device__ constexpr int lut_stage_bytes() {
+    return Geo<BITS>::ENTRIES * Geo<BITS>::ENTRY_BYTES;
+}
+// log2 of the number of copies that makes the entry stride 256 bytes
+template <int BITS>
+__host__ __device__ constexpr int perm_log2_copies() {
+    return Geo<BITS>::ENTRY_BYTES == 8 ? 5 : 6;
+}
 
-// Per-lane constants of the lookup: the shift that turns an entry number into a byte offset, and
-// the LDS byte address of entry 0 of this lane's private copy (table base included).
 typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
 typedef __attribute__((address_space(3))) const u32x2 lds_cu64;
 
+// Per-lane constants of the lookup: the shift that turns an entry number into a byte offset, and
+// the LDS byte address of entry 0 of this lane's private copy (table base included; for the
+// v_perm form the table must start at LDS address 0, which it does as the first dynamic array).
 struct LutAddr {
     int sh;
     uint32_t lane_base;
@@ -104,11 +147,22 @@ __device__ __forceinline__ LutAddr make_lut_addr(const char* lut_lds, int log2c,
     return a;
 }
 
-__device__ __forceinline__ uint32_t lds_u32(uint32_t idx, LutAddr la) {
-    return *reinterpret_cast<lds_cu32*>((uintptr_t)((idx << la.sh) + la.lane_base));
+// Address of the entry selected by byte `p` of `word`.  PERM: bytes {lane_base.0, word.p, lane_base.2,
+// lane_base.3}; v_perm_b32 numbers the bytes of its second operand 0..3 and of its first 4..7.
+template <bool PERM, int P>
+__device__ __forceinline__ uint32_t entry_addr(uint32_t word, LutAddr la) {
+    if constexpr (PERM) {
+        return __builtin_amdgcn_perm(word, la.lane_base, 0x03020000u | ((4u + P) << 8));
+    } else {
+        const uint32_t idx = (P == 3) ? (word >> 24) : ((word >> (8 * P)) & 0xffu);
+        return (idx << la.sh) + la.lane_base;
+    }
 }
-__device__ __forceinline__ u32x2 lds_u64(uint32_t idx, LutAddr la) {
-    return *reinterpret_cast<lds_cu64*>((uintptr_t)((idx << la.sh) + la.lane_base));
+__device__ __forceinline__ uint32_t lds_u32(uint32_t addr) {
+    return *reinterpret_cast<lds_cu32*>((uintptr_t)addr);
+}
+__device__ __forceinline__ u32x2 lds_u64(uint32_t addr) {
+    return *reinterpret_cast<lds_cu64*>((uintptr_t)addr);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -146,31 +200,31 @@ __device__ __forceinline__ uint32_t scale_pair(uint32_t pair, ScaleReg<BF16> s) 
 // They are separate so that the caller can issue the LDS reads of the next step before it consumes
 // the current one.
 // ---------------------------------------------------------------------------------------
-template <int BITS>
+template <int BITS, bool PERM>
 __device__ __forceinline__ u32x4 lookup_step(const WFrag<BITS>& f, int step, LutAddr la) {
     u32x4 a;
     if constexpr (BITS == 4) {
         const uint32_t w = f.w[step];
-        a.x = lds_u32(w & 0xffu, la);
-        a.y = lds_u32((w >> 8) & 0xffu, la);
-        a.z = lds_u32((w >> 16) & 0xffu, la);
-        a.w = lds_u32(w >> 24, la);
+        a.x = lds_u32(entry_addr<PERM, 0>(w, la));
+        a.y = lds_u32(entry_addr<PERM, 1>(w, la));
+        a.z = lds_u32(entry_addr<PERM, 2>(w, la));
+        a.w = lds_u32(entry_addr<PERM, 3>(w, la));
     } else if constexpr (BITS == 3) {
         // combine the two bit-slices: bits 0..3 of each byte from the low slice, bits 4..5 from the
-        // high slice; bits 6..7 are don't-care and dropped by the 6-bit field extract.
+        // high slice, bits 6..7 cleared: four 6-bit pair-table indices, one per byte.
         const uint32_t lo = (step & 1) ? (f.w[step >> 1] >> 4) : f.w[step >> 1];
         const int u = step & 3;
         const uint32_t h = f.hi[step >> 2];
         const uint32_t hs = (u == 0) ? (h << 4) : (u == 1) ? (h << 2) : (u == 2) ? h : (h >> 2);
-        const uint32_t c = (hs & 0x30303030u) | (lo & ~0x30303030u);
-        a.x = lds_u32(c & 0x3fu, la);
-        a.y = lds_u32((c >> 8) & 0x3fu, la);
-        a.z = lds_u32((c >> 16) & 0x3fu, la);
-        a.w = lds_u32((c >> 24) & 0x3fu, la);
+        const uint32_t c = (hs & 0x30303030u) | (lo & 0x0f0f0f0fu);
+        a.x = lds_u32(entry_addr<PERM, 0>(c, la));
+        a.y = lds_u32(entry_addr<PERM, 1>(c, la));
+        a.z = lds_u32(entry_addr<PERM, 2>(c, la));
+        a.w = lds_u32(entry_addr<PERM, 3>(c, la));
     } else {
-        const uint32_t w = f.w[step >> 1] >> (16 * (step & 1));
-        const u32x2 q0 = lds_u64(w & 0xffu, la);
-        const u32x2 q1 = lds_u64((w >> 8) & 0xffu, la);
+        const uint32_t w = f.w[step >> 1];
+        const u32x2 q0 = (step & 1) ? lds_u64(entry_addr<PERM, 2>(w, la)) : lds_u64(entry_addr<PERM, 0>(w, la));
+        const u32x2 q1 = (step & 1) ? lds_u64(entry_addr<PERM, 3>(w, la)) : lds_u64(entry_addr<PERM, 1>(w, la));
         a.x = q0.x; a.y = q0.y; a.z = q1.x; a.w = q1.y;
     }
     return a;
@@ -214,8 +268,20 @@ template <> __device__ __forceinline__ u32x2 pack4<BF16>(f32x4 v) {
 template <int NS> struct ScaleWords { uint32_t w[(NS + 1) / 2]; };
 
 template <int NS>
-__device__ __forceinline__ void load_scales(ScaleWords<NS>& s, const uint16_t* p) {
-    if constexpr (NS == 1) s.w[0] = *p;
+__device__ __forceinline__ void load_scales(ScaleWords<NS>& s, rsrc_t scales, uint32_t byte_off) {
+    if constexpr (NS == 1) s.w[0] = __builtin_amdgcn_raw_buffer_load_b16(scales, byte_off, 0, kAuxNone);
+    else if constexpr (NS == 2) s.w[0] = __builtin_amdgcn_raw_buffer_load_b32(scales, byte_off, 0, kAuxNone);
+    else if constexpr (NS == 4) {
+        u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(scales, byte_off, 0, kAuxNone);
+        s.w[0] = v.x; s.w[1] = v.y;
+    } else {
+        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(scales, byte_off, 0, kAuxNone);
+        s.w[0] = v.x; s.w[1] = v.y; s.w[2] = v.z; s.w[3] = v.w;
+    }
+}
+template <int NS>
+__device__ __forceinline__ void lds_load_scales(ScaleWords<NS>& s, const char* p) {
+    if constexpr (NS == 1) s.w[0] = *reinterpret_cast<const uint16_t*>(p);
     else if constexpr (NS == 2) s.w[0] = *reinterpret_cast<const uint32_t*>(p);
     else if constexpr (NS == 4) {
         u32x2 v = *reinterpret_cast<const u32x2*>(p);

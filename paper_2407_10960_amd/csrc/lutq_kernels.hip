@@ -13,23 +13,38 @@ namespace lutq {
 
 namespace {
 
-template <int GROUP, int MB, int R>
+template <int GROUP, int MB, int R, int NW, bool SCH>
 hipError_t launch_one(const MatmulParams& p, int lds_bytes, hipStream_t stream) {
-    hipLaunchKernelGGL((matmul_kernel<LUTQ_INST_BITS, GROUP, MB, R, LUTQ_INST_DT>), dim3(p.G), dim3(256), lds_bytes,
-                       stream, p);
+    auto kernel = matmul_kernel<LUTQ_INST_BITS, GROUP, MB, R, LUTQ_INST_DT, NW, SCH>;
+    if (lds_bytes > 64 * 1024) {
+        // more than 64 KiB of dynamic LDS has to be enabled once per kernel
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr != hipSuccess) return attr;
+    }
+    hipLaunchKernelGGL(kernel, dim3(p.G), dim3(NW * 64), lds_bytes, stream, p);
     return hipGetLastError();
 }
 
+template <int GROUP, int MB, int R>
+hipError_t launch_r(int nw, bool sch, const MatmulParams& p, int lds_bytes, hipStream_t stream) {
+    if (nw == 4) return sch ? launch_one<GROUP, MB, R, 4, true>(p, lds_bytes, stream)
+                             : launch_one<GROUP, MB, R, 4, false>(p, lds_bytes, stream);
+    if (nw == 8) return sch ? launch_one<GROUP, MB, R, 8, true>(p, lds_bytes, stream)
+                             : launch_one<GROUP, MB, R, 8, false>(p, lds_bytes, stream);
+    return hipErrorInvalidValue;
+}
+
 template <int GROUP>
-hipError_t launch_group(int mb, int r, const MatmulParams& p, int lds_bytes, hipStream_t stream) {
+hipError_t launch_group(int mb, int r, int nw, bool sch, const MatmulParams& p, int lds_bytes, hipStream_t stream) {
     if (mb == 1) {
-        if (r == 1) return launch_one<GROUP, 1, 1>(p, lds_bytes, stream);
-        if (r == 2) return launch_one<GROUP, 1, 2>(p, lds_bytes, stream);
-        if (r == 4) return launch_one<GROUP, 1, 4>(p, lds_bytes, stream);
+        if (r == 1) return launch_r<GROUP, 1, 1>(nw, sch, p, lds_bytes, stream);
+        if (r == 2) return launch_r<GROUP, 1, 2>(nw, sch, p, lds_bytes, stream);
+        if (r == 4) return launch_r<GROUP, 1, 4>(nw, sch, p, lds_bytes, stream);
     } else if (mb == 2) {
-        if (r == 1) return launch_one<GROUP, 2, 1>(p, lds_bytes, stream);
-        if (r == 2) return launch_one<GROUP, 2, 2>(p, lds_bytes, stream);
-        if (r == 4) return launch_one<GROUP, 2, 4>(p, lds_bytes, stream);
+        if (r == 1) return launch_r<GROUP, 2, 1>(nw, sch, p, lds_bytes, stream);
+        if (r == 2) return launch_r<GROUP, 2, 2>(nw, sch, p, lds_bytes, stream);
+        if (r == 4) return launch_r<GROUP, 2, 4>(nw, sch, p, lds_bytes, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -42,12 +57,13 @@ hipError_t launch_dq(const DequantParams& p, int grid, int lds_bytes, hipStream_
 
 }  // namespace
 
-hipError_t LUTQ_NAME(launch_matmul_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int r, const MatmulParams& p,
-                                                                    int lds_bytes, hipStream_t stream) {
+hipError_t LUTQ_NAME(launch_matmul_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int r, int nw, bool sch,
+                                                                    const MatmulParams& p, int lds_bytes,
+                                                                    hipStream_t stream) {
     switch (group) {
-        case 32: return launch_group<32>(mb, r, p, lds_bytes, stream);
-        case 64: return launch_group<64>(mb, r, p, lds_bytes, stream);
-        case 128: return launch_group<128>(mb, r, p, lds_bytes, stream);
+        case 32: return launch_group<32>(mb, r, nw, sch, p, lds_bytes, stream);
+        case 64: return launch_group<64>(mb, r, nw, sch, p, lds_bytes, stream);
+        case 128: return launch_group<128>(mb, r, nw, sch, p, lds_bytes, stream);
     }
     return hipErrorInvalidValue;
 }

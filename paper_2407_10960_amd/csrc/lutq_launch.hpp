@@ -9,8 +9,8 @@
 namespace lutq {
 
 #define LUTQ_DECLARE_LAUNCHERS(B, DT)                                                                   \
-    hipError_t launch_matmul_b##B##_##DT(int group, int mb, int r, const MatmulParams& p, int lds_bytes, \
-                                         hipStream_t stream);                                            \
+    hipError_t launch_matmul_b##B##_##DT(int group, int mb, int r, int nw, bool sch, const MatmulParams& p,    \
+                                         int lds_bytes, hipStream_t stream);                                            \
     hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes,     \
                                           hipStream_t stream);
 

@@ -28,11 +28,11 @@ struct MatmulParams {
     uint16_t* Y;              // [M, N]
     uint32_t* counters;       // [NRG], zero on entry, zero on exit
     float* slots;             // [G][2][SLOT_FLOATS]
+    uint32_t packed_bytes;
     int M, N, K;
     int KT;                   // K tiles per row block
     int NRG;                  // row groups (N / (16 R))
     int G;                    // workgroups
-    int log2c;                // log2 of table copies
     int SG;                   // scales per row (K / group)
 };
 
@@ -44,14 +44,23 @@ __device__ __forceinline__ int owner_of(int64_t t, int64_t T, int G) {
     return (int)(((t + 1) * G - 1) / T);
 }
 
-template <int BITS, int GROUP, int MB, int R, typename DT>
-__global__ __launch_bounds__(256) void matmul_kernel(const MatmulParams p) {
+// Template parameters: bit width, group size, MB = 16-row halves of M (1: M <= 16, 2: M <= 32),
+// R = 16-row weight blocks a wave streams together (they share the activation fragments),
+// NW = waves per workgroup (they split the K range of the workgroup's segment and are reduced
+// through LDS), SCH = scales are fetched as 16-byte chunks per row (needs K/group % 8 == 0) and
+// handed to the lanes through LDS instead of being loaded tile by tile.
+template <int BITS, int GROUP, int MB, int R, typename DT, int NW, bool SCH>
+__global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
     using Gm = Geo<BITS>;
     constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
     constexpr int NS = TK / GROUP;           // scales per tile per row
     constexpr int SPG = GROUP / 32;          // steps per group
     constexpr int NREG = R * MB * 4;         // accumulator registers per lane
-    constexpr int P = 2;                     // tiles in flight per wave
+    constexpr int TPC = 8 / NS;              // tiles covered by one 16-byte scale chunk
+    // tiles in flight per wave, bounded by the registers one tile's loads occupy
+    constexpr int STAGE_REGS = R * (BITS == 3 ? 6 : 4) + STEPS * MB * 4 + (SCH ? 4 : R * ((NS + 1) / 2));
+    constexpr int P = STAGE_REGS <= 36 ? 4 : STAGE_REGS <= 44 ? 3 : 2;
+    constexpr int LOG2C = perm_log2_copies<BITS>();
 
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
@@ -60,21 +69,32 @@ __global__ __launch_bounds__(256) void matmul_kernel(const MatmulParams p) {
     const int li = lane & 15;                // row inside a 16-row block (A side) / activation row (B side)
     const int lo = lane >> 4;                // K octet
 
+    // LDS: [table, 256-byte entry stride][one partial-sum slot, also the table staging area][scale chunks]
+    constexpr int RED_BYTES = NREG * 256 > 2048 ? NREG * 256 : 2048;
     char* lut = smem;
-    float* red = reinterpret_cast<float*>(smem + lut_lds_bytes<BITS>(p.log2c));   // [3][NREG][64]
+    float* red = reinterpret_cast<float*>(smem + lut_lds_bytes<BITS>(LOG2C));
+    char* sc_lds = smem + lut_lds_bytes<BITS>(LOG2C) + RED_BYTES + wave * 1024;      // this wave's 64 rows x 16 B
 
-    build_lut<BITS>(lut, p.lut, p.log2c, tid);
-    const LutAddr la = make_lut_addr<BITS>(lut, p.log2c, lane);
+    build_lut<BITS>(lut, reinterpret_cast<char*>(red), p.lut, LOG2C, tid, NW * 64);
+    const LutAddr la = make_lut_addr<BITS>(lut, LOG2C, lane);
     __syncthreads();
 
+    const rsrc_t rW = make_rsrc(p.packed, p.packed_bytes);
+    const rsrc_t rS = make_rsrc(p.scales, (uint32_t)p.N * (uint32_t)p.SG * 2u);
+    const rsrc_t rX = make_rsrc(p.X, (uint32_t)p.M * (uint32_t)p.K * 2u);
+
+    // activation rows m >= M fall outside the X buffer and read as zero: the padding of the
+    // matrix instruction's 16 (or 32) columns costs no memory traffic
     bool valid[MB];
-    const uint16_t* xlane[MB];
+    uint32_t xlane[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = li + 16 * mb;
         valid[mb] = m < p.M;
-        xlane[mb] = p.X + (size_t)(valid[mb] ? m : 0) * p.K + 8 * lo;
+        xlane[mb] = ((uint32_t)m * (uint32_t)p.K + 8u * lo) * 2u;
     }
+    const uint32_t row_block_bytes = (uint32_t)p.KT * TILE_BYTES;       // packed bytes of one 16-row block
+    const uint32_t srow_bytes = 16u * (uint32_t)p.SG * 2u;             // scale bytes of one 16-row block
 
     const int64_t T = (int64_t)p.NRG * p.KT;
     int64_t t0 = (int64_t)blockIdx.x * T / p.G;
@@ -83,7 +103,8 @@ __global__ __launch_bounds__(256) void matmul_kernel(const MatmulParams p) {
 
     struct Stage {
         WFrag<BITS> w[R];
-        ScaleWords<NS> s[R];
+        ScaleWords<NS> s[SCH ? 1 : R];     // direct mode: this lane's scales of the tile, per row block
+        u32x4 chunk;                       // chunk mode: 8 consecutive scales of row `lane` of the wave's rows
         u32x4 x[STEPS][MB];
     };
 
@@ -92,8 +113,8 @@ __global__ __launch_bounds__(256) void matmul_kernel(const MatmulParams p) {
         const int ka = (int)(t0 - (int64_t)rg * p.KT);
         const int rem = (int)((t1 - t0 < (int64_t)(p.KT - ka)) ? (t1 - t0) : (int64_t)(p.KT - ka));
         const int kb = ka + rem;
-        const int wa = ka + (wave * rem) / 4;
-        const int wb = ka + ((wave + 1) * rem) / 4;
+        const int wa = ka + (wave * rem) / NW;
+        const int wb = ka + ((wave + 1) * rem) / NW;
 
         f32x4 acc[R][MB];
 #pragma unroll
@@ -101,39 +122,63 @@ __global__ __launch_bounds__(256) void matmul_kernel(const MatmulParams p) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) acc[r][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        const uint8_t* wrow = p.packed + (size_t)rg * R * p.KT * TILE_BYTES;           // wave-uniform
-        const uint16_t* srow = p.scales + ((size_t)rg * R * 16 + li) * p.SG;           // + r*16*SG per block
+        const uint32_t wrow = (uint32_t)rg * R * row_block_bytes;                        // wave-uniform
+        const uint32_t slane = (uint32_t)rg * R * srow_bytes + (uint32_t)li * p.SG * 2u; // direct mode
+        const uint32_t clane = lane < 16 * R ? (uint32_t)rg * R * srow_bytes + (uint32_t)lane * p.SG * 2u
+                                             : kOutOfRange;                              // chunk mode
 
+        // Loads of tile kt; kt >= wb turns every offset out of range (zeros, no traffic).
         auto load_stage = [&](Stage& st, int kt) {
+            const bool in = kt < wb;
+            const uint32_t tw = in ? wrow + (uint32_t)kt * TILE_BYTES : kOutOfRange;
+            const uint32_t tx = in ? (uint32_t)kt * (TK * 2) : kOutOfRange;
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-                load_wfrag<BITS>(st.w[r], wrow + ((size_t)r * p.KT + kt) * TILE_BYTES, lane);
+            for (int r = 0; r < R; ++r) load_wfrag<BITS>(st.w[r], rW, tw + r * row_block_bytes, lane);
+            if constexpr (SCH) {
+                const bool first = in && ((kt % TPC) == 0 || kt == wa);
+                const uint32_t tc = first ? (uint32_t)(kt / TPC) * 16u : kOutOfRange;
+                st.chunk = __builtin_amdgcn_raw_buffer_load_b128(rS, tc + clane, 0, kAuxNone);
+            } else {
+                const uint32_t ts = in ? (uint32_t)kt * (NS * 2) : kOutOfRange;
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-                load_scales<NS>(st.s[r], srow + (size_t)r * 16 * p.SG + (size_t)kt * NS);
+                for (int r = 0; r < R; ++r) load_scales<NS>(st.s[r], rS, ts + slane + r * srow_bytes);
+            }
 #pragma unroll
             for (int s = 0; s < STEPS; ++s)
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    u32x4 v = u32x4{0u, 0u, 0u, 0u};
-                    if (valid[mb]) v = *reinterpret_cast<const u32x4*>(xlane[mb] + (size_t)kt * TK + 32 * s);
-                    st.x[s][mb] = v;
-                }
+                for (int mb = 0; mb < MB; ++mb)
+                    st.x[s][mb] = __builtin_amdgcn_raw_buffer_load_b128(rX, tx + xlane[mb] + 64u * s, 0, kAuxNone);
         };
-        auto compute_stage = [&](const Stage& st) {
+        auto compute_stage = [&](const Stage& st, int kt) {
+            ScaleWords<NS> sw[R];
+            if constexpr (SCH) {
+                // a new chunk starts at this tile: every lane parks its row's 8 scales in LDS, then each
+                // lane picks the scales of its own rows (LDS operations of one wave complete in order)
+                if ((kt % TPC) == 0 || kt == wa) {
+                    asm volatile("" ::: "memory");      // keep earlier reads of the old chunk before this store
+                    *reinterpret_cast<u32x4*>(sc_lds + 16 * lane) = st.chunk;
+                    asm volatile("" ::: "memory");      // and the reads below after it
+                }
+                const char* src = sc_lds + 16 * li + (kt % TPC) * (NS * 2);
+#pragma unroll
+                for (int r = 0; r < R; ++r) lds_load_scales<NS>(sw[r], src + 256 * r);
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) sw[r] = st.s[r];
+            }
             // table reads of step s+1 are issued before step s is scaled and multiplied
             u32x4 raw[2][R];
 #pragma unroll
-            for (int r = 0; r < R; ++r) raw[0][r] = lookup_step<BITS>(st.w[r], 0, la);
+            for (int r = 0; r < R; ++r) raw[0][r] = lookup_step<BITS, true>(st.w[r], 0, la);
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 if (s + 1 < STEPS) {
 #pragma unroll
-                    for (int r = 0; r < R; ++r) raw[(s + 1) & 1][r] = lookup_step<BITS>(st.w[r], s + 1, la);
+                    for (int r = 0; r < R; ++r) raw[(s + 1) & 1][r] = lookup_step<BITS, true>(st.w[r], s + 1, la);
                 }
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    const ScaleReg<DT> sc = make_scale<DT>(scale_bits<NS>(st.s[r], s / SPG));
+                    const ScaleReg<DT> sc = make_scale<DT>(scale_bits<NS>(sw[r], s / SPG));
                     const u32x4 a = scale4<DT>(raw[s & 1][r], sc);
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb) acc[r][mb] = mfma16x16x32<DT>(a, st.x[s][mb], acc[r][mb]);
@@ -141,45 +186,53 @@ __global__ __launch_bounds__(256) void matmul_kernel(const MatmulParams p) {
             }
         };
 
+        // The scheduling barriers keep the loads of different stages in program order, so that the
+        // wait before a stage's first use only has to cover that stage's own loads.
         Stage st[P];
 #pragma unroll
-        for (int q = 0; q < P; ++q)
-            if (wa + q < wb) load_stage(st[q], wa + q);
+        for (int q = 0; q < P; ++q) {
+            load_stage(st[q], wa + q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         for (int kt = wa; kt < wb; kt += P) {
 #pragma unroll
             for (int q = 0; q < P; ++q) {
-                if (kt + q < wb) {
-                    compute_stage(st[q]);
-                    if (kt + q + P < wb) load_stage(st[q], kt + q + P);
-                }
+                if (q == 0 || kt + q < wb) compute_stage(st[q], kt + q);
+                __builtin_amdgcn_sched_barrier(0);
+                load_stage(st[q], kt + q + P);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
 
-        // ---- reduce the four waves of the workgroup through LDS ----
-        if (wave != 0) {
-            float* dst = red + (size_t)(wave - 1) * NREG * 64 + lane;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) dst[((r * MB + mb) * 4 + i) * 64] = acc[r][mb][i];
-        }
-        __syncthreads();
-        if (wave == 0) {
-            for (int w = 0; w < 3; ++w) {
-                const float* src = red + (size_t)w * NREG * 64 + lane;
+        // ---- reduce the waves of the workgroup through one LDS slot, in wave order ----
+        for (int w = 1; w < NW; ++w) {
+            if (wave == w) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) acc[r][mb][i] += src[((r * MB + mb) * 4 + i) * 64];
+                        for (int i = 0; i < 4; ++i) red[((r * MB + mb) * 4 + i) * 64 + lane] = acc[r][mb][i];
             }
+            __syncthreads();
+            if (wave == 0) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[r][mb][i] += red[((r * MB + mb) * 4 + i) * 64 + lane];
+            }
+            __syncthreads();
         }
-        __syncthreads();
 
         // ---- emit: whole output tile -> Y; otherwise the Stream-K fix-up ----
+        // Partial sums and counters are moved with device-scope (agent) atomic loads/stores, which
+        // bypass the per-XCD L2 for coherence.  No device-scope fence is used: on this multi-die part
+        // such a fence writes back and invalidates the whole L2 and costs far more than the kernel.
+        // Ordering comes from completion instead: the writer waits until its stores are acknowledged
+        // before it bumps the counter, and the reader issues its loads only after the counter value
+        // that proves it is last has come back.
         if (wave == 0) {
             bool write_y = (ka == 0 && kb == p.KT);
             if (!write_y) {
@@ -197,13 +250,14 @@ __global__ __launch_bounds__(256) void matmul_kernel(const MatmulParams p) {
                             for (int i = 0; i < 4; ++i)
                                 __hip_atomic_store(slot + ((r * MB + mb) * 4 + i) * 64, acc[r][mb][i],
                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __threadfence();       // partial sums visible device-wide before the arrival is counted
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // wait for the stores to complete
+                __builtin_amdgcn_s_waitcnt(0);
                 uint32_t old = 0;
                 if (lane == 0)
-                    old = __hip_atomic_fetch_add(p.counters + rg, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+                    old = __hip_atomic_fetch_add(p.counters + rg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 old = __builtin_amdgcn_readfirstlane(old);
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
                 if (old == (uint32_t)(g_last - g_first)) {
-                    __threadfence();
                     // last contributor: add every slot in workgroup order (own one included)
 #pragma unroll
                     for (int r = 0; r < R; ++r)
@@ -253,6 +307,7 @@ struct DequantParams {
     const uint16_t* scales;
     const uint16_t* lut;
     uint16_t* W;      // [N, K]
+    uint32_t packed_bytes;
     int N, K, KT, SG;
     int64_t tiles;    // (N/16) * KT
     int log2c;
@@ -266,22 +321,24 @@ __global__ __launch_bounds__(256) void dequant_kernel(const DequantParams p) {
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    build_lut<BITS>(smem, p.lut, p.log2c, tid);
+    build_lut<BITS>(smem, smem + lut_lds_bytes<BITS>(p.log2c), p.lut, p.log2c, tid, 256);
     const LutAddr la = make_lut_addr<BITS>(smem, p.log2c, lane);
     __syncthreads();
     const int li = lane & 15, lo = lane >> 4;
+    const rsrc_t rW = make_rsrc(p.packed, p.packed_bytes);
+    const rsrc_t rS = make_rsrc(p.scales, (uint32_t)p.N * (uint32_t)p.SG * 2u);
     for (int64_t t = (int64_t)blockIdx.x * 4 + wave; t < p.tiles; t += (int64_t)gridDim.x * 4) {
         const int64_t rb = t / p.KT;
         const int kt = (int)(t - rb * p.KT);
         WFrag<BITS> f;
-        load_wfrag<BITS>(f, p.packed + (size_t)t * TILE_BYTES, lane);
+        load_wfrag<BITS>(f, rW, (uint32_t)t * TILE_BYTES, lane);
         ScaleWords<NS> sw;
-        load_scales<NS>(sw, p.scales + ((size_t)rb * 16 + li) * p.SG + (size_t)kt * NS);
+        load_scales<NS>(sw, rS, (((uint32_t)rb * 16 + li) * (uint32_t)p.SG + (uint32_t)kt * NS) * 2u);
         uint16_t* out = p.W + ((size_t)rb * 16 + li) * p.K + (size_t)kt * TK + 8 * lo;
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
             const ScaleReg<DT> sc = make_scale<DT>(scale_bits<NS>(sw, s / SPG));
-            const u32x4 a = scale4<DT>(lookup_step<BITS>(f, s, la), sc);
+            const u32x4 a = scale4<DT>(lookup_step<BITS, false>(f, s, la), sc);
             *reinterpret_cast<u32x4*>(out + 32 * s) = a;
         }
     }

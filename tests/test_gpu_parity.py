@@ -128,10 +128,10 @@ def test_result_independent_of_work_decomposition(lutq, bits, dtype):
         c = gen.make_case(40 + M, M, N, K, bits, group, dtype, "nf")
         d = DeviceCase(lutq, c)
         results = []
-        max_copies = 16 if bits == 2 else 32
-        for plan in [lutq.Plan(4, 1, 0), lutq.Plan(4, 2, 0), lutq.Plan(4, 3, 1), lutq.Plan(4, 7, 4), lutq.Plan(4, 31, 0),
-                     lutq.Plan(2, 5, 0), lutq.Plan(2, 64, 8), lutq.Plan(1, 16, 0), lutq.Plan(1, 33, 2),
-                     lutq.Plan(1, 128, max_copies), lutq.Plan(1, 2048, 0), lutq.Plan(0, 0, 0)]:
+        for plan in [lutq.Plan(4, 1), lutq.Plan(4, 2, 8), lutq.Plan(4, 3), lutq.Plan(4, 7, 8), lutq.Plan(4, 31),
+                     lutq.Plan(2, 5), lutq.Plan(2, 64, 4), lutq.Plan(1, 16, 8), lutq.Plan(1, 33),
+                     lutq.Plan(1, 128), lutq.Plan(1, 128, 8), lutq.Plan(1, 2048),
+                     lutq.Plan(0, 0, 8), lutq.Plan(0, 0, 0)]:
             Y1 = to_bits(d.matmul(lutq, plan=plan))
             assert not d.ws[:65536].any().item(), f"arrival counters not left zero by plan {plan}"
             Y2 = to_bits(d.matmul(lutq, plan=plan))
@@ -140,6 +140,24 @@ def test_result_independent_of_work_decomposition(lutq, bits, dtype):
             results.append(orc.to_f64(Y1, dtype))
         spread = max(orc.rel_fro_err(r, results[0]) for r in results)
         assert spread <= TOL[dtype]
+
+
+def test_workspace_reuse_across_different_problems(lutq):
+    """One workspace serves calls with different data, shapes and split plans back to back: stale
+    partial sums of an earlier call must never leak into a later result."""
+    cases = [gen.make_case(60 + i, M, N, K, bits, 64, dtype, "nf")
+             for i, (M, N, K, bits, dtype) in enumerate([(1, 256, 2048, 4, "f16"), (16, 128, 1024, 3, "f16"),
+                                                          (32, 256, 1024, 2, "bf16"), (3, 64, 4096, 4, "bf16")])]
+    devs = [DeviceCase(lutq, c) for c in cases]
+    shared = devs[0].ws
+    for d in devs:
+        d.ws = shared
+    for rnd in range(3):
+        for c, d in zip(cases, devs):
+            for plan in (lutq.Plan(1, 7 + rnd, 0), lutq.Plan(0, 0, 0), lutq.Plan(1, 64, 8)):
+                check_y(to_bits(d.matmul(lutq, plan=plan)), c, f"round {rnd} {plan}")
+    assert not shared[:65536].any().item()
+
 
 
 def test_edge_cases(lutq):
@@ -169,7 +187,7 @@ def test_bad_plan_is_rejected_and_y_untouched(lutq):
     c = gen.make_case(3, 2, 48, 256, 4, 64, "f16", "nf")            # 3 row blocks: R = 2, 4 do not divide
     d = DeviceCase(lutq, c)
     Y = torch.full((2, 48), 7.0, dtype=torch.float16, device="cuda")
-    for plan in (lutq.Plan(2, 0, 0), lutq.Plan(3, 0, 0), lutq.Plan(0, 4096, 0), lutq.Plan(0, 0, 3), lutq.Plan(0, 0, 64)):
+    for plan in (lutq.Plan(2, 0, 0), lutq.Plan(3, 0, 0), lutq.Plan(0, 4096, 0), lutq.Plan(0, 0, 3), lutq.Plan(0, 0, 16)):
         with pytest.raises(lutq.LutqError) as e:
             lutq.lutq_matmul(d.X, d.packed, d.S, d.T, 4, 64, Y, d.ws, plan=plan)
         assert e.value.code == 10
