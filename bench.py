@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the LUT-quantised matmul hot path on one MI355X.
+
+A step is one decode token's pass through the quantised linear layers of a LLaMA-3-8B-shaped model:
+32 layers x [fused QKV (6144x4096), O (4096x4096), fused gate+up (28672x4096), down (4096x14336)],
+4-bit NormalFloat table, group 128, fp16, M = 1 -- 128 calls of lutq_matmul on 128 distinct weight
+buffers (3.4 GB), so every call streams its weights from HBM.  Inputs are synthetic and seeded
+(lutq_inputs.py); one layer is quantised on the host and its packed bytes are replicated on the
+device for the other layers.
+
+Prints ONE JSON line.  `value` is the whole step's algorithmic bytes (packed weights + scales + X + Y)
+divided by the step time.  `roofline` prices the fused kernel against the 8 TB/s HBM peak with HIP
+events over the same timed region; `cpu_baseline` times the CPU oracle on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import lutq_inputs as gen  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+LAYERS = 32
+BITS, GROUP, DTYPE, M = 4, 128, "f16", 1
+
+
+def _to_dev(bits_u16, torch):
+    return torch.from_numpy(np.ascontiguousarray(bits_u16).view(np.int16).copy()).view(torch.float16).cuda()
+
+
+def build_layer(lutq, torch, seed):
+    """One layer's four quantised matrices (host-quantised, seeded), uploaded once."""
+    mats = {}
+    for i, (name, (N, K)) in enumerate(gen.LLAMA3_8B_SHAPES.items()):
+        c = gen.make_case(seed * 16 + i, M, N, K, BITS, GROUP, DTYPE, "nf")
+        packed = torch.from_numpy(lutq.lutq_pack(c.Q, BITS, GROUP)).cuda()
+        mats[name] = dict(N=N, K=K, case=c, packed=packed, S=_to_dev(c.S, torch), T=_to_dev(c.T, torch),
+                          X=_to_dev(c.X, torch))
+    return mats
+
+
+def time_region(torch, fn, iters):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / iters          # seconds per iteration
+
+
+def cpu_baseline(case, budget_s=12.0):
+    """The oracle as it stands, on the host cores, on the O-projection shape of the same workload."""
+    from oracle import lutq_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    packed = orc.pack(case.Q, case.bits)
+    t0 = time.perf_counter()
+    n = 0
+    while True:
+        orc.lut_matmul(case.X, packed, case.S, case.T, case.bits, case.group_size, case.N, case.K, case.dtype)
+        n += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = (time.perf_counter() - t0) / n
+    by = gen.algorithmic_bytes(case.M, case.N, case.K, case.bits, case.group_size)
+    return {"value": by / dt * 1e-9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n} calls of the numpy oracle (unpack + table lookup + scale + fp64 matmul) on the "
+                      f"O-projection shape N={case.N} K={case.K} M={case.M} W4 g128; {dt * 1e3:.0f} ms per call; "
+                      f"only the fp64 matmul step is multi-threaded"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-shape table and the dense fp16 comparison")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path has no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2407_10960_amd as lutq
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    lutq.load_library()          # fails loudly if liblutq.so is missing: there is no fallback path
+
+    layer0 = build_layer(lutq, torch, seed=0)
+    names = list(layer0.keys())
+    # 32 layers of distinct device buffers (replicas of layer 0's bytes: only the addresses matter for HBM)
+    layers = []
+    for li in range(LAYERS):
+        L = {}
+        for n in names:
+            m = layer0[n]
+            L[n] = dict(packed=m["packed"] if li == 0 else m["packed"].clone(),
+                        S=m["S"] if li == 0 else m["S"].clone())
+        layers.append(L)
+    Y = {n: torch.empty((M, layer0[n]["N"]), dtype=torch.float16, device="cuda") for n in names}
+    ws = lutq.new_workspace(28672, 4096, BITS, GROUP)
+
+    def one_call(n, li):
+        m = layer0[n]
+        lutq.lutq_matmul(m["X"], layers[li][n]["packed"], layers[li][n]["S"], m["T"], BITS, GROUP, Y[n], ws)
+
+    def step_direct():
+        for li in range(LAYERS):
+            for n in names:
+                one_call(n, li)
+
+    step_bytes = LAYERS * sum(gen.algorithmic_bytes(M, layer0[n]["N"], layer0[n]["K"], BITS, GROUP) for n in names)
+    launches = LAYERS * len(names)
+
+    step_direct()          # first launches: module load, device query
+    torch.cuda.synchronize()
+
+    use_graph = not args.no_graph
+    graph = None
+    if use_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step_direct()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step_direct()
+        step = graph.replay
+    else:
+        step = step_direct
+
+    for _ in range(args.warmup):
+        step()
+    sec = time_region(torch, step, args.steps)
+    value = step_bytes / sec * 1e-9
+    per_launch_s = sec / launches
+    roof_achieved = (step_bytes / launches) / per_launch_s * 1e-9
+
+    out = {
+        "metric": "effective HBM GB/s of LUT-GEMM (packed weights + scales + X + Y bytes per call / time), M=1",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "llama3-8b decode linears, W4 NormalFloat table g128 fp16 M=1: 32 layers x "
+                               "[qkv 6144x4096, o 4096x4096, gate_up 28672x4096, down 4096x14336] = 128 lutq_matmul "
+                               "calls per step on 128 distinct weight buffers (3.4 GB, HBM-cold)",
+                   "bits": BITS, "group_size": GROUP, "M": M, "launch": "hipgraph replay" if use_graph else "python loop",
+                   "calls_per_step": launches, "bytes_per_step": step_bytes,
+                   "percent_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "achieved": roof_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": roof_achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "lutq::matmul_kernel<4,128,1,R,F16,NW,true>", "bytes_per_launch": step_bytes / launches,
+                     "us_per_launch": per_launch_s * 1e6},
+    }
+
+    if not args.no_extras:
+        per_shape = {}
+        for n in names:
+            m = layer0[n]
+            N, K = m["N"], m["K"]
+            by = gen.algorithmic_bytes(M, N, K, BITS, GROUP)
+            state = {"i": 0}
+
+            def cold_call(n=n, state=state):
+                one_call(n, state["i"] % LAYERS)
+                state["i"] += 1
+            for _ in range(LAYERS):
+                cold_call()
+            t = time_region(torch, cold_call, 4 * LAYERS)
+            # dense fp16 GEMM on the same shape (torch.mm -> hipBLASLt/rocBLAS), ring of weights > 1 GB
+            dense_bytes = N * K * 2
+            ring = max(2, min(LAYERS, int(1.3e9 // dense_bytes) + 1))
+            Wd = [torch.randn((N, K), dtype=torch.float16, device="cuda") * 0.02 for _ in range(ring)]
+            Yd = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            dstate = {"i": 0}
+
+            def dense_call(dstate=dstate, Wd=Wd, Yd=Yd, m=m):
+                torch.mm(m["X"], Wd[dstate["i"] % len(Wd)].t(), out=Yd)
+                dstate["i"] += 1
+            for _ in range(ring):
+                dense_call()
+            td = time_region(torch, dense_call, 4 * ring)
+            del Wd
+            per_shape[n] = {"N": N, "K": K, "us": t * 1e6, "GBps": by / t * 1e-9, "frac_of_8TBps": by / t * 1e-9 / HBM_PEAK_GBS,
+                            "TFLOPs": 2.0 * M * N * K / t * 1e-12, "dense_fp16_us": td * 1e6, "speedup_vs_dense_fp16": td / t}
+        out["per_shape_cold_python_launch"] = per_shape
+        # achievable streaming-read bandwidth over one gate_up-sized buffer per launch (same ring)
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        rstate = {"i": 0}
+
+        def read_call():
+            lutq.calib_stream_read(layers[rstate["i"] % LAYERS]["gate_up"]["packed"], 512, sink)
+            rstate["i"] += 1
+        for _ in range(LAYERS):
+            read_call()
+        tr = time_region(torch, read_call, 4 * LAYERS)
+        out["stream_read_calibrator"] = {"bytes": int(layer0["gate_up"]["packed"].numel()), "us": tr * 1e6,
+                                         "GBps": layer0["gate_up"]["packed"].numel() / tr * 1e-9}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layer0["o"]["case"])
+    else:
+        out["cpu_baseline"] = None
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

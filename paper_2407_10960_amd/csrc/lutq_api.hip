@@ -66,40 +66,35 @@ int ilog2(int v) {
     return l;
 }
 
-// Default work decomposition.  Tiles = (N / 16R) row groups x (K / TK) K tiles; the grid is a small
-// multiple of the CU count (Stream-K: blocks proportional to the number of processors), reduced when
-// there is too little work per workgroup or when M is large enough for the partial-sum traffic of
-// split output tiles to matter.
+// Default work decomposition (host part of Algorithm 1: the tile scheduler and the number of blocks).
+// Tiles = (N / 16R) row groups x (K / TK) K tiles, cut into `grid` equal contiguous ranges.
+//
+// Measured on MI355X, the cross-workgroup fix-up costs three dependent device-scope round trips
+// (store partials, bump the counter, read the slots), several microseconds, which is more than the
+// wave quantisation it would remove on these decode shapes.  So the default keeps every output tile
+// inside one workgroup whenever that still gives each compute unit a workgroup: R is the largest of
+// 4, 2, 1 with at least one row group per compute unit, and grid = number of row groups.  Only when
+// N is too small for that (fewer 16-row blocks than compute units) is K split across workgroups,
+// into j equal parts per row group, with the Stream-K style fix-up.
 lutq_status default_plan(int bits, int group_size, int64_t M, int64_t N, int64_t K, int cus, int force_r,
                          lutq_plan* plan) {
-    (void)group_size;
+    (void)group_size; (void)M;
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     int r = 4;
-    while (r > 1 && nb % r != 0) r >>= 1;
-    const char* env_r = std::getenv("LUTQ_R");
-    if (env_r) { int v = std::atoi(env_r); if ((v == 1 || v == 2 || v == 4) && nb % v == 0) r = v; }
+    while (r > 1 && (nb % r != 0 || nb / r < cus)) r >>= 1;
     if (force_r) r = force_r;
-    const int64_t tiles = (nb / r) * kt;
-    int64_t grid = 2 * (int64_t)cus;
-    const char* env_wgs = std::getenv("LUTQ_WGS_PER_CU");
-    if (env_wgs) { int v = std::atoi(env_wgs); if (v >= 1 && v <= 8) grid = (int64_t)v * cus; }
-    if (grid > tiles / 4) grid = tiles / 4;                 // about one tile per wavefront at least
-    if (M > 8) {
-        // keep whole output tiles in one workgroup when there are enough of them to fill the chip
-        const int64_t groups = nb / r;
-        if (groups >= cus && groups < grid) grid = groups;
+    const int64_t groups = nb / r;
+    int64_t grid = groups;
+    if (groups < cus) {
+        int64_t j = (cus + groups - 1) / groups;         // K parts per row group
+        if (j > kt / 4) j = kt / 4;                      // keep at least one K tile per wavefront
+        if (j < 1) j = 1;
+        grid = groups * j;
     }
-    if (grid < 1) grid = 1;
-    if (grid > kMaxGrid) grid = kMaxGrid;
-    const char* env_g = std::getenv("LUTQ_GRID");
-    if (env_g) { int v = std::atoi(env_g); if (v >= 1 && v <= kMaxGrid) grid = v; }
-    if (grid > tiles) grid = tiles;
-    int nw = 4;
-    const char* env_nw = std::getenv("LUTQ_NW");
-    if (env_nw) { int v = std::atoi(env_nw); if (v == 4 || v == 8) nw = v; }
+    while (grid > kMaxGrid) grid = (grid + 1) / 2;
     plan->row_blocks_per_wave = r;
     plan->grid = (int)grid;
-    plan->waves_per_workgroup = nw;
+    plan->waves_per_workgroup = 4;
     plan->reserved = 0;
     return LUTQ_OK;
 }
