@@ -136,10 +136,13 @@ def quantize(W, T_bits, group_size: int, dtype: str):
 # matrix-unit operand order, and 3-bit weights split into a 2-bit and a 1-bit
 # slice so that every load is a power-of-two number of bits)
 # ----------------------------------------------------------------------------
-# N is cut into row blocks of 16, K into tiles of TK (128 for 4-bit, 256 for
-# 2- and 3-bit).  Tiles are stored row-block-major, K-tile fastest.  Inside a
-# tile, "lane" l = 16*o + i (i = row inside the block, o = 0..3) owns, for each
-# 32-wide K step t of the tile, the 8 consecutive indices
+# N is cut into row blocks of 16, K into tiles of TK (128 for 4-bit, 256 for 2- and 3-bit).
+# Row blocks are grouped into super-blocks of SB = 4 (if N/16 is a multiple of 4, else 2, else 1)
+# consecutive row blocks.  Storage order: super-block, then K tile, then row block inside the
+# super-block; tile (rb, kt) is tile number ((rb // SB) * (K/TK) + kt) * SB + rb % SB.  (So the SB
+# tiles that cover 16*SB rows x TK columns are adjacent in memory.)  Inside a tile, "lane"
+# l = 16*o + i (i = row inside the block, o = 0..3) owns, for each 32-wide K step t of the tile,
+# the 8 consecutive indices
 #       Q[16*rb + i, TK*kt + 32*t + 8*o + j],  j = 0..7.
 #
 # 4-bit: tile = 64 lanes x 16 B.  Lane l: four little-endian uint32 words d = 0..3
@@ -161,14 +164,23 @@ def packed_bytes(N: int, K: int, bits: int) -> int:
     return N * K * bits // 8
 
 
+def super_block(N: int) -> int:
+    """Row blocks per super-block: 4 if N/16 is a multiple of 4, else 2, else 1."""
+    nb = N // 16
+    return 4 if nb % 4 == 0 else 2 if nb % 2 == 0 else 1
+
+
 def _lane_view(Q: np.ndarray, bits: int) -> np.ndarray:
-    """Q [N,K] -> A[rb, kt, o, i, t, j] = Q[16rb+i, TK*kt + 32t + 8o + j]."""
+    """Q [N,K] -> A[tile, o, i, t, j] in storage order of the tiles;
+    tile = ((rb // SB) * KT + kt) * SB + rb % SB holds Q[16rb+i, TK*kt + 32t + 8o + j]."""
     N, K = Q.shape
     TK = TILE_K[bits]
     if N % 16 or K % TK:
         raise ValueError("N must be a multiple of 16 and K of the tile width")
-    A = Q.reshape(N // 16, 16, K // TK, TK // 32, 4, 8)      # rb, i, kt, t, o, j
-    return A.transpose(0, 2, 4, 1, 3, 5)                      # rb, kt, o, i, t, j
+    SB = super_block(N)
+    A = Q.reshape(N // 16 // SB, SB, 16, K // TK, TK // 32, 4, 8)   # sb, r, i, kt, t, o, j
+    A = A.transpose(0, 3, 1, 5, 2, 4, 6)                             # sb, kt, r, o, i, t, j
+    return A.reshape(N // 16, K // TK, 4, 16, TK // 32, 8)          # (sb,kt,r) flattened as [NB, KT]: storage order
 
 
 def pack(Q, bits: int) -> np.ndarray:
@@ -238,8 +250,10 @@ def unpack(packed, N: int, K: int, bits: int) -> np.ndarray:
                 A[..., t, j] = low2 | (bit2 << np.uint32(2))
     else:
         raise ValueError("bits must be 2, 3 or 4")
-    # rb,kt,o,i,t,j -> rb,i,kt,t,o,j
-    return np.ascontiguousarray(A.transpose(0, 3, 1, 4, 2, 5)).reshape(N, K)
+    # A is in storage order (sb, kt, r) x (o, i, t, j); undo it: -> sb, r, i, kt, t, o, j
+    SB = super_block(N)
+    A = A.reshape(NB // SB, KT, SB, 4, 16, TK // 32, 8)
+    return np.ascontiguousarray(A.transpose(0, 2, 4, 1, 5, 3, 6)).reshape(N, K)
 
 
 # ----------------------------------------------------------------------------

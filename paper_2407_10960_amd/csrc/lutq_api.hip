@@ -56,8 +56,8 @@ DeviceInfo device_info() {
     return cache[dev];
 }
 
-// bytes of the replicated table in LDS: 256-byte entry stride in the fused kernel, 8 copies in lutq_dequant
-int lut_bytes_matmul(int bits) { return (bits == 3 ? 64 : 256) * 256; }
+// bytes of the replicated table in LDS of lutq_dequant (8 copies)
+inline int super_block(int64_t nb) { return nb % 4 == 0 ? 4 : nb % 2 == 0 ? 2 : 1; }
 int lut_bytes(int bits, int log2c) { return (bits == 3 ? 64 * 4 : bits == 4 ? 256 * 4 : 256 * 8) << log2c; }
 
 int ilog2(int v) {
@@ -78,10 +78,10 @@ int ilog2(int v) {
 // into j equal parts per row group, with the Stream-K style fix-up.
 lutq_status default_plan(int bits, int group_size, int64_t M, int64_t N, int64_t K, int cus, int force_r,
                          lutq_plan* plan) {
-    (void)group_size; (void)M;
+    (void)group_size;
     const int64_t nb = N / 16, kt = K / tile_k(bits);
-    int r = 4;
-    while (r > 1 && (nb % r != 0 || nb / r < cus)) r >>= 1;
+    int r = super_block(nb);                              // R has to divide the layout's super-block
+    while (r > 1 && nb / r < cus) r >>= 1;
     if (force_r) r = force_r;
     const int64_t groups = nb / r;
     int64_t grid = groups;
@@ -95,11 +95,11 @@ lutq_status default_plan(int bits, int group_size, int64_t M, int64_t N, int64_t
     plan->row_blocks_per_wave = r;
     plan->grid = (int)grid;
     plan->waves_per_workgroup = 4;
-    plan->reserved = 0;
+    plan->tiles_in_flight = (r == 4 && M > 16) ? 2 : 4;
     return LUTQ_OK;
 }
 
-typedef hipError_t (*matmul_launcher)(int, int, int, int, bool, const MatmulParams&, int, hipStream_t);
+typedef hipError_t (*matmul_launcher)(int, int, int, int, int, bool, const MatmulParams&, hipStream_t);
 typedef hipError_t (*dequant_launcher)(int, const DequantParams&, int, int, hipStream_t);
 
 matmul_launcher pick_matmul(int bits, lutq_dtype dt) {
@@ -167,9 +167,11 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     int force_r = 0;
     if (user_plan) {
         const int w = user_plan->waves_per_workgroup;
-        if ((w != 0 && w != 4 && w != 8) || user_plan->reserved != 0) return LUTQ_ERR_PLAN;
+        const int f = user_plan->tiles_in_flight;
+        if ((w != 0 && w != 4 && w != 8) || (f != 0 && f != 2 && f != 4)) return LUTQ_ERR_PLAN;
         force_r = user_plan->row_blocks_per_wave;
-        if (force_r != 0 && ((force_r != 1 && force_r != 2 && force_r != 4) || nb % force_r != 0)) return LUTQ_ERR_PLAN;
+        if (force_r != 0 && ((force_r != 1 && force_r != 2 && force_r != 4) || super_block(nb) % force_r != 0))
+            return LUTQ_ERR_PLAN;
     }
     lutq_plan plan;
     default_plan(bits, group_size, M, N, K, di.cus, force_r, &plan);
@@ -179,6 +181,7 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
             plan.grid = user_plan->grid;
         }
         if (user_plan->waves_per_workgroup != 0) plan.waves_per_workgroup = user_plan->waves_per_workgroup;
+        if (user_plan->tiles_in_flight != 0) plan.tiles_in_flight = user_plan->tiles_in_flight;
     }
     const int r = plan.row_blocks_per_wave;
     const int64_t tiles = (nb / r) * kt;
@@ -198,15 +201,15 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     p.NRG = (int)(nb / r);
     p.G = plan.grid;
     p.SG = (int)(K / group_size);
+    p.SB = super_block(nb);
     const int mb = M > 16 ? 2 : 1;
-    const int nw = plan.waves_per_workgroup;
     const bool sch = (K / group_size) % 8 == 0;            // scale rows are 16-byte aligned: chunked scale path
-    const int slot = r * mb * 4 * 64 * (int)sizeof(float);
-    const int lds = lut_bytes_matmul(bits) + (slot > 2048 ? slot : 2048) + (sch ? nw * 1024 : 0);
-    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, nw, sch, p, lds, static_cast<hipStream_t>(stream));
+    int nw = plan.waves_per_workgroup, stages = plan.tiles_in_flight;
+    if (!sch) { nw = 4; stages = 2; }                      // the per-tile scale path exists in one shape only
+    if (!matmul_instance_exists(nw, stages, sch)) return LUTQ_ERR_PLAN;
+    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, nw, stages, sch, p, static_cast<hipStream_t>(stream));
     if (e != hipSuccess && std::getenv("LUTQ_VERBOSE"))
-        std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d, lds %d)\n", hipGetErrorString(e), p.G,
-                     nw * 64, lds);
+        std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d)\n", hipGetErrorString(e), p.G, nw * 64);
     return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
 }
 
@@ -237,6 +240,7 @@ extern "C" lutq_status lutq_dequant(const void* packed, const void* scales, cons
     p.N = (int)N; p.K = (int)K;
     p.KT = (int)(K / tile_k(bits));
     p.SG = (int)(K / group_size);
+    p.SB = super_block(N / 16);
     p.tiles = (N / 16) * (int64_t)p.KT;
     p.log2c = 3;
     int64_t grid = (p.tiles + 3) / 4;

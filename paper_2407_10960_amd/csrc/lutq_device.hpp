@@ -79,23 +79,41 @@ __device__ __forceinline__ void load_wfrag(WFrag<BITS>& f, rsrc_t packed, uint32
 //
 // Built in two phases so that the LDS writes are conflict-free 128-bit stores: first one copy of
 // the table into `stage`, then every thread expands consecutive 16-byte chunks of the replicated
-// table.  Called by all `nthreads` threads; contains one barrier; the caller synchronises after it.
+// table.  lut_build is called by all `nthreads` threads, contains one barrier, and the caller
+// synchronises after it.
 // ---------------------------------------------------------------------------------------
+// Global reads of T for this thread's entry of the single-copy table (threads >= ENTRIES read
+// nothing).  Separate from lut_build so that the caller can issue these loads first, then its
+// weight prefetch, and build the table while the prefetch is in flight.
 template <int BITS>
-__device__ __forceinline__ void build_lut(char* lds, char* stage, const uint16_t* __restrict__ T, int log2c,
-                                          int tid, int nthreads) {
+__device__ __forceinline__ u32x2 lut_fetch(const uint16_t* __restrict__ T, int tid) {
     using Gm = Geo<BITS>;
-    uint32_t* st32 = reinterpret_cast<uint32_t*>(stage);
+    u32x2 e = u32x2{0u, 0u};
     if (tid < Gm::ENTRIES) {
         if constexpr (BITS == 4) {
-            st32[tid] = (uint32_t)T[tid & 15] | ((uint32_t)T[tid >> 4] << 16);
+            e.x = (uint32_t)T[tid & 15] | ((uint32_t)T[tid >> 4] << 16);
         } else if constexpr (BITS == 3) {
             const int q0 = (tid & 3) | (((tid >> 4) & 1) << 2);
             const int q1 = ((tid >> 2) & 3) | (((tid >> 5) & 1) << 2);
-            st32[tid] = (uint32_t)T[q0] | ((uint32_t)T[q1] << 16);
+            e.x = (uint32_t)T[q0] | ((uint32_t)T[q1] << 16);
         } else {
-            st32[2 * tid] = (uint32_t)T[tid & 3] | ((uint32_t)T[(tid >> 2) & 3] << 16);
-            st32[2 * tid + 1] = (uint32_t)T[(tid >> 4) & 3] | ((uint32_t)T[tid >> 6] << 16);
+            e.x = (uint32_t)T[tid & 3] | ((uint32_t)T[(tid >> 2) & 3] << 16);
+            e.y = (uint32_t)T[(tid >> 4) & 3] | ((uint32_t)T[tid >> 6] << 16);
+        }
+    }
+    return e;
+}
+
+template <int BITS>
+__device__ __forceinline__ void lut_build(char* lds, char* stage, u32x2 seed, int log2c, int tid, int nthreads) {
+    using Gm = Geo<BITS>;
+    uint32_t* st32 = reinterpret_cast<uint32_t*>(stage);
+    if (tid < Gm::ENTRIES) {
+        if constexpr (Gm::ENTRY_BYTES == 8) {
+            st32[2 * tid] = seed.x;
+            st32[2 * tid + 1] = seed.y;
+        } else {
+            st32[tid] = seed.x;
         }
     }
     __syncthreads();
@@ -112,6 +130,12 @@ __device__ __forceinline__ void build_lut(char* lds, char* stage, const uint16_t
         }
         *reinterpret_cast<u32x4*>(lds + (size_t)ch * 16) = v;
     }
+}
+
+template <int BITS>
+__device__ __forceinline__ void build_lut(char* lds, char* stage, const uint16_t* __restrict__ T, int log2c,
+                                          int tid, int nthreads) {
+    lut_build<BITS>(lds, stage, lut_fetch<BITS>(T, tid), log2c, tid, nthreads);
 }
 
 template <int BITS>

@@ -1,5 +1,6 @@
 // Instantiates the kernels for one (bit width, dtype) pair and dispatches the remaining template
-// parameters (group size, M blocks, row blocks per wave) at run time.
+// parameters (group size, M blocks, row blocks per wave, waves per workgroup, tiles in flight,
+// scale path) at run time.
 #include "lutq_launch.hpp"
 
 #ifndef LUTQ_INST_BITS
@@ -13,9 +14,10 @@ namespace lutq {
 
 namespace {
 
-template <int GROUP, int MB, int R, int NW, bool SCH>
-hipError_t launch_one(const MatmulParams& p, int lds_bytes, hipStream_t stream) {
-    auto kernel = matmul_kernel<LUTQ_INST_BITS, GROUP, MB, R, LUTQ_INST_DT, NW, SCH>;
+template <int GROUP, int MB, int R, int NW, int P, bool SCH>
+hipError_t launch_one(const MatmulParams& p, hipStream_t stream) {
+    auto kernel = matmul_kernel<LUTQ_INST_BITS, GROUP, MB, R, LUTQ_INST_DT, NW, P, SCH>;
+    constexpr int lds_bytes = matmul_lds_bytes<LUTQ_INST_BITS>(R, MB, NW, SCH);
     if (lds_bytes > 64 * 1024) {
         // more than 64 KiB of dynamic LDS has to be enabled once per kernel
         static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -27,24 +29,25 @@ hipError_t launch_one(const MatmulParams& p, int lds_bytes, hipStream_t stream) 
 }
 
 template <int GROUP, int MB, int R>
-hipError_t launch_r(int nw, bool sch, const MatmulParams& p, int lds_bytes, hipStream_t stream) {
-    if (nw == 4) return sch ? launch_one<GROUP, MB, R, 4, true>(p, lds_bytes, stream)
-                             : launch_one<GROUP, MB, R, 4, false>(p, lds_bytes, stream);
-    if (nw == 8) return sch ? launch_one<GROUP, MB, R, 8, true>(p, lds_bytes, stream)
-                             : launch_one<GROUP, MB, R, 8, false>(p, lds_bytes, stream);
+hipError_t launch_r(int nw, int stages, bool sch, const MatmulParams& p, hipStream_t stream) {
+    if (!sch) return (nw == 4 && stages == 2) ? launch_one<GROUP, MB, R, 4, 2, false>(p, stream) : hipErrorInvalidValue;
+    if (nw == 4 && stages == 2) return launch_one<GROUP, MB, R, 4, 2, true>(p, stream);
+    if (nw == 4 && stages == 4) return launch_one<GROUP, MB, R, 4, 4, true>(p, stream);
+    if (nw == 8 && stages == 2) return launch_one<GROUP, MB, R, 8, 2, true>(p, stream);
+    if (nw == 8 && stages == 4) return launch_one<GROUP, MB, R, 8, 4, true>(p, stream);
     return hipErrorInvalidValue;
 }
 
 template <int GROUP>
-hipError_t launch_group(int mb, int r, int nw, bool sch, const MatmulParams& p, int lds_bytes, hipStream_t stream) {
+hipError_t launch_group(int mb, int r, int nw, int stages, bool sch, const MatmulParams& p, hipStream_t stream) {
     if (mb == 1) {
-        if (r == 1) return launch_r<GROUP, 1, 1>(nw, sch, p, lds_bytes, stream);
-        if (r == 2) return launch_r<GROUP, 1, 2>(nw, sch, p, lds_bytes, stream);
-        if (r == 4) return launch_r<GROUP, 1, 4>(nw, sch, p, lds_bytes, stream);
+        if (r == 1) return launch_r<GROUP, 1, 1>(nw, stages, sch, p, stream);
+        if (r == 2) return launch_r<GROUP, 1, 2>(nw, stages, sch, p, stream);
+        if (r == 4) return launch_r<GROUP, 1, 4>(nw, stages, sch, p, stream);
     } else if (mb == 2) {
-        if (r == 1) return launch_r<GROUP, 2, 1>(nw, sch, p, lds_bytes, stream);
-        if (r == 2) return launch_r<GROUP, 2, 2>(nw, sch, p, lds_bytes, stream);
-        if (r == 4) return launch_r<GROUP, 2, 4>(nw, sch, p, lds_bytes, stream);
+        if (r == 1) return launch_r<GROUP, 2, 1>(nw, stages, sch, p, stream);
+        if (r == 2) return launch_r<GROUP, 2, 2>(nw, stages, sch, p, stream);
+        if (r == 4) return launch_r<GROUP, 2, 4>(nw, stages, sch, p, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -57,13 +60,13 @@ hipError_t launch_dq(const DequantParams& p, int grid, int lds_bytes, hipStream_
 
 }  // namespace
 
-hipError_t LUTQ_NAME(launch_matmul_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int r, int nw, bool sch,
-                                                                    const MatmulParams& p, int lds_bytes,
+hipError_t LUTQ_NAME(launch_matmul_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int r, int nw, int stages,
+                                                                    bool sch, const MatmulParams& p,
                                                                     hipStream_t stream) {
     switch (group) {
-        case 32: return launch_group<32>(mb, r, nw, sch, p, lds_bytes, stream);
-        case 64: return launch_group<64>(mb, r, nw, sch, p, lds_bytes, stream);
-        case 128: return launch_group<128>(mb, r, nw, sch, p, lds_bytes, stream);
+        case 32: return launch_group<32>(mb, r, nw, stages, sch, p, stream);
+        case 64: return launch_group<64>(mb, r, nw, stages, sch, p, stream);
+        case 128: return launch_group<128>(mb, r, nw, stages, sch, p, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -8,10 +8,17 @@
 
 namespace lutq {
 
-#define LUTQ_DECLARE_LAUNCHERS(B, DT)                                                                   \
-    hipError_t launch_matmul_b##B##_##DT(int group, int mb, int r, int nw, bool sch, const MatmulParams& p,    \
-                                         int lds_bytes, hipStream_t stream);                                            \
-    hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes,     \
+// Kernel instances that exist: waves per workgroup x tiles in flight.  (The per-tile scale path,
+// used only when K/group is not a multiple of 8, exists for 4 waves and 2 tiles in flight.)
+inline bool matmul_instance_exists(int nw, int stages, bool sch) {
+    if (!sch) return nw == 4 && stages == 2;
+    return (nw == 4 || nw == 8) && (stages == 2 || stages == 4);
+}
+
+#define LUTQ_DECLARE_LAUNCHERS(B, DT)                                                               \
+    hipError_t launch_matmul_b##B##_##DT(int group, int mb, int r, int nw, int stages, bool sch,     \
+                                         const MatmulParams& p, hipStream_t stream);                 \
+    hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes, \
                                           hipStream_t stream);
 
 LUTQ_DECLARE_LAUNCHERS(2, F16)

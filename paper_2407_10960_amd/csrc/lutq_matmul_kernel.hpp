@@ -34,6 +34,7 @@ struct MatmulParams {
     int NRG;                  // row groups (N / (16 R))
     int G;                    // workgroups
     int SG;                   // scales per row (K / group)
+    int SB;                   // row blocks per super-block of the packed layout (multiple of R)
 };
 
 // Largest partial-sum slot: R = 4 row blocks x 2 M-halves x 4 registers x 64 lanes.
@@ -44,12 +45,20 @@ __device__ __forceinline__ int owner_of(int64_t t, int64_t T, int G) {
     return (int)(((t + 1) * G - 1) / T);
 }
 
+// LDS bytes of one launch (host and device agree through this one function).
+template <int BITS>
+__host__ __device__ constexpr int red_bytes(int nreg) { return nreg * 256 > 2048 ? nreg * 256 : 2048; }
+template <int BITS>
+__host__ __device__ constexpr int matmul_lds_bytes(int r, int mb, int nw, bool sch) {
+    return lut_lds_bytes<BITS>(perm_log2_copies<BITS>()) + red_bytes<BITS>(r * mb * 4) + (sch ? nw * 1024 : 0);
+}
+
 // Template parameters: bit width, group size, MB = 16-row halves of M (1: M <= 16, 2: M <= 32),
 // R = 16-row weight blocks a wave streams together (they share the activation fragments),
 // NW = waves per workgroup (they split the K range of the workgroup's segment and are reduced
-// through LDS), SCH = scales are fetched as 16-byte chunks per row (needs K/group % 8 == 0) and
-// handed to the lanes through LDS instead of being loaded tile by tile.
-template <int BITS, int GROUP, int MB, int R, typename DT, int NW, bool SCH>
+// through LDS), P = tiles in flight per wave, SCH = scales are fetched as 16-byte chunks per row
+// (needs K/group % 8 == 0) and handed to the lanes through LDS instead of being loaded per tile.
+template <int BITS, int GROUP, int MB, int R, typename DT, int NW, int P, bool SCH>
 __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
     using Gm = Geo<BITS>;
     constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
@@ -57,10 +66,12 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
     constexpr int SPG = GROUP / 32;          // steps per group
     constexpr int NREG = R * MB * 4;         // accumulator registers per lane
     constexpr int TPC = 8 / NS;              // tiles covered by one 16-byte scale chunk
-    // tiles in flight per wave, bounded by the registers one tile's loads occupy
-    constexpr int STAGE_REGS = R * (BITS == 3 ? 6 : 4) + STEPS * MB * 4 + (SCH ? 4 : R * ((NS + 1) / 2));
-    constexpr int P = STAGE_REGS <= 36 ? 4 : STAGE_REGS <= 44 ? 3 : 2;
     constexpr int LOG2C = perm_log2_copies<BITS>();
+    constexpr int LUT_BYTES = lut_lds_bytes<BITS>(LOG2C);
+    constexpr int U = STEPS * R;             // (step, row block) items of one tile
+    constexpr int D = U < 4 ? U : 4;         // table reads kept in flight ahead of their use
+    // all waves' partial sums fit in the table area: reduce there in one go after the last segment
+    constexpr bool FAST_REDUCE = (NW - 1) * NREG * 256 <= LUT_BYTES;
 
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
@@ -70,14 +81,14 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
     const int lo = lane >> 4;                // K octet
 
     // LDS: [table, 256-byte entry stride][one partial-sum slot, also the table staging area][scale chunks]
-    constexpr int RED_BYTES = NREG * 256 > 2048 ? NREG * 256 : 2048;
     char* lut = smem;
-    float* red = reinterpret_cast<float*>(smem + lut_lds_bytes<BITS>(LOG2C));
-    char* sc_lds = smem + lut_lds_bytes<BITS>(LOG2C) + RED_BYTES + wave * 1024;      // this wave's 64 rows x 16 B
+    float* red = reinterpret_cast<float*>(smem + LUT_BYTES);
+    char* sc_lds = smem + LUT_BYTES + red_bytes<BITS>(NREG) + wave * 1024;      // this wave's 64 rows x 16 B
 
-    build_lut<BITS>(lut, reinterpret_cast<char*>(red), p.lut, LOG2C, tid, NW * 64);
+    const u32x2 lut_seed = lut_fetch<BITS>(p.lut, tid);      // issued before any weight load (see below)
+    __builtin_amdgcn_sched_barrier(0);
     const LutAddr la = make_lut_addr<BITS>(lut, LOG2C, lane);
-    __syncthreads();
+    bool lut_ready = false;
 
     const rsrc_t rW = make_rsrc(p.packed, p.packed_bytes);
     const rsrc_t rS = make_rsrc(p.scales, (uint32_t)p.N * (uint32_t)p.SG * 2u);
@@ -93,7 +104,8 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
         valid[mb] = m < p.M;
         xlane[mb] = ((uint32_t)m * (uint32_t)p.K + 8u * lo) * 2u;
     }
-    const uint32_t row_block_bytes = (uint32_t)p.KT * TILE_BYTES;       // packed bytes of one 16-row block
+    const uint32_t tile_stride = (uint32_t)p.SB * TILE_BYTES;          // bytes from K tile kt to kt+1
+    const uint32_t sblock_bytes = (uint32_t)p.KT * tile_stride;         // packed bytes of one super-block
     const uint32_t srow_bytes = 16u * (uint32_t)p.SG * 2u;             // scale bytes of one 16-row block
 
     const int64_t T = (int64_t)p.NRG * p.KT;
@@ -115,6 +127,7 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
         const int kb = ka + rem;
         const int wa = ka + (wave * rem) / NW;
         const int wb = ka + ((wave + 1) * rem) / NW;
+        const bool last_segment = (t0 + rem == t1);
 
         f32x4 acc[R][MB];
 #pragma unroll
@@ -122,18 +135,19 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) acc[r][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        const uint32_t wrow = (uint32_t)rg * R * row_block_bytes;                        // wave-uniform
-        const uint32_t slane = (uint32_t)rg * R * srow_bytes + (uint32_t)li * p.SG * 2u; // direct mode
-        const uint32_t clane = lane < 16 * R ? (uint32_t)rg * R * srow_bytes + (uint32_t)lane * p.SG * 2u
+        const int rb0 = rg * R;                                                          // first row block
+        const uint32_t wrow = (uint32_t)(rb0 / p.SB) * sblock_bytes + (uint32_t)(rb0 % p.SB) * TILE_BYTES;
+        const uint32_t slane = (uint32_t)rb0 * srow_bytes + (uint32_t)li * p.SG * 2u;    // direct mode
+        const uint32_t clane = lane < 16 * R ? (uint32_t)rb0 * srow_bytes + (uint32_t)lane * p.SG * 2u
                                              : kOutOfRange;                              // chunk mode
 
         // Loads of tile kt; kt >= wb turns every offset out of range (zeros, no traffic).
         auto load_stage = [&](Stage& st, int kt) {
             const bool in = kt < wb;
-            const uint32_t tw = in ? wrow + (uint32_t)kt * TILE_BYTES : kOutOfRange;
+            const uint32_t tw = in ? wrow + (uint32_t)kt * tile_stride : kOutOfRange;
             const uint32_t tx = in ? (uint32_t)kt * (TK * 2) : kOutOfRange;
 #pragma unroll
-            for (int r = 0; r < R; ++r) load_wfrag<BITS>(st.w[r], rW, tw + r * row_block_bytes, lane);
+            for (int r = 0; r < R; ++r) load_wfrag<BITS>(st.w[r], rW, tw + r * TILE_BYTES, lane);
             if constexpr (SCH) {
                 const bool first = in && ((kt % TPC) == 0 || kt == wa);
                 const uint32_t tc = first ? (uint32_t)(kt / TPC) * 16u : kOutOfRange;
@@ -166,22 +180,35 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
 #pragma unroll
                 for (int r = 0; r < R; ++r) sw[r] = st.s[r];
             }
-            // table reads of step s+1 are issued before step s is scaled and multiplied
-            u32x4 raw[2][R];
+            // items u = (step s, row block r), r fastest; the table reads of item u + D are issued
+            // before item u is scaled and multiplied
+            // (scheduling barriers pin this order: left alone, the compiler sinks part of an item's
+            // table reads to just before their use and every item then waits out the LDS latency)
+            u32x4 raw[D];
 #pragma unroll
-            for (int r = 0; r < R; ++r) raw[0][r] = lookup_step<BITS, true>(st.w[r], 0, la);
+            for (int u = 0; u < D; ++u) raw[u] = lookup_step<BITS, true>(st.w[u % R], u / R, la);
+            __builtin_amdgcn_sched_barrier(0);
+            // the matrix instruction of item u is issued after the scaling of item u + 1, so that it
+            // never has to wait for operands that were written by the instructions just before it
+            u32x4 a[2];
 #pragma unroll
-            for (int s = 0; s < STEPS; ++s) {
-                if (s + 1 < STEPS) {
-#pragma unroll
-                    for (int r = 0; r < R; ++r) raw[(s + 1) & 1][r] = lookup_step<BITS, true>(st.w[r], s + 1, la);
-                }
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
+            for (int u = 0; u <= U; ++u) {
+                if (u < U) {
+                    const int s = u / R, r = u % R;
                     const ScaleReg<DT> sc = make_scale<DT>(scale_bits<NS>(sw[r], s / SPG));
-                    const u32x4 a = scale4<DT>(raw[s & 1][r], sc);
+                    a[u & 1] = scale4<DT>(raw[u % D], sc);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (u + D < U) {
+                        raw[u % D] = lookup_step<BITS, true>(st.w[(u + D) % R], (u + D) / R, la);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                if (u > 0) {
+                    const int s = (u - 1) / R, r = (u - 1) % R;
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) acc[r][mb] = mfma16x16x32<DT>(a, st.x[s][mb], acc[r][mb]);
+                    for (int mb = 0; mb < MB; ++mb)
+                        acc[r][mb] = mfma16x16x32<DT>(a[(u - 1) & 1], st.x[s][mb], acc[r][mb]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         };
@@ -194,6 +221,14 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
             load_stage(st[q], wa + q);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (!lut_ready) {
+            // first segment: the table is built while the first tiles are in flight (its own reads
+            // of T were issued before them, so waiting for T does not wait for the tiles)
+            lut_build<BITS>(lut, reinterpret_cast<char*>(red), lut_seed, LOG2C, tid, NW * 64);
+            __syncthreads();
+            lut_ready = true;
+            __builtin_amdgcn_sched_barrier(0);
+        }
         for (int kt = wa; kt < wb; kt += P) {
 #pragma unroll
             for (int q = 0; q < P; ++q) {
@@ -204,26 +239,53 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
             }
         }
 
-        // ---- reduce the waves of the workgroup through one LDS slot, in wave order ----
-        for (int w = 1; w < NW; ++w) {
-            if (wave == w) {
+        // ---- reduce the waves of the workgroup through LDS, in wave order ----
+        if (FAST_REDUCE && last_segment) {
+            // nobody needs the table any more: every wave parks its sums there, wave 0 adds them up
+            __syncthreads();
+            float* area = reinterpret_cast<float*>(lut);
+            if (wave != 0) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) red[((r * MB + mb) * 4 + i) * 64 + lane] = acc[r][mb][i];
+                        for (int i = 0; i < 4; ++i)
+                            area[((wave - 1) * NREG + (r * MB + mb) * 4 + i) * 64 + lane] = acc[r][mb][i];
             }
             __syncthreads();
             if (wave == 0) {
+                for (int w = 0; w < NW - 1; ++w) {
 #pragma unroll
-                for (int r = 0; r < R; ++r)
+                    for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
+                        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) acc[r][mb][i] += red[((r * MB + mb) * 4 + i) * 64 + lane];
+                            for (int i = 0; i < 4; ++i)
+                                acc[r][mb][i] += area[(w * NREG + (r * MB + mb) * 4 + i) * 64 + lane];
+                }
             }
-            __syncthreads();
+        } else {
+            for (int w = 1; w < NW; ++w) {
+                if (wave == w) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) red[((r * MB + mb) * 4 + i) * 64 + lane] = acc[r][mb][i];
+                }
+                __syncthreads();
+                if (wave == 0) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) acc[r][mb][i] += red[((r * MB + mb) * 4 + i) * 64 + lane];
+                }
+                __syncthreads();
+            }
         }
 
         // ---- emit: whole output tile -> Y; otherwise the Stream-K fix-up ----
@@ -309,6 +371,7 @@ struct DequantParams {
     uint16_t* W;      // [N, K]
     uint32_t packed_bytes;
     int N, K, KT, SG;
+    int SB;           // row blocks per super-block of the packed layout
     int64_t tiles;    // (N/16) * KT
     int log2c;
 };
@@ -328,8 +391,12 @@ __global__ __launch_bounds__(256) void dequant_kernel(const DequantParams p) {
     const rsrc_t rW = make_rsrc(p.packed, p.packed_bytes);
     const rsrc_t rS = make_rsrc(p.scales, (uint32_t)p.N * (uint32_t)p.SG * 2u);
     for (int64_t t = (int64_t)blockIdx.x * 4 + wave; t < p.tiles; t += (int64_t)gridDim.x * 4) {
-        const int64_t rb = t / p.KT;
-        const int kt = (int)(t - rb * p.KT);
+        // t counts tiles in storage order: super-block, K tile, row block inside the super-block
+        const int64_t per_sb = (int64_t)p.KT * p.SB;
+        const int64_t sb = t / per_sb;
+        const int in_sb = (int)(t - sb * per_sb);
+        const int kt = in_sb / p.SB;
+        const int64_t rb = sb * p.SB + in_sb % p.SB;
         WFrag<BITS> f;
         load_wfrag<BITS>(f, rW, (uint32_t)t * TILE_BYTES, lane);
         ScaleWords<NS> sw;

@@ -5,11 +5,15 @@
 //
 // Packed layout (this library's own; the paper's is tied to NVIDIA Ampere fragments).
 //
-// Q is [N, K] row-major.  N is cut into row blocks of 16 rows, K into tiles of TK
-// columns (TK = 128 for 4-bit, 256 for 2- and 3-bit).  Tiles are stored one after the
-// other, row block major, K tile fastest: tile (rb, kt) starts at byte
-// (rb * K/TK + kt) * TILE_BYTES.  A tile is what one 64-lane wavefront loads with one
-// 128-bit load per lane (plus one 64-bit load for the 3-bit high slice).
+// Q is [N, K] row-major.  N is cut into row blocks of 16 rows, K into tiles of TK columns
+// (TK = 128 for 4-bit, 256 for 2- and 3-bit).  Row blocks are grouped into super-blocks of SB
+// consecutive row blocks (SB = 4 if N/16 is a multiple of 4, else 2, else 1).  Storage order is
+// super-block, then K tile, then row block inside the super-block: tile (rb, kt) starts at byte
+//        (((rb / SB) * K/TK + kt) * SB + rb % SB) * TILE_BYTES,
+// so the SB tiles that cover 16*SB rows x TK columns are adjacent: a wavefront that owns a whole
+// super-block streams one contiguous run of memory along K instead of SB separate runs.  A tile is
+// what one 64-lane wavefront loads with one 128-bit load per lane (plus one 64-bit load for the
+// 3-bit high slice).
 //
 // The gfx950 instruction v_mfma_f32_16x16x32_{f16,bf16} takes, from lane l = 16*o + i
 // (i = 0..15, o = 0..3), the eight A-matrix elements of row i and columns 8*o .. 8*o+7
@@ -41,6 +45,8 @@ namespace {
 
 inline int tile_k(int bits) { return bits == 4 ? 128 : 256; }
 inline int tile_bytes(int bits) { return bits == 3 ? 1536 : 1024; }
+inline int super_block(int64_t nb) { return nb % 4 == 0 ? 4 : nb % 2 == 0 ? 2 : 1; }
+inline int64_t tile_index(int64_t rb, int64_t kt, int64_t KT, int SB) { return ((rb / SB) * KT + kt) * SB + rb % SB; }
 
 lutq_status check_pack_args(int64_t N, int64_t K, int bits, int group_size) {
     if (bits < 2 || bits > 4) return LUTQ_ERR_BITS;
@@ -80,13 +86,14 @@ extern "C" lutq_status lutq_pack(const uint8_t* indices, int64_t N, int64_t K, i
     if (st != LUTQ_OK) return st;
     const int TK = tile_k(bits), TB = tile_bytes(bits), steps = TK / 32;
     const int64_t NB = N / 16, KT = K / TK;
+    const int SB = super_block(NB);
     const uint32_t limit = 1u << bits;
     uint8_t* out = static_cast<uint8_t*>(packed_out);
     int bad = 0;
 #pragma omp parallel for schedule(static) reduction(| : bad)
     for (int64_t rb = 0; rb < NB; ++rb) {
         for (int64_t kt = 0; kt < KT; ++kt) {
-            uint8_t* tile = out + (rb * KT + kt) * TB;
+            uint8_t* tile = out + tile_index(rb, kt, KT, SB) * TB;
             std::memset(tile, 0, TB);
             for (int l = 0; l < 64; ++l) {
                 const int i = l & 15, o = l >> 4;
@@ -118,11 +125,12 @@ extern "C" lutq_status lutq_unpack(const void* packed, int64_t N, int64_t K, int
     if (st != LUTQ_OK) return st;
     const int TK = tile_k(bits), TB = tile_bytes(bits), steps = TK / 32;
     const int64_t NB = N / 16, KT = K / TK;
+    const int SB = super_block(NB);
     const uint8_t* in = static_cast<const uint8_t*>(packed);
 #pragma omp parallel for schedule(static)
     for (int64_t rb = 0; rb < NB; ++rb) {
         for (int64_t kt = 0; kt < KT; ++kt) {
-            const uint8_t* tile = in + (rb * KT + kt) * TB;
+            const uint8_t* tile = in + tile_index(rb, kt, KT, SB) * TB;
             for (int l = 0; l < 64; ++l) {
                 const int i = l & 15, o = l >> 4;
                 uint8_t* row = indices_out + (16 * rb + i) * K + kt * TK + 8 * o;

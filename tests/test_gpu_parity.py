@@ -128,9 +128,9 @@ def test_result_independent_of_work_decomposition(lutq, bits, dtype):
         c = gen.make_case(40 + M, M, N, K, bits, group, dtype, "nf")
         d = DeviceCase(lutq, c)
         results = []
-        for plan in [lutq.Plan(4, 1), lutq.Plan(4, 2, 8), lutq.Plan(4, 3), lutq.Plan(4, 7, 8), lutq.Plan(4, 31),
-                     lutq.Plan(2, 5), lutq.Plan(2, 64, 4), lutq.Plan(1, 16, 8), lutq.Plan(1, 33),
-                     lutq.Plan(1, 128), lutq.Plan(1, 128, 8), lutq.Plan(1, 2048),
+        for plan in [lutq.Plan(4, 1), lutq.Plan(4, 2, 8), lutq.Plan(4, 3, 4, 2), lutq.Plan(4, 7, 8, 2), lutq.Plan(4, 31),
+                     lutq.Plan(2, 5), lutq.Plan(2, 64, 4, 4), lutq.Plan(1, 16, 8), lutq.Plan(1, 33, 0, 2),
+                     lutq.Plan(1, 128), lutq.Plan(1, 128, 8, 4), lutq.Plan(1, 2048),
                      lutq.Plan(0, 0, 8), lutq.Plan(0, 0, 0)]:
             Y1 = to_bits(d.matmul(lutq, plan=plan))
             assert not d.ws[:65536].any().item(), f"arrival counters not left zero by plan {plan}"
@@ -187,7 +187,7 @@ def test_bad_plan_is_rejected_and_y_untouched(lutq):
     c = gen.make_case(3, 2, 48, 256, 4, 64, "f16", "nf")            # 3 row blocks: R = 2, 4 do not divide
     d = DeviceCase(lutq, c)
     Y = torch.full((2, 48), 7.0, dtype=torch.float16, device="cuda")
-    for plan in (lutq.Plan(2, 0, 0), lutq.Plan(3, 0, 0), lutq.Plan(0, 4096, 0), lutq.Plan(0, 0, 3), lutq.Plan(0, 0, 16)):
+    for plan in (lutq.Plan(2, 0, 0), lutq.Plan(3, 0, 0), lutq.Plan(0, 4096, 0), lutq.Plan(0, 0, 3), lutq.Plan(0, 0, 16), lutq.Plan(0, 0, 0, 3)):
         with pytest.raises(lutq.LutqError) as e:
             lutq.lutq_matmul(d.X, d.packed, d.S, d.T, 4, 64, Y, d.ws, plan=plan)
         assert e.value.code == 10
