@@ -93,7 +93,7 @@ size_t lutq_workspace_bytes(int64_t N, int64_t K, int bits, int group_size);
  * 8-byte entry), which is conflict-free by construction and makes the entry stride 256 bytes. */
 typedef struct {
     int row_blocks_per_wave;  /* 16-row blocks each wavefront streams together: 0,1,2,4; must divide N/16 */
-    int grid;                 /* number of workgroups: 0 or 1..2048 */
+    int grid;                 /* number of workgroups: 0 or 1..4096 */
     int waves_per_workgroup;  /* wavefronts that share one table and split a K range: 0, 4 or 8 */
     int tiles_in_flight;      /* K tiles each wavefront keeps in flight (software pipeline depth): 0, 2 or 4 */
 } lutq_plan;

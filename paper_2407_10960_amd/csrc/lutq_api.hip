@@ -13,7 +13,7 @@ namespace {
 
 using namespace lutq;
 
-constexpr int kMaxGrid = 2048;
+constexpr int kMaxGrid = 4096;
 constexpr size_t kCounterBytes = 64 * 1024;                                   // 16384 row groups
 constexpr size_t kSlotBytes = (size_t)kSlotFloats * sizeof(float);            // 8 KiB
 constexpr size_t kWorkspaceBytes = kCounterBytes + (size_t)kMaxGrid * 2 * kSlotBytes;
@@ -99,7 +99,7 @@ lutq_status default_plan(int bits, int group_size, int64_t M, int64_t N, int64_t
     return LUTQ_OK;
 }
 
-typedef hipError_t (*matmul_launcher)(int, int, int, int, int, bool, const MatmulParams&, hipStream_t);
+typedef hipError_t (*matmul_launcher)(int, int, int, int, int, bool, int, const MatmulParams&, hipStream_t);
 typedef hipError_t (*dequant_launcher)(int, const DequantParams&, int, int, hipStream_t);
 
 matmul_launcher pick_matmul(int bits, lutq_dtype dt) {
@@ -200,14 +200,19 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     p.KT = (int)kt;
     p.NRG = (int)(nb / r);
     p.G = plan.grid;
+    p.TQ = (int)(tiles / plan.grid);
+    p.TR = (int)(tiles % plan.grid);
     p.SG = (int)(K / group_size);
-    p.SB = super_block(nb);
+    p.SBL = ilog2(super_block(nb));
     const int mb = M > 16 ? 2 : 1;
     const bool sch = (K / group_size) % 8 == 0;            // scale rows are 16-byte aligned: chunked scale path
     int nw = plan.waves_per_workgroup, stages = plan.tiles_in_flight;
     if (!sch) { nw = 4; stages = 2; }                      // the per-tile scale path exists in one shape only
     if (!matmul_instance_exists(nw, stages, sch)) return LUTQ_ERR_PLAN;
-    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, nw, stages, sch, p, static_cast<hipStream_t>(stream));
+    // M <= 4: four K steps of activations per load, rotated into place (a quarter of the registers)
+    int xm = (M <= 4) ? 4 : 16;
+    if (const char* ev = std::getenv("LUTQ_XM")) xm = (std::atoi(ev) == 16 || M > 4) ? 16 : 4;
+    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, nw, stages, sch, xm, p, static_cast<hipStream_t>(stream));
     if (e != hipSuccess && std::getenv("LUTQ_VERBOSE"))
         std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d)\n", hipGetErrorString(e), p.G, nw * 64);
     return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;

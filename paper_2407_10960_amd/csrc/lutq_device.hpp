@@ -77,65 +77,59 @@ __device__ __forceinline__ void load_wfrag(WFrag<BITS>& f, rsrc_t packed, uint32
 // address is "index byte in bits 8..15, lane offset in bits 0..7", which one v_perm_b32 assembles
 // straight from a packed word: one VALU instruction per lookup instead of extract + shift-add.
 //
-// Built in two phases so that the LDS writes are conflict-free 128-bit stores: first one copy of
-// the table into `stage`, then every thread expands consecutive 16-byte chunks of the replicated
-// table.  lut_build is called by all `nthreads` threads, contains one barrier, and the caller
-// synchronises after it.
+// Built without staging: entry e is a row of `stride` bytes (the same value repeated), and the
+// ENTRIES rows are dealt to the threads, nthreads / ENTRIES threads per row (nthreads is a multiple
+// of ENTRIES: 256 or more threads, at most 256 entries).  Every thread fetches the one or two table
+// values of its row straight from global memory (lut_fetch), and later writes its part of the row
+// as 128-bit stores (lut_build).  The 16-byte chunk a lane starts with is skewed by its row number,
+// so that the lanes of one store instruction, whose rows are 256 bytes apart, hit different banks.
+// The two halves are separate so that the caller can issue the reads of T first, then its weight
+// prefetch, and only then wait for T: lut_fetch returns the raw loaded values and does no arithmetic
+// on them.  lut_build is called by all `nthreads` threads; the caller synchronises after it.
 // ---------------------------------------------------------------------------------------
-// Global reads of T for this thread's entry of the single-copy table (threads >= ENTRIES read
-// nothing).  Separate from lut_build so that the caller can issue these loads first, then its
-// weight prefetch, and build the table while the prefetch is in flight.
+struct LutSeed { uint32_t v[4]; };     // raw 16-bit table values of this thread's row
+
 template <int BITS>
-__device__ __forceinline__ u32x2 lut_fetch(const uint16_t* __restrict__ T, int tid) {
-    using Gm = Geo<BITS>;
-    u32x2 e = u32x2{0u, 0u};
-    if (tid < Gm::ENTRIES) {
-        if constexpr (BITS == 4) {
-            e.x = (uint32_t)T[tid & 15] | ((uint32_t)T[tid >> 4] << 16);
-        } else if constexpr (BITS == 3) {
-            const int q0 = (tid & 3) | (((tid >> 4) & 1) << 2);
-            const int q1 = ((tid >> 2) & 3) | (((tid >> 5) & 1) << 2);
-            e.x = (uint32_t)T[q0] | ((uint32_t)T[q1] << 16);
-        } else {
-            e.x = (uint32_t)T[tid & 3] | ((uint32_t)T[(tid >> 2) & 3] << 16);
-            e.y = (uint32_t)T[(tid >> 4) & 3] | ((uint32_t)T[tid >> 6] << 16);
-        }
+__device__ __forceinline__ LutSeed lut_fetch(const uint16_t* __restrict__ T, int tid, int nthreads) {
+    const int e = tid / (nthreads / Geo<BITS>::ENTRIES);
+    LutSeed s;
+    if constexpr (BITS == 4) {
+        s.v[0] = T[e & 15]; s.v[1] = T[(e >> 4) & 15]; s.v[2] = 0; s.v[3] = 0;
+    } else if constexpr (BITS == 3) {
+        const int q0 = (e & 3) | (((e >> 4) & 1) << 2);
+        const int q1 = ((e >> 2) & 3) | (((e >> 5) & 1) << 2);
+        s.v[0] = T[q0]; s.v[1] = T[q1]; s.v[2] = 0; s.v[3] = 0;
+    } else {
+        s.v[0] = T[e & 3]; s.v[1] = T[(e >> 2) & 3]; s.v[2] = T[(e >> 4) & 3]; s.v[3] = T[(e >> 6) & 3];
     }
-    return e;
+    return s;
 }
 
 template <int BITS>
-__device__ __forceinline__ void lut_build(char* lds, char* stage, u32x2 seed, int log2c, int tid, int nthreads) {
+__device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int log2c, int tid, int nthreads) {
     using Gm = Geo<BITS>;
-    uint32_t* st32 = reinterpret_cast<uint32_t*>(stage);
-    if (tid < Gm::ENTRIES) {
-        if constexpr (Gm::ENTRY_BYTES == 8) {
-            st32[2 * tid] = seed.x;
-            st32[2 * tid + 1] = seed.y;
-        } else {
-            st32[tid] = seed.x;
-        }
-    }
-    __syncthreads();
     constexpr int ESH = Gm::ENTRY_BYTES == 8 ? 3 : 2;
-    const int sh = log2c + ESH;                                   // log2 of the entry stride in bytes
-    const int chunks = (Gm::ENTRIES << sh) >> 4;
-    for (int ch = tid; ch < chunks; ch += nthreads) {
-        u32x4 v;
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const uint32_t byte = (uint32_t)ch * 16u + 4u * d;
-            const uint32_t idx = byte >> sh;
-            v[d] = (Gm::ENTRY_BYTES == 8) ? st32[2 * idx + ((byte >> 2) & 1)] : st32[idx];
-        }
-        *reinterpret_cast<u32x4*>(lds + (size_t)ch * 16) = v;
+    const int stride = 1 << (log2c + ESH);                        // bytes of one row
+    const int chunks = stride >> 4;                               // 16-byte chunks of one row (power of two)
+    const int tpe = nthreads / Gm::ENTRIES;                       // threads per row (>= 1)
+    const int e = tid / tpe, part = tid % tpe;
+    const int per = chunks / tpe > 0 ? chunks / tpe : 1;          // chunks written by this thread
+    if (e >= Gm::ENTRIES || part * per >= chunks) return;
+    u32x4 v;
+    v.x = seed.v[0] | (seed.v[1] << 16);
+    if constexpr (Gm::ENTRY_BYTES == 8) { v.y = seed.v[2] | (seed.v[3] << 16); v.z = v.x; v.w = v.y; }
+    else { v.y = v.x; v.z = v.x; v.w = v.x; }
+    char* row = lds + (size_t)e * stride;
+    for (int i = 0; i < per; ++i) {
+        const int c = (part * per + i + e) & (chunks - 1);
+        *reinterpret_cast<u32x4*>(row + 16 * c) = v;
     }
 }
 
 template <int BITS>
-__device__ __forceinline__ void build_lut(char* lds, char* stage, const uint16_t* __restrict__ T, int log2c,
-                                          int tid, int nthreads) {
-    lut_build<BITS>(lds, stage, lut_fetch<BITS>(T, tid), log2c, tid, nthreads);
+__device__ __forceinline__ void build_lut(char* lds, const uint16_t* __restrict__ T, int log2c, int tid, int nthreads) {
+    const LutSeed s = lut_fetch<BITS>(T, tid, nthreads);
+    lut_build<BITS>(lds, s, log2c, tid, nthreads);
 }
 
 template <int BITS>
@@ -198,12 +192,13 @@ template <typename DT> struct ScaleReg;
 template <> struct ScaleReg<F16> { uint32_t s2; };    // scale in both halves
 template <> struct ScaleReg<BF16> { float s; };
 
-template <typename DT> __device__ __forceinline__ ScaleReg<DT> make_scale(uint32_t bits16);
-template <> __device__ __forceinline__ ScaleReg<F16> make_scale<F16>(uint32_t b) {
-    ScaleReg<F16> r; r.s2 = (b & 0xffffu) | (b << 16); return r;
+// Scale register from 16-bit half `hi` (0: low, 1: high) of a 32-bit word: one instruction each.
+template <typename DT> __device__ __forceinline__ ScaleReg<DT> make_scale(uint32_t word, int hi);
+template <> __device__ __forceinline__ ScaleReg<F16> make_scale<F16>(uint32_t w, int hi) {
+    ScaleReg<F16> r; r.s2 = __builtin_amdgcn_perm(w, w, hi ? 0x03020302u : 0x01000100u); return r;
 }
-template <> __device__ __forceinline__ ScaleReg<BF16> make_scale<BF16>(uint32_t b) {
-    ScaleReg<BF16> r; r.s = __builtin_bit_cast(float, b << 16); return r;
+template <> __device__ __forceinline__ ScaleReg<BF16> make_scale<BF16>(uint32_t w, int hi) {
+    ScaleReg<BF16> r; r.s = __builtin_bit_cast(float, hi ? (w & 0xffff0000u) : (w << 16)); return r;
 }
 
 __device__ __forceinline__ uint32_t scale_pair(uint32_t pair, ScaleReg<F16> s) {
@@ -264,6 +259,26 @@ __device__ __forceinline__ u32x4 scale4(u32x4 raw, ScaleReg<DT> sc) {
     return a;
 }
 
+// Lane i of every 16-lane row receives the value of lane (i + n) mod 16 of the same row
+// (a DPP row rotate to the right by 16 - n lanes), for each of the four registers; n in {0, 4, 8, 12}.
+template <int CTRL>
+__device__ __forceinline__ u32x4 dpp4(u32x4 v) {
+    u32x4 r;
+    r.x = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.x, CTRL, 0xf, 0xf, false);
+    r.y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.y, CTRL, 0xf, 0xf, false);
+    r.z = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.z, CTRL, 0xf, 0xf, false);
+    r.w = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.w, CTRL, 0xf, 0xf, false);
+    return r;
+}
+__device__ __forceinline__ u32x4 rotate_rows(u32x4 v, int n) {
+    switch (n) {                       // row_ror:k is control 0x120 + k
+        case 4: return dpp4<0x120 + 12>(v);
+        case 8: return dpp4<0x120 + 8>(v);
+        case 12: return dpp4<0x120 + 4>(v);
+        default: return v;
+    }
+}
+
 // v_mfma_f32_16x16x32: D(16x16, fp32) += A(16x32) * B(32x16).  Lane l = 16*o + i supplies A[i][8o..8o+7]
 // and B[8o..8o+7][i]; it receives D[4o..4o+3][i].
 template <typename DT>
@@ -315,9 +330,9 @@ __device__ __forceinline__ void lds_load_scales(ScaleWords<NS>& s, const char* p
         s.w[0] = v.x; s.w[1] = v.y; s.w[2] = v.z; s.w[3] = v.w;
     }
 }
-template <int NS>
-__device__ __forceinline__ uint32_t scale_bits(const ScaleWords<NS>& s, int g) {
-    return (g & 1) ? (s.w[g >> 1] >> 16) : (s.w[g >> 1] & 0xffffu);
+template <typename DT, int NS>
+__device__ __forceinline__ ScaleReg<DT> scale_of(const ScaleWords<NS>& s, int g) {
+    return make_scale<DT>(s.w[g >> 1], g & 1);
 }
 
 }  // namespace lutq

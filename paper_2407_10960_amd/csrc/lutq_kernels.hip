@@ -14,9 +14,9 @@ namespace lutq {
 
 namespace {
 
-template <int GROUP, int MB, int R, int NW, int P, bool SCH>
+template <int GROUP, int MB, int R, int NW, int P, bool SCH, int XM>
 hipError_t launch_one(const MatmulParams& p, hipStream_t stream) {
-    auto kernel = matmul_kernel<LUTQ_INST_BITS, GROUP, MB, R, LUTQ_INST_DT, NW, P, SCH>;
+    auto kernel = matmul_kernel<LUTQ_INST_BITS, GROUP, MB, R, LUTQ_INST_DT, NW, P, SCH, XM>;
     constexpr int lds_bytes = matmul_lds_bytes<LUTQ_INST_BITS>(R, MB, NW, SCH);
     if (lds_bytes > 64 * 1024) {
         // more than 64 KiB of dynamic LDS has to be enabled once per kernel
@@ -28,26 +28,30 @@ hipError_t launch_one(const MatmulParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int GROUP, int MB, int R>
+template <int GROUP, int MB, int R, int XM>
 hipError_t launch_r(int nw, int stages, bool sch, const MatmulParams& p, hipStream_t stream) {
-    if (!sch) return (nw == 4 && stages == 2) ? launch_one<GROUP, MB, R, 4, 2, false>(p, stream) : hipErrorInvalidValue;
-    if (nw == 4 && stages == 2) return launch_one<GROUP, MB, R, 4, 2, true>(p, stream);
-    if (nw == 4 && stages == 4) return launch_one<GROUP, MB, R, 4, 4, true>(p, stream);
-    if (nw == 8 && stages == 2) return launch_one<GROUP, MB, R, 8, 2, true>(p, stream);
-    if (nw == 8 && stages == 4) return launch_one<GROUP, MB, R, 8, 4, true>(p, stream);
+    if (!sch) return (nw == 4 && stages == 2) ? launch_one<GROUP, MB, R, 4, 2, false, XM>(p, stream) : hipErrorInvalidValue;
+    if (nw == 4 && stages == 2) return launch_one<GROUP, MB, R, 4, 2, true, XM>(p, stream);
+    if (nw == 4 && stages == 4) return launch_one<GROUP, MB, R, 4, 4, true, XM>(p, stream);
+    if (nw == 8 && stages == 2) return launch_one<GROUP, MB, R, 8, 2, true, XM>(p, stream);
+    if (nw == 8 && stages == 4) return launch_one<GROUP, MB, R, 8, 4, true, XM>(p, stream);
     return hipErrorInvalidValue;
 }
 
 template <int GROUP>
-hipError_t launch_group(int mb, int r, int nw, int stages, bool sch, const MatmulParams& p, hipStream_t stream) {
-    if (mb == 1) {
-        if (r == 1) return launch_r<GROUP, 1, 1>(nw, stages, sch, p, stream);
-        if (r == 2) return launch_r<GROUP, 1, 2>(nw, stages, sch, p, stream);
-        if (r == 4) return launch_r<GROUP, 1, 4>(nw, stages, sch, p, stream);
-    } else if (mb == 2) {
-        if (r == 1) return launch_r<GROUP, 2, 1>(nw, stages, sch, p, stream);
-        if (r == 2) return launch_r<GROUP, 2, 2>(nw, stages, sch, p, stream);
-        if (r == 4) return launch_r<GROUP, 2, 4>(nw, stages, sch, p, stream);
+hipError_t launch_group(int mb, int r, int nw, int stages, bool sch, int xm, const MatmulParams& p, hipStream_t stream) {
+    if (mb == 1 && xm == 4) {
+        if (r == 1) return launch_r<GROUP, 1, 1, 4>(nw, stages, sch, p, stream);
+        if (r == 2) return launch_r<GROUP, 1, 2, 4>(nw, stages, sch, p, stream);
+        if (r == 4) return launch_r<GROUP, 1, 4, 4>(nw, stages, sch, p, stream);
+    } else if (mb == 1 && xm == 16) {
+        if (r == 1) return launch_r<GROUP, 1, 1, 16>(nw, stages, sch, p, stream);
+        if (r == 2) return launch_r<GROUP, 1, 2, 16>(nw, stages, sch, p, stream);
+        if (r == 4) return launch_r<GROUP, 1, 4, 16>(nw, stages, sch, p, stream);
+    } else if (mb == 2 && xm == 16) {
+        if (r == 1) return launch_r<GROUP, 2, 1, 16>(nw, stages, sch, p, stream);
+        if (r == 2) return launch_r<GROUP, 2, 2, 16>(nw, stages, sch, p, stream);
+        if (r == 4) return launch_r<GROUP, 2, 4, 16>(nw, stages, sch, p, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -61,12 +65,12 @@ hipError_t launch_dq(const DequantParams& p, int grid, int lds_bytes, hipStream_
 }  // namespace
 
 hipError_t LUTQ_NAME(launch_matmul_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int r, int nw, int stages,
-                                                                    bool sch, const MatmulParams& p,
+                                                                    bool sch, int xm, const MatmulParams& p,
                                                                     hipStream_t stream) {
     switch (group) {
-        case 32: return launch_group<32>(mb, r, nw, stages, sch, p, stream);
-        case 64: return launch_group<64>(mb, r, nw, stages, sch, p, stream);
-        case 128: return launch_group<128>(mb, r, nw, stages, sch, p, stream);
+        case 32: return launch_group<32>(mb, r, nw, stages, sch, xm, p, stream);
+        case 64: return launch_group<64>(mb, r, nw, stages, sch, xm, p, stream);
+        case 128: return launch_group<128>(mb, r, nw, stages, sch, xm, p, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -17,7 +17,7 @@ inline bool matmul_instance_exists(int nw, int stages, bool sch) {
 
 #define LUTQ_DECLARE_LAUNCHERS(B, DT)                                                               \
     hipError_t launch_matmul_b##B##_##DT(int group, int mb, int r, int nw, int stages, bool sch,     \
-                                         const MatmulParams& p, hipStream_t stream);                 \
+                                         int xm, const MatmulParams& p, hipStream_t stream);         \
     hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes, \
                                           hipStream_t stream);
 

@@ -33,21 +33,37 @@ struct MatmulParams {
     int KT;                   // K tiles per row block
     int NRG;                  // row groups (N / (16 R))
     int G;                    // workgroups
+    int TQ, TR;               // NRG * KT = TQ * G + TR: workgroup b owns TQ (+1 if b < TR) iterations
     int SG;                   // scales per row (K / group)
-    int SB;                   // row blocks per super-block of the packed layout (multiple of R)
+    int SBL;                  // log2 of the row blocks per super-block of the packed layout (R divides it)
 };
 
 // Largest partial-sum slot: R = 4 row blocks x 2 M-halves x 4 registers x 64 lanes.
 constexpr int kSlotFloats = 4 * 2 * 4 * 64;
 
-// Workgroup that owns iteration t when T iterations are cut into G ranges [floor(gT/G), floor((g+1)T/G)).
-__device__ __forceinline__ int owner_of(int64_t t, int64_t T, int G) {
-    return (int)(((t + 1) * G - 1) / T);
+// The NRG * KT iterations (row group major) are cut into G contiguous ranges; the first TR ranges hold
+// TQ + 1 iterations, the others TQ.  All of it fits 32 bits (checked on the host).
+__device__ __forceinline__ int range_begin(int g, int tq, int tr) { return g * tq + (g < tr ? g : tr); }
+__device__ __forceinline__ int owner_of(int t, int tq, int tr) {
+    const int big = tr * (tq + 1);
+    return t < big ? t / (tq + 1) : tr + (t - big) / tq;
 }
 
 // LDS bytes of one launch (host and device agree through this one function).
 template <int BITS>
 __host__ __device__ constexpr int red_bytes(int nreg) { return nreg * 256 > 2048 ? nreg * 256 : 2048; }
+// Waves per SIMD the register allocation is held to.  An 8-wave workgroup puts two waves on each of
+// the four SIMDs, and two such workgroups (two 64 KiB tables) fit the 160 KiB of LDS: four waves per
+// SIMD, 128 registers each.  That is only asked for when a rough count of the live registers (tiles
+// in flight, accumulators, lookup ring, addresses) says it fits without spilling in the K loop.
+template <int BITS>
+__host__ __device__ constexpr int matmul_waves_per_simd(int r, int mb, int nw, int p, int xm) {
+    const int wregs = BITS == 3 ? 6 : 4;
+    const int xl = Geo<BITS>::STEPS * xm / 16;
+    const int est = p * (r * wregs + xl * mb * 4 + 4) + r * mb * 4 + 52;
+    return (nw >= 8 && est <= 124) ? 4 : 2;
+}
+
 template <int BITS>
 __host__ __device__ constexpr int matmul_lds_bytes(int r, int mb, int nw, bool sch) {
     return lut_lds_bytes<BITS>(perm_log2_copies<BITS>()) + red_bytes<BITS>(r * mb * 4) + (sch ? nw * 1024 : 0);
@@ -58,8 +74,15 @@ __host__ __device__ constexpr int matmul_lds_bytes(int r, int mb, int nw, bool s
 // NW = waves per workgroup (they split the K range of the workgroup's segment and are reduced
 // through LDS), P = tiles in flight per wave, SCH = scales are fetched as 16-byte chunks per row
 // (needs K/group % 8 == 0) and handed to the lanes through LDS instead of being loaded per tile.
-template <int BITS, int GROUP, int MB, int R, typename DT, int NW, int P, bool SCH>
-__global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
+// XM = activation rows that one 16-lane row of the B operand is loaded for: 16 is the plain layout
+// (lane i holds row i; one 128-bit load per 32-wide K step).  XM = 4 (M <= 4 only) packs four K steps
+// into one load: lane i holds row i % 4 of step i / 4, and the steps after the first are brought to
+// lanes 0..3 by rotating the 16-lane rows.  The other twelve columns of the matrix instruction then
+// multiply activations of the wrong steps; they are never read.  This cuts the registers that hold
+// activations in flight to a quarter, which is what lets eight waves per SIMD pair stay resident.
+template <int BITS, int GROUP, int MB, int R, typename DT, int NW, int P, bool SCH, int XM>
+__global__ __launch_bounds__(NW * 64, matmul_waves_per_simd<BITS>(R, MB, NW, P, XM)) void matmul_kernel(const MatmulParams p) {
+    static_assert(XM == 16 || (XM == 4 && MB == 1), "packed activation loads exist for M <= 4 only");
     using Gm = Geo<BITS>;
     constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
     constexpr int NS = TK / GROUP;           // scales per tile per row
@@ -70,8 +93,16 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
     constexpr int LUT_BYTES = lut_lds_bytes<BITS>(LOG2C);
     constexpr int U = STEPS * R;             // (step, row block) items of one tile
     constexpr int D = U < 4 ? U : 4;         // table reads kept in flight ahead of their use
+    constexpr int XS = 16 / XM;              // K steps covered by one activation load
+    constexpr int XL = STEPS / XS;           // activation loads per tile (per 16-row half of M)
     // all waves' partial sums fit in the table area: reduce there in one go after the last segment
     constexpr bool FAST_REDUCE = (NW - 1) * NREG * 256 <= LUT_BYTES;
+
+    // Every scalar of the parameter block is used in the entry block, so that the argument segment
+    // is fetched with one round trip instead of one per basic block that first needs a field.
+    asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.counters), "s"(p.slots));
+    asm volatile("" ::"s"(p.packed_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.KT), "s"(p.NRG), "s"(p.G), "s"(p.TQ),
+                 "s"(p.TR), "s"(p.SG), "s"(p.SBL));
 
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
@@ -85,7 +116,7 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
     float* red = reinterpret_cast<float*>(smem + LUT_BYTES);
     char* sc_lds = smem + LUT_BYTES + red_bytes<BITS>(NREG) + wave * 1024;      // this wave's 64 rows x 16 B
 
-    const u32x2 lut_seed = lut_fetch<BITS>(p.lut, tid);      // issued before any weight load (see below)
+    const LutSeed lut_seed = lut_fetch<BITS>(p.lut, tid, NW * 64);   // issued before any weight load (see below)
     __builtin_amdgcn_sched_barrier(0);
     const LutAddr la = make_lut_addr<BITS>(lut, LOG2C, lane);
     bool lut_ready = false;
@@ -102,28 +133,29 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
     for (int mb = 0; mb < MB; ++mb) {
         const int m = li + 16 * mb;
         valid[mb] = m < p.M;
-        xlane[mb] = ((uint32_t)m * (uint32_t)p.K + 8u * lo) * 2u;
+        // packed form: row li % XM, K step li / XM of the load's group of XS steps
+        xlane[mb] = ((uint32_t)(XM == 16 ? m : li % XM) * (uint32_t)p.K + 32u * (uint32_t)(XM == 16 ? 0 : li / XM)
+                     + 8u * lo) * 2u;
     }
-    const uint32_t tile_stride = (uint32_t)p.SB * TILE_BYTES;          // bytes from K tile kt to kt+1
+    const uint32_t tile_stride = (uint32_t)TILE_BYTES << p.SBL;        // bytes from K tile kt to kt+1
     const uint32_t sblock_bytes = (uint32_t)p.KT * tile_stride;         // packed bytes of one super-block
     const uint32_t srow_bytes = 16u * (uint32_t)p.SG * 2u;             // scale bytes of one 16-row block
 
-    const int64_t T = (int64_t)p.NRG * p.KT;
-    int64_t t0 = (int64_t)blockIdx.x * T / p.G;
-    const int64_t t1 = (int64_t)(blockIdx.x + 1) * T / p.G;
-    const int64_t tbeg = t0;
+    int t0 = range_begin((int)blockIdx.x, p.TQ, p.TR);
+    const int t1 = t0 + p.TQ + ((int)blockIdx.x < p.TR ? 1 : 0);
+    const int tbeg = t0;
 
     struct Stage {
         WFrag<BITS> w[R];
         ScaleWords<NS> s[SCH ? 1 : R];     // direct mode: this lane's scales of the tile, per row block
         u32x4 chunk;                       // chunk mode: 8 consecutive scales of row `lane` of the wave's rows
-        u32x4 x[STEPS][MB];
+        u32x4 x[XL][MB];
     };
 
     while (t0 < t1) {
-        const int rg = (int)(t0 / p.KT);
-        const int ka = (int)(t0 - (int64_t)rg * p.KT);
-        const int rem = (int)((t1 - t0 < (int64_t)(p.KT - ka)) ? (t1 - t0) : (int64_t)(p.KT - ka));
+        const int rg = t0 / p.KT;
+        const int ka = t0 - rg * p.KT;
+        const int rem = (t1 - t0 < p.KT - ka) ? (t1 - t0) : (p.KT - ka);
         const int kb = ka + rem;
         const int wa = ka + (wave * rem) / NW;
         const int wb = ka + ((wave + 1) * rem) / NW;
@@ -136,7 +168,7 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
             for (int mb = 0; mb < MB; ++mb) acc[r][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         const int rb0 = rg * R;                                                          // first row block
-        const uint32_t wrow = (uint32_t)(rb0 / p.SB) * sblock_bytes + (uint32_t)(rb0 % p.SB) * TILE_BYTES;
+        const uint32_t wrow = (uint32_t)(rb0 >> p.SBL) * sblock_bytes + (uint32_t)(rb0 & ((1 << p.SBL) - 1)) * TILE_BYTES;
         const uint32_t slane = (uint32_t)rb0 * srow_bytes + (uint32_t)li * p.SG * 2u;    // direct mode
         const uint32_t clane = lane < 16 * R ? (uint32_t)rb0 * srow_bytes + (uint32_t)lane * p.SG * 2u
                                              : kOutOfRange;                              // chunk mode
@@ -158,10 +190,10 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
                 for (int r = 0; r < R; ++r) load_scales<NS>(st.s[r], rS, ts + slane + r * srow_bytes);
             }
 #pragma unroll
-            for (int s = 0; s < STEPS; ++s)
+            for (int j = 0; j < XL; ++j)
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
-                    st.x[s][mb] = __builtin_amdgcn_raw_buffer_load_b128(rX, tx + xlane[mb] + 64u * s, 0, kAuxNone);
+                    st.x[j][mb] = __builtin_amdgcn_raw_buffer_load_b128(rX, tx + xlane[mb] + 64u * XS * j, 0, kAuxNone);
         };
         auto compute_stage = [&](const Stage& st, int kt) {
             ScaleWords<NS> sw[R];
@@ -191,11 +223,12 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
             // the matrix instruction of item u is issued after the scaling of item u + 1, so that it
             // never has to wait for operands that were written by the instructions just before it
             u32x4 a[2];
+            u32x4 xb = u32x4{0u, 0u, 0u, 0u};   // packed activations: the current step's B operand
 #pragma unroll
             for (int u = 0; u <= U; ++u) {
                 if (u < U) {
                     const int s = u / R, r = u % R;
-                    const ScaleReg<DT> sc = make_scale<DT>(scale_bits<NS>(sw[r], s / SPG));
+                    const ScaleReg<DT> sc = scale_of<DT, NS>(sw[r], s / SPG);
                     a[u & 1] = scale4<DT>(raw[u % D], sc);
                     __builtin_amdgcn_sched_barrier(0);
                     if (u + D < U) {
@@ -205,9 +238,14 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
                 }
                 if (u > 0) {
                     const int s = (u - 1) / R, r = (u - 1) % R;
+                    if constexpr (XM == 16) {
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-                        acc[r][mb] = mfma16x16x32<DT>(a[(u - 1) & 1], st.x[s][mb], acc[r][mb]);
+                        for (int mb = 0; mb < MB; ++mb)
+                            acc[r][mb] = mfma16x16x32<DT>(a[(u - 1) & 1], st.x[s][mb], acc[r][mb]);
+                    } else {
+                        if (r == 0) xb = rotate_rows(st.x[s / XS][0], XM * (s % XS));
+                        acc[r][0] = mfma16x16x32<DT>(a[(u - 1) & 1], xb, acc[r][0]);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -224,7 +262,11 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
         if (!lut_ready) {
             // first segment: the table is built while the first tiles are in flight (its own reads
             // of T were issued before them, so waiting for T does not wait for the tiles)
-            lut_build<BITS>(lut, reinterpret_cast<char*>(red), lut_seed, LOG2C, tid, NW * 64);
+            // (the empty statement keeps the wait for T, and the arithmetic on it, from being hoisted
+            // out of the segment loop to a point before the prefetch)
+            LutSeed seed = lut_seed;
+            asm volatile("" : "+v"(seed.v[0]), "+v"(seed.v[1]), "+v"(seed.v[2]), "+v"(seed.v[3]));
+            lut_build<BITS>(lut, seed, LOG2C, tid, NW * 64);
             __syncthreads();
             lut_ready = true;
             __builtin_amdgcn_sched_barrier(0);
@@ -298,9 +340,9 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
         if (wave == 0) {
             bool write_y = (ka == 0 && kb == p.KT);
             if (!write_y) {
-                const int64_t tile0 = (int64_t)rg * p.KT;
-                const int g_first = owner_of(tile0, T, p.G);
-                const int g_last = owner_of(tile0 + p.KT - 1, T, p.G);
+                const int tile0 = rg * p.KT;
+                const int g_first = owner_of(tile0, p.TQ, p.TR);
+                const int g_last = owner_of(tile0 + p.KT - 1, p.TQ, p.TR);
                 const int which = (t0 == tbeg) ? 0 : 1;
                 float* slot = p.slots + ((size_t)blockIdx.x * 2 + which) * kSlotFloats + lane;
 #pragma unroll
@@ -326,7 +368,7 @@ __global__ __launch_bounds__(NW * 64) void matmul_kernel(const MatmulParams p) {
 #pragma unroll
                         for (int mb = 0; mb < MB; ++mb) acc[r][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
                     for (int g = g_first; g <= g_last; ++g) {
-                        const int64_t gbeg = (int64_t)g * T / p.G;
+                        const int gbeg = range_begin(g, p.TQ, p.TR);
                         const int gw = (gbeg / p.KT == rg) ? 0 : 1;     // slot 0 iff rg is g's first row group
                         const float* src = p.slots + ((size_t)g * 2 + gw) * kSlotFloats + lane;
 #pragma unroll
@@ -384,7 +426,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const DequantParams p) {
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    build_lut<BITS>(smem, smem + lut_lds_bytes<BITS>(p.log2c), p.lut, p.log2c, tid, 256);
+    build_lut<BITS>(smem, p.lut, p.log2c, tid, 256);
     const LutAddr la = make_lut_addr<BITS>(smem, p.log2c, lane);
     __syncthreads();
     const int li = lane & 15, lo = lane >> 4;
@@ -404,7 +446,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const DequantParams p) {
         uint16_t* out = p.W + ((size_t)rb * 16 + li) * p.K + (size_t)kt * TK + 8 * lo;
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
-            const ScaleReg<DT> sc = make_scale<DT>(scale_bits<NS>(sw, s / SPG));
+            const ScaleReg<DT> sc = scale_of<DT, NS>(sw, s / SPG);
             const u32x4 a = scale4<DT>(lookup_step<BITS, false>(f, s, la), sc);
             *reinterpret_cast<u32x4*>(out + 32 * s) = a;
         }

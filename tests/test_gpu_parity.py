@@ -187,7 +187,7 @@ def test_bad_plan_is_rejected_and_y_untouched(lutq):
     c = gen.make_case(3, 2, 48, 256, 4, 64, "f16", "nf")            # 3 row blocks: R = 2, 4 do not divide
     d = DeviceCase(lutq, c)
     Y = torch.full((2, 48), 7.0, dtype=torch.float16, device="cuda")
-    for plan in (lutq.Plan(2, 0, 0), lutq.Plan(3, 0, 0), lutq.Plan(0, 4096, 0), lutq.Plan(0, 0, 3), lutq.Plan(0, 0, 16), lutq.Plan(0, 0, 0, 3)):
+    for plan in (lutq.Plan(2, 0, 0), lutq.Plan(3, 0, 0), lutq.Plan(0, 4097, 0), lutq.Plan(0, 0, 3), lutq.Plan(0, 0, 16), lutq.Plan(0, 0, 0, 3)):
         with pytest.raises(lutq.LutqError) as e:
             lutq.lutq_matmul(d.X, d.packed, d.S, d.T, 4, 64, Y, d.ws, plan=plan)
         assert e.value.code == 10
