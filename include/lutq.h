@@ -92,10 +92,13 @@ size_t lutq_workspace_bytes(int64_t N, int64_t K, int bits, int group_size);
  * tuning knob in the paper, is fixed here: one copy per lane (64 copies of a 4-byte entry, 32 of an
  * 8-byte entry), which is conflict-free by construction and makes the entry stride 256 bytes. */
 typedef struct {
-    int row_blocks_per_wave;  /* 16-row blocks each wavefront streams together: 0,1,2,4; must divide N/16 */
-    int grid;                 /* number of workgroups: 0 or 1..4096 */
-    int waves_per_workgroup;  /* wavefronts that share one table and split a K range: 0, 4 or 8 */
+    int row_blocks_per_wave;  /* R: 16-row blocks each wavefront streams together: 0,1,2,4; must divide N/16 */
+    int grid;                 /* number of workgroups: 0 or 1..4096 (grid x row groups per workgroup <= 4096) */
+    int waves_per_workgroup;  /* wavefronts that share one table: 0 or 4..16, a multiple of the next-but-one field */
     int tiles_in_flight;      /* K tiles each wavefront keeps in flight (software pipeline depth): 0, 2 or 4 */
+    int row_groups_per_workgroup; /* teams: row groups (of R blocks) a workgroup works on side by side, each
+                                     by waves_per_workgroup / this many wavefronts that split K: 0 or 1..16;
+                                     must divide N / (16 R) */
 } lutq_plan;
 
 /* Fills *plan with the library's choice for this problem. */

@@ -27,7 +27,8 @@ class LutqError(RuntimeError):
 
 class _CPlan(ctypes.Structure):
     _fields_ = [("row_blocks_per_wave", ctypes.c_int), ("grid", ctypes.c_int),
-                ("waves_per_workgroup", ctypes.c_int), ("tiles_in_flight", ctypes.c_int)]
+                ("waves_per_workgroup", ctypes.c_int), ("tiles_in_flight", ctypes.c_int),
+                ("row_groups_per_workgroup", ctypes.c_int)]
 
 
 @dataclass
@@ -37,9 +38,11 @@ class Plan:
     grid: int = 0
     waves_per_workgroup: int = 0
     tiles_in_flight: int = 0
+    row_groups_per_workgroup: int = 0
 
     def _c(self) -> _CPlan:
-        return _CPlan(self.row_blocks_per_wave, self.grid, self.waves_per_workgroup, self.tiles_in_flight)
+        return _CPlan(self.row_blocks_per_wave, self.grid, self.waves_per_workgroup, self.tiles_in_flight,
+                      self.row_groups_per_workgroup)
 
 
 def lib_path() -> str:
@@ -162,7 +165,8 @@ def lutq_plan_default(bits: int, group_size: int, M: int, N: int, K: int, dtype_
     cp = _CPlan()
     _check(load_library().lutq_plan_default(bits, group_size, M, N, K, dtype_code, ctypes.byref(cp)),
            "lutq_plan_default")
-    return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup, cp.tiles_in_flight)
+    return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup, cp.tiles_in_flight,
+                cp.row_groups_per_workgroup)
 
 
 def lutq_matmul(X, packed, scales, lut, bits: int, group_size: int, Y, workspace, stream=None,

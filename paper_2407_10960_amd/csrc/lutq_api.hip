@@ -66,21 +66,62 @@ int ilog2(int v) {
     return l;
 }
 
+// Everything the launch needs to know about the work decomposition.
+struct Decomp {
+    int r, grid, nw, stages, rs;      // the five plan fields, all chosen
+};
+
+bool wide_exists(int bits, int r, int mb, int stages, int xm) {
+    return matmul_instance_exists(bits, r, mb, stages, true, xm, true);
+}
+
 // Default work decomposition (host part of Algorithm 1: the tile scheduler and the number of blocks).
-// Tiles = (N / 16R) row groups x (K / TK) K tiles, cut into `grid` equal contiguous ranges.
 //
-// Measured on MI355X, the cross-workgroup fix-up costs three dependent device-scope round trips
-// (store partials, bump the counter, read the slots), several microseconds, which is more than the
-// wave quantisation it would remove on these decode shapes.  So the default keeps every output tile
-// inside one workgroup whenever that still gives each compute unit a workgroup: R is the largest of
-// 4, 2, 1 with at least one row group per compute unit, and grid = number of row groups.  Only when
-// N is too small for that (fewer 16-row blocks than compute units) is K split across workgroups,
-// into j equal parts per row group, with the Stream-K style fix-up.
-lutq_status default_plan(int bits, int group_size, int64_t M, int64_t N, int64_t K, int cus, int force_r,
-                         lutq_plan* plan) {
-    (void)group_size;
+// Measured on MI355X, a launch of this kernel is a few microseconds of fixed latencies (argument
+// fetch, first HBM round trip, table build, final reduction) around a streaming phase that runs at
+// HBM speed, and the cross-workgroup fix-up costs three more dependent device-scope round trips.
+// What matters is therefore that every compute unit streams the same number of bytes, that one
+// workgroup (one table build) per compute unit does all of it, and that no partial sum leaves the
+// workgroup.  When the 16-row blocks divide evenly over the compute units, the workgroup is
+// arranged as RS teams x KS waves: `per` = N/16/CUs row blocks per workgroup = RS teams x R blocks,
+// and the KS waves of a team split K.  Otherwise R is the largest of 4, 2, 1 with at least one row
+// group per compute unit and grid = number of row groups; only when N is too small for that is K
+// split across workgroups, with the Stream-K style fix-up.
+Decomp default_decomp(int bits, int64_t M, int64_t N, int64_t K, int cus, int force_r) {
     const int64_t nb = N / 16, kt = K / tile_k(bits);
-    int r = super_block(nb);                              // R has to divide the layout's super-block
+    const int mb = M > 16 ? 2 : 1, xm = M <= 4 ? 4 : 16;
+    const int sb = super_block(nb);
+    Decomp d;
+    if (nb % cus == 0 && nb / cus <= 64) {
+        int64_t per = nb / cus;                           // row blocks per compute unit
+        int grid = cus;
+        int r = force_r ? force_r : sb;
+        while (r > 1 && per % r != 0) r >>= 1;
+        // registers: prefer R <= 2 so that 128 registers hold two tiles in flight
+        if (!force_r) while (r > 2) r >>= 1;
+        int64_t rs = per / r;
+        while (rs > 8 && rs % 2 == 0) { rs /= 2; grid *= 2; }
+        if (rs <= 16 && (int64_t)grid * rs <= kMaxGrid) {
+            int ks = (int)(16 / rs);
+            while (ks > 1 && kt / ks < 4) --ks;           // at least four K tiles per wave
+            if (ks < 1) ks = 1;
+            int nw = (int)rs * ks;
+            while (nw < 4) { ++ks; nw = (int)rs * ks; }  // the table build needs four waves
+            const int stages = 2;                         // measured: deeper prefetch does not pay at 14-16 waves
+            if (nw > 8) {
+                if (!wide_exists(bits, r, mb, 2, xm)) {   // too many registers for 16 waves: 8 at most
+                    ks = (int)(8 / rs) > 0 ? (int)(8 / rs) : 1;
+                    nw = (int)rs * ks;
+                    while (nw < 4) { ++ks; nw = (int)rs * ks; }
+                }
+            }
+            if (nw <= 16 && (nw <= 8 || wide_exists(bits, r, mb, stages, xm))) {
+                d.r = r; d.grid = grid; d.nw = nw; d.stages = stages; d.rs = (int)rs;
+                return d;
+            }
+        }
+    }
+    int r = sb;                                           // R has to divide the layout's super-block
     while (r > 1 && nb / r < cus) r >>= 1;
     if (force_r) r = force_r;
     const int64_t groups = nb / r;
@@ -92,14 +133,12 @@ lutq_status default_plan(int bits, int group_size, int64_t M, int64_t N, int64_t
         grid = groups * j;
     }
     while (grid > kMaxGrid) grid = (grid + 1) / 2;
-    plan->row_blocks_per_wave = r;
-    plan->grid = (int)grid;
-    plan->waves_per_workgroup = 4;
-    plan->tiles_in_flight = (r == 4 && M > 16) ? 2 : 4;
-    return LUTQ_OK;
+    d.r = r; d.grid = (int)grid; d.nw = 4; d.rs = 1;
+    d.stages = (r == 4 && M > 16) ? 2 : 4;
+    return d;
 }
 
-typedef hipError_t (*matmul_launcher)(int, int, int, int, int, bool, int, const MatmulParams&, hipStream_t);
+typedef hipError_t (*matmul_launcher)(int, int, int, int, bool, int, bool, const MatmulParams&, hipStream_t);
 typedef hipError_t (*dequant_launcher)(int, const DequantParams&, int, int, hipStream_t);
 
 matmul_launcher pick_matmul(int bits, lutq_dtype dt) {
@@ -144,7 +183,13 @@ extern "C" lutq_status lutq_plan_default(int bits, int group_size, int64_t M, in
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
     DeviceInfo di = device_info();
     if (!di.ok) return LUTQ_ERR_DEVICE;
-    return default_plan(bits, group_size, M, N, K, di.cus, 0, plan);
+    const Decomp d = default_decomp(bits, M, N, K, di.cus, 0);
+    plan->row_blocks_per_wave = d.r;
+    plan->grid = d.grid;
+    plan->waves_per_workgroup = d.nw;
+    plan->tiles_in_flight = d.stages;
+    plan->row_groups_per_workgroup = d.rs;
+    return LUTQ_OK;
 }
 
 extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scales, const void* lut,
@@ -164,28 +209,49 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     DeviceInfo di = device_info();
     if (!di.ok) return LUTQ_ERR_DEVICE;
     const int64_t nb = N / 16, kt = K / tile_k(bits);
+    const int mb = M > 16 ? 2 : 1;
+    // M <= 4: four K steps of activations per load, rotated into place (a quarter of the registers)
+    const int xm = (M <= 4) ? 4 : 16;
+    const bool sch = (K / group_size) % 8 == 0;            // scale rows are 16-byte aligned: chunked scale path
     int force_r = 0;
     if (user_plan) {
-        const int w = user_plan->waves_per_workgroup;
-        const int f = user_plan->tiles_in_flight;
-        if ((w != 0 && w != 4 && w != 8) || (f != 0 && f != 2 && f != 4)) return LUTQ_ERR_PLAN;
+        const int w = user_plan->waves_per_workgroup, f = user_plan->tiles_in_flight;
+        const int t = user_plan->row_groups_per_workgroup;
+        if ((w != 0 && (w < 4 || w > 16)) || (f != 0 && f != 2 && f != 4) || t < 0 || t > 16) return LUTQ_ERR_PLAN;
         force_r = user_plan->row_blocks_per_wave;
         if (force_r != 0 && ((force_r != 1 && force_r != 2 && force_r != 4) || super_block(nb) % force_r != 0))
             return LUTQ_ERR_PLAN;
+        if (user_plan->grid != 0 && (user_plan->grid < 1 || user_plan->grid > kMaxGrid)) return LUTQ_ERR_PLAN;
     }
-    lutq_plan plan;
-    default_plan(bits, group_size, M, N, K, di.cus, force_r, &plan);
+    Decomp d = default_decomp(bits, M, N, K, di.cus, force_r);
     if (user_plan) {
-        if (user_plan->grid != 0) {
-            if (user_plan->grid < 1 || user_plan->grid > kMaxGrid) return LUTQ_ERR_PLAN;
-            plan.grid = user_plan->grid;
+        // a field the caller fixes replaces the default; teams and waves default to one team of the
+        // default number of waves once anything about the workgroup's shape is fixed by the caller
+        const bool shaped = user_plan->grid || user_plan->waves_per_workgroup || user_plan->row_groups_per_workgroup;
+        if (shaped) {
+            d.rs = user_plan->row_groups_per_workgroup ? user_plan->row_groups_per_workgroup : 1;
+            d.nw = user_plan->waves_per_workgroup ? user_plan->waves_per_workgroup : (d.rs > 4 ? d.rs : 4);
+            if (!user_plan->grid) d.grid = (int)((nb / d.r / d.rs) > 0 ? (nb / d.r / d.rs) : 1);
+            if (!user_plan->tiles_in_flight) d.stages = 2;
         }
-        if (user_plan->waves_per_workgroup != 0) plan.waves_per_workgroup = user_plan->waves_per_workgroup;
-        if (user_plan->tiles_in_flight != 0) plan.tiles_in_flight = user_plan->tiles_in_flight;
+        if (user_plan->grid) d.grid = user_plan->grid;
+        if (user_plan->tiles_in_flight) d.stages = user_plan->tiles_in_flight;
     }
-    const int r = plan.row_blocks_per_wave;
-    const int64_t tiles = (nb / r) * kt;
-    if (plan.grid > tiles) plan.grid = (int)tiles;      // every workgroup must own at least one tile
+    if (!sch) { if (d.nw > 8) d.nw = 8 / d.rs > 0 ? (8 / d.rs) * d.rs : d.rs; d.stages = 2; }   // per-tile scale path: one shape only
+    const int r = d.r;
+    const int64_t nrg = nb / r;
+    if (d.nw % d.rs != 0 || nrg % d.rs != 0 || d.nw < 4 || d.nw > 16) return LUTQ_ERR_PLAN;
+    const int64_t tiles = (nrg / d.rs) * kt;
+    if (d.grid > tiles) d.grid = (int)tiles;              // every workgroup must own at least one iteration
+    if ((int64_t)d.grid * d.rs > kMaxGrid) return LUTQ_ERR_PLAN;   // partial-sum slots of the workspace
+    // more than 8 waves need an instance held to 128 registers; up to 8 waves take one when it
+    // exists, so that two workgroups fit a compute unit
+    const bool wide = d.nw > 8 || (d.nw > 4 && sch && wide_exists(bits, r, mb, d.stages, xm));
+    if (!matmul_instance_exists(bits, r, mb, d.stages, sch, xm, wide)) return LUTQ_ERR_PLAN;
+    const int lds_bytes = bits == 2 ? matmul_lds_bytes<2>(r, mb, d.nw, d.rs, sch)
+                        : bits == 3 ? matmul_lds_bytes<3>(r, mb, d.nw, d.rs, sch)
+                                    : matmul_lds_bytes<4>(r, mb, d.nw, d.rs, sch);
+    if (lds_bytes > 160 * 1024) return LUTQ_ERR_PLAN;
 
     MatmulParams p;
     p.X = static_cast<const uint16_t*>(X);
@@ -198,23 +264,22 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     p.packed_bytes = (uint32_t)(N * K * bits / 8);
     p.M = (int)M; p.N = (int)N; p.K = (int)K;
     p.KT = (int)kt;
-    p.NRG = (int)(nb / r);
-    p.G = plan.grid;
-    p.TQ = (int)(tiles / plan.grid);
-    p.TR = (int)(tiles % plan.grid);
+    p.NRG = (int)nrg;
+    p.G = d.grid;
+    p.TQ = (int)(tiles / d.grid);
+    p.TR = (int)(tiles % d.grid);
     p.SG = (int)(K / group_size);
     p.SBL = ilog2(super_block(nb));
-    const int mb = M > 16 ? 2 : 1;
-    const bool sch = (K / group_size) % 8 == 0;            // scale rows are 16-byte aligned: chunked scale path
-    int nw = plan.waves_per_workgroup, stages = plan.tiles_in_flight;
-    if (!sch) { nw = 4; stages = 2; }                      // the per-tile scale path exists in one shape only
-    if (!matmul_instance_exists(nw, stages, sch)) return LUTQ_ERR_PLAN;
-    // M <= 4: four K steps of activations per load, rotated into place (a quarter of the registers)
-    int xm = (M <= 4) ? 4 : 16;
-    if (const char* ev = std::getenv("LUTQ_XM")) xm = (std::atoi(ev) == 16 || M > 4) ? 16 : 4;
-    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, nw, stages, sch, xm, p, static_cast<hipStream_t>(stream));
+    p.NW = d.nw; p.RS = d.rs; p.KS = d.nw / d.rs;
+    p.kt_magic = p.KT == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KT);
+    p.ks_magic = p.KS == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KS);
+    p.fast_reduce = (d.nw - d.rs) * (r * mb * 4) * 256 <= lut_bytes(bits, bits == 2 ? 5 : 6) ? 1 : 0;
+    if (std::getenv("LUTQ_VERBOSE"))
+        std::fprintf(stderr, "lutq_matmul: R=%d grid=%d waves=%d (teams %d x %d) stages=%d wide=%d xm=%d lds=%d\n", r, d.grid,
+                     d.nw, d.rs, p.KS, d.stages, (int)wide, xm, lds_bytes);
+    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, d.stages, sch, xm, wide, p, static_cast<hipStream_t>(stream));
     if (e != hipSuccess && std::getenv("LUTQ_VERBOSE"))
-        std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d)\n", hipGetErrorString(e), p.G, nw * 64);
+        std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d)\n", hipGetErrorString(e), p.G, d.nw * 64);
     return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
 }
 

@@ -78,8 +78,8 @@ __device__ __forceinline__ void load_wfrag(WFrag<BITS>& f, rsrc_t packed, uint32
 // straight from a packed word: one VALU instruction per lookup instead of extract + shift-add.
 //
 // Built without staging: entry e is a row of `stride` bytes (the same value repeated), and the
-// ENTRIES rows are dealt to the threads, nthreads / ENTRIES threads per row (nthreads is a multiple
-// of ENTRIES: 256 or more threads, at most 256 entries).  Every thread fetches the one or two table
+// ENTRIES rows are dealt to the threads, a power of two of threads per row (the largest that
+// nthreads / ENTRIES allows; nthreads >= ENTRIES, threads left over do nothing).  Every thread fetches the one or two table
 // values of its row straight from global memory (lut_fetch), and later writes its part of the row
 // as 128-bit stores (lut_build).  The 16-byte chunk a lane starts with is skewed by its row number,
 // so that the lanes of one store instruction, whose rows are 256 bytes apart, hit different banks.
@@ -89,9 +89,16 @@ __device__ __forceinline__ void load_wfrag(WFrag<BITS>& f, rsrc_t packed, uint32
 // ---------------------------------------------------------------------------------------
 struct LutSeed { uint32_t v[4]; };     // raw 16-bit table values of this thread's row
 
+// log2 of the threads that share one row
+template <int BITS>
+__device__ __forceinline__ int lut_log2_threads_per_row(int nthreads) {
+    const int t = nthreads / Geo<BITS>::ENTRIES;
+    return t >= 16 ? 4 : t >= 8 ? 3 : t >= 4 ? 2 : t >= 2 ? 1 : 0;
+}
+
 template <int BITS>
 __device__ __forceinline__ LutSeed lut_fetch(const uint16_t* __restrict__ T, int tid, int nthreads) {
-    const int e = tid / (nthreads / Geo<BITS>::ENTRIES);
+    const int e = (tid >> lut_log2_threads_per_row<BITS>(nthreads)) & (Geo<BITS>::ENTRIES - 1);
     LutSeed s;
     if constexpr (BITS == 4) {
         s.v[0] = T[e & 15]; s.v[1] = T[(e >> 4) & 15]; s.v[2] = 0; s.v[3] = 0;
@@ -111,8 +118,9 @@ __device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int lo
     constexpr int ESH = Gm::ENTRY_BYTES == 8 ? 3 : 2;
     const int stride = 1 << (log2c + ESH);                        // bytes of one row
     const int chunks = stride >> 4;                               // 16-byte chunks of one row (power of two)
-    const int tpe = nthreads / Gm::ENTRIES;                       // threads per row (>= 1)
-    const int e = tid / tpe, part = tid % tpe;
+    const int ltpe = lut_log2_threads_per_row<BITS>(nthreads);
+    const int tpe = 1 << ltpe;                                    // threads per row
+    const int e = tid >> ltpe, part = tid & (tpe - 1);
     const int per = chunks / tpe > 0 ? chunks / tpe : 1;          // chunks written by this thread
     if (e >= Gm::ENTRIES || part * per >= chunks) return;
     u32x4 v;
@@ -261,13 +269,14 @@ __device__ __forceinline__ u32x4 scale4(u32x4 raw, ScaleReg<DT> sc) {
 
 // Lane i of every 16-lane row receives the value of lane (i + n) mod 16 of the same row
 // (a DPP row rotate to the right by 16 - n lanes), for each of the four registers; n in {0, 4, 8, 12}.
+// A rotation reads a valid lane for every lane, so the destination needs no previous value.
 template <int CTRL>
 __device__ __forceinline__ u32x4 dpp4(u32x4 v) {
     u32x4 r;
-    r.x = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.x, CTRL, 0xf, 0xf, false);
-    r.y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.y, CTRL, 0xf, 0xf, false);
-    r.z = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.z, CTRL, 0xf, 0xf, false);
-    r.w = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.w, CTRL, 0xf, 0xf, false);
+    r.x = (uint32_t)__builtin_amdgcn_mov_dpp((int)v.x, CTRL, 0xf, 0xf, true);
+    r.y = (uint32_t)__builtin_amdgcn_mov_dpp((int)v.y, CTRL, 0xf, 0xf, true);
+    r.z = (uint32_t)__builtin_amdgcn_mov_dpp((int)v.z, CTRL, 0xf, 0xf, true);
+    r.w = (uint32_t)__builtin_amdgcn_mov_dpp((int)v.w, CTRL, 0xf, 0xf, true);
     return r;
 }
 __device__ __forceinline__ u32x4 rotate_rows(u32x4 v, int n) {

@@ -1,6 +1,6 @@
 // Instantiates the kernels for one (bit width, dtype) pair and dispatches the remaining template
-// parameters (group size, M blocks, row blocks per wave, waves per workgroup, tiles in flight,
-// scale path) at run time.
+// parameters (group size, M blocks, row blocks per wave, tiles in flight, scale path, activation
+// packing, register budget) at run time.
 #include "lutq_launch.hpp"
 
 #ifndef LUTQ_INST_BITS
@@ -14,44 +14,51 @@ namespace lutq {
 
 namespace {
 
-template <int GROUP, int MB, int R, int NW, int P, bool SCH, int XM>
+template <int GROUP, int MB, int R, int P, bool SCH, int XM, bool WIDE>
 hipError_t launch_one(const MatmulParams& p, hipStream_t stream) {
-    auto kernel = matmul_kernel<LUTQ_INST_BITS, GROUP, MB, R, LUTQ_INST_DT, NW, P, SCH, XM>;
-    constexpr int lds_bytes = matmul_lds_bytes<LUTQ_INST_BITS>(R, MB, NW, SCH);
-    if (lds_bytes > 64 * 1024) {
-        // more than 64 KiB of dynamic LDS has to be enabled once per kernel
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (attr != hipSuccess) return attr;
+    if constexpr (WIDE && !matmul_wide_fits<LUTQ_INST_BITS>(R, MB, P, XM)) {
+        return hipErrorInvalidValue;         // would not fit 128 registers: not instantiated
+    } else {
+        auto kernel = matmul_kernel<LUTQ_INST_BITS, GROUP, MB, R, LUTQ_INST_DT, P, SCH, XM, WIDE>;
+        const int lds_bytes = matmul_lds_bytes<LUTQ_INST_BITS>(R, MB, p.NW, p.RS, SCH);
+        if (lds_bytes > 64 * 1024) {
+            // more than 64 KiB of dynamic LDS has to be enabled once per kernel
+            static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (attr != hipSuccess) return attr;
+        }
+        hipLaunchKernelGGL(kernel, dim3(p.G), dim3(p.NW * 64), lds_bytes, stream, p);
+        return hipGetLastError();
     }
-    hipLaunchKernelGGL(kernel, dim3(p.G), dim3(NW * 64), lds_bytes, stream, p);
-    return hipGetLastError();
 }
 
 template <int GROUP, int MB, int R, int XM>
-hipError_t launch_r(int nw, int stages, bool sch, const MatmulParams& p, hipStream_t stream) {
-    if (!sch) return (nw == 4 && stages == 2) ? launch_one<GROUP, MB, R, 4, 2, false, XM>(p, stream) : hipErrorInvalidValue;
-    if (nw == 4 && stages == 2) return launch_one<GROUP, MB, R, 4, 2, true, XM>(p, stream);
-    if (nw == 4 && stages == 4) return launch_one<GROUP, MB, R, 4, 4, true, XM>(p, stream);
-    if (nw == 8 && stages == 2) return launch_one<GROUP, MB, R, 8, 2, true, XM>(p, stream);
-    if (nw == 8 && stages == 4) return launch_one<GROUP, MB, R, 8, 4, true, XM>(p, stream);
+hipError_t launch_r(int stages, bool sch, bool wide, const MatmulParams& p, hipStream_t stream) {
+    if (!sch) return (!wide && stages == 2) ? launch_one<GROUP, MB, R, 2, false, XM, false>(p, stream) : hipErrorInvalidValue;
+    if (wide) {
+        if (stages == 2) return launch_one<GROUP, MB, R, 2, true, XM, true>(p, stream);
+        if (stages == 4) return launch_one<GROUP, MB, R, 4, true, XM, true>(p, stream);
+    } else {
+        if (stages == 2) return launch_one<GROUP, MB, R, 2, true, XM, false>(p, stream);
+        if (stages == 4) return launch_one<GROUP, MB, R, 4, true, XM, false>(p, stream);
+    }
     return hipErrorInvalidValue;
 }
 
 template <int GROUP>
-hipError_t launch_group(int mb, int r, int nw, int stages, bool sch, int xm, const MatmulParams& p, hipStream_t stream) {
+hipError_t launch_group(int mb, int r, int stages, bool sch, int xm, bool wide, const MatmulParams& p, hipStream_t stream) {
     if (mb == 1 && xm == 4) {
-        if (r == 1) return launch_r<GROUP, 1, 1, 4>(nw, stages, sch, p, stream);
-        if (r == 2) return launch_r<GROUP, 1, 2, 4>(nw, stages, sch, p, stream);
-        if (r == 4) return launch_r<GROUP, 1, 4, 4>(nw, stages, sch, p, stream);
+        if (r == 1) return launch_r<GROUP, 1, 1, 4>(stages, sch, wide, p, stream);
+        if (r == 2) return launch_r<GROUP, 1, 2, 4>(stages, sch, wide, p, stream);
+        if (r == 4) return launch_r<GROUP, 1, 4, 4>(stages, sch, wide, p, stream);
     } else if (mb == 1 && xm == 16) {
-        if (r == 1) return launch_r<GROUP, 1, 1, 16>(nw, stages, sch, p, stream);
-        if (r == 2) return launch_r<GROUP, 1, 2, 16>(nw, stages, sch, p, stream);
-        if (r == 4) return launch_r<GROUP, 1, 4, 16>(nw, stages, sch, p, stream);
+        if (r == 1) return launch_r<GROUP, 1, 1, 16>(stages, sch, wide, p, stream);
+        if (r == 2) return launch_r<GROUP, 1, 2, 16>(stages, sch, wide, p, stream);
+        if (r == 4) return launch_r<GROUP, 1, 4, 16>(stages, sch, wide, p, stream);
     } else if (mb == 2 && xm == 16) {
-        if (r == 1) return launch_r<GROUP, 2, 1, 16>(nw, stages, sch, p, stream);
-        if (r == 2) return launch_r<GROUP, 2, 2, 16>(nw, stages, sch, p, stream);
-        if (r == 4) return launch_r<GROUP, 2, 4, 16>(nw, stages, sch, p, stream);
+        if (r == 1) return launch_r<GROUP, 2, 1, 16>(stages, sch, wide, p, stream);
+        if (r == 2) return launch_r<GROUP, 2, 2, 16>(stages, sch, wide, p, stream);
+        if (r == 4) return launch_r<GROUP, 2, 4, 16>(stages, sch, wide, p, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -64,13 +71,13 @@ hipError_t launch_dq(const DequantParams& p, int grid, int lds_bytes, hipStream_
 
 }  // namespace
 
-hipError_t LUTQ_NAME(launch_matmul_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int r, int nw, int stages,
-                                                                    bool sch, int xm, const MatmulParams& p,
+hipError_t LUTQ_NAME(launch_matmul_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int r, int stages, bool sch,
+                                                                    int xm, bool wide, const MatmulParams& p,
                                                                     hipStream_t stream) {
     switch (group) {
-        case 32: return launch_group<32>(mb, r, nw, stages, sch, xm, p, stream);
-        case 64: return launch_group<64>(mb, r, nw, stages, sch, xm, p, stream);
-        case 128: return launch_group<128>(mb, r, nw, stages, sch, xm, p, stream);
+        case 32: return launch_group<32>(mb, r, stages, sch, xm, wide, p, stream);
+        case 64: return launch_group<64>(mb, r, stages, sch, xm, wide, p, stream);
+        case 128: return launch_group<128>(mb, r, stages, sch, xm, wide, p, stream);
     }
     return hipErrorInvalidValue;
 }

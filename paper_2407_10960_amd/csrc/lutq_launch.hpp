@@ -8,16 +8,20 @@
 
 namespace lutq {
 
-// Kernel instances that exist: waves per workgroup x tiles in flight.  (The per-tile scale path,
-// used only when K/group is not a multiple of 8, exists for 4 waves and 2 tiles in flight.)
-inline bool matmul_instance_exists(int nw, int stages, bool sch) {
-    if (!sch) return nw == 4 && stages == 2;
-    return (nw == 4 || nw == 8) && (stages == 2 || stages == 4);
+// Kernel instances that exist.  `wide` instances run up to 16 waves per workgroup within 128
+// registers and exist only where the register estimate fits; the others run up to 8 waves.  The
+// per-tile scale path (K/group not a multiple of 8) exists for 2 tiles in flight, not wide.
+inline bool matmul_instance_exists(int bits, int r, int mb, int stages, bool sch, int xm, bool wide) {
+    if (stages != 2 && stages != 4) return false;
+    if (!sch) return stages == 2 && !wide;
+    if (!wide) return true;
+    return bits == 2 ? matmul_wide_fits<2>(r, mb, stages, xm)
+         : bits == 3 ? matmul_wide_fits<3>(r, mb, stages, xm) : matmul_wide_fits<4>(r, mb, stages, xm);
 }
 
 #define LUTQ_DECLARE_LAUNCHERS(B, DT)                                                               \
-    hipError_t launch_matmul_b##B##_##DT(int group, int mb, int r, int nw, int stages, bool sch,     \
-                                         int xm, const MatmulParams& p, hipStream_t stream);         \
+    hipError_t launch_matmul_b##B##_##DT(int group, int mb, int r, int stages, bool sch, int xm,     \
+                                         bool wide, const MatmulParams& p, hipStream_t stream);      \
     hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes, \
                                           hipStream_t stream);
 

@@ -1,5 +1,5 @@
 // The fused kernel: stream packed weights HBM -> registers, dequantise through the LDS table,
-// scale, multiply on the matrix cores, reduce partial sums across workgroups.
+// scale, multiply on the matrix cores, reduce partial sums across wavefronts and workgroups.
 //
 // Follows Algorithm 1 / Algorithm 2 of the paper in what is computed; the data path is
 // re-designed for gfx950:
@@ -8,12 +8,17 @@
 //   * the only LDS resident is the vectorised table (Section 3.2), one private copy per bank column;
 //   * M < 16 (or < 32) is padded with zero B-operand lanes in registers (the paper pads in shared
 //     memory, "Limitations"), which costs no memory traffic;
-//   * work is split Stream-K style (Section 3.3): the (row group x K tile) iteration space is cut
-//     into `grid` equal contiguous ranges, so a workgroup's range may start and end in the middle of
-//     an output tile.  Partial sums go to a global scratch slot per (workgroup, end); an arrival
-//     counter per output tile elects the last contributor, which adds the slots in a fixed order
-//     (bit-reproducible results), writes Y and resets the counter.  Nobody ever waits on another
-//     workgroup, so the kernel cannot deadlock whatever the number of resident workgroups.
+//   * a workgroup is RS teams of KS wavefronts.  Team j works on row group RS*s + j of the
+//     workgroup's current super-group s (a row group is R 16-row blocks streamed together by every
+//     wave of the team, which share the activation fragments); the KS waves of a team split the K
+//     range and are reduced through LDS.  With RS * R * (number of workgroups) = N / 16 every compute
+//     unit streams the same number of bytes and no partial sum ever leaves the workgroup;
+//   * otherwise work is split Stream-K style (Section 3.3): the (super-group x K tile) iteration
+//     space is cut into `grid` contiguous ranges, so a workgroup's range may start and end in the
+//     middle of an output tile.  Partial sums go to a global scratch slot per (workgroup, end, team);
+//     an arrival counter per row group elects the last contributor, which adds the slots in a fixed
+//     order (bit-reproducible results), writes Y and resets the counter.  Nobody ever waits on
+//     another workgroup, so the kernel cannot deadlock whatever the number of resident workgroups.
 #pragma once
 
 #include "lutq_device.hpp"
@@ -27,61 +32,78 @@ struct MatmulParams {
     const uint16_t* lut;
     uint16_t* Y;              // [M, N]
     uint32_t* counters;       // [NRG], zero on entry, zero on exit
-    float* slots;             // [G][2][SLOT_FLOATS]
+    float* slots;             // [G][2][RS][SLOT_FLOATS]
     uint32_t packed_bytes;
     int M, N, K;
     int KT;                   // K tiles per row block
-    int NRG;                  // row groups (N / (16 R))
+    int NRG;                  // row groups (N / (16 R)), a multiple of RS
     int G;                    // workgroups
-    int TQ, TR;               // NRG * KT = TQ * G + TR: workgroup b owns TQ (+1 if b < TR) iterations
+    int TQ, TR;               // (NRG / RS) * KT = TQ * G + TR: workgroup b owns TQ (+1 if b < TR) iterations
     int SG;                   // scales per row (K / group)
     int SBL;                  // log2 of the row blocks per super-block of the packed layout (R divides it)
+    int NW, KS, RS;           // waves per workgroup = KS waves per team x RS teams
+    uint32_t kt_magic;        // floor(2^32 / KT) and floor(2^32 / KS): division by multiply-high, see div_magic
+    uint32_t ks_magic;
+    int fast_reduce;          // the partial sums of all non-leading waves fit in the table area
 };
 
 // Largest partial-sum slot: R = 4 row blocks x 2 M-halves x 4 registers x 64 lanes.
 constexpr int kSlotFloats = 4 * 2 * 4 * 64;
 
-// The NRG * KT iterations (row group major) are cut into G contiguous ranges; the first TR ranges hold
-// TQ + 1 iterations, the others TQ.  All of it fits 32 bits (checked on the host).
+// n / d for 0 <= n < 2^31 with m = floor(2^32 / d) (0xffffffff for d = 1) computed on the host: the
+// multiply-high is the quotient or one less, so one correction step makes it exact.  A run-time
+// integer division costs some thirty instructions here, and the prologue runs in every wave.
+__device__ __forceinline__ int div_magic(int n, uint32_t m, int d) {
+    int q = (int)__umulhi((uint32_t)n, m);
+    if (n - q * d >= d) ++q;
+    return q;
+}
+
+// The (NRG / RS) * KT iterations (super-group major) are cut into G contiguous ranges; the first TR
+// ranges hold TQ + 1 iterations, the others TQ.  All of it fits 32 bits (checked on the host).
 __device__ __forceinline__ int range_begin(int g, int tq, int tr) { return g * tq + (g < tr ? g : tr); }
 __device__ __forceinline__ int owner_of(int t, int tq, int tr) {
     const int big = tr * (tq + 1);
     return t < big ? t / (tq + 1) : tr + (t - big) / tq;
 }
 
-// LDS bytes of one launch (host and device agree through this one function).
+// LDS bytes of one launch (host and device agree through these functions):
+// [table, 256-byte entry stride][one partial-sum slot per team][one 1 KiB scale-chunk area per wave]
+__host__ __device__ constexpr int red_bytes(int nreg, int rs) { return nreg * 256 * rs; }
 template <int BITS>
-__host__ __device__ constexpr int red_bytes(int nreg) { return nreg * 256 > 2048 ? nreg * 256 : 2048; }
-// Waves per SIMD the register allocation is held to.  An 8-wave workgroup puts two waves on each of
-// the four SIMDs, and two such workgroups (two 64 KiB tables) fit the 160 KiB of LDS: four waves per
-// SIMD, 128 registers each.  That is only asked for when a rough count of the live registers (tiles
-// in flight, accumulators, lookup ring, addresses) says it fits without spilling in the K loop.
-template <int BITS>
-__host__ __device__ constexpr int matmul_waves_per_simd(int r, int mb, int nw, int p, int xm) {
-    const int wregs = BITS == 3 ? 6 : 4;
-    const int xl = Geo<BITS>::STEPS * xm / 16;
-    const int est = p * (r * wregs + xl * mb * 4 + 4) + r * mb * 4 + 52;
-    return (nw >= 8 && est <= 124) ? 4 : 2;
+__host__ __device__ constexpr int matmul_lds_bytes(int r, int mb, int nw, int rs, bool sch) {
+    return lut_lds_bytes<BITS>(perm_log2_copies<BITS>()) + red_bytes(r * mb * 4, rs) + (sch ? nw * 1024 : 0);
 }
 
+// Rough count of the registers live in the K loop (tiles in flight, accumulators, lookup ring,
+// addresses): decides which instances can be held to 128 registers, i.e. four waves per SIMD.
 template <int BITS>
-__host__ __device__ constexpr int matmul_lds_bytes(int r, int mb, int nw, bool sch) {
-    return lut_lds_bytes<BITS>(perm_log2_copies<BITS>()) + red_bytes<BITS>(r * mb * 4) + (sch ? nw * 1024 : 0);
+__host__ __device__ constexpr int matmul_reg_estimate(int r, int mb, int p, int xm) {
+    const int wregs = BITS == 3 ? 6 : 4;
+    const int xl = Geo<BITS>::STEPS * xm / 16;
+    return p * (r * wregs + xl * mb * 4 + 4) + r * mb * 4 + 52;
+}
+template <int BITS>
+__host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm) {
+    return matmul_reg_estimate<BITS>(r, mb, p, xm) <= 124;
 }
 
 // Template parameters: bit width, group size, MB = 16-row halves of M (1: M <= 16, 2: M <= 32),
-// R = 16-row weight blocks a wave streams together (they share the activation fragments),
-// NW = waves per workgroup (they split the K range of the workgroup's segment and are reduced
-// through LDS), P = tiles in flight per wave, SCH = scales are fetched as 16-byte chunks per row
-// (needs K/group % 8 == 0) and handed to the lanes through LDS instead of being loaded per tile.
+// R = 16-row weight blocks a wave streams together, P = tiles in flight per wave, SCH = scales are
+// fetched as 16-byte chunks per row (needs K/group % 8 == 0) and handed to the lanes through LDS
+// instead of being loaded per tile.
 // XM = activation rows that one 16-lane row of the B operand is loaded for: 16 is the plain layout
 // (lane i holds row i; one 128-bit load per 32-wide K step).  XM = 4 (M <= 4 only) packs four K steps
 // into one load: lane i holds row i % 4 of step i / 4, and the steps after the first are brought to
 // lanes 0..3 by rotating the 16-lane rows.  The other twelve columns of the matrix instruction then
 // multiply activations of the wrong steps; they are never read.  This cuts the registers that hold
-// activations in flight to a quarter, which is what lets eight waves per SIMD pair stay resident.
-template <int BITS, int GROUP, int MB, int R, typename DT, int NW, int P, bool SCH, int XM>
-__global__ __launch_bounds__(NW * 64, matmul_waves_per_simd<BITS>(R, MB, NW, P, XM)) void matmul_kernel(const MatmulParams p) {
+// activations in flight to a quarter.
+// WIDE: the instance is compiled for up to 16 waves per workgroup and therefore at most 128
+// registers (four waves per SIMD, or two 8-wave workgroups with their two 64 KiB tables in the
+// 160 KiB of LDS); otherwise for up to 8 waves and as many registers as it likes.
+// The number of waves and their arrangement in teams are run-time values.
+template <int BITS, int GROUP, int MB, int R, typename DT, int P, bool SCH, int XM, bool WIDE>
+__global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulParams p) {
     static_assert(XM == 16 || (XM == 4 && MB == 1), "packed activation loads exist for M <= 4 only");
     using Gm = Geo<BITS>;
     constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
@@ -95,28 +117,29 @@ __global__ __launch_bounds__(NW * 64, matmul_waves_per_simd<BITS>(R, MB, NW, P, 
     constexpr int D = U < 4 ? U : 4;         // table reads kept in flight ahead of their use
     constexpr int XS = 16 / XM;              // K steps covered by one activation load
     constexpr int XL = STEPS / XS;           // activation loads per tile (per 16-row half of M)
-    // all waves' partial sums fit in the table area: reduce there in one go after the last segment
-    constexpr bool FAST_REDUCE = (NW - 1) * NREG * 256 <= LUT_BYTES;
 
     // Every scalar of the parameter block is used in the entry block, so that the argument segment
     // is fetched with one round trip instead of one per basic block that first needs a field.
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.counters), "s"(p.slots));
     asm volatile("" ::"s"(p.packed_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.KT), "s"(p.NRG), "s"(p.G), "s"(p.TQ),
-                 "s"(p.TR), "s"(p.SG), "s"(p.SBL));
+                 "s"(p.TR), "s"(p.SG), "s"(p.SBL), "s"(p.NW), "s"(p.KS), "s"(p.RS), "s"(p.fast_reduce),
+                 "s"(p.kt_magic), "s"(p.ks_magic));
 
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int team = div_magic(wave, p.ks_magic, p.KS);   // which row group of the super-group
+    const int kpart = wave - team * p.KS;    // which part of the K range
     const int li = lane & 15;                // row inside a 16-row block (A side) / activation row (B side)
     const int lo = lane >> 4;                // K octet
+    const int nthreads = p.NW * 64;
 
-    // LDS: [table, 256-byte entry stride][one partial-sum slot, also the table staging area][scale chunks]
     char* lut = smem;
-    float* red = reinterpret_cast<float*>(smem + LUT_BYTES);
-    char* sc_lds = smem + LUT_BYTES + red_bytes<BITS>(NREG) + wave * 1024;      // this wave's 64 rows x 16 B
+    float* red = reinterpret_cast<float*>(smem + LUT_BYTES) + team * (NREG * 64);   // this team's slot
+    char* sc_lds = smem + LUT_BYTES + red_bytes(NREG, p.RS) + wave * 1024;         // this wave's 64 rows x 16 B
 
-    const LutSeed lut_seed = lut_fetch<BITS>(p.lut, tid, NW * 64);   // issued before any weight load (see below)
+    const LutSeed lut_seed = lut_fetch<BITS>(p.lut, tid, nthreads);   // issued before any weight load (see below)
     __builtin_amdgcn_sched_barrier(0);
     const LutAddr la = make_lut_addr<BITS>(lut, LOG2C, lane);
     bool lut_ready = false;
@@ -153,12 +176,13 @@ __global__ __launch_bounds__(NW * 64, matmul_waves_per_simd<BITS>(R, MB, NW, P, 
     };
 
     while (t0 < t1) {
-        const int rg = t0 / p.KT;
-        const int ka = t0 - rg * p.KT;
+        const int sg = div_magic(t0, p.kt_magic, p.KT); // super-group
+        const int ka = t0 - sg * p.KT;
         const int rem = (t1 - t0 < p.KT - ka) ? (t1 - t0) : (p.KT - ka);
         const int kb = ka + rem;
-        const int wa = ka + (wave * rem) / NW;
-        const int wb = ka + ((wave + 1) * rem) / NW;
+        const int rg = sg * p.RS + team;                // this team's row group
+        const int wa = ka + div_magic(kpart * rem, p.ks_magic, p.KS);
+        const int wb = ka + div_magic((kpart + 1) * rem, p.ks_magic, p.KS);
         const bool last_segment = (t0 + rem == t1);
 
         f32x4 acc[R][MB];
@@ -266,7 +290,7 @@ __global__ __launch_bounds__(NW * 64, matmul_waves_per_simd<BITS>(R, MB, NW, P, 
             // out of the segment loop to a point before the prefetch)
             LutSeed seed = lut_seed;
             asm volatile("" : "+v"(seed.v[0]), "+v"(seed.v[1]), "+v"(seed.v[2]), "+v"(seed.v[3]));
-            lut_build<BITS>(lut, seed, LOG2C, tid, NW * 64);
+            lut_build<BITS>(lut, seed, LOG2C, tid, nthreads);
             __syncthreads();
             lut_ready = true;
             __builtin_amdgcn_sched_barrier(0);
@@ -281,52 +305,55 @@ __global__ __launch_bounds__(NW * 64, matmul_waves_per_simd<BITS>(R, MB, NW, P, 
             }
         }
 
-        // ---- reduce the waves of the workgroup through LDS, in wave order ----
-        if (FAST_REDUCE && last_segment) {
-            // nobody needs the table any more: every wave parks its sums there, wave 0 adds them up
-            __syncthreads();
-            float* area = reinterpret_cast<float*>(lut);
-            if (wave != 0) {
-#pragma unroll
-                for (int r = 0; r < R; ++r)
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            area[((wave - 1) * NREG + (r * MB + mb) * 4 + i) * 64 + lane] = acc[r][mb][i];
-            }
-            __syncthreads();
-            if (wave == 0) {
-                for (int w = 0; w < NW - 1; ++w) {
+        // ---- reduce the waves of each team through LDS, in wave order ----
+        if (p.KS > 1) {
+            if (p.fast_reduce && last_segment) {
+                // nobody needs the table any more: every non-leading wave parks its sums there, the
+                // team's leading wave adds them up
+                __syncthreads();
+                float* area = reinterpret_cast<float*>(lut);
+                if (kpart != 0) {
+                    float* dst = area + (size_t)(team * (p.KS - 1) + kpart - 1) * (NREG * 64) + lane;
 #pragma unroll
                     for (int r = 0; r < R; ++r)
 #pragma unroll
                         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                            for (int i = 0; i < 4; ++i)
-                                acc[r][mb][i] += area[(w * NREG + (r * MB + mb) * 4 + i) * 64 + lane];
-                }
-            }
-        } else {
-            for (int w = 1; w < NW; ++w) {
-                if (wave == w) {
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) red[((r * MB + mb) * 4 + i) * 64 + lane] = acc[r][mb][i];
+                            for (int i = 0; i < 4; ++i) dst[((r * MB + mb) * 4 + i) * 64] = acc[r][mb][i];
                 }
                 __syncthreads();
-                if (wave == 0) {
+                if (kpart == 0) {
+                    for (int w = 0; w < p.KS - 1; ++w) {
+                        const float* src = area + (size_t)(team * (p.KS - 1) + w) * (NREG * 64) + lane;
 #pragma unroll
-                    for (int r = 0; r < R; ++r)
+                        for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int mb = 0; mb < MB; ++mb)
+                            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) acc[r][mb][i] += red[((r * MB + mb) * 4 + i) * 64 + lane];
+                                for (int i = 0; i < 4; ++i) acc[r][mb][i] += src[((r * MB + mb) * 4 + i) * 64];
+                    }
                 }
-                __syncthreads();
+            } else {
+                for (int w = 1; w < p.KS; ++w) {
+                    if (kpart == w) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) red[((r * MB + mb) * 4 + i) * 64 + lane] = acc[r][mb][i];
+                    }
+                    __syncthreads();
+                    if (kpart == 0) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) acc[r][mb][i] += red[((r * MB + mb) * 4 + i) * 64 + lane];
+                    }
+                    __syncthreads();
+                }
             }
         }
 
@@ -337,14 +364,18 @@ __global__ __launch_bounds__(NW * 64, matmul_waves_per_simd<BITS>(R, MB, NW, P, 
         // Ordering comes from completion instead: the writer waits until its stores are acknowledged
         // before it bumps the counter, and the reader issues its loads only after the counter value
         // that proves it is last has come back.
-        if (wave == 0) {
+        if (kpart == 0) {
             bool write_y = (ka == 0 && kb == p.KT);
             if (!write_y) {
-                const int tile0 = rg * p.KT;
-                const int g_first = owner_of(tile0, p.TQ, p.TR);
-                const int g_last = owner_of(tile0 + p.KT - 1, p.TQ, p.TR);
+                // (the split is re-read through an empty statement so that the divisions below stay on
+                // this rarely taken path instead of being hoisted into every wave's prologue)
+                int tq = p.TQ, tr = p.TR;
+                asm volatile("" : "+s"(tq), "+s"(tr));
+                const int tile0 = sg * p.KT;
+                const int g_first = owner_of(tile0, tq, tr);
+                const int g_last = owner_of(tile0 + p.KT - 1, tq, tr);
                 const int which = (t0 == tbeg) ? 0 : 1;
-                float* slot = p.slots + ((size_t)blockIdx.x * 2 + which) * kSlotFloats + lane;
+                float* slot = p.slots + (((size_t)blockIdx.x * 2 + which) * p.RS + team) * kSlotFloats + lane;
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -368,9 +399,9 @@ __global__ __launch_bounds__(NW * 64, matmul_waves_per_simd<BITS>(R, MB, NW, P, 
 #pragma unroll
                         for (int mb = 0; mb < MB; ++mb) acc[r][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
                     for (int g = g_first; g <= g_last; ++g) {
-                        const int gbeg = range_begin(g, p.TQ, p.TR);
-                        const int gw = (gbeg / p.KT == rg) ? 0 : 1;     // slot 0 iff rg is g's first row group
-                        const float* src = p.slots + ((size_t)g * 2 + gw) * kSlotFloats + lane;
+                        const int gbeg = range_begin(g, tq, tr);
+                        const int gw = (div_magic(gbeg, p.kt_magic, p.KT) == sg) ? 0 : 1;   // slot 0 iff sg is g's first super-group
+                        const float* src = p.slots + (((size_t)g * 2 + gw) * p.RS + team) * kSlotFloats + lane;
 #pragma unroll
                         for (int r = 0; r < R; ++r)
 #pragma unroll

@@ -131,7 +131,14 @@ def test_result_independent_of_work_decomposition(lutq, bits, dtype):
         for plan in [lutq.Plan(4, 1), lutq.Plan(4, 2, 8), lutq.Plan(4, 3, 4, 2), lutq.Plan(4, 7, 8, 2), lutq.Plan(4, 31),
                      lutq.Plan(2, 5), lutq.Plan(2, 64, 4, 4), lutq.Plan(1, 16, 8), lutq.Plan(1, 33, 0, 2),
                      lutq.Plan(1, 128), lutq.Plan(1, 128, 8, 4), lutq.Plan(1, 2048),
-                     lutq.Plan(0, 0, 8), lutq.Plan(0, 0, 0)]:
+                     lutq.Plan(0, 0, 8), lutq.Plan(0, 0, 0),
+                     # teams: several row groups side by side in one workgroup, with and without a K split
+                     # inside the team, with and without tiles split across workgroups
+                     lutq.Plan(1, 4, 4, 2, 4), lutq.Plan(1, 3, 8, 2, 2), lutq.Plan(2, 2, 8, 4, 4), lutq.Plan(1, 0, 6, 2, 2),
+                     lutq.Plan(4, 5, 4, 2, 2), lutq.Plan(1, 1, 8, 2, 8), lutq.Plan(1, 7, 7, 2, 1)] + (
+                    # more than 8 waves: instances held to 128 registers, which exist for M <= 4
+                    [lutq.Plan(1, 0, 16, 2, 2), lutq.Plan(1, 5, 14, 2, 1), lutq.Plan(2, 3, 12, 2, 4), lutq.Plan(1, 1, 16, 2, 16),
+                     lutq.Plan(1, 9, 10, 2, 2)] if M <= 4 else []):
             Y1 = to_bits(d.matmul(lutq, plan=plan))
             assert not d.ws[:65536].any().item(), f"arrival counters not left zero by plan {plan}"
             Y2 = to_bits(d.matmul(lutq, plan=plan))
@@ -187,7 +194,8 @@ def test_bad_plan_is_rejected_and_y_untouched(lutq):
     c = gen.make_case(3, 2, 48, 256, 4, 64, "f16", "nf")            # 3 row blocks: R = 2, 4 do not divide
     d = DeviceCase(lutq, c)
     Y = torch.full((2, 48), 7.0, dtype=torch.float16, device="cuda")
-    for plan in (lutq.Plan(2, 0, 0), lutq.Plan(3, 0, 0), lutq.Plan(0, 4097, 0), lutq.Plan(0, 0, 3), lutq.Plan(0, 0, 16), lutq.Plan(0, 0, 0, 3)):
+    for plan in (lutq.Plan(2, 0, 0), lutq.Plan(3, 0, 0), lutq.Plan(0, 4097, 0), lutq.Plan(0, 0, 3), lutq.Plan(0, 0, 17), lutq.Plan(0, 0, 0, 3),
+                 lutq.Plan(1, 0, 8, 2, 3), lutq.Plan(1, 0, 8, 2, 2), lutq.Plan(0, 0, 0, 0, 17)):
         with pytest.raises(lutq.LutqError) as e:
             lutq.lutq_matmul(d.X, d.packed, d.S, d.T, 4, 64, Y, d.ws, plan=plan)
         assert e.value.code == 10
