@@ -47,6 +47,16 @@ def build_layer(lutq, torch, seed):
     return mats
 
 
+def warm(torch, fn, seconds=0.1):
+    """Runs fn (untimed) for a while: after any idle period the GPU needs some tens of milliseconds of
+    load before its clocks are back up, and a single replay is far shorter than that."""
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    while time.perf_counter() - t < seconds:
+        fn()
+        torch.cuda.synchronize()
+
+
 def time_region(torch, fn, iters):
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -133,23 +143,27 @@ def main():
     torch.cuda.synchronize()
 
     use_graph = not args.no_graph
-    graph = None
-    if use_graph:
+
+    def capture(fn):
+        """A HIP graph of fn's launches (replayed as one unit: no per-call Python or launch-API time)."""
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            step_direct()
+            fn()
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step_direct()
-        step = graph.replay
-    else:
-        step = step_direct
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g
+
+    step = capture(step_direct).replay if use_graph else step_direct
 
     for _ in range(args.warmup):
         step()
+    # the GPU raises its clocks only after some tens of milliseconds of load: keep warming up (untimed)
+    # until the step time has had that long to settle, whatever --warmup says
+    warm(torch, step, 0.15)
     sec = time_region(torch, step, args.steps)
     value = step_bytes / sec * 1e-9
     per_launch_s = sec / launches
@@ -168,53 +182,49 @@ def main():
                    "percent_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": roof_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": roof_achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "lutq::matmul_kernel<4,128,1,R,F16,NW,true>", "bytes_per_launch": step_bytes / launches,
-                     "us_per_launch": per_launch_s * 1e6},
+                     "kernel": "lutq::matmul_kernel<4,128,1,R,F16,P,true,4,WIDE> (all 128 launches of the step)",
+                     "bytes_per_launch": step_bytes / launches, "us_per_launch": per_launch_s * 1e6},
     }
 
     if not args.no_extras:
         per_shape = {}
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
         for n in names:
             m = layer0[n]
             N, K = m["N"], m["K"]
             by = gen.algorithmic_bytes(M, N, K, BITS, GROUP)
-            state = {"i": 0}
 
-            def cold_call(n=n, state=state):
-                one_call(n, state["i"] % LAYERS)
-                state["i"] += 1
-            for _ in range(LAYERS):
-                cold_call()
-            t = time_region(torch, cold_call, 4 * LAYERS)
+            def shape_pass(n=n):
+                for li in range(LAYERS):
+                    one_call(n, li)
+            run = capture(shape_pass).replay if use_graph else shape_pass
+            warm(torch, run)
+            t = time_region(torch, run, 10) / LAYERS
+            # a plain streaming read of the same packed bytes (no table, no arithmetic): what one launch
+            # per call can reach on this shape at all
+            def read_pass(n=n):
+                for li in range(LAYERS):
+                    lutq.calib_stream_read(layers[li][n]["packed"], 512, sink)
+            rrun = capture(read_pass).replay if use_graph else read_pass
+            warm(torch, rrun)
+            tr = time_region(torch, rrun, 10) / LAYERS
             # dense fp16 GEMM on the same shape (torch.mm -> hipBLASLt/rocBLAS), ring of weights > 1 GB
             dense_bytes = N * K * 2
             ring = max(2, min(LAYERS, int(1.3e9 // dense_bytes) + 1))
             Wd = [torch.randn((N, K), dtype=torch.float16, device="cuda") * 0.02 for _ in range(ring)]
             Yd = torch.empty((M, N), dtype=torch.float16, device="cuda")
-            dstate = {"i": 0}
 
-            def dense_call(dstate=dstate, Wd=Wd, Yd=Yd, m=m):
-                torch.mm(m["X"], Wd[dstate["i"] % len(Wd)].t(), out=Yd)
-                dstate["i"] += 1
-            for _ in range(ring):
-                dense_call()
-            td = time_region(torch, dense_call, 4 * ring)
-            del Wd
+            def dense_pass(Wd=Wd, Yd=Yd, m=m):
+                for w in Wd:
+                    torch.mm(m["X"], w.t(), out=Yd)
+            drun = capture(dense_pass).replay if use_graph else dense_pass
+            warm(torch, drun)
+            td = time_region(torch, drun, 10) / ring
+            del Wd, drun
             per_shape[n] = {"N": N, "K": K, "us": t * 1e6, "GBps": by / t * 1e-9, "frac_of_8TBps": by / t * 1e-9 / HBM_PEAK_GBS,
-                            "TFLOPs": 2.0 * M * N * K / t * 1e-12, "dense_fp16_us": td * 1e6, "speedup_vs_dense_fp16": td / t}
-        out["per_shape_cold_python_launch"] = per_shape
-        # achievable streaming-read bandwidth over one gate_up-sized buffer per launch (same ring)
-        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
-        rstate = {"i": 0}
-
-        def read_call():
-            lutq.calib_stream_read(layers[rstate["i"] % LAYERS]["gate_up"]["packed"], 512, sink)
-            rstate["i"] += 1
-        for _ in range(LAYERS):
-            read_call()
-        tr = time_region(torch, read_call, 4 * LAYERS)
-        out["stream_read_calibrator"] = {"bytes": int(layer0["gate_up"]["packed"].numel()), "us": tr * 1e6,
-                                         "GBps": layer0["gate_up"]["packed"].numel() / tr * 1e-9}
+                            "TFLOPs": 2.0 * M * N * K / t * 1e-12, "dense_fp16_us": td * 1e6, "speedup_vs_dense_fp16": td / t,
+                            "stream_read_us": tr * 1e6, "stream_read_GBps": m["packed"].numel() / tr * 1e-9}
+        out["per_shape_cold"] = per_shape
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layer0["o"]["case"])

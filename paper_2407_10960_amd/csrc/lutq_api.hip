@@ -75,50 +75,69 @@ bool wide_exists(int bits, int r, int mb, int stages, int xm) {
     return matmul_instance_exists(bits, r, mb, stages, true, xm, true);
 }
 
+int64_t gcd64(int64_t a, int64_t b) {
+    while (b) { const int64_t t = a % b; a = b; b = t; }
+    return a;
+}
+
 // Default work decomposition (host part of Algorithm 1: the tile scheduler and the number of blocks).
 //
 // Measured on MI355X, a launch of this kernel is a few microseconds of fixed latencies (argument
 // fetch, first HBM round trip, table build, final reduction) around a streaming phase that runs at
 // HBM speed, and the cross-workgroup fix-up costs three more dependent device-scope round trips.
 // What matters is therefore that every compute unit streams the same number of bytes, that one
-// workgroup (one table build) per compute unit does all of it, and that no partial sum leaves the
-// workgroup.  When the 16-row blocks divide evenly over the compute units, the workgroup is
-// arranged as RS teams x KS waves: `per` = N/16/CUs row blocks per workgroup = RS teams x R blocks,
-// and the KS waves of a team split K.  Otherwise R is the largest of 4, 2, 1 with at least one row
-// group per compute unit and grid = number of row groups; only when N is too small for that is K
-// split across workgroups, with the Stream-K style fix-up.
+// workgroup (one table build) per compute unit does all of it with about 24 KiB or more of weights
+// in flight, and that partial sums leave the workgroup only when the kernel is long enough to hide it.
+//   * N/16 = per x CUs: one workgroup per compute unit, arranged as RS teams x KS waves, per = RS x R.
+//     No output tile is split across workgroups.
+//   * N/16 = (p/q) x CUs with small p, q and at least 128 KiB per compute unit: RS = p row blocks
+//     side by side, one workgroup per compute unit, every super-group's K range cut into q parts
+//     (Stream-K fix-up for every tile, but perfectly balanced).
+//   * otherwise one workgroup of 8 waves per row group, R the largest of 4, 2, 1 that still gives
+//     every compute unit a row group; only when N is too small even for that is K split across
+//     workgroups, with the fix-up.
 Decomp default_decomp(int bits, int64_t M, int64_t N, int64_t K, int cus, int force_r) {
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1, xm = M <= 4 ? 4 : 16;
     const int sb = super_block(nb);
+    const int64_t g = gcd64(nb, cus), pn = nb / g, qn = cus / g;     // nb / cus = pn / qn
+    const int64_t bytes_per_cu = N * K * bits / 8 / cus;
     Decomp d;
-    if (nb % cus == 0 && nb / cus <= 64) {
-        int64_t per = nb / cus;                           // row blocks per compute unit
+    d.stages = 2;                                         // measured: deeper prefetch does not pay at 8-16 waves
+    // waves for `rs` teams of `r` row blocks: enough for 24 KiB in flight (r KiB per tile, two tiles
+    // per wave), at least 8, at most 16, a multiple of rs, two K tiles or more per wave
+    auto waves_for = [&](int r, int64_t rs, int64_t tiles_per_team) -> int {
+        int ks = 1;
+        while ((int64_t)rs * (ks + 1) <= 16 && tiles_per_team / (ks + 1) >= 2 &&
+               (rs * ks < 8 || rs * ks * r * 2 < 24)) ++ks;
+        int nw = (int)rs * ks;
+        if (nw > 8 && !wide_exists(bits, r, mb, 2, xm)) {          // too many registers for more than 8 waves
+            ks = (int)(8 / rs);
+            nw = (int)rs * ks;
+        }
+        while (nw < 4 && ks > 0) { ++ks; nw = (int)rs * ks; }     // the table build needs four waves
+        return nw;
+    };
+    if (qn == 1 && pn <= 64) {
+        int64_t per = pn;                                 // row blocks per compute unit
         int grid = cus;
         int r = force_r ? force_r : sb;
         while (r > 1 && per % r != 0) r >>= 1;
-        // registers: prefer R <= 2 so that 128 registers hold two tiles in flight
-        if (!force_r) while (r > 2) r >>= 1;
+        if (!force_r) while (r > 2) r >>= 1;              // R <= 2 keeps two tiles in flight within 128 registers
+        if (!force_r && r == 2 && per <= 16 && !wide_exists(bits, 2, mb, 2, xm) && wide_exists(bits, 1, mb, 2, xm))
+            r = 1;                                        // more, narrower teams rather than half the waves
         int64_t rs = per / r;
         while (rs > 8 && rs % 2 == 0) { rs /= 2; grid *= 2; }
-        if (rs <= 16 && (int64_t)grid * rs <= kMaxGrid) {
-            int ks = (int)(16 / rs);
-            while (ks > 1 && kt / ks < 4) --ks;           // at least four K tiles per wave
-            if (ks < 1) ks = 1;
-            int nw = (int)rs * ks;
-            while (nw < 4) { ++ks; nw = (int)rs * ks; }  // the table build needs four waves
-            const int stages = 2;                         // measured: deeper prefetch does not pay at 14-16 waves
-            if (nw > 8) {
-                if (!wide_exists(bits, r, mb, 2, xm)) {   // too many registers for 16 waves: 8 at most
-                    ks = (int)(8 / rs) > 0 ? (int)(8 / rs) : 1;
-                    nw = (int)rs * ks;
-                    while (nw < 4) { ++ks; nw = (int)rs * ks; }
-                }
-            }
-            if (nw <= 16 && (nw <= 8 || wide_exists(bits, r, mb, stages, xm))) {
-                d.r = r; d.grid = grid; d.nw = nw; d.stages = stages; d.rs = (int)rs;
-                return d;
-            }
+        const int nw = rs <= 16 ? waves_for(r, rs, kt) : 0;
+        if (nw >= 4 && nw <= 16 && (int64_t)grid * rs <= kMaxGrid) {
+            d.r = r; d.grid = grid; d.nw = nw; d.rs = (int)rs;
+            return d;
+        }
+    } else if (!force_r && qn <= 4 && pn <= 8 && bytes_per_cu >= 128 * 1024 && kt / qn >= 8) {
+        const int nw = waves_for(1, pn, kt / qn);
+        if (nw >= 4 && nw <= 16 && nw % pn == 0) {
+            d.r = 1; d.grid = cus; d.nw = nw; d.rs = (int)pn;
+            return d;
         }
     }
     int r = sb;                                           // R has to divide the layout's super-block
@@ -133,8 +152,8 @@ Decomp default_decomp(int bits, int64_t M, int64_t N, int64_t K, int cus, int fo
         grid = groups * j;
     }
     while (grid > kMaxGrid) grid = (grid + 1) / 2;
-    d.r = r; d.grid = (int)grid; d.nw = 4; d.rs = 1;
-    d.stages = (r == 4 && M > 16) ? 2 : 4;
+    d.r = r; d.grid = (int)grid; d.rs = 1;
+    d.nw = 8;
     return d;
 }
 

@@ -81,7 +81,8 @@ template <int BITS>
 __host__ __device__ constexpr int matmul_reg_estimate(int r, int mb, int p, int xm) {
     const int wregs = BITS == 3 ? 6 : 4;
     const int xl = Geo<BITS>::STEPS * xm / 16;
-    return p * (r * wregs + xl * mb * 4 + 4) + r * mb * 4 + 52;
+    const int na = xm == 16 ? mb : 16 / xm;               // accumulators per row block
+    return p * (r * wregs + xl * mb * 4 + 4) + r * na * 4 + 46;
 }
 template <int BITS>
 __host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm) {
@@ -94,10 +95,12 @@ __host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm
 // instead of being loaded per tile.
 // XM = activation rows that one 16-lane row of the B operand is loaded for: 16 is the plain layout
 // (lane i holds row i; one 128-bit load per 32-wide K step).  XM = 4 (M <= 4 only) packs four K steps
-// into one load: lane i holds row i % 4 of step i / 4, and the steps after the first are brought to
-// lanes 0..3 by rotating the 16-lane rows.  The other twelve columns of the matrix instruction then
-// multiply activations of the wrong steps; they are never read.  This cuts the registers that hold
-// activations in flight to a quarter.
+// into one load: lane i holds row i % 4 of step i / 4.  The matrix instruction of step s then gets the
+// right activations in columns 4 (s % 4) .. 4 (s % 4) + 3 only, so each of the four step positions
+// accumulates into its own registers (the other twelve columns multiply activations of other steps
+// and are never read), and the four accumulators are folded together, with three row rotations, once
+// per output tile.  This cuts the registers that hold activations in flight to a quarter and issues a
+// quarter of the activation loads.
 // WIDE: the instance is compiled for up to 16 waves per workgroup and therefore at most 128
 // registers (four waves per SIMD, or two 8-wave workgroups with their two 64 KiB tables in the
 // 160 KiB of LDS); otherwise for up to 8 waves and as many registers as it likes.
@@ -117,6 +120,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
     constexpr int D = U < 4 ? U : 4;         // table reads kept in flight ahead of their use
     constexpr int XS = 16 / XM;              // K steps covered by one activation load
     constexpr int XL = STEPS / XS;           // activation loads per tile (per 16-row half of M)
+    constexpr int NA = XM == 16 ? MB : XS;   // accumulators per row block: M halves, or step positions
 
     // Every scalar of the parameter block is used in the entry block, so that the argument segment
     // is fetched with one round trip instead of one per basic block that first needs a field.
@@ -185,11 +189,11 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
         const int wb = ka + div_magic((kpart + 1) * rem, p.ks_magic, p.KS);
         const bool last_segment = (t0 + rem == t1);
 
-        f32x4 acc[R][MB];
+        f32x4 acc[R][NA];
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) acc[r][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int a = 0; a < NA; ++a) acc[r][a] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         const int rb0 = rg * R;                                                          // first row block
         const uint32_t wrow = (uint32_t)(rb0 >> p.SBL) * sblock_bytes + (uint32_t)(rb0 & ((1 << p.SBL) - 1)) * TILE_BYTES;
@@ -247,7 +251,6 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             // the matrix instruction of item u is issued after the scaling of item u + 1, so that it
             // never has to wait for operands that were written by the instructions just before it
             u32x4 a[2];
-            u32x4 xb = u32x4{0u, 0u, 0u, 0u};   // packed activations: the current step's B operand
 #pragma unroll
             for (int u = 0; u <= U; ++u) {
                 if (u < U) {
@@ -267,8 +270,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                         for (int mb = 0; mb < MB; ++mb)
                             acc[r][mb] = mfma16x16x32<DT>(a[(u - 1) & 1], st.x[s][mb], acc[r][mb]);
                     } else {
-                        if (r == 0) xb = rotate_rows(st.x[s / XS][0], XM * (s % XS));
-                        acc[r][0] = mfma16x16x32<DT>(a[(u - 1) & 1], xb, acc[r][0]);
+                        acc[r][s % XS] = mfma16x16x32<DT>(a[(u - 1) & 1], st.x[s / XS][0], acc[r][s % XS]);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -303,6 +305,17 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                 load_stage(st[q], kt + q + P);
                 __builtin_amdgcn_sched_barrier(0);
             }
+        }
+
+        if constexpr (XM != 16) {
+            // fold the step positions: columns 4 j .. 4 j + 3 of accumulator j move to columns 0 .. 3
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int j = 1; j < XS; ++j) {
+                    const u32x4 t = rotate_rows(__builtin_bit_cast(u32x4, acc[r][j]), XM * j);
+                    acc[r][0] += __builtin_bit_cast(f32x4, t);
+                }
         }
 
         // ---- reduce the waves of each team through LDS, in wave order ----

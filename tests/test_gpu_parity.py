@@ -136,8 +136,8 @@ def test_result_independent_of_work_decomposition(lutq, bits, dtype):
                      # inside the team, with and without tiles split across workgroups
                      lutq.Plan(1, 4, 4, 2, 4), lutq.Plan(1, 3, 8, 2, 2), lutq.Plan(2, 2, 8, 4, 4), lutq.Plan(1, 0, 6, 2, 2),
                      lutq.Plan(4, 5, 4, 2, 2), lutq.Plan(1, 1, 8, 2, 8), lutq.Plan(1, 7, 7, 2, 1)] + (
-                    # more than 8 waves: instances held to 128 registers, which exist for M <= 4
-                    [lutq.Plan(1, 0, 16, 2, 2), lutq.Plan(1, 5, 14, 2, 1), lutq.Plan(2, 3, 12, 2, 4), lutq.Plan(1, 1, 16, 2, 16),
+                    # more than 8 waves: instances held to 128 registers, which exist for M <= 4 and R = 1 at every bit width
+                    [lutq.Plan(1, 0, 16, 2, 2), lutq.Plan(1, 5, 14, 2, 1), lutq.Plan(1, 3, 12, 2, 4), lutq.Plan(1, 1, 16, 2, 16),
                      lutq.Plan(1, 9, 10, 2, 2)] if M <= 4 else []):
             Y1 = to_bits(d.matmul(lutq, plan=plan))
             assert not d.ws[:65536].any().item(), f"arrival counters not left zero by plan {plan}"
