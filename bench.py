@@ -28,6 +28,11 @@ sys.path.insert(0, ROOT)
 import lutq_inputs as gen  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of this workload (fetched + written), from the FETCH_SIZE / WRITE_SIZE counter runs
+# summarised in profiles/matmul_kernel_llama3_8b_w4g128_m1_hbm_traffic.txt (counters scaled by a copy
+# kernel of known size).  A counter run cannot be made from inside this script; the figure belongs to
+# this exact workload and is reported as measured there.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 28.34e6
 LAYERS = 32
 BITS, GROUP, DTYPE, M = 4, 128, "f16", 1
 
@@ -100,6 +105,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-shape table and the dense fp16 comparison")
+    ap.add_argument("--pmc-calib", action="store_true",
+                    help="also launch the plain copy kernel on 256 MiB a few times, so that a counter run "
+                         "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a dispatch of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path has no collectives); use --gpus 1", file=sys.stderr)
@@ -141,6 +149,13 @@ def main():
 
     step_direct()          # first launches: module load, device query
     torch.cuda.synchronize()
+    if args.pmc_calib:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            lutq.calib_copy(src, dst, 2048)
+        torch.cuda.synchronize()
+        del src, dst
 
     use_graph = not args.no_graph
 
@@ -181,7 +196,7 @@ def main():
                    "calls_per_step": launches, "bytes_per_step": step_bytes,
                    "percent_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": roof_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": roof_achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": roof_achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
                      "kernel": "lutq::matmul_kernel<4,128,1,R,F16,P,true,4,WIDE> (all 128 launches of the step)",
                      "bytes_per_launch": step_bytes / launches, "us_per_launch": per_launch_s * 1e6},
     }

@@ -14,7 +14,11 @@ namespace lutq {
 inline bool matmul_instance_exists(int bits, int r, int mb, int stages, bool sch, int xm, bool wide) {
     if (stages != 2 && stages != 4) return false;
     if (!sch) return stages == 2 && !wide;
-    if (!wide) return true;
+    if (!wide) {                                        // up to 256 registers; beyond that the K loop would spill
+        const int est = bits == 2 ? matmul_reg_estimate<2>(r, mb, stages, xm)
+                      : bits == 3 ? matmul_reg_estimate<3>(r, mb, stages, xm) : matmul_reg_estimate<4>(r, mb, stages, xm);
+        return est <= 250;
+    }
     return bits == 2 ? matmul_wide_fits<2>(r, mb, stages, xm)
          : bits == 3 ? matmul_wide_fits<3>(r, mb, stages, xm) : matmul_wide_fits<4>(r, mb, stages, xm);
 }
