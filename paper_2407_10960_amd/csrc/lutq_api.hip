@@ -90,7 +90,7 @@ int64_t gcd64(int64_t a, int64_t b) {
 // in flight, and that partial sums leave the workgroup only when the kernel is long enough to hide it.
 //   * N/16 = per x CUs: one workgroup per compute unit, arranged as RS teams x KS waves, per = RS x R.
 //     No output tile is split across workgroups.
-//   * N/16 = (p/q) x CUs with small p, q and at least 128 KiB per compute unit: RS = p row blocks
+//   * N/16 = (p/q) x CUs with small p, q and at least 96 KiB per compute unit: RS = p row blocks
 //     side by side, one workgroup per compute unit, every super-group's K range cut into q parts
 //     (Stream-K fix-up for every tile, but perfectly balanced).
 //   * otherwise one workgroup of 8 waves per row group, R the largest of 4, 2, 1 that still gives
@@ -118,11 +118,36 @@ Decomp default_decomp(int bits, int64_t M, int64_t N, int64_t K, int cus, int fo
         while (nw < 4 && ks > 0) { ++ks; nw = (int)rs * ks; }     // the table build needs four waves
         return nw;
     };
-    if (qn == 1 && pn <= 64) {
+    if (M > 4) {
+        // More than four activation rows use the plain activation layout: every row group reads
+        // M x K activations (through L2/L1) next to its 8 R K bytes of weights, so what matters
+        // first is a large R; then one workgroup per row group (no teams: they would each re-read
+        // the activations), K split across workgroups when there are too few row groups.
+        int r = force_r;
+        if (!r) {
+            r = sb;
+            while (r > 1 && nb / r < (int64_t)cus * 7 / 10) r >>= 1;
+            if (r == 1 && sb >= 2 && kt >= 64) r = 2;     // long K: split it across workgroups instead
+            while (r > 1 && !matmul_instance_exists(bits, r, mb, 2, true, xm, false)) r >>= 1;   // registers
+        }
+        const int64_t groups = nb / r;
+        int64_t grid = groups;
+        if (groups < (int64_t)cus * 7 / 10) {
+            int64_t j = (cus + groups - 1) / groups;      // K parts per row group
+            if (j > kt / 8) j = kt / 8;
+            if (j < 1) j = 1;
+            grid = groups * j;
+        }
+        while (grid > kMaxGrid) grid = (grid + 1) / 2;
+        d.r = r; d.grid = (int)grid; d.rs = 1;
+        d.nw = r == 4 ? 4 : 8;
+        return d;
+    }
+    if (qn == 1 && pn <= 64 && (!force_r || pn % force_r == 0)) {
         int64_t per = pn;                                 // row blocks per compute unit
         int grid = cus;
         int r = force_r ? force_r : sb;
-        while (r > 1 && per % r != 0) r >>= 1;
+        while (!force_r && r > 1 && per % r != 0) r >>= 1;
         if (!force_r) while (r > 2) r >>= 1;              // R <= 2 keeps two tiles in flight within 128 registers
         if (!force_r && r == 2 && per <= 16 && !wide_exists(bits, 2, mb, 2, xm) && wide_exists(bits, 1, mb, 2, xm))
             r = 1;                                        // more, narrower teams rather than half the waves
@@ -133,7 +158,7 @@ Decomp default_decomp(int bits, int64_t M, int64_t N, int64_t K, int cus, int fo
             d.r = r; d.grid = grid; d.nw = nw; d.rs = (int)rs;
             return d;
         }
-    } else if (!force_r && qn <= 4 && pn <= 8 && bytes_per_cu >= 128 * 1024 && kt / qn >= 8) {
+    } else if (!force_r && qn <= 4 && pn <= 8 && bytes_per_cu >= 96 * 1024 && kt / qn >= 8) {
         const int nw = waves_for(1, pn, kt / qn);
         if (nw >= 4 && nw <= 16 && nw % pn == 0) {
             d.r = 1; d.grid = cus; d.nw = nw; d.rs = (int)pn;
