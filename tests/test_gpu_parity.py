@@ -218,6 +218,15 @@ FULL_SIZE = [
     ("8B qkv W3 g64", 6144, 4096, 3, 64, "f16", 32),
     ("70B o W3 g64 bf16", 8192, 8192, 3, 64, "bf16", 16),
     ("8192^2 W2 g32", 8192, 8192, 2, 32, "f16", 4),
+    # one case per branch of the default work decomposition
+    ("8B o W4 g128 M1 (12 waves split K)", 4096, 4096, 4, 128, "f16", 1),
+    ("8B qkv W4 g128 M1 (one workgroup per row group)", 6144, 4096, 4, 128, "f16", 1),
+    ("70B qkv W4 g64 bf16 M1 (5 teams, every tile split in two)", 10240, 8192, 4, 64, "bf16", 1),
+    ("70B o W4 g64 bf16 M1 (R = 2)", 8192, 8192, 4, 64, "bf16", 1),
+    ("8B gate_up W3 g128 M1 (7 teams x 2)", 28672, 4096, 3, 128, "f16", 1),
+    ("8B gate_up W3 g128 M8 (R = 4, plain activations)", 28672, 4096, 3, 128, "f16", 8),
+    ("8B gate_up W3 g64 M32 (R limited by registers)", 28672, 4096, 3, 64, "f16", 32),
+    ("8B down W2 g128 M3", 4096, 14336, 2, 128, "bf16", 3),
 ]
 
 
