@@ -315,6 +315,8 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     p.SG = (int)(K / group_size);
     p.SBL = ilog2(super_block(nb));
     p.NW = d.nw; p.RS = d.rs; p.KS = d.nw / d.rs;
+    p.lut_ltpe = bits == 2 ? lut_log2_threads_per_row<2>(d.nw * 64)
+               : bits == 3 ? lut_log2_threads_per_row<3>(d.nw * 64) : lut_log2_threads_per_row<4>(d.nw * 64);
     p.kt_magic = p.KT == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KT);
     p.ks_magic = p.KS == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KS);
     p.fast_reduce = (d.nw - d.rs) * (r * mb * 4) * 256 <= lut_bytes(bits, bits == 2 ? 5 : 6) ? 1 : 0;

@@ -89,16 +89,16 @@ __device__ __forceinline__ void load_wfrag(WFrag<BITS>& f, rsrc_t packed, uint32
 // ---------------------------------------------------------------------------------------
 struct LutSeed { uint32_t v[4]; };     // raw 16-bit table values of this thread's row
 
-// log2 of the threads that share one row
+// log2 of the threads that share one row (the fused kernel gets it from the host)
 template <int BITS>
-__device__ __forceinline__ int lut_log2_threads_per_row(int nthreads) {
+__host__ __device__ constexpr int lut_log2_threads_per_row(int nthreads) {
     const int t = nthreads / Geo<BITS>::ENTRIES;
     return t >= 16 ? 4 : t >= 8 ? 3 : t >= 4 ? 2 : t >= 2 ? 1 : 0;
 }
 
 template <int BITS>
-__device__ __forceinline__ LutSeed lut_fetch(const uint16_t* __restrict__ T, int tid, int nthreads) {
-    const int e = (tid >> lut_log2_threads_per_row<BITS>(nthreads)) & (Geo<BITS>::ENTRIES - 1);
+__device__ __forceinline__ LutSeed lut_fetch(const uint16_t* __restrict__ T, int tid, int ltpe) {
+    const int e = (tid >> ltpe) & (Geo<BITS>::ENTRIES - 1);
     LutSeed s;
     if constexpr (BITS == 4) {
         s.v[0] = T[e & 15]; s.v[1] = T[(e >> 4) & 15]; s.v[2] = 0; s.v[3] = 0;
@@ -113,12 +113,11 @@ __device__ __forceinline__ LutSeed lut_fetch(const uint16_t* __restrict__ T, int
 }
 
 template <int BITS>
-__device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int log2c, int tid, int nthreads) {
+__device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int log2c, int tid, int ltpe) {
     using Gm = Geo<BITS>;
     constexpr int ESH = Gm::ENTRY_BYTES == 8 ? 3 : 2;
     const int stride = 1 << (log2c + ESH);                        // bytes of one row
     const int chunks = stride >> 4;                               // 16-byte chunks of one row (power of two)
-    const int ltpe = lut_log2_threads_per_row<BITS>(nthreads);
     const int tpe = 1 << ltpe;                                    // threads per row
     const int e = tid >> ltpe, part = tid & (tpe - 1);
     const int per = chunks / tpe > 0 ? chunks / tpe : 1;          // chunks written by this thread
@@ -128,6 +127,7 @@ __device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int lo
     if constexpr (Gm::ENTRY_BYTES == 8) { v.y = seed.v[2] | (seed.v[3] << 16); v.z = v.x; v.w = v.y; }
     else { v.y = v.x; v.z = v.x; v.w = v.x; }
     char* row = lds + (size_t)e * stride;
+#pragma unroll 1
     for (int i = 0; i < per; ++i) {
         const int c = (part * per + i + e) & (chunks - 1);
         *reinterpret_cast<u32x4*>(row + 16 * c) = v;
@@ -136,8 +136,9 @@ __device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int lo
 
 template <int BITS>
 __device__ __forceinline__ void build_lut(char* lds, const uint16_t* __restrict__ T, int log2c, int tid, int nthreads) {
-    const LutSeed s = lut_fetch<BITS>(T, tid, nthreads);
-    lut_build<BITS>(lds, s, log2c, tid, nthreads);
+    const int ltpe = lut_log2_threads_per_row<BITS>(nthreads);
+    const LutSeed s = lut_fetch<BITS>(T, tid, ltpe);
+    lut_build<BITS>(lds, s, log2c, tid, ltpe);
 }
 
 template <int BITS>

@@ -44,6 +44,7 @@ struct MatmulParams {
     int NW, KS, RS;           // waves per workgroup = KS waves per team x RS teams
     uint32_t kt_magic;        // floor(2^32 / KT) and floor(2^32 / KS): division by multiply-high, see div_magic
     uint32_t ks_magic;
+    int lut_ltpe;             // log2 of the threads that build one table row together
     int fast_reduce;          // the partial sums of all non-leading waves fit in the table area
 };
 
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.counters), "s"(p.slots));
     asm volatile("" ::"s"(p.packed_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.KT), "s"(p.NRG), "s"(p.G), "s"(p.TQ),
                  "s"(p.TR), "s"(p.SG), "s"(p.SBL), "s"(p.NW), "s"(p.KS), "s"(p.RS), "s"(p.fast_reduce),
-                 "s"(p.kt_magic), "s"(p.ks_magic));
+                 "s"(p.kt_magic), "s"(p.ks_magic), "s"(p.lut_ltpe));
 
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
@@ -137,13 +138,12 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
     const int kpart = wave - team * p.KS;    // which part of the K range
     const int li = lane & 15;                // row inside a 16-row block (A side) / activation row (B side)
     const int lo = lane >> 4;                // K octet
-    const int nthreads = p.NW * 64;
 
     char* lut = smem;
     float* red = reinterpret_cast<float*>(smem + LUT_BYTES) + team * (NREG * 64);   // this team's slot
     char* sc_lds = smem + LUT_BYTES + red_bytes(NREG, p.RS) + wave * 1024;         // this wave's 64 rows x 16 B
 
-    const LutSeed lut_seed = lut_fetch<BITS>(p.lut, tid, nthreads);   // issued before any weight load (see below)
+    const LutSeed lut_seed = lut_fetch<BITS>(p.lut, tid, p.lut_ltpe);   // issued before any weight load (see below)
     __builtin_amdgcn_sched_barrier(0);
     const LutAddr la = make_lut_addr<BITS>(lut, LOG2C, lane);
     bool lut_ready = false;
@@ -292,7 +292,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             // out of the segment loop to a point before the prefetch)
             LutSeed seed = lut_seed;
             asm volatile("" : "+v"(seed.v[0]), "+v"(seed.v[1]), "+v"(seed.v[2]), "+v"(seed.v[3]));
-            lut_build<BITS>(lut, seed, LOG2C, tid, nthreads);
+            lut_build<BITS>(lut, seed, LOG2C, tid, p.lut_ltpe);
             __syncthreads();
             lut_ready = true;
             __builtin_amdgcn_sched_barrier(0);
@@ -336,6 +336,8 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                 }
                 __syncthreads();
                 if (kpart == 0) {
+                    // (four partial sums per round: their LDS reads are in flight together)
+#pragma unroll 4
                     for (int w = 0; w < p.KS - 1; ++w) {
                         const float* src = area + (size_t)(team * (p.KS - 1) + w) * (NREG * 64) + lane;
 #pragma unroll
@@ -347,6 +349,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                     }
                 }
             } else {
+#pragma unroll 1
                 for (int w = 1; w < p.KS; ++w) {
                     if (kpart == w) {
 #pragma unroll
@@ -411,6 +414,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                     for (int r = 0; r < R; ++r)
 #pragma unroll
                         for (int mb = 0; mb < MB; ++mb) acc[r][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
                     for (int g = g_first; g <= g_last; ++g) {
                         const int gbeg = range_begin(g, tq, tr);
                         const int gw = (div_magic(gbeg, p.kt_magic, p.KT) == sg) ? 0 : 1;   // slot 0 iff sg is g's first super-group
