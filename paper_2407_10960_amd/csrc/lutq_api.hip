@@ -58,7 +58,11 @@ DeviceInfo device_info() {
 
 // bytes of the replicated table in LDS of lutq_dequant (8 copies)
 inline int super_block(int64_t nb) { return nb % 4 == 0 ? 4 : nb % 2 == 0 ? 2 : 1; }
-int lut_bytes(int bits, int log2c) { return (bits == 3 ? 64 * 4 : bits == 4 ? 256 * 4 : 256 * 8) << log2c; }
+// bytes of lutq_dequant's table (log2c copies); entries are 8 bytes for the 2-bit quad table and for the
+// widened bf16 pair tables, else 4
+int lut_bytes(int bits, bool bf16, int log2c) {
+    return ((bits == 3 ? 64 : 256) * ((bits == 2 || bf16) ? 8 : 4)) << log2c;
+}
 
 int ilog2(int v) {
     int l = 0;
@@ -71,8 +75,8 @@ struct Decomp {
     int r, grid, nw, stages, rs;      // the five plan fields, all chosen
 };
 
-bool wide_exists(int bits, int r, int mb, int stages, int xm) {
-    return matmul_instance_exists(bits, r, mb, stages, true, xm, true);
+bool wide_exists(int bits, bool bf16, int r, int mb, int stages, int xm) {
+    return matmul_instance_exists(bits, bf16, r, mb, stages, true, xm, true);
 }
 
 int64_t gcd64(int64_t a, int64_t b) {
@@ -96,7 +100,7 @@ int64_t gcd64(int64_t a, int64_t b) {
 //   * otherwise one workgroup of 8 waves per row group, R the largest of 4, 2, 1 that still gives
 //     every compute unit a row group; only when N is too small even for that is K split across
 //     workgroups, with the fix-up.
-Decomp default_decomp(int bits, int64_t M, int64_t N, int64_t K, int cus, int force_r) {
+Decomp default_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int cus, int force_r) {
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1, xm = M <= 4 ? 4 : 16;
     const int sb = super_block(nb);
@@ -111,7 +115,7 @@ Decomp default_decomp(int bits, int64_t M, int64_t N, int64_t K, int cus, int fo
         while ((int64_t)rs * (ks + 1) <= 16 && tiles_per_team / (ks + 1) >= 2 &&
                (rs * ks < 8 || rs * ks * r * 2 < 24)) ++ks;
         int nw = (int)rs * ks;
-        if (nw > 8 && !wide_exists(bits, r, mb, 2, xm)) {          // too many registers for more than 8 waves
+        if (nw > 8 && !wide_exists(bits, bf16, r, mb, 2, xm)) {          // too many registers for more than 8 waves
             ks = (int)(8 / rs);
             nw = (int)rs * ks;
         }
@@ -128,7 +132,7 @@ Decomp default_decomp(int bits, int64_t M, int64_t N, int64_t K, int cus, int fo
             r = sb;
             while (r > 1 && nb / r < (int64_t)cus * 7 / 10) r >>= 1;
             if (r == 1 && sb >= 2 && kt >= 64) r = 2;     // long K: split it across workgroups instead
-            while (r > 1 && !matmul_instance_exists(bits, r, mb, 2, true, xm, false)) r >>= 1;   // registers
+            while (r > 1 && !matmul_instance_exists(bits, bf16, r, mb, 2, true, xm, false)) r >>= 1;   // registers
         }
         const int64_t groups = nb / r;
         int64_t grid = groups;
@@ -149,10 +153,10 @@ Decomp default_decomp(int bits, int64_t M, int64_t N, int64_t K, int cus, int fo
         int r = force_r ? force_r : sb;
         while (!force_r && r > 1 && per % r != 0) r >>= 1;
         if (!force_r) while (r > 2) r >>= 1;              // R <= 2 keeps two tiles in flight within 128 registers
-        if (!force_r && r == 2 && per <= 16 && !wide_exists(bits, 2, mb, 2, xm) && wide_exists(bits, 1, mb, 2, xm))
+        if (!force_r && r == 2 && per <= 16 && !wide_exists(bits, bf16, 2, mb, 2, xm) && wide_exists(bits, bf16, 1, mb, 2, xm))
             r = 1;                                        // more, narrower teams rather than half the waves
         int64_t rs = per / r;
-        while (rs > 8 && rs % 2 == 0) { rs /= 2; grid *= 2; }
+        while (rs > 16 && rs % 2 == 0) { rs /= 2; grid *= 2; }
         const int nw = rs <= 16 ? waves_for(r, rs, kt) : 0;
         if (nw >= 4 && nw <= 16 && (int64_t)grid * rs <= kMaxGrid) {
             d.r = r; d.grid = grid; d.nw = nw; d.rs = (int)rs;
@@ -227,7 +231,7 @@ extern "C" lutq_status lutq_plan_default(int bits, int group_size, int64_t M, in
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
     DeviceInfo di = device_info();
     if (!di.ok) return LUTQ_ERR_DEVICE;
-    const Decomp d = default_decomp(bits, M, N, K, di.cus, 0);
+    const Decomp d = default_decomp(bits, dtype == LUTQ_BF16, M, N, K, di.cus, 0);
     plan->row_blocks_per_wave = d.r;
     plan->grid = d.grid;
     plan->waves_per_workgroup = d.nw;
@@ -254,6 +258,7 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     if (!di.ok) return LUTQ_ERR_DEVICE;
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1;
+    const bool bf16 = dtype == LUTQ_BF16;
     // M <= 4: four K steps of activations per load, rotated into place (a quarter of the registers)
     const int xm = (M <= 4) ? 4 : 16;
     const bool sch = (K / group_size) % 8 == 0;            // scale rows are 16-byte aligned: chunked scale path
@@ -267,7 +272,7 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
             return LUTQ_ERR_PLAN;
         if (user_plan->grid != 0 && (user_plan->grid < 1 || user_plan->grid > kMaxGrid)) return LUTQ_ERR_PLAN;
     }
-    Decomp d = default_decomp(bits, M, N, K, di.cus, force_r);
+    Decomp d = default_decomp(bits, bf16, M, N, K, di.cus, force_r);
     if (user_plan) {
         // a field the caller fixes replaces the default; teams and waves default to one team of the
         // default number of waves once anything about the workgroup's shape is fixed by the caller
@@ -290,8 +295,8 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     if ((int64_t)d.grid * d.rs > kMaxGrid) return LUTQ_ERR_PLAN;   // partial-sum slots of the workspace
     // more than 8 waves need an instance held to 128 registers; up to 8 waves take one when it
     // exists, so that two workgroups fit a compute unit
-    const bool wide = d.nw > 8 || (d.nw > 4 && sch && wide_exists(bits, r, mb, d.stages, xm));
-    if (!matmul_instance_exists(bits, r, mb, d.stages, sch, xm, wide)) return LUTQ_ERR_PLAN;
+    const bool wide = d.nw > 8 || (d.nw > 4 && sch && wide_exists(bits, bf16, r, mb, d.stages, xm));
+    if (!matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide)) return LUTQ_ERR_PLAN;
     const int lds_bytes = bits == 2 ? matmul_lds_bytes<2>(r, mb, d.nw, d.rs, sch)
                         : bits == 3 ? matmul_lds_bytes<3>(r, mb, d.nw, d.rs, sch)
                                     : matmul_lds_bytes<4>(r, mb, d.nw, d.rs, sch);
@@ -319,7 +324,7 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
                : bits == 3 ? lut_log2_threads_per_row<3>(d.nw * 64) : lut_log2_threads_per_row<4>(d.nw * 64);
     p.kt_magic = p.KT == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KT);
     p.ks_magic = p.KS == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KS);
-    p.fast_reduce = (d.nw - d.rs) * (r * mb * 4) * 256 <= lut_bytes(bits, bits == 2 ? 5 : 6) ? 1 : 0;
+    p.fast_reduce = (d.nw - d.rs) * (r * mb * 4) * 256 <= (bits == 3 ? 64 : 256) * 256 ? 1 : 0;
     if (std::getenv("LUTQ_VERBOSE"))
         std::fprintf(stderr, "lutq_matmul: R=%d grid=%d waves=%d (teams %d x %d) stages=%d wide=%d xm=%d lds=%d\n", r, d.grid,
                      d.nw, d.rs, p.KS, d.stages, (int)wide, xm, lds_bytes);
@@ -362,7 +367,7 @@ extern "C" lutq_status lutq_dequant(const void* packed, const void* scales, cons
     int64_t grid = (p.tiles + 3) / 4;
     const int64_t cap = (int64_t)di.cus * 8;
     if (grid > cap) grid = cap;
-    hipError_t e = pick_dequant(bits, dtype)(group_size, p, (int)grid, lut_bytes(bits, p.log2c) + 2048,
+    hipError_t e = pick_dequant(bits, dtype)(group_size, p, (int)grid, lut_bytes(bits, dtype == LUTQ_BF16, p.log2c) + 2048,
                                              static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
 }

@@ -38,6 +38,17 @@ template <> struct Geo<2> {
     static constexpr int ENTRIES = 256, ENTRY_BYTES = 8, MAX_LOG2_COPIES = 4;   // quad table
 };
 
+// What one table entry holds.  fp16: the two (pair table) or four (quad table) 16-bit values.  bf16 has
+// no packed multiply: the group scale is applied in fp32, so the 4- and 3-bit pair tables hold their
+// two values already widened to fp32 (8 bytes), which saves the two widening instructions per pair;
+// the 2-bit quad table stays four 16-bit values.
+template <int BITS, typename DT> struct Tab {
+    static constexpr bool WIDE = false;
+    static constexpr int ENTRY_BYTES = Geo<BITS>::ENTRY_BYTES;
+};
+template <> struct Tab<4, BF16> { static constexpr bool WIDE = true; static constexpr int ENTRY_BYTES = 8; };
+template <> struct Tab<3, BF16> { static constexpr bool WIDE = true; static constexpr int ENTRY_BYTES = 8; };
+
 // Packed words of one tile as held by one lane.
 template <int BITS> struct WFrag { u32x4 w; };
 template <> struct WFrag<3> { u32x4 w; u32x2 hi; };
@@ -112,10 +123,10 @@ __device__ __forceinline__ LutSeed lut_fetch(const uint16_t* __restrict__ T, int
     return s;
 }
 
-template <int BITS>
+template <int BITS, typename DT>
 __device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int log2c, int tid, int ltpe) {
     using Gm = Geo<BITS>;
-    constexpr int ESH = Gm::ENTRY_BYTES == 8 ? 3 : 2;
+    constexpr int ESH = Tab<BITS, DT>::ENTRY_BYTES == 8 ? 3 : 2;
     const int stride = 1 << (log2c + ESH);                        // bytes of one row
     const int chunks = stride >> 4;                               // 16-byte chunks of one row (power of two)
     const int tpe = 1 << ltpe;                                    // threads per row
@@ -123,9 +134,13 @@ __device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int lo
     const int per = chunks / tpe > 0 ? chunks / tpe : 1;          // chunks written by this thread
     if (e >= Gm::ENTRIES || part * per >= chunks) return;
     u32x4 v;
-    v.x = seed.v[0] | (seed.v[1] << 16);
-    if constexpr (Gm::ENTRY_BYTES == 8) { v.y = seed.v[2] | (seed.v[3] << 16); v.z = v.x; v.w = v.y; }
-    else { v.y = v.x; v.z = v.x; v.w = v.x; }
+    if constexpr (Tab<BITS, DT>::WIDE) {          // {T[q0], T[q1]} as fp32
+        v.x = seed.v[0] << 16; v.y = seed.v[1] << 16; v.z = v.x; v.w = v.y;
+    } else {
+        v.x = seed.v[0] | (seed.v[1] << 16);
+        if constexpr (Gm::ENTRY_BYTES == 8) { v.y = seed.v[2] | (seed.v[3] << 16); v.z = v.x; v.w = v.y; }
+        else { v.y = v.x; v.z = v.x; v.w = v.x; }
+    }
     char* row = lds + (size_t)e * stride;
 #pragma unroll 1
     for (int i = 0; i < per; ++i) {
@@ -134,26 +149,25 @@ __device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int lo
     }
 }
 
-template <int BITS>
+template <int BITS, typename DT>
 __device__ __forceinline__ void build_lut(char* lds, const uint16_t* __restrict__ T, int log2c, int tid, int nthreads) {
     const int ltpe = lut_log2_threads_per_row<BITS>(nthreads);
     const LutSeed s = lut_fetch<BITS>(T, tid, ltpe);
-    lut_build<BITS>(lds, s, log2c, tid, ltpe);
+    lut_build<BITS, DT>(lds, s, log2c, tid, ltpe);
 }
 
-template <int BITS>
+template <int BITS, typename DT>
 __host__ __device__ constexpr int lut_lds_bytes(int log2c) {
-    return (Geo<BITS>::ENTRIES * Geo<BITS>::ENTRY_BYTES) << log2c;
-}
-template <int BITS>
-__host__ __device__ constexpr int lut_stage_bytes() {
-    return Geo<BITS>::ENTRIES * Geo<BITS>::ENTRY_BYTES;
+    return (Geo<BITS>::ENTRIES * Tab<BITS, DT>::ENTRY_BYTES) << log2c;
 }
 // log2 of the number of copies that makes the entry stride 256 bytes
-template <int BITS>
+template <int BITS, typename DT>
 __host__ __device__ constexpr int perm_log2_copies() {
-    return Geo<BITS>::ENTRY_BYTES == 8 ? 5 : 6;
+    return Tab<BITS, DT>::ENTRY_BYTES == 8 ? 5 : 6;
 }
+// bytes of the fused kernel's table: every entry is one 256-byte row, whatever it holds
+template <int BITS>
+__host__ __device__ constexpr int lut_row_table_bytes() { return Geo<BITS>::ENTRIES * 256; }
 
 typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
 typedef __attribute__((address_space(3))) const u32x2 lds_cu64;
@@ -165,12 +179,12 @@ struct LutAddr {
     int sh;
     uint32_t lane_base;
 };
-template <int BITS>
+template <int BITS, typename DT>
 __device__ __forceinline__ LutAddr make_lut_addr(const char* lut_lds, int log2c, int lane) {
     LutAddr a;
-    a.sh = log2c + (Geo<BITS>::ENTRY_BYTES == 8 ? 3 : 2);
+    a.sh = log2c + (Tab<BITS, DT>::ENTRY_BYTES == 8 ? 3 : 2);
     const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lut_lds;
-    a.lane_base = base + (uint32_t)(lane & ((1 << log2c) - 1)) * Geo<BITS>::ENTRY_BYTES;
+    a.lane_base = base + (uint32_t)(lane & ((1 << log2c) - 1)) * Tab<BITS, DT>::ENTRY_BYTES;
     return a;
 }
 
@@ -228,15 +242,17 @@ __device__ __forceinline__ uint32_t scale_pair(uint32_t pair, ScaleReg<BF16> s) 
 // They are separate so that the caller can issue the LDS reads of the next step before it consumes
 // the current one.
 // ---------------------------------------------------------------------------------------
-template <int BITS, bool PERM>
-__device__ __forceinline__ u32x4 lookup_step(const WFrag<BITS>& f, int step, LutAddr la) {
-    u32x4 a;
+// Unscaled table values of one step: four registers (16-bit pairs in A-operand order), or, for the
+// widened bf16 tables, eight fp32 values.
+template <int BITS, typename DT> struct Raw { u32x4 v; };
+template <> struct Raw<4, BF16> { u32x4 even, odd; };    // values 2p (even) and 2p + 1 (odd), p = 0..3
+template <> struct Raw<3, BF16> { u32x4 even, odd; };
+
+// The four table addresses of a step come from the four bytes of one 32-bit word of indices.
+template <int BITS>
+__device__ __forceinline__ uint32_t index_word(const WFrag<BITS>& f, int step) {
     if constexpr (BITS == 4) {
-        const uint32_t w = f.w[step];
-        a.x = lds_u32(entry_addr<PERM, 0>(w, la));
-        a.y = lds_u32(entry_addr<PERM, 1>(w, la));
-        a.z = lds_u32(entry_addr<PERM, 2>(w, la));
-        a.w = lds_u32(entry_addr<PERM, 3>(w, la));
+        return f.w[step];
     } else if constexpr (BITS == 3) {
         // combine the two bit-slices: bits 0..3 of each byte from the low slice, bits 4..5 from the
         // high slice, bits 6..7 cleared: four 6-bit pair-table indices, one per byte.
@@ -244,27 +260,56 @@ __device__ __forceinline__ u32x4 lookup_step(const WFrag<BITS>& f, int step, Lut
         const int u = step & 3;
         const uint32_t h = f.hi[step >> 2];
         const uint32_t hs = (u == 0) ? (h << 4) : (u == 1) ? (h << 2) : (u == 2) ? h : (h >> 2);
-        const uint32_t c = (hs & 0x30303030u) | (lo & 0x0f0f0f0fu);
-        a.x = lds_u32(entry_addr<PERM, 0>(c, la));
-        a.y = lds_u32(entry_addr<PERM, 1>(c, la));
-        a.z = lds_u32(entry_addr<PERM, 2>(c, la));
-        a.w = lds_u32(entry_addr<PERM, 3>(c, la));
+        return (hs & 0x30303030u) | (lo & 0x0f0f0f0fu);
     } else {
-        const uint32_t w = f.w[step >> 1];
+        return f.w[step >> 1];             // two steps per word: bytes 0,1 and 2,3
+    }
+}
+
+template <int BITS, typename DT, bool PERM>
+__device__ __forceinline__ Raw<BITS, DT> lookup_step(const WFrag<BITS>& f, int step, LutAddr la) {
+    Raw<BITS, DT> a;
+    const uint32_t w = index_word<BITS>(f, step);
+    if constexpr (Tab<BITS, DT>::WIDE) {
+        const u32x2 p0 = lds_u64(entry_addr<PERM, 0>(w, la));
+        const u32x2 p1 = lds_u64(entry_addr<PERM, 1>(w, la));
+        const u32x2 p2 = lds_u64(entry_addr<PERM, 2>(w, la));
+        const u32x2 p3 = lds_u64(entry_addr<PERM, 3>(w, la));
+        a.even = u32x4{p0.x, p1.x, p2.x, p3.x};
+        a.odd = u32x4{p0.y, p1.y, p2.y, p3.y};
+    } else if constexpr (BITS == 2) {
         const u32x2 q0 = (step & 1) ? lds_u64(entry_addr<PERM, 2>(w, la)) : lds_u64(entry_addr<PERM, 0>(w, la));
         const u32x2 q1 = (step & 1) ? lds_u64(entry_addr<PERM, 3>(w, la)) : lds_u64(entry_addr<PERM, 1>(w, la));
-        a.x = q0.x; a.y = q0.y; a.z = q1.x; a.w = q1.y;
+        a.v.x = q0.x; a.v.y = q0.y; a.v.z = q1.x; a.v.w = q1.y;
+    } else {
+        a.v.x = lds_u32(entry_addr<PERM, 0>(w, la));
+        a.v.y = lds_u32(entry_addr<PERM, 1>(w, la));
+        a.v.z = lds_u32(entry_addr<PERM, 2>(w, la));
+        a.v.w = lds_u32(entry_addr<PERM, 3>(w, la));
     }
     return a;
 }
 
-template <typename DT>
-__device__ __forceinline__ u32x4 scale4(u32x4 raw, ScaleReg<DT> sc) {
+// Group scale applied to the eight values of a step; result in A-operand order.  Each product is
+// rounded once to the 16-bit type (fp16: packed half multiply; bf16: exact fp32 product, one conversion).
+template <int BITS, typename DT>
+__device__ __forceinline__ u32x4 scale4(const Raw<BITS, DT>& raw, ScaleReg<DT> sc) {
     u32x4 a;
-    a.x = scale_pair(raw.x, sc);
-    a.y = scale_pair(raw.y, sc);
-    a.z = scale_pair(raw.z, sc);
-    a.w = scale_pair(raw.w, sc);
+    if constexpr (Tab<BITS, DT>::WIDE) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t e = raw.even[j], o = raw.odd[j];
+            f32x2 v;
+            v.x = __builtin_bit_cast(float, e) * sc.s;
+            v.y = __builtin_bit_cast(float, o) * sc.s;
+            a[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+        }
+    } else {
+        a.x = scale_pair(raw.v.x, sc);
+        a.y = scale_pair(raw.v.y, sc);
+        a.z = scale_pair(raw.v.z, sc);
+        a.w = scale_pair(raw.v.w, sc);
+    }
     return a;
 }
 

@@ -16,7 +16,7 @@ namespace {
 
 template <int GROUP, int MB, int R, int P, bool SCH, int XM, bool WIDE>
 hipError_t launch_one(const MatmulParams& p, hipStream_t stream) {
-    if constexpr (WIDE && !matmul_wide_fits<LUTQ_INST_BITS>(R, MB, P, XM)) {
+    if constexpr (WIDE && !matmul_wide_fits<LUTQ_INST_BITS>(R, MB, P, XM, Tab<LUTQ_INST_BITS, LUTQ_INST_DT>::WIDE)) {
         return hipErrorInvalidValue;         // would not fit 128 registers: not instantiated
     } else {
         auto kernel = matmul_kernel<LUTQ_INST_BITS, GROUP, MB, R, LUTQ_INST_DT, P, SCH, XM, WIDE>;

@@ -73,21 +73,21 @@ __device__ __forceinline__ int owner_of(int t, int tq, int tr) {
 __host__ __device__ constexpr int red_bytes(int nreg, int rs) { return nreg * 256 * rs; }
 template <int BITS>
 __host__ __device__ constexpr int matmul_lds_bytes(int r, int mb, int nw, int rs, bool sch) {
-    return lut_lds_bytes<BITS>(perm_log2_copies<BITS>()) + red_bytes(r * mb * 4, rs) + (sch ? nw * 1024 : 0);
+    return lut_row_table_bytes<BITS>() + red_bytes(r * mb * 4, rs) + (sch ? nw * 1024 : 0);
 }
 
 // Rough count of the registers live in the K loop (tiles in flight, accumulators, lookup ring,
 // addresses): decides which instances can be held to 128 registers, i.e. four waves per SIMD.
 template <int BITS>
-__host__ __device__ constexpr int matmul_reg_estimate(int r, int mb, int p, int xm) {
+__host__ __device__ constexpr int matmul_reg_estimate(int r, int mb, int p, int xm, bool wide_table) {
     const int wregs = BITS == 3 ? 6 : 4;
     const int xl = Geo<BITS>::STEPS * xm / 16;
     const int na = xm == 16 ? mb : 16 / xm;               // accumulators per row block
-    return p * (r * wregs + xl * mb * 4 + 4) + r * na * 4 + 46;
+    return p * (r * wregs + xl * mb * 4 + 4) + r * na * 4 + 46 + (wide_table ? 12 : 0);   // lookup ring of pairs
 }
 template <int BITS>
-__host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm) {
-    return matmul_reg_estimate<BITS>(r, mb, p, xm) <= 124;
+__host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm, bool wide_table) {
+    return matmul_reg_estimate<BITS>(r, mb, p, xm, wide_table) <= 124;
 }
 
 // Template parameters: bit width, group size, MB = 16-row halves of M (1: M <= 16, 2: M <= 32),
@@ -115,8 +115,9 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
     constexpr int SPG = GROUP / 32;          // steps per group
     constexpr int NREG = R * MB * 4;         // accumulator registers per lane
     constexpr int TPC = 8 / NS;              // tiles covered by one 16-byte scale chunk
-    constexpr int LOG2C = perm_log2_copies<BITS>();
-    constexpr int LUT_BYTES = lut_lds_bytes<BITS>(LOG2C);
+    constexpr int LOG2C = perm_log2_copies<BITS, DT>();
+    constexpr int LUT_BYTES = lut_lds_bytes<BITS, DT>(LOG2C);
+    static_assert(LUT_BYTES == lut_row_table_bytes<BITS>(), "one 256-byte row per entry");
     constexpr int U = STEPS * R;             // (step, row block) items of one tile
     constexpr int D = U < 4 ? U : 4;         // table reads kept in flight ahead of their use
     constexpr int XS = 16 / XM;              // K steps covered by one activation load
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
 
     const LutSeed lut_seed = lut_fetch<BITS>(p.lut, tid, p.lut_ltpe);   // issued before any weight load (see below)
     __builtin_amdgcn_sched_barrier(0);
-    const LutAddr la = make_lut_addr<BITS>(lut, LOG2C, lane);
+    const LutAddr la = make_lut_addr<BITS, DT>(lut, LOG2C, lane);
     bool lut_ready = false;
 
     const rsrc_t rW = make_rsrc(p.packed, p.packed_bytes);
@@ -244,9 +245,9 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             // before item u is scaled and multiplied
             // (scheduling barriers pin this order: left alone, the compiler sinks part of an item's
             // table reads to just before their use and every item then waits out the LDS latency)
-            u32x4 raw[D];
+            Raw<BITS, DT> raw[D];
 #pragma unroll
-            for (int u = 0; u < D; ++u) raw[u] = lookup_step<BITS, true>(st.w[u % R], u / R, la);
+            for (int u = 0; u < D; ++u) raw[u] = lookup_step<BITS, DT, true>(st.w[u % R], u / R, la);
             __builtin_amdgcn_sched_barrier(0);
             // the matrix instruction of item u is issued after the scaling of item u + 1, so that it
             // never has to wait for operands that were written by the instructions just before it
@@ -256,10 +257,10 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                 if (u < U) {
                     const int s = u / R, r = u % R;
                     const ScaleReg<DT> sc = scale_of<DT, NS>(sw[r], s / SPG);
-                    a[u & 1] = scale4<DT>(raw[u % D], sc);
+                    a[u & 1] = scale4<BITS, DT>(raw[u % D], sc);
                     __builtin_amdgcn_sched_barrier(0);
                     if (u + D < U) {
-                        raw[u % D] = lookup_step<BITS, true>(st.w[(u + D) % R], (u + D) / R, la);
+                        raw[u % D] = lookup_step<BITS, DT, true>(st.w[(u + D) % R], (u + D) / R, la);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -292,7 +293,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             // out of the segment loop to a point before the prefetch)
             LutSeed seed = lut_seed;
             asm volatile("" : "+v"(seed.v[0]), "+v"(seed.v[1]), "+v"(seed.v[2]), "+v"(seed.v[3]));
-            lut_build<BITS>(lut, seed, LOG2C, tid, p.lut_ltpe);
+            lut_build<BITS, DT>(lut, seed, LOG2C, tid, p.lut_ltpe);
             __syncthreads();
             lut_ready = true;
             __builtin_amdgcn_sched_barrier(0);
@@ -474,8 +475,8 @@ __global__ __launch_bounds__(256) void dequant_kernel(const DequantParams p) {
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    build_lut<BITS>(smem, p.lut, p.log2c, tid, 256);
-    const LutAddr la = make_lut_addr<BITS>(smem, p.log2c, lane);
+    build_lut<BITS, DT>(smem, p.lut, p.log2c, tid, 256);
+    const LutAddr la = make_lut_addr<BITS, DT>(smem, p.log2c, lane);
     __syncthreads();
     const int li = lane & 15, lo = lane >> 4;
     const rsrc_t rW = make_rsrc(p.packed, p.packed_bytes);
@@ -495,7 +496,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const DequantParams p) {
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
             const ScaleReg<DT> sc = scale_of<DT, NS>(sw, s / SPG);
-            const u32x4 a = scale4<DT>(lookup_step<BITS, false>(f, s, la), sc);
+            const u32x4 a = scale4<BITS, DT>(lookup_step<BITS, DT, false>(f, s, la), sc);
             *reinterpret_cast<u32x4*>(out + 32 * s) = a;
         }
     }
