@@ -153,6 +153,38 @@ def test_result_independent_of_work_decomposition(lutq, bits, dtype):
         assert spread <= TOL[dtype]
 
 
+def test_default_plan_over_seeded_random_shapes(lutq):
+    """The library's own work decomposition over shapes it was not tuned for: odd and prime numbers of
+    row blocks (every branch of the default plan: balanced teams, fractions of a compute unit's share,
+    too few row groups), short and long K, every M class, all bit widths and both dtypes.  Each default
+    plan must be accepted, reproducible, and match the oracle."""
+    rng = np.random.default_rng(2024)
+    nbs = [1, 2, 3, 5, 7, 12, 13, 31, 64, 96, 127, 128, 129, 192, 255, 256, 257, 320, 384, 512, 513, 640, 768, 1024]
+    workspace = None
+    for i in range(48):
+        bits = int(rng.choice([2, 3, 4]))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        group = int(rng.choice([32, 64, 128]))
+        M = int(rng.choice([1, 2, 3, 4, 5, 8, 15, 16, 17, 24, 32]))
+        nb = int(rng.choice(nbs))
+        kt = int(rng.choice([1, 2, 3, 4, 7, 8, 16, 33]))
+        if nb * kt > 4096:                      # keep the oracle's share of the test in seconds
+            kt = max(1, 4096 // nb)
+        N, K = 16 * nb, tk(bits) * kt
+        c = gen.make_case(1000 + i, M, N, K, bits, group, dtype, "random_index")
+        d = DeviceCase(lutq, c)
+        if workspace is None:
+            workspace = d.ws
+        d.ws = workspace
+        plan = lutq.lutq_plan_default(bits, group, M, N, K, 0 if dtype == "f16" else 1)
+        what = f"case {i}: b{bits} {dtype} g{group} M{M} N{N} K{K} {plan}"
+        Y1 = to_bits(d.matmul(lutq))
+        Y2 = to_bits(d.matmul(lutq, plan=plan))
+        assert np.array_equal(Y1, Y2), what
+        check_y(Y1, c, what)
+    assert not workspace[:65536].any().item()
+
+
 def test_workspace_reuse_across_different_problems(lutq):
     """One workspace serves calls with different data, shapes and split plans back to back: stale
     partial sums of an earlier call must never leak into a later result."""
