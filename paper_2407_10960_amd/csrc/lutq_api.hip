@@ -75,6 +75,10 @@ struct Decomp {
     int r, grid, nw, stages, rs;      // the five plan fields, all chosen
 };
 
+inline int steps_per_tile(int bits) { return bits == 4 ? 4 : 8; }
+// Activations can be shared through LDS when the teams are enough to stage a tile's pieces between them.
+inline bool teams_can_share_x(int bits, int mb, int rs) { return rs * kXPiecesPerWave >= steps_per_tile(bits) * mb; }
+
 bool wide_exists(int bits, bool bf16, int r, int mb, int stages, int xm) {
     return matmul_instance_exists(bits, bf16, r, mb, stages, true, xm, true);
 }
@@ -100,7 +104,7 @@ int64_t gcd64(int64_t a, int64_t b) {
 //   * otherwise one workgroup of 8 waves per row group, R the largest of 4, 2, 1 that still gives
 //     every compute unit a row group; only when N is too small even for that is K split across
 //     workgroups, with the fix-up.
-Decomp default_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int cus, int force_r) {
+Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K, int cus, int force_r) {
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1, xm = M <= 4 ? 4 : 16;
     const int sb = super_block(nb);
@@ -122,6 +126,30 @@ Decomp default_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int 
         while (nw < 4 && ks > 0) { ++ks; nw = (int)rs * ks; }     // the table build needs four waves
         return nw;
     };
+    if (M > 4 && sch && !force_r && qn == 1 && pn <= 32) {
+        // More than four activation rows, row blocks that divide evenly over the compute units:
+        // one workgroup per compute unit with its row blocks as teams that share the activations
+        // through LDS (needs enough teams to stage a tile between them, and chunked scales)
+        // (R = 2 only: with one row block per wave the operand reads from LDS are as many bytes as with
+        // per-team loads and the plan below, which favours a large R, is faster)
+        // (a 2- or 3-bit tile with M > 16 is sixteen operand fragments per team: there sharing pays
+        // even at R = 1)
+        for (int r = 2; r >= ((mb == 2 && bits != 4) ? 1 : 2); --r) {
+            if (pn % r != 0 || sb % r != 0) continue;
+            const int64_t rs = pn / r;
+            if (rs > 16 || !teams_can_share_x(bits, mb, (int)rs)) continue;
+            int ks = 1;
+            while (rs * (ks + 1) <= 16 && kt / (ks + 1) >= 4 && rs * ks < 12) ++ks;
+            int nw = (int)rs * ks;
+            if (nw > 8 && !matmul_instance_exists(bits, bf16, r, mb, 2, true, 16, true, true)) {
+                ks = (int)(8 / rs);
+                nw = (int)rs * ks;
+            }
+            if (ks < 1 || nw < 4 || !matmul_instance_exists(bits, bf16, r, mb, 2, true, 16, nw > 8, true)) continue;
+            d.r = r; d.grid = cus; d.nw = nw; d.rs = (int)rs;
+            return d;
+        }
+    }
     if (M > 4) {
         // More than four activation rows use the plain activation layout: every row group reads
         // M x K activations (through L2/L1) next to its 8 R K bytes of weights, so what matters
@@ -186,7 +214,7 @@ Decomp default_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int 
     return d;
 }
 
-typedef hipError_t (*matmul_launcher)(int, int, int, int, bool, int, bool, const MatmulParams&, hipStream_t);
+typedef hipError_t (*matmul_launcher)(int, int, int, int, bool, int, bool, bool, const MatmulParams&, hipStream_t);
 typedef hipError_t (*dequant_launcher)(int, const DequantParams&, int, int, hipStream_t);
 
 matmul_launcher pick_matmul(int bits, lutq_dtype dt) {
@@ -231,7 +259,7 @@ extern "C" lutq_status lutq_plan_default(int bits, int group_size, int64_t M, in
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
     DeviceInfo di = device_info();
     if (!di.ok) return LUTQ_ERR_DEVICE;
-    const Decomp d = default_decomp(bits, dtype == LUTQ_BF16, M, N, K, di.cus, 0);
+    const Decomp d = default_decomp(bits, dtype == LUTQ_BF16, (K / group_size) % 8 == 0, M, N, K, di.cus, 0);
     plan->row_blocks_per_wave = d.r;
     plan->grid = d.grid;
     plan->waves_per_workgroup = d.nw;
@@ -272,7 +300,7 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
             return LUTQ_ERR_PLAN;
         if (user_plan->grid != 0 && (user_plan->grid < 1 || user_plan->grid > kMaxGrid)) return LUTQ_ERR_PLAN;
     }
-    Decomp d = default_decomp(bits, bf16, M, N, K, di.cus, force_r);
+    Decomp d = default_decomp(bits, bf16, sch, M, N, K, di.cus, force_r);
     if (user_plan) {
         // a field the caller fixes replaces the default; teams and waves default to one team of the
         // default number of waves once anything about the workgroup's shape is fixed by the caller
@@ -295,11 +323,26 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     if ((int64_t)d.grid * d.rs > kMaxGrid) return LUTQ_ERR_PLAN;   // partial-sum slots of the workspace
     // more than 8 waves need an instance held to 128 registers; up to 8 waves take one when it
     // exists, so that two workgroups fit a compute unit
-    const bool wide = d.nw > 8 || (d.nw > 4 && sch && wide_exists(bits, bf16, r, mb, d.stages, xm));
-    if (!matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide)) return LUTQ_ERR_PLAN;
-    const int lds_bytes = bits == 2 ? matmul_lds_bytes<2>(r, mb, d.nw, d.rs, sch)
-                        : bits == 3 ? matmul_lds_bytes<3>(r, mb, d.nw, d.rs, sch)
-                                    : matmul_lds_bytes<4>(r, mb, d.nw, d.rs, sch);
+    // M > 4 with enough teams: the activations are staged in LDS once per workgroup instead of being
+    // fetched by every team (LUTQ_NO_SHARED_X=1 switches that off, for comparisons)
+    bool xsh = M > 4 && sch && d.stages == 2 && teams_can_share_x(bits, mb, d.rs) && !std::getenv("LUTQ_NO_SHARED_X");
+    bool wide = d.nw > 8 || (d.nw > 4 && sch && matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, true, xsh));
+    if (xsh && !matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, true)) {
+        xsh = false;
+        wide = d.nw > 8 || (d.nw > 4 && sch && wide_exists(bits, bf16, r, mb, d.stages, xm));
+    }
+    if (!matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, xsh)) return LUTQ_ERR_PLAN;
+    int lds_bytes = bits == 2 ? matmul_lds_bytes<2>(r, mb, d.nw, d.rs, sch, xsh)
+                  : bits == 3 ? matmul_lds_bytes<3>(r, mb, d.nw, d.rs, sch, xsh)
+                              : matmul_lds_bytes<4>(r, mb, d.nw, d.rs, sch, xsh);
+    if (xsh && lds_bytes > 160 * 1024) {                  // the buffers do not fit: fetch per team
+        xsh = false;
+        wide = d.nw > 8 || (d.nw > 4 && sch && wide_exists(bits, bf16, r, mb, d.stages, xm));
+        if (!matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, false)) return LUTQ_ERR_PLAN;
+        lds_bytes = bits == 2 ? matmul_lds_bytes<2>(r, mb, d.nw, d.rs, sch, false)
+                  : bits == 3 ? matmul_lds_bytes<3>(r, mb, d.nw, d.rs, sch, false)
+                              : matmul_lds_bytes<4>(r, mb, d.nw, d.rs, sch, false);
+    }
     if (lds_bytes > 160 * 1024) return LUTQ_ERR_PLAN;
 
     MatmulParams p;
@@ -320,15 +363,17 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     p.SG = (int)(K / group_size);
     p.SBL = ilog2(super_block(nb));
     p.NW = d.nw; p.RS = d.rs; p.KS = d.nw / d.rs;
+    p.xbuf_off = bits == 2 ? matmul_xbuf_offset<2>(r, mb, d.nw, d.rs, sch)
+               : bits == 3 ? matmul_xbuf_offset<3>(r, mb, d.nw, d.rs, sch) : matmul_xbuf_offset<4>(r, mb, d.nw, d.rs, sch);
     p.lut_ltpe = bits == 2 ? lut_log2_threads_per_row<2>(d.nw * 64)
                : bits == 3 ? lut_log2_threads_per_row<3>(d.nw * 64) : lut_log2_threads_per_row<4>(d.nw * 64);
     p.kt_magic = p.KT == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KT);
     p.ks_magic = p.KS == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KS);
     p.fast_reduce = (d.nw - d.rs) * (r * mb * 4) * 256 <= (bits == 3 ? 64 : 256) * 256 ? 1 : 0;
     if (std::getenv("LUTQ_VERBOSE"))
-        std::fprintf(stderr, "lutq_matmul: R=%d grid=%d waves=%d (teams %d x %d) stages=%d wide=%d xm=%d lds=%d\n", r, d.grid,
-                     d.nw, d.rs, p.KS, d.stages, (int)wide, xm, lds_bytes);
-    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, d.stages, sch, xm, wide, p, static_cast<hipStream_t>(stream));
+        std::fprintf(stderr, "lutq_matmul: R=%d grid=%d waves=%d (teams %d x %d) stages=%d wide=%d xm=%d shared_x=%d lds=%d\n", r, d.grid,
+                     d.nw, d.rs, p.KS, d.stages, (int)wide, xm, (int)xsh, lds_bytes);
+    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, d.stages, sch, xm, wide, xsh, p, static_cast<hipStream_t>(stream));
     if (e != hipSuccess && std::getenv("LUTQ_VERBOSE"))
         std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d)\n", hipGetErrorString(e), p.G, d.nw * 64);
     return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;

@@ -11,22 +11,25 @@ namespace lutq {
 // Kernel instances that exist.  `wide` instances run up to 16 waves per workgroup within 128
 // registers and exist only where the register estimate fits; the others run up to 8 waves.  The
 // per-tile scale path (K/group not a multiple of 8) exists for 2 tiles in flight, not wide.
-inline bool matmul_instance_exists(int bits, bool bf16, int r, int mb, int stages, bool sch, int xm, bool wide) {
+inline bool matmul_instance_exists(int bits, bool bf16, int r, int mb, int stages, bool sch, int xm, bool wide,
+                                   bool xsh = false) {
     const bool wt = bf16 && bits != 2;                  // widened table: a larger lookup ring
+    if (xsh && (xm != 16 || !sch || stages != 2)) return false;
     if (stages != 2 && stages != 4) return false;
     if (!sch) return stages == 2 && !wide;
     if (!wide) {                                        // up to 256 registers; beyond that the K loop would spill
-        const int est = bits == 2 ? matmul_reg_estimate<2>(r, mb, stages, xm, wt)
-                      : bits == 3 ? matmul_reg_estimate<3>(r, mb, stages, xm, wt) : matmul_reg_estimate<4>(r, mb, stages, xm, wt);
+        const int est = bits == 2 ? matmul_reg_estimate<2>(r, mb, stages, xm, wt, xsh)
+                      : bits == 3 ? matmul_reg_estimate<3>(r, mb, stages, xm, wt, xsh) : matmul_reg_estimate<4>(r, mb, stages, xm, wt, xsh);
         return est <= 250;
     }
-    return bits == 2 ? matmul_wide_fits<2>(r, mb, stages, xm, wt)
-         : bits == 3 ? matmul_wide_fits<3>(r, mb, stages, xm, wt) : matmul_wide_fits<4>(r, mb, stages, xm, wt);
+    return bits == 2 ? matmul_wide_fits<2>(r, mb, stages, xm, wt, xsh)
+         : bits == 3 ? matmul_wide_fits<3>(r, mb, stages, xm, wt, xsh) : matmul_wide_fits<4>(r, mb, stages, xm, wt, xsh);
 }
 
 #define LUTQ_DECLARE_LAUNCHERS(B, DT)                                                               \
     hipError_t launch_matmul_b##B##_##DT(int group, int mb, int r, int stages, bool sch, int xm,     \
-                                         bool wide, const MatmulParams& p, hipStream_t stream);      \
+                                         bool wide, bool xsh, const MatmulParams& p,                 \
+                                         hipStream_t stream);                                        \
     hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes, \
                                           hipStream_t stream);
 

@@ -45,6 +45,7 @@ struct MatmulParams {
     uint32_t kt_magic;        // floor(2^32 / KT) and floor(2^32 / KS): division by multiply-high, see div_magic
     uint32_t ks_magic;
     int lut_ltpe;             // log2 of the threads that build one table row together
+    int xbuf_off;             // LDS byte offset of the shared activation buffers (XSH instances)
     int fast_reduce;          // the partial sums of all non-leading waves fit in the table area
 };
 
@@ -71,23 +72,36 @@ __device__ __forceinline__ int owner_of(int t, int tq, int tr) {
 // LDS bytes of one launch (host and device agree through these functions):
 // [table, 256-byte entry stride][one partial-sum slot per team][one 1 KiB scale-chunk area per wave]
 __host__ __device__ constexpr int red_bytes(int nreg, int rs) { return nreg * 256 * rs; }
+// Activation pieces: one piece is the B operand of one (K step, 16-row half of M) = 64 lanes x 16 bytes.
+constexpr int kXPiecesPerWave = 2;       // pieces of a tile that one wave stages (shared-activation instances)
 template <int BITS>
-__host__ __device__ constexpr int matmul_lds_bytes(int r, int mb, int nw, int rs, bool sch) {
+__host__ __device__ constexpr int x_pieces(int mb) { return Geo<BITS>::STEPS * mb; }
+// offset of the shared activation buffers = end of the other areas
+template <int BITS>
+__host__ __device__ constexpr int matmul_xbuf_offset(int r, int mb, int nw, int rs, bool sch) {
     return lut_row_table_bytes<BITS>() + red_bytes(r * mb * 4, rs) + (sch ? nw * 1024 : 0);
+}
+// [..][shared-activation instances: 2 (double buffer) x KS (K parts) x pieces x 1 KiB]
+template <int BITS>
+__host__ __device__ constexpr int matmul_lds_bytes(int r, int mb, int nw, int rs, bool sch, bool xsh) {
+    return matmul_xbuf_offset<BITS>(r, mb, nw, rs, sch) + (xsh ? 2 * (nw / rs) * x_pieces<BITS>(mb) * 1024 : 0);
 }
 
 // Rough count of the registers live in the K loop (tiles in flight, accumulators, lookup ring,
 // addresses): decides which instances can be held to 128 registers, i.e. four waves per SIMD.
 template <int BITS>
-__host__ __device__ constexpr int matmul_reg_estimate(int r, int mb, int p, int xm, bool wide_table) {
+__host__ __device__ constexpr int matmul_reg_estimate(int r, int mb, int p, int xm, bool wide_table, bool xsh) {
     const int wregs = BITS == 3 ? 6 : 4;
     const int xl = Geo<BITS>::STEPS * xm / 16;
     const int na = xm == 16 ? mb : 16 / xm;               // accumulators per row block
-    return p * (r * wregs + xl * mb * 4 + 4) + r * na * 4 + 46 + (wide_table ? 12 : 0);   // lookup ring of pairs
+    // activations in flight per tile: the wave's own fragments, or its share of the staged pieces
+    // (plus two steps' worth of operands read back from LDS)
+    const int xregs = xsh ? kXPiecesPerWave * 4 : xl * mb * 4;
+    return p * (r * wregs + xregs + 4) + (xsh ? 2 * mb * 4 : 0) + r * na * 4 + 46 + (wide_table ? 12 : 0);
 }
 template <int BITS>
-__host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm, bool wide_table) {
-    return matmul_reg_estimate<BITS>(r, mb, p, xm, wide_table) <= 124;
+__host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm, bool wide_table, bool xsh) {
+    return matmul_reg_estimate<BITS>(r, mb, p, xm, wide_table, xsh) <= 124;
 }
 
 // Template parameters: bit width, group size, MB = 16-row halves of M (1: M <= 16, 2: M <= 32),
@@ -105,10 +119,18 @@ __host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm
 // WIDE: the instance is compiled for up to 16 waves per workgroup and therefore at most 128
 // registers (four waves per SIMD, or two 8-wave workgroups with their two 64 KiB tables in the
 // 160 KiB of LDS); otherwise for up to 8 waves and as many registers as it likes.
+// XSH (plain layout, M > 4): the activations go through LDS and are shared by the teams.  All teams
+// of a workgroup walk the same K tiles, so without sharing each of them fetches the same M x TK
+// activations per tile, which for M = 16..32 is one to two times the weight bytes through the
+// 64 B/clk vector memory path.  With XSH the waves that work on the same K part (one per team) split
+// the tile's pieces between them (at most two each), store them in LDS in operand order one tile
+// ahead, double buffered, and every wave reads its B operands from there; one workgroup barrier per
+// tile keeps writers and readers apart, and every wave runs the same number of rounds.
 // The number of waves and their arrangement in teams are run-time values.
-template <int BITS, int GROUP, int MB, int R, typename DT, int P, bool SCH, int XM, bool WIDE>
+template <int BITS, int GROUP, int MB, int R, typename DT, int P, bool SCH, int XM, bool WIDE, bool XSH>
 __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulParams p) {
     static_assert(XM == 16 || (XM == 4 && MB == 1), "packed activation loads exist for M <= 4 only");
+    static_assert(!XSH || XM == 16, "activations are shared through LDS in the plain layout only");
     using Gm = Geo<BITS>;
     constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
     constexpr int NS = TK / GROUP;           // scales per tile per row
@@ -123,13 +145,17 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
     constexpr int XS = 16 / XM;              // K steps covered by one activation load
     constexpr int XL = STEPS / XS;           // activation loads per tile (per 16-row half of M)
     constexpr int NA = XM == 16 ? MB : XS;   // accumulators per row block: M halves, or step positions
+    constexpr int NP = STEPS * MB;           // activation pieces (K step, M half) of one tile, 1 KiB each
+    constexpr int XPW = kXPiecesPerWave;     // pieces one wave stages (RS * XPW >= NP is checked on the host)
+    constexpr int NX = XSH ? XPW : XL;       // activation loads per tile held in a stage
+    constexpr int NXM = XSH ? 1 : MB;
 
     // Every scalar of the parameter block is used in the entry block, so that the argument segment
     // is fetched with one round trip instead of one per basic block that first needs a field.
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.counters), "s"(p.slots));
     asm volatile("" ::"s"(p.packed_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.KT), "s"(p.NRG), "s"(p.G), "s"(p.TQ),
                  "s"(p.TR), "s"(p.SG), "s"(p.SBL), "s"(p.NW), "s"(p.KS), "s"(p.RS), "s"(p.fast_reduce),
-                 "s"(p.kt_magic), "s"(p.ks_magic), "s"(p.lut_ltpe));
+                 "s"(p.kt_magic), "s"(p.ks_magic), "s"(p.lut_ltpe), "s"(p.xbuf_off));
 
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
@@ -165,6 +191,21 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
         xlane[mb] = ((uint32_t)(XM == 16 ? m : li % XM) * (uint32_t)p.K + 32u * (uint32_t)(XM == 16 ? 0 : li / XM)
                      + 8u * lo) * 2u;
     }
+    // shared activations: the pieces this wave stages (team, team + RS, ...), where they come from
+    // and where they go in a buffer; the buffer of K part `kpart` and parity b starts at
+    // xbuf + (b * KS + kpart) * NP KiB
+    char* xbuf = smem + p.xbuf_off;
+    bool xp_ok[XPW];
+    uint32_t xp_src[XPW], xp_dst[XPW];
+#pragma unroll
+    for (int i = 0; i < XPW; ++i) {
+        const int pi = team + p.RS * i;                       // piece = step * MB + M half
+        xp_ok[i] = XSH && pi < NP;
+        const int m = li + 16 * (pi % MB);
+        xp_src[i] = ((uint32_t)m * (uint32_t)p.K + 32u * (uint32_t)(pi / MB) + 8u * lo) * 2u;
+        xp_dst[i] = ((uint32_t)(kpart * NP + pi) * 64u + (uint32_t)lane) * 16u;
+    }
+    const uint32_t xpar_bytes = (uint32_t)(p.KS * NP) * 1024u;       // one parity's buffers
     const uint32_t tile_stride = (uint32_t)TILE_BYTES << p.SBL;        // bytes from K tile kt to kt+1
     const uint32_t sblock_bytes = (uint32_t)p.KT * tile_stride;         // packed bytes of one super-block
     const uint32_t srow_bytes = 16u * (uint32_t)p.SG * 2u;             // scale bytes of one 16-row block
@@ -177,7 +218,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
         WFrag<BITS> w[R];
         ScaleWords<NS> s[SCH ? 1 : R];     // direct mode: this lane's scales of the tile, per row block
         u32x4 chunk;                       // chunk mode: 8 consecutive scales of row `lane` of the wave's rows
-        u32x4 x[XL][MB];
+        u32x4 x[NX][NXM];                  // XSH: this wave's pieces of the *next* tile
     };
 
     while (t0 < t1) {
@@ -218,13 +259,31 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
 #pragma unroll
                 for (int r = 0; r < R; ++r) load_scales<NS>(st.s[r], rS, ts + slane + r * srow_bytes);
             }
+            if constexpr (XSH) {
+                // pieces of tile kt + 1: they are stored to LDS while tile kt is computed
+                const uint32_t tx1 = kt + 1 < wb ? (uint32_t)(kt + 1) * (TK * 2) : kOutOfRange;
 #pragma unroll
-            for (int j = 0; j < XL; ++j)
+                for (int i = 0; i < XPW; ++i)
+                    st.x[i][0] = __builtin_amdgcn_raw_buffer_load_b128(rX, xp_ok[i] ? tx1 + xp_src[i] : kOutOfRange, 0, kAuxNone);
+            } else {
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-                    st.x[j][mb] = __builtin_amdgcn_raw_buffer_load_b128(rX, tx + xlane[mb] + 64u * XS * j, 0, kAuxNone);
+                for (int j = 0; j < XL; ++j)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+                        st.x[j][mb] = __builtin_amdgcn_raw_buffer_load_b128(rX, tx + xlane[mb] + 64u * XS * j, 0, kAuxNone);
+            }
         };
-        auto compute_stage = [&](const Stage& st, int kt) {
+        // `round` counts the tiles of this segment (same in every wave of the workgroup); XSH only
+        auto compute_stage = [&](const Stage& st, int kt, int round) {
+            const char* bsrc = xbuf + (uint32_t)(round & 1) * xpar_bytes + ((uint32_t)(kpart * NP) * 64u + (uint32_t)lane) * 16u;
+            if constexpr (XSH) {
+                // next tile's pieces into the other buffer (its readers passed the last barrier)
+                char* dst = xbuf + (uint32_t)((round + 1) & 1) * xpar_bytes;
+#pragma unroll
+                for (int i = 0; i < XPW; ++i)
+                    if (xp_ok[i]) *reinterpret_cast<u32x4*>(dst + xp_dst[i]) = st.x[i][0];
+                if (kt >= wb) return;                   // nothing of this wave's own left (the caller still syncs)
+            }
             ScaleWords<NS> sw[R];
             if constexpr (SCH) {
                 // a new chunk starts at this tile: every lane parks its row's 8 scales in LDS, then each
@@ -252,6 +311,11 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             // the matrix instruction of item u is issued after the scaling of item u + 1, so that it
             // never has to wait for operands that were written by the instructions just before it
             u32x4 a[2];
+            u32x4 bx[2][MB];                            // XSH: B operands of the current and the next step
+            if constexpr (XSH) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) bx[0][mb] = *reinterpret_cast<const u32x4*>(bsrc + mb * 1024);
+            }
 #pragma unroll
             for (int u = 0; u <= U; ++u) {
                 if (u < U) {
@@ -266,7 +330,18 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                 }
                 if (u > 0) {
                     const int s = (u - 1) / R, r = (u - 1) % R;
-                    if constexpr (XM == 16) {
+                    if constexpr (XSH) {
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb)
+                            acc[r][mb] = mfma16x16x32<DT>(a[(u - 1) & 1], bx[s & 1][mb], acc[r][mb]);
+                        // the operands of step s + 1 are fetched as soon as the last product of step
+                        // s - 1 (which used the same registers) has been issued
+                        if (r == 0 && s + 1 < STEPS) {
+#pragma unroll
+                            for (int mb = 0; mb < MB; ++mb)
+                                bx[(s + 1) & 1][mb] = *reinterpret_cast<const u32x4*>(bsrc + ((s + 1) * MB + mb) * 1024);
+                        }
+                    } else if constexpr (XM == 16) {
 #pragma unroll
                         for (int mb = 0; mb < MB; ++mb)
                             acc[r][mb] = mfma16x16x32<DT>(a[(u - 1) & 1], st.x[s][mb], acc[r][mb]);
@@ -281,6 +356,14 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
         // The scheduling barriers keep the loads of different stages in program order, so that the
         // wait before a stage's first use only has to cover that stage's own loads.
         Stage st[P];
+        u32x4 xfirst[XPW];                              // XSH: this wave's pieces of the segment's first tile
+        if constexpr (XSH) {
+            const uint32_t tx0 = wa < wb ? (uint32_t)wa * (TK * 2) : kOutOfRange;
+#pragma unroll
+            for (int i = 0; i < XPW; ++i)
+                xfirst[i] = __builtin_amdgcn_raw_buffer_load_b128(rX, xp_ok[i] ? tx0 + xp_src[i] : kOutOfRange, 0, kAuxNone);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
         for (int q = 0; q < P; ++q) {
             load_stage(st[q], wa + q);
@@ -294,17 +377,39 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             LutSeed seed = lut_seed;
             asm volatile("" : "+v"(seed.v[0]), "+v"(seed.v[1]), "+v"(seed.v[2]), "+v"(seed.v[3]));
             lut_build<BITS, DT>(lut, seed, LOG2C, tid, p.lut_ltpe);
-            __syncthreads();
+            if constexpr (!XSH) __syncthreads();
             lut_ready = true;
             __builtin_amdgcn_sched_barrier(0);
         }
-        for (int kt = wa; kt < wb; kt += P) {
+        if constexpr (XSH) {
+            // first tile's pieces into buffer 0 (every reader of the previous segment has passed its
+            // last barrier); the barrier also publishes the table
 #pragma unroll
-            for (int q = 0; q < P; ++q) {
-                if (q == 0 || kt + q < wb) compute_stage(st[q], kt + q);
-                __builtin_amdgcn_sched_barrier(0);
-                load_stage(st[q], kt + q + P);
-                __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < XPW; ++i)
+                if (xp_ok[i]) *reinterpret_cast<u32x4*>(xbuf + xp_dst[i]) = xfirst[i];
+            __syncthreads();
+            // every wave of the workgroup runs the same number of rounds (the longest K part's), one
+            // barrier each, whether or not it still has tiles of its own
+            const int rounds = div_magic(rem + p.KS - 1, p.ks_magic, p.KS);
+            for (int it = 0; it < rounds; it += P) {
+#pragma unroll
+                for (int q = 0; q < P; ++q) {
+                    compute_stage(st[q], wa + it + q, it + q);
+                    __syncthreads();
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_stage(st[q], wa + it + q + P);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        } else {
+            for (int kt = wa; kt < wb; kt += P) {
+#pragma unroll
+                for (int q = 0; q < P; ++q) {
+                    if (q == 0 || kt + q < wb) compute_stage(st[q], kt + q, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_stage(st[q], kt + q + P);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
 
