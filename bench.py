@@ -197,7 +197,7 @@ def main():
                    "percent_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": roof_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": roof_achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "lutq::matmul_kernel<4,128,1,R,F16,P,true,4,WIDE> (all 128 launches of the step)",
+                     "kernel": "lutq::matmul_kernel<4,128,1,1,F16,2,true,4,true,false> (all 128 launches of the step)",
                      "bytes_per_launch": step_bytes / launches, "us_per_launch": per_launch_s * 1e6},
     }
 
