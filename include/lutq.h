@@ -132,6 +132,31 @@ lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scal
                              void* workspace, size_t workspace_bytes, void* stream,
                              const lutq_plan* plan);
 
+/* Instance selection by measurement (Section 4.1: the fastest kernel configuration is picked per
+ * shape; Section 3.3: how the K range is cut across workgroups is part of that choice).  Times the
+ * default plan and the candidate plans that lutq_tune_candidates lists, first with a few launches
+ * each, then the eight fastest and the default with `reps` launches, with events on `stream`, and
+ * writes the fastest to *best and, if best_us is not NULL, its microseconds per launch to *best_us.
+ *   packed, scales  host arrays of `ring` >= 1 device pointers each: weight sets of the same shape
+ *                   (copies of one matrix will do) that successive launches visit in turn, so that
+ *                   with a ring larger than the caches every launch streams from HBM as it would
+ *                   inside a model; ring = 1 tunes for weights that stay in cache.
+ *   the other arguments are those of lutq_matmul.  Y is overwritten by every candidate.
+ * Blocks until the measurements on `stream` are done (it creates and destroys two events, nothing
+ * else); must not be called while `stream` is being captured.
+ * Errors: those of lutq_matmul; SHAPE also for ring < 1 or reps < 1. */
+lutq_status lutq_tune(const void* X, const void* const* packed, const void* const* scales, int ring,
+                      const void* lut, int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                      lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes, void* stream,
+                      int reps, lutq_plan* best, float* best_us);
+
+/* The plans lutq_tune tries for this problem on the current device, the default plan first.
+ * Writes min(*count, capacity) of them to plans (host) and their number to *count; plans may be
+ * NULL when capacity is 0.  Some of them have no kernel instance: lutq_matmul_plan answers those
+ * with LUTQ_ERR_PLAN, and lutq_tune skips them. */
+lutq_status lutq_tune_candidates(int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                 lutq_dtype dtype, lutq_plan* plans, int capacity, int* count);
+
 /* The separate-kernel path of Section 3 (dequantise to memory): writes
  * W_out[n, k] = round16(T[Q[n,k]] * S[n, k/group_size]), device [N, K] row-major, dtype,
  * using the same on-chip lookup + scale routine as lutq_matmul.  Asynchronous on `stream`. */

@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     lutq_pack,
     lutq_packed_bytes,
     lutq_plan_default,
+    lutq_tune,
+    lutq_tune_candidates,
     lutq_unpack,
     lutq_workspace_bytes,
     new_workspace,

@@ -12,7 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "lutq_status_string", "lutq_packed_bytes", "lutq_pack", "lutq_unpack", "lutq_workspace_bytes",
-    "lutq_plan_default", "lutq_matmul", "lutq_matmul_plan", "lutq_dequant",
+    "lutq_plan_default", "lutq_matmul", "lutq_matmul_plan", "lutq_tune", "lutq_tune_candidates", "lutq_dequant",
     "lutq_calib_stream_read", "lutq_calib_copy",
 )
 
@@ -77,6 +77,12 @@ def load_library():
     lib.lutq_matmul_plan.restype = ci
     lib.lutq_matmul_plan.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp,
                                      ctypes.POINTER(_CPlan)]
+    lib.lutq_tune.restype = ci
+    lib.lutq_tune.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, ci, ci, i64, i64, i64, ci, vp, vp,
+                              sz, vp, ci, ctypes.POINTER(_CPlan), ctypes.POINTER(ctypes.c_float)]
+    lib.lutq_tune_candidates.restype = ci
+    lib.lutq_tune_candidates.argtypes = [ci, ci, i64, i64, i64, ci, ctypes.POINTER(_CPlan), ci,
+                                         ctypes.POINTER(ctypes.c_int)]
     lib.lutq_dequant.restype = ci
     lib.lutq_dequant.argtypes = [vp, vp, vp, ci, ci, i64, i64, ci, vp, vp]
     lib.lutq_calib_stream_read.restype = ci
@@ -196,6 +202,50 @@ def lutq_matmul(X, packed, scales, lut, bits: int, group_size: int, Y, workspace
         cp = plan._c()
         _check(lib.lutq_matmul_plan(*args, ctypes.byref(cp)), "lutq_matmul_plan")
     return Y
+
+
+def lutq_tune_candidates(bits: int, group_size: int, M: int, N: int, K: int, dtype_code: int = LUTQ_F16) -> list:
+    lib = load_library()
+    n = ctypes.c_int(0)
+    _check(lib.lutq_tune_candidates(bits, group_size, M, N, K, dtype_code, None, 0, ctypes.byref(n)),
+           "lutq_tune_candidates")
+    arr = (_CPlan * max(n.value, 1))()
+    _check(lib.lutq_tune_candidates(bits, group_size, M, N, K, dtype_code, arr, n.value, ctypes.byref(n)),
+           "lutq_tune_candidates")
+    return [Plan(c.row_blocks_per_wave, c.grid, c.waves_per_workgroup, c.tiles_in_flight,
+                 c.row_groups_per_workgroup) for c in arr[:n.value]]
+
+
+def lutq_tune(X, packed_ring, scales_ring, lut, bits: int, group_size: int, Y, workspace, stream=None,
+              reps: int = 50):
+    """Fastest plan for this problem by measurement: returns (Plan, microseconds per launch).
+    packed_ring / scales_ring: lists of equally shaped weight sets visited in turn."""
+    lib = load_library()
+    if len(packed_ring) != len(scales_ring) or not packed_ring:
+        raise ValueError("packed_ring and scales_ring must have the same, non-zero length")
+    for t in (X, lut, Y, workspace, *packed_ring, *scales_ring):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("lutq_tune needs contiguous CUDA (HIP) tensors")
+    code = _dtype_code(X)
+    M, K = X.shape
+    N = scales_ring[0].shape[0]
+    if tuple(Y.shape) != (M, N) or lut.numel() != (1 << bits):
+        raise ValueError("inconsistent shapes")
+    for pk, sc in zip(packed_ring, scales_ring):
+        if tuple(sc.shape) != (N, K // group_size) or _dtype_code(sc) != code:
+            raise ValueError("inconsistent scales")
+        if pk.numel() != lib.lutq_packed_bytes(N, K, bits, group_size):
+            raise ValueError("packed buffer has the wrong size for (N, K, bits)")
+    n = len(packed_ring)
+    pk = (ctypes.c_void_p * n)(*[t.data_ptr() for t in packed_ring])
+    sc = (ctypes.c_void_p * n)(*[t.data_ptr() for t in scales_ring])
+    cp = _CPlan()
+    us = ctypes.c_float(0.0)
+    _check(lib.lutq_tune(X.data_ptr(), pk, sc, n, lut.data_ptr(), bits, group_size, M, N, K, code, Y.data_ptr(),
+                         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(stream),
+                         reps, ctypes.byref(cp), ctypes.byref(us)), "lutq_tune")
+    return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup, cp.tiles_in_flight,
+                cp.row_groups_per_workgroup), us.value
 
 
 def lutq_dequant(packed, scales, lut, bits: int, group_size: int, W_out, stream=None):

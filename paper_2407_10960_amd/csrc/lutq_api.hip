@@ -4,7 +4,9 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
 #include <mutex>
+#include <vector>
 
 #include "lutq.h"
 #include "lutq_launch.hpp"
@@ -384,6 +386,146 @@ extern "C" lutq_status lutq_matmul(const void* X, const void* packed, const void
                                    void* Y, void* workspace, size_t workspace_bytes, void* stream) {
     return lutq_matmul_plan(X, packed, scales, lut, bits, group_size, M, N, K, dtype, Y, workspace,
                             workspace_bytes, stream, nullptr);
+}
+
+namespace {
+
+// Candidate work decompositions of lutq_tune: the default plan first, then every combination of row
+// blocks per wave, teams, waves per team, grid (one workgroup per set of row groups, or 1/2, 1, 2, 4
+// workgroups per compute unit with the K range cut where they do not divide the tiles) and pipeline
+// depth that passes the ranges of lutq_plan.  Combinations without a kernel instance are rejected by
+// lutq_matmul_plan when they are tried.
+std::vector<lutq_plan> tune_candidates(int bits, int group_size, int64_t M, int64_t N, int64_t K, lutq_dtype dtype,
+                                       int cus) {
+    std::vector<lutq_plan> out;
+    lutq_plan def;
+    if (lutq_plan_default(bits, group_size, M, N, K, dtype, &def) == LUTQ_OK) out.push_back(def);
+    const int64_t nb = N / 16, kt = K / tile_k(bits);
+    for (int r : {1, 2, 4}) {
+        if (super_block(nb) % r != 0) continue;
+        const int64_t nrg = nb / r;
+        for (int rs = 1; rs <= 16; ++rs) {
+            if (nrg % rs != 0) continue;
+            const int64_t sets = nrg / rs, tiles = sets * kt;
+            for (int ks = 1; ks * rs <= 16; ++ks) {
+                const int nw = ks * rs;
+                if (nw < 4 || (nw > 8 && nw % 2 != 0)) continue;
+                int64_t grids[5] = {sets, cus / 2, cus, 2 * cus, 4 * cus};
+                for (int gi = 0; gi < 5; ++gi) {
+                    const int64_t g = grids[gi];
+                    if (g < 1 || g > tiles || g * rs > kMaxGrid) continue;
+                    if (gi > 0 && g == sets) continue;
+                    for (int stages : {2, 4}) {
+                        const lutq_plan c{r, (int)g, nw, stages, rs};
+                        bool dup = false;
+                        for (const lutq_plan& o : out)
+                            dup = dup || (o.row_blocks_per_wave == c.row_blocks_per_wave && o.grid == c.grid &&
+                                          o.waves_per_workgroup == c.waves_per_workgroup &&
+                                          o.tiles_in_flight == c.tiles_in_flight &&
+                                          o.row_groups_per_workgroup == c.row_groups_per_workgroup);
+                        if (!dup) out.push_back(c);
+                    }
+                }
+            }
+        }
+    }
+    return out;
+}
+
+}  // namespace
+
+extern "C" lutq_status lutq_tune_candidates(int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                            lutq_dtype dtype, lutq_plan* plans, int capacity, int* count) {
+    if (!count || (capacity > 0 && !plans)) return LUTQ_ERR_NULL;
+    lutq_status st = check_problem(bits, group_size, N, K);
+    if (st != LUTQ_OK) return st;
+    if (M < 1 || M > 32) return LUTQ_ERR_SHAPE;
+    if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
+    DeviceInfo di = device_info();
+    if (!di.ok) return LUTQ_ERR_DEVICE;
+    const std::vector<lutq_plan> c = tune_candidates(bits, group_size, M, N, K, dtype, di.cus);
+    *count = (int)c.size();
+    for (int i = 0; i < (int)c.size() && i < capacity; ++i) plans[i] = c[i];
+    return LUTQ_OK;
+}
+
+extern "C" lutq_status lutq_tune(const void* X, const void* const* packed, const void* const* scales, int ring,
+                                 const void* lut, int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                 lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes, void* stream,
+                                 int reps, lutq_plan* best, float* best_us) {
+    if (!packed || !scales || !best) return LUTQ_ERR_NULL;
+    if (ring < 1 || reps < 1) return LUTQ_ERR_SHAPE;
+    for (int i = 0; i < ring; ++i)
+        if (!packed[i] || !scales[i]) return LUTQ_ERR_NULL;
+    lutq_plan def;
+    lutq_status st = lutq_plan_default(bits, group_size, M, N, K, dtype, &def);
+    if (st != LUTQ_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the default plan validates every other argument; its launches also bring the clocks up
+    int next = 0;
+    auto run = [&](const lutq_plan& c, int n) {
+        lutq_status r = LUTQ_OK;
+        for (int i = 0; i < n && r == LUTQ_OK; ++i) {
+            r = lutq_matmul_plan(X, packed[next], scales[next], lut, bits, group_size, M, N, K, dtype, Y, workspace,
+                                 workspace_bytes, s, &c);
+            next = next + 1 == ring ? 0 : next + 1;
+        }
+        return r;
+    };
+    st = run(def, 1);
+    if (st != LUTQ_OK) return st;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return LUTQ_ERR_DEVICE;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return LUTQ_ERR_DEVICE; }
+    auto cleanup = [&](lutq_status r) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return r; };
+    // microseconds per launch of n launches of plan c; negative if the plan has no instance
+    auto time_plan = [&](const lutq_plan& c, int n, float* us) {
+        lutq_status r = run(c, 2);
+        if (r != LUTQ_OK) return r;
+        if (hipEventRecord(e0, s) != hipSuccess) return LUTQ_ERR_DEVICE;
+        r = run(c, n);
+        if (r != LUTQ_OK) return r;
+        float ms = 0.f;
+        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+            return LUTQ_ERR_DEVICE;
+        *us = ms * 1000.f / (float)n;
+        return LUTQ_OK;
+    };
+    float us = 0.f;
+    for (float spent = 0.f; spent < 50000.f; spent += us * 20.f)          // about 50 ms of load before timing
+        if ((st = time_plan(def, 20, &us)) != LUTQ_OK) return cleanup(st);
+    DeviceInfo di = device_info();
+    if (!di.ok) return cleanup(LUTQ_ERR_DEVICE);
+    const std::vector<lutq_plan> cands = tune_candidates(bits, group_size, M, N, K, dtype, di.cus);
+    // first pass: a few launches each; second pass: the best eight at full length
+    std::vector<std::pair<float, int>> order;
+    const int quick = reps < 8 ? reps : 8;
+    for (int i = 0; i < (int)cands.size(); ++i) {
+        st = time_plan(cands[i], quick, &us);
+        if (st == LUTQ_ERR_PLAN) continue;
+        if (st != LUTQ_OK) return cleanup(st);
+        order.emplace_back(us, i);
+    }
+    if (order.empty()) return cleanup(LUTQ_ERR_PLAN);
+    std::sort(order.begin(), order.end());
+    bool have_default = false;
+    const int finalists = (int)order.size() < 8 ? (int)order.size() : 8;
+    for (int j = 0; j < finalists; ++j) have_default = have_default || order[j].second == 0;
+    float best_time = 0.f;
+    int best_i = -1;
+    for (int j = 0; j < finalists + (have_default ? 0 : 1); ++j) {
+        const int i = j < finalists ? order[j].second : 0;
+        if ((st = time_plan(cands[i], reps, &us)) != LUTQ_OK) return cleanup(st);
+        if (std::getenv("LUTQ_VERBOSE"))
+            std::fprintf(stderr, "lutq_tune: %s R=%d grid=%d waves=%d stages=%d teams=%d: %.2f us\n", i == 0 ? "default" : "candidate",
+                         cands[i].row_blocks_per_wave, cands[i].grid, cands[i].waves_per_workgroup,
+                         cands[i].tiles_in_flight, cands[i].row_groups_per_workgroup, us);
+        if (best_i < 0 || us < best_time) { best_time = us; best_i = i; }
+    }
+    *best = cands[best_i];
+    if (best_us) *best_us = best_time;
+    return cleanup(LUTQ_OK);
 }
 
 extern "C" lutq_status lutq_dequant(const void* packed, const void* scales, const void* lut, int bits,

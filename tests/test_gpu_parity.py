@@ -185,6 +185,52 @@ def test_default_plan_over_seeded_random_shapes(lutq):
     assert not workspace[:65536].any().item()
 
 
+@pytest.mark.parametrize("bits,dtype,M,nb,kt", [(4, "f16", 1, 24, 4), (3, "bf16", 8, 24, 3), (2, "f16", 32, 16, 5),
+                                              (4, "bf16", 16, 28, 8), (3, "f16", 3, 12, 6)])
+def test_every_tuner_candidate_matches_oracle(lutq, bits, dtype, M, nb, kt):
+    """Every plan the tuner may time (Section 4.1: instance selection per shape) is either rejected
+    with LUTQ_ERR_PLAN before anything is launched or gives the oracle's result."""
+    N, K, group = 16 * nb, tk(bits) * kt, 64
+    c = gen.make_case(300 + bits + M, M, N, K, bits, group, dtype, "random_index")
+    d = DeviceCase(lutq, c)
+    cands = lutq.lutq_tune_candidates(bits, group, M, N, K, 0 if dtype == "f16" else 1)
+    assert cands[0] == lutq.lutq_plan_default(bits, group, M, N, K, 0 if dtype == "f16" else 1)
+    assert len(cands) > 20 and len(set(map(repr, cands))) == len(cands)
+    What = orc.dequant(c.Q, c.T, c.S, group, dtype)
+    Yref = orc.matmul_f64(c.X, What, dtype)
+    mag = np.abs(orc.to_f64(c.X, dtype)) @ np.abs(orc.to_f64(What, dtype)).T
+    bound = 0.5 * ulp16(Yref, dtype) * (1 + 1e-9) + 1e-5 * mag
+    ran = 0
+    for plan in cands:
+        try:
+            Y = orc.to_f64(to_bits(d.matmul(lutq, plan=plan)), dtype)
+        except lutq.LutqError as e:
+            assert e.code == 10, f"{plan}: {e}"
+            continue
+        ran += 1
+        assert np.isfinite(Y).all(), plan
+        assert orc.rel_fro_err(Y, Yref) <= TOL[dtype], plan
+        assert np.max(np.abs(Y - Yref) - bound) <= 0, plan
+    assert ran >= len(cands) // 4
+    assert not d.ws[:65536].any().item()
+
+
+def test_tune_picks_a_candidate_that_matches_oracle(lutq):
+    """lutq_tune returns one of its candidates with a positive time, and the product computed with it
+    matches the oracle; weights are visited through a ring of two buffers."""
+    bits, group, dtype, M, N, K = 4, 128, "f16", 2, 1536, 2048
+    c = gen.make_case(77, M, N, K, bits, group, dtype, "nf")
+    d = DeviceCase(lutq, c)
+    import torch
+    Y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    plan, us = lutq.lutq_tune(d.X, [d.packed, d.packed.clone()], [d.S, d.S.clone()], d.T, bits, group, Y, d.ws, reps=20)
+    assert 0.5 < us < 1e4
+    assert repr(plan) in set(map(repr, lutq.lutq_tune_candidates(bits, group, M, N, K, 0)))
+    check_y(to_bits(d.matmul(lutq, plan=plan)), c, f"tuned {plan}")
+    with pytest.raises(lutq.LutqError):
+        lutq.lutq_tune(d.X, [d.packed], [d.S], d.T, bits, group, Y, d.ws, reps=0)
+
+
 def test_workspace_reuse_across_different_problems(lutq):
     """One workspace serves calls with different data, shapes and split plans back to back: stale
     partial sums of an earlier call must never leak into a later result."""
