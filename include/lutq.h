@@ -20,7 +20,7 @@
  * does).  A group is `group_size` consecutive elements along K inside one row.
  * round16 is one round-to-nearest-even to the 16-bit type `dtype`.
  *
- * Supported domain: bits in {2,3,4}; group_size in {32,64,128}; 1 <= M <= 32;
+ * Supported domain: bits in {2,3,4}; group_size in {32,64,128,256}; 1 <= M <= 32;
  * N a multiple of 16; K a multiple of the K-tile of the bit width (128 for
  * 4-bit, 256 for 2- and 3-bit) and of group_size; device pointers 16-byte aligned.
  */
@@ -38,7 +38,7 @@ typedef enum {
     LUTQ_OK = 0,
     LUTQ_ERR_NULL = 1,         /* a required pointer is NULL */
     LUTQ_ERR_BITS = 2,         /* bits not in {2,3,4} */
-    LUTQ_ERR_GROUP = 3,        /* group_size not in {32,64,128} or does not divide K */
+    LUTQ_ERR_GROUP = 3,        /* group_size not in {32,64,128,256} or does not divide K */
     LUTQ_ERR_SHAPE = 4,        /* M, N or K outside the supported domain */
     LUTQ_ERR_ALIGN = 5,        /* a device pointer is not 16-byte aligned */
     LUTQ_ERR_INDEX_RANGE = 6,  /* lutq_pack: an index is >= 2^bits */

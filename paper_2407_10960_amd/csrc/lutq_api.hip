@@ -24,7 +24,7 @@ inline int tile_k(int bits) { return bits == 4 ? 128 : 256; }
 
 lutq_status check_problem(int bits, int group_size, int64_t N, int64_t K) {
     if (bits < 2 || bits > 4) return LUTQ_ERR_BITS;
-    if (group_size != 32 && group_size != 64 && group_size != 128) return LUTQ_ERR_GROUP;
+    if (group_size != 32 && group_size != 64 && group_size != 128 && group_size != 256) return LUTQ_ERR_GROUP;
     if (N <= 0 || K <= 0 || N % 16 != 0 || K % tile_k(bits) != 0) return LUTQ_ERR_SHAPE;
     if (N / 16 > (int64_t)(kCounterBytes / 4) || N > (1 << 24) || K > (1 << 24)) return LUTQ_ERR_SHAPE;
     // the kernels address every buffer with 32-bit offsets and use offsets >= 2 GiB as "out of range"
@@ -235,7 +235,7 @@ extern "C" const char* lutq_status_string(lutq_status s) {
         case LUTQ_OK: return "ok";
         case LUTQ_ERR_NULL: return "null pointer";
         case LUTQ_ERR_BITS: return "bits must be 2, 3 or 4";
-        case LUTQ_ERR_GROUP: return "group_size must be 32, 64 or 128 and divide K";
+        case LUTQ_ERR_GROUP: return "group_size must be 32, 64, 128 or 256 and divide K";
         case LUTQ_ERR_SHAPE: return "unsupported shape (1 <= M <= 32, N % 16 == 0, K % K-tile == 0)";
         case LUTQ_ERR_ALIGN: return "device pointer not 16-byte aligned";
         case LUTQ_ERR_INDEX_RANGE: return "index out of range for the bit width";

@@ -89,6 +89,7 @@ hipError_t LUTQ_NAME(launch_matmul_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, i
         case 32: return launch_group<32>(mb, r, stages, sch, xm, wide, xsh, p, stream);
         case 64: return launch_group<64>(mb, r, stages, sch, xm, wide, xsh, p, stream);
         case 128: return launch_group<128>(mb, r, stages, sch, xm, wide, xsh, p, stream);
+        case 256: return launch_group<256>(mb, r, stages, sch, xm, wide, xsh, p, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -99,6 +100,7 @@ hipError_t LUTQ_NAME(launch_dequant_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, 
         case 32: return launch_dq<32>(p, grid, lds_bytes, stream);
         case 64: return launch_dq<64>(p, grid, lds_bytes, stream);
         case 128: return launch_dq<128>(p, grid, lds_bytes, stream);
+        case 256: return launch_dq<256>(p, grid, lds_bytes, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -133,10 +133,11 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
     static_assert(!XSH || XM == 16, "activations are shared through LDS in the plain layout only");
     using Gm = Geo<BITS>;
     constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
-    constexpr int NS = TK / GROUP;           // scales per tile per row
+    constexpr int TPS = GROUP > TK ? GROUP / TK : 1;   // tiles that share one scale (a group longer than a tile)
+    constexpr int NS = GROUP > TK ? 1 : TK / GROUP;    // scales per tile per row
     constexpr int SPG = GROUP / 32;          // steps per group
     constexpr int NREG = R * MB * 4;         // accumulator registers per lane
-    constexpr int TPC = 8 / NS;              // tiles covered by one 16-byte scale chunk
+    constexpr int TPC = 8 * TPS / NS;        // tiles covered by one 16-byte scale chunk
     constexpr int LOG2C = perm_log2_copies<BITS, DT>();
     constexpr int LUT_BYTES = lut_lds_bytes<BITS, DT>(LOG2C);
     static_assert(LUT_BYTES == lut_row_table_bytes<BITS>(), "one 256-byte row per entry");
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                 const uint32_t tc = first ? (uint32_t)(kt / TPC) * 16u : kOutOfRange;
                 st.chunk = __builtin_amdgcn_raw_buffer_load_b128(rS, tc + clane, 0, kAuxNone);
             } else {
-                const uint32_t ts = in ? (uint32_t)kt * (NS * 2) : kOutOfRange;
+                const uint32_t ts = in ? (uint32_t)(kt / TPS) * (NS * 2) : kOutOfRange;
 #pragma unroll
                 for (int r = 0; r < R; ++r) load_scales<NS>(st.s[r], rS, ts + slane + r * srow_bytes);
             }
@@ -293,7 +294,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                     *reinterpret_cast<u32x4*>(sc_lds + 16 * lane) = st.chunk;
                     asm volatile("" ::: "memory");      // and the reads below after it
                 }
-                const char* src = sc_lds + 16 * li + (kt % TPC) * (NS * 2);
+                const char* src = sc_lds + 16 * li + ((kt % TPC) / TPS) * (NS * 2);
 #pragma unroll
                 for (int r = 0; r < R; ++r) lds_load_scales<NS>(sw[r], src + 256 * r);
             } else {
@@ -576,7 +577,7 @@ template <int BITS, int GROUP, typename DT>
 __global__ __launch_bounds__(256) void dequant_kernel(const DequantParams p) {
     using Gm = Geo<BITS>;
     constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
-    constexpr int NS = TK / GROUP, SPG = GROUP / 32;
+    constexpr int TPS = GROUP > TK ? GROUP / TK : 1, NS = GROUP > TK ? 1 : TK / GROUP, SPG = GROUP / 32;
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -596,7 +597,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const DequantParams p) {
         WFrag<BITS> f;
         load_wfrag<BITS>(f, rW, (uint32_t)t * TILE_BYTES, lane);
         ScaleWords<NS> sw;
-        load_scales<NS>(sw, rS, (((uint32_t)rb * 16 + li) * (uint32_t)p.SG + (uint32_t)kt * NS) * 2u);
+        load_scales<NS>(sw, rS, (((uint32_t)rb * 16 + li) * (uint32_t)p.SG + (uint32_t)(kt / TPS) * NS) * 2u);
         uint16_t* out = p.W + ((size_t)rb * 16 + li) * p.K + (size_t)kt * TK + 8 * lo;
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {

@@ -50,7 +50,7 @@ inline int64_t tile_index(int64_t rb, int64_t kt, int64_t KT, int SB) { return (
 
 lutq_status check_pack_args(int64_t N, int64_t K, int bits, int group_size) {
     if (bits < 2 || bits > 4) return LUTQ_ERR_BITS;
-    if (group_size != 32 && group_size != 64 && group_size != 128) return LUTQ_ERR_GROUP;
+    if (group_size != 32 && group_size != 64 && group_size != 128 && group_size != 256) return LUTQ_ERR_GROUP;
     if (N <= 0 || K <= 0 || N % 16 != 0 || K % tile_k(bits) != 0) return LUTQ_ERR_SHAPE;
     if (K % group_size != 0) return LUTQ_ERR_GROUP;
     return LUTQ_OK;

@@ -107,6 +107,26 @@ def test_matmul_matches_oracle(lutq, bits, group, dtype):
 
 
 @pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_group_256(lutq, bits, dtype):
+    """Groups longer than a 4-bit K tile (one scale serves two tiles): dequantised weights bit-exact,
+    products against the oracle with the per-tile scale path (K/256 not a multiple of 8) and the
+    chunked one, under plans whose K ranges start in the middle of a group and of a scale chunk."""
+    import torch
+    group = 256
+    for (N, K, Ms, lut) in [(128, 1024, (1, 7, 32), "nf"), (192, 4096, (2, 16), "learned"), (64, 6144, (4, 24), "random_index")]:
+        for M in Ms:
+            c = gen.make_case(60 + M, M, N, K, bits, group, dtype, lut)
+            d = DeviceCase(lutq, c)
+            W = torch.empty((N, K), dtype=torch_dtype(dtype), device="cuda")
+            lutq.lutq_dequant(d.packed, d.S, d.T, bits, group, W)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_bits(W), orc.dequant(c.Q, c.T, c.S, group, dtype))
+            for plan in (None, lutq.Plan(1, 3, 4), lutq.Plan(1, 7, 8, 2, 1), lutq.Plan(2, 5, 6, 2, 2), lutq.Plan(1, 1, 5)):
+                check_y(to_bits(d.matmul(lutq, plan=plan)), c, f"b{bits} g256 {dtype} M{M} N{N} K{K} {plan}")
+
+
+@pytest.mark.parametrize("bits", BITS)
 def test_every_batch_size_1_to_32(lutq, bits):
     N, K, group, dtype = 128, 4 * tk(bits), 64, "f16"
     base = gen.make_case(0, 32, N, K, bits, group, dtype, "nf")

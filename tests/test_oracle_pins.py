@@ -138,7 +138,7 @@ def check_all_ones_table(o, bits, group):
     dtype = "f16"
     rng = np.random.default_rng(2)
     TK = 128 if bits == 4 else 256
-    N, K, M = 48, 2 * TK, 5
+    N, K, M = 48, 2 * max(TK, group), 5
     Q = rng.integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
     T = gen.encode16(np.ones(1 << bits), dtype)
     S = rand16(rng, (N, K // group), dtype, 0.05)
@@ -150,7 +150,7 @@ def check_all_ones_table(o, bits, group):
 
 
 @pytest.mark.parametrize("bits", BITS)
-@pytest.mark.parametrize("group", (32, 64, 128))
+@pytest.mark.parametrize("group", (32, 64, 128, 256))
 def test_all_ones_table(bits, group):
     check_all_ones_table(orc, bits, group)
 
