@@ -20,7 +20,9 @@
  * does).  A group is `group_size` consecutive elements along K inside one row.
  * round16 is one round-to-nearest-even to the 16-bit type `dtype`.
  *
- * Supported domain: bits in {2,3,4}; group_size in {32,64,128,256}; 1 <= M <= 32;
+ * Supported domain: bits in {2,3,4}; group_size in {32,64,128,256}; 1 <= M <= 128
+ * (the kernel works on up to 32 activation rows; more are served in slices of 32, one launch
+ * each, so the weights are streamed once per slice);
  * N a multiple of 16; K a multiple of the K-tile of the bit width (128 for
  * 4-bit, 256 for 2- and 3-bit) and of group_size; device pointers 16-byte aligned.
  */
@@ -83,7 +85,7 @@ lutq_status lutq_unpack(const void* packed, int64_t N, int64_t K, int bits, int 
  * instruction, Stream-K style partial-sum fix-up through global scratch).
  * ------------------------------------------------------------------------- */
 
-/* Bytes of device scratch lutq_matmul may need for any M <= 32 with these arguments
+/* Bytes of device scratch lutq_matmul may need for any M with these arguments
  * (the semaphore and partial-sum areas of Algorithm 2).  0 if unsupported. */
 size_t lutq_workspace_bytes(int64_t N, int64_t K, int bits, int group_size);
 

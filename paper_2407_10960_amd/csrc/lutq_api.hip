@@ -16,6 +16,7 @@ namespace {
 using namespace lutq;
 
 constexpr int kMaxGrid = 4096;
+constexpr int64_t kMaxRows = 128;                  // activation rows of one call (slices of 32 per launch)
 constexpr size_t kCounterBytes = 64 * 1024;                                   // 16384 row groups
 constexpr size_t kSlotBytes = (size_t)kSlotFloats * sizeof(float);            // 8 KiB
 constexpr size_t kWorkspaceBytes = kCounterBytes + (size_t)kMaxGrid * 2 * kSlotBytes;
@@ -236,7 +237,7 @@ extern "C" const char* lutq_status_string(lutq_status s) {
         case LUTQ_ERR_NULL: return "null pointer";
         case LUTQ_ERR_BITS: return "bits must be 2, 3 or 4";
         case LUTQ_ERR_GROUP: return "group_size must be 32, 64, 128 or 256 and divide K";
-        case LUTQ_ERR_SHAPE: return "unsupported shape (1 <= M <= 32, N % 16 == 0, K % K-tile == 0)";
+        case LUTQ_ERR_SHAPE: return "unsupported shape (1 <= M <= 128, N % 16 == 0, K % K-tile == 0)";
         case LUTQ_ERR_ALIGN: return "device pointer not 16-byte aligned";
         case LUTQ_ERR_INDEX_RANGE: return "index out of range for the bit width";
         case LUTQ_ERR_WORKSPACE: return "workspace missing or too small";
@@ -257,7 +258,8 @@ extern "C" lutq_status lutq_plan_default(int bits, int group_size, int64_t M, in
     if (!plan) return LUTQ_ERR_NULL;
     lutq_status st = check_problem(bits, group_size, N, K);
     if (st != LUTQ_OK) return st;
-    if (M < 1 || M > 32) return LUTQ_ERR_SHAPE;
+    if (M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
+    if (M > 32) M = 32;                                   // the plan of the 32-row slices
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
     DeviceInfo di = device_info();
     if (!di.ok) return LUTQ_ERR_DEVICE;
@@ -270,10 +272,20 @@ extern "C" lutq_status lutq_plan_default(int bits, int group_size, int64_t M, in
     return LUTQ_OK;
 }
 
-extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scales, const void* lut,
-                                        int bits, int group_size, int64_t M, int64_t N, int64_t K,
-                                        lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
-                                        void* stream, const lutq_plan* user_plan) {
+namespace {
+
+// One validated launch: everything lutq_matmul_plan decides before it touches the device.
+struct Prepared {
+    MatmulParams p;
+    int mb, r, stages, xm;
+    bool sch, wide, xsh;
+};
+
+// Validates the arguments of one launch (M <= 32) and fills *out; launches nothing.
+lutq_status prepare_matmul(const void* X, const void* packed, const void* scales, const void* lut,
+                           int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                           lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
+                           const lutq_plan* user_plan, Prepared* out) {
     if (!X || !packed || !scales || !lut || !Y) return LUTQ_ERR_NULL;
     lutq_status st = check_problem(bits, group_size, N, K);
     if (st != LUTQ_OK) return st;
@@ -375,10 +387,52 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     if (std::getenv("LUTQ_VERBOSE"))
         std::fprintf(stderr, "lutq_matmul: R=%d grid=%d waves=%d (teams %d x %d) stages=%d wide=%d xm=%d shared_x=%d lds=%d\n", r, d.grid,
                      d.nw, d.rs, p.KS, d.stages, (int)wide, xm, (int)xsh, lds_bytes);
-    hipError_t e = pick_matmul(bits, dtype)(group_size, mb, r, d.stages, sch, xm, wide, xsh, p, static_cast<hipStream_t>(stream));
+    out->p = p;
+    out->mb = mb; out->r = r; out->stages = d.stages; out->xm = xm;
+    out->sch = sch; out->wide = wide; out->xsh = xsh;
+    return LUTQ_OK;
+}
+
+lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dtype dtype, void* stream) {
+    hipError_t e = pick_matmul(bits, dtype)(group_size, q.mb, q.r, q.stages, q.sch, q.xm, q.wide, q.xsh, q.p,
+                                            static_cast<hipStream_t>(stream));
     if (e != hipSuccess && std::getenv("LUTQ_VERBOSE"))
-        std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d)\n", hipGetErrorString(e), p.G, d.nw * 64);
+        std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d)\n", hipGetErrorString(e), q.p.G, q.p.NW * 64);
     return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
+}
+
+}  // namespace
+
+extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scales, const void* lut,
+                                        int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                        lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
+                                        void* stream, const lutq_plan* user_plan) {
+    if (!X || !Y) return LUTQ_ERR_NULL;
+    if (M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
+    // More than 32 activation rows: slices of 32 rows, one launch each on the same stream (the
+    // weights are streamed once per slice).  Every slice is validated before the first launch.
+    const int64_t full = M / 32, rest = M % 32;
+    Prepared body{}, tail{};
+    const size_t xrow = (size_t)K * 2, yrow = (size_t)N * 2;
+    if (full > 0) {
+        lutq_status st = prepare_matmul(X, packed, scales, lut, bits, group_size, 32, N, K, dtype, Y, workspace,
+                                        workspace_bytes, user_plan, &body);
+        if (st != LUTQ_OK) return st;
+    }
+    if (rest > 0) {
+        lutq_status st = prepare_matmul(static_cast<const char*>(X) + (size_t)full * 32 * xrow, packed, scales, lut, bits,
+                                        group_size, rest, N, K, dtype, static_cast<char*>(Y) + (size_t)full * 32 * yrow,
+                                        workspace, workspace_bytes, user_plan, &tail);
+        if (st != LUTQ_OK) return st;
+    }
+    for (int64_t i = 0; i < full; ++i) {
+        Prepared q = body;
+        q.p.X = reinterpret_cast<const uint16_t*>(static_cast<const char*>(X) + (size_t)i * 32 * xrow);
+        q.p.Y = reinterpret_cast<uint16_t*>(static_cast<char*>(Y) + (size_t)i * 32 * yrow);
+        lutq_status st = launch_prepared(q, bits, group_size, dtype, stream);
+        if (st != LUTQ_OK) return st;
+    }
+    return rest > 0 ? launch_prepared(tail, bits, group_size, dtype, stream) : LUTQ_OK;
 }
 
 extern "C" lutq_status lutq_matmul(const void* X, const void* packed, const void* scales, const void* lut,
@@ -439,7 +493,7 @@ extern "C" lutq_status lutq_tune_candidates(int bits, int group_size, int64_t M,
     if (!count || (capacity > 0 && !plans)) return LUTQ_ERR_NULL;
     lutq_status st = check_problem(bits, group_size, N, K);
     if (st != LUTQ_OK) return st;
-    if (M < 1 || M > 32) return LUTQ_ERR_SHAPE;
+    if (M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
     DeviceInfo di = device_info();
     if (!di.ok) return LUTQ_ERR_DEVICE;

@@ -106,6 +106,35 @@ def test_matmul_matches_oracle(lutq, bits, group, dtype):
             check_y(to_bits(d.matmul(lutq)), c, f"b{bits} g{group} {dtype} M{M} N{N} K{K}")
 
 
+@pytest.mark.parametrize("bits,dtype", [(4, "f16"), (3, "bf16"), (2, "f16")])
+def test_more_than_32_rows(lutq, bits, dtype):
+    """33..128 activation rows are served in slices of 32 (one launch each, one workspace); a plan
+    that one of the slices cannot run is refused before any slice is launched."""
+    import torch
+    N, K, group = 208, 8 * tk(bits), 64
+    base = gen.make_case(90 + bits, 32, N, K, bits, group, dtype, "nf")
+    d = DeviceCase(lutq, base)
+    rng = np.random.default_rng(5)
+    for M in (33, 36, 64, 97, 128):
+        X = gen.encode16(rng.standard_normal((M, K)), dtype)
+        c = gen.Case(M, N, K, bits, group, dtype, X, base.Q, base.S, base.T)
+        for plan in (None, lutq.Plan(1, 5, 8, 2, 1)):
+            Y = to_bits(d.matmul(lutq, X=to_dev(X, dtype), plan=plan))
+            assert Y.shape == (M, N)
+            check_y(Y, c, f"b{bits} {dtype} M{M} {plan}")
+    # 16 waves exist for M <= 4 only: fine for the 4-row tail of M = 36, not for its 32-row slice
+    Xd = to_dev(gen.encode16(rng.standard_normal((36, K)), dtype), dtype)
+    Y = torch.full((36, N), 7.0, dtype=Xd.dtype, device="cuda")
+    with pytest.raises(lutq.LutqError) as e:
+        lutq.lutq_matmul(Xd, d.packed, d.S, d.T, bits, group, Y, d.ws, plan=lutq.Plan(1, 0, 16, 2, 1))
+    assert e.value.code == 10
+    torch.cuda.synchronize()
+    assert (Y == 7.0).all().item()
+    with pytest.raises(lutq.LutqError):
+        d.matmul(lutq, X=torch.zeros((129, K), dtype=Xd.dtype, device="cuda"))
+    assert not d.ws[:65536].any().item()
+
+
 @pytest.mark.parametrize("bits", BITS)
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_group_256(lutq, bits, dtype):

@@ -106,7 +106,7 @@ def test_matmul_validation_returns_codes_before_any_launch():
     assert call(bits=5) == 2
     assert call(g=100) == 3
     assert call(g=64, K=128 + 32) == 4          # K not a tile multiple
-    assert call(M=0) == 4 and call(M=33) == 4
+    assert call(M=0) == 4 and call(M=129) == 4
     assert call(N=24) == 4
     assert call(dt=2) == 8
     assert call(X=a + 2) == 5 and call(Y=a + 8) == 5 and call(S=a + 4) == 5
