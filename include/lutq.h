@@ -159,6 +159,24 @@ lutq_status lutq_tune(const void* X, const void* const* packed, const void* cons
 lutq_status lutq_tune_candidates(int bits, int group_size, int64_t M, int64_t N, int64_t K,
                                  lutq_dtype dtype, lutq_plan* plans, int capacity, int* count);
 
+/* Quantiser on the GPU (Section 3, first equation: each weight is replaced by the index of the
+ * nearest table entry; Section 4.1 "LUT quantization method" / Section 4.2: one absmax scale per
+ * group, kept in the 16-bit type), fused with the restructuring of Section 3.1: a dense weight
+ * matrix already in device memory becomes scales + packed indices in one pass, ready for lutq_matmul.
+ *   scale S[n, g] = round16( max |W[n, k]| over the group )
+ *   Q[n, k]       = the lowest c that minimises | W[n, k] / S[n, g] - T[c] |   (u = 0 where S = 0)
+ * with the division, the difference and the comparison in IEEE fp64 on the exact input values, so
+ * the result depends on the inputs only, not on the launch.
+ *   W           device, [N, K] row-major; fp32 if w_is_f32 != 0, else `dtype`; 16-byte aligned; finite
+ *   lut         device, 2^bits entries, dtype
+ *   scales_out  device, [N, K / group_size] row-major, dtype, fully overwritten
+ *   packed_out  device, lutq_packed_bytes() bytes, 16-byte aligned, fully overwritten (the bytes
+ *               lutq_pack would produce from Q)
+ * Asynchronous on `stream`; allocates nothing.  Errors: NULL, BITS, GROUP, SHAPE, DTYPE, ALIGN, DEVICE. */
+lutq_status lutq_quantize(const void* W, int w_is_f32, const void* lut, int bits, int group_size,
+                          int64_t N, int64_t K, lutq_dtype dtype, void* scales_out, void* packed_out,
+                          void* stream);
+
 /* The separate-kernel path of Section 3 (dequantise to memory): writes
  * W_out[n, k] = round16(T[Q[n,k]] * S[n, k/group_size]), device [N, K] row-major, dtype,
  * using the same on-chip lookup + scale routine as lutq_matmul.  Asynchronous on `stream`. */

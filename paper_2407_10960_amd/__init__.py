@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     lutq_pack,
     lutq_packed_bytes,
     lutq_plan_default,
+    lutq_quantize,
     lutq_tune,
     lutq_tune_candidates,
     lutq_unpack,

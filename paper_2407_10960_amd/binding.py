@@ -12,7 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "lutq_status_string", "lutq_packed_bytes", "lutq_pack", "lutq_unpack", "lutq_workspace_bytes",
-    "lutq_plan_default", "lutq_matmul", "lutq_matmul_plan", "lutq_tune", "lutq_tune_candidates", "lutq_dequant",
+    "lutq_plan_default", "lutq_matmul", "lutq_matmul_plan", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
     "lutq_calib_stream_read", "lutq_calib_copy",
 )
 
@@ -83,6 +83,8 @@ def load_library():
     lib.lutq_tune_candidates.restype = ci
     lib.lutq_tune_candidates.argtypes = [ci, ci, i64, i64, i64, ci, ctypes.POINTER(_CPlan), ci,
                                          ctypes.POINTER(ctypes.c_int)]
+    lib.lutq_quantize.restype = ci
+    lib.lutq_quantize.argtypes = [vp, ci, vp, ci, ci, i64, i64, ci, vp, vp, vp]
     lib.lutq_dequant.restype = ci
     lib.lutq_dequant.argtypes = [vp, vp, vp, ci, ci, i64, i64, ci, vp, vp]
     lib.lutq_calib_stream_read.restype = ci
@@ -246,6 +248,30 @@ def lutq_tune(X, packed_ring, scales_ring, lut, bits: int, group_size: int, Y, w
                          reps, ctypes.byref(cp), ctypes.byref(us)), "lutq_tune")
     return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup, cp.tiles_in_flight,
                 cp.row_groups_per_workgroup), us.value
+
+
+def lutq_quantize(W, lut, bits: int, group_size: int, scales_out, packed_out, stream=None):
+    """Quantises the dense device matrix W[N,K] (float32, or the 16-bit dtype of lut) against the table:
+    writes the group scales and the packed indices that lutq_matmul consumes."""
+    import torch
+    lib = load_library()
+    for t in (W, lut, scales_out, packed_out):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("lutq_quantize needs contiguous CUDA (HIP) tensors")
+    code = _dtype_code(lut)
+    w_f32 = W.dtype == torch.float32
+    if not w_f32 and _dtype_code(W) != code:
+        raise TypeError("W must be float32 or share the dtype of lut")
+    if _dtype_code(scales_out) != code:
+        raise TypeError("scales_out and lut must share one dtype")
+    N, K = W.shape
+    if tuple(scales_out.shape) != (N, K // group_size) or lut.numel() != (1 << bits):
+        raise ValueError("inconsistent shapes")
+    if packed_out.numel() * packed_out.element_size() != lib.lutq_packed_bytes(N, K, bits, group_size):
+        raise ValueError("packed buffer has the wrong size for (N, K, bits)")
+    _check(lib.lutq_quantize(W.data_ptr(), int(w_f32), lut.data_ptr(), bits, group_size, N, K, code,
+                             scales_out.data_ptr(), packed_out.data_ptr(), _stream_ptr(stream)), "lutq_quantize")
+    return scales_out, packed_out
 
 
 def lutq_dequant(packed, scales, lut, bits: int, group_size: int, W_out, stream=None):

@@ -106,6 +106,49 @@ def test_matmul_matches_oracle(lutq, bits, group, dtype):
             check_y(to_bits(d.matmul(lutq)), c, f"b{bits} g{group} {dtype} M{M} N{N} K{K}")
 
 
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("group", (32, 64, 128, 256))
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_quantize_bit_exact(lutq, bits, group, dtype):
+    """The GPU quantiser (Section 3, first equation; absmax group scale of Section 4.1/4.2) against
+    the oracle's quantiser followed by the oracle's packer: scales and packed bytes bit for bit, for
+    fp32 and 16-bit weights, a NormalFloat table, an unsorted table with a duplicated entry, a dead
+    group, exact ties, and super-blocks of 1, 2 and 4 row blocks."""
+    import torch
+    rng = np.random.default_rng(17 * bits + group)
+    E = 1 << bits
+    tables = [orc.from_f64(orc.nf_table(bits), dtype)]
+    t2 = rng.standard_normal(E)
+    t2[E - 1] = t2[0]                                           # duplicate: the lower index must win
+    tables.append(gen.encode16(t2, dtype))
+    for N, K in ((48, 512), (96, 768 if group < 256 and bits == 4 else 1024), (128, 256)):
+        for ti, T in enumerate(tables):
+            W32 = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+            W32[1, :group] = 0.0                                # dead group: scale 0, index of the entry nearest 0
+            t = orc.to_f64(T, dtype)
+            # exact ties: with absmax 1 in the group, weights halfway between two table entries
+            W32[2, :group] = 0.0
+            W32[2, 0] = 1.0
+            mids = ((t[:-1] + t[1:]) / 2).astype(np.float32)
+            W32[2, 1:1 + len(mids)] = np.clip(mids, -1, 1)
+            for w16 in (False, True):
+                if w16:
+                    Wb = gen.encode16(W32.astype(np.float64), dtype)
+                    Wd, W64 = to_dev(Wb, dtype), orc.to_f64(Wb, dtype)
+                else:
+                    Wd, W64 = torch.from_numpy(W32).cuda(), W32.astype(np.float64)
+                Q, S = orc.quantize(W64, T, group, dtype)
+                S_out = torch.zeros((N, K // group), dtype=torch_dtype(dtype), device="cuda")
+                P_out = torch.zeros(lutq.lutq_packed_bytes(N, K, bits, group), dtype=torch.uint8, device="cuda")
+                lutq.lutq_quantize(Wd, to_dev(T, dtype), bits, group, S_out, P_out)
+                torch.cuda.synchronize()
+                what = f"b{bits} g{group} {dtype} N{N} K{K} table{ti} w16={w16}"
+                assert np.array_equal(to_bits(S_out), S), what
+                got = lutq.lutq_unpack(P_out.cpu().numpy(), N, K, bits, group)
+                assert np.array_equal(got, Q), f"{what}: {np.count_nonzero(got != Q)} indices differ"
+                assert np.array_equal(P_out.cpu().numpy(), orc.pack(Q, bits)), what
+
+
 @pytest.mark.parametrize("bits,dtype", [(4, "f16"), (3, "bf16"), (2, "f16")])
 def test_more_than_32_rows(lutq, bits, dtype):
     """33..128 activation rows are served in slices of 32 (one launch each, one workspace); a plan
