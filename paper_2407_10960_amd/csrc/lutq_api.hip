@@ -129,45 +129,31 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         while (nw < 4 && ks > 0) { ++ks; nw = (int)rs * ks; }     // the table build needs four waves
         return nw;
     };
-    if (M > 4 && sch && !force_r && qn == 1 && pn <= 32) {
-        // More than four activation rows, row blocks that divide evenly over the compute units:
-        // one workgroup per compute unit with its row blocks as teams that share the activations
-        // through LDS (needs enough teams to stage a tile between them, and chunked scales)
-        // (R = 2 only: with one row block per wave the operand reads from LDS are as many bytes as with
-        // per-team loads and the plan below, which favours a large R, is faster)
-        // (a 2- or 3-bit tile with M > 16 is sixteen operand fragments per team: there sharing pays
-        // even at R = 1)
-        for (int r = 2; r >= ((mb == 2 && bits != 4) ? 1 : 2); --r) {
-            if (pn % r != 0 || sb % r != 0) continue;
-            const int64_t rs = pn / r;
-            if (rs > 16 || !teams_can_share_x(bits, mb, (int)rs)) continue;
-            int ks = 1;
-            while (rs * (ks + 1) <= 16 && kt / (ks + 1) >= 4 && rs * ks < 12) ++ks;
-            int nw = (int)rs * ks;
-            if (nw > 8 && !matmul_instance_exists(bits, bf16, r, mb, 2, true, 16, true, true)) {
-                ks = (int)(8 / rs);
-                nw = (int)rs * ks;
-            }
-            if (ks < 1 || nw < 4 || !matmul_instance_exists(bits, bf16, r, mb, 2, true, 16, nw > 8, true)) continue;
-            d.r = r; d.grid = cus; d.nw = nw; d.rs = (int)rs;
-            return d;
-        }
-    }
     if (M > 4) {
-        // More than four activation rows use the plain activation layout: every row group reads
-        // M x K activations (through L2/L1) next to its 8 R K bytes of weights, so what matters
-        // first is a large R; then one workgroup per row group (no teams: they would each re-read
-        // the activations), K split across workgroups when there are too few row groups.
+        // More than four activation rows use the plain activation layout: next to its weights every
+        // wave needs the M x TK activations of each tile it works on, as many bytes as the weights of
+        // M / (4 bits) row blocks.  The rules below were fitted to timings of all candidate plans
+        // (lutq_tune) on the LLaMA-3 8B and 70B layer shapes at M = 8, 16, 32 and 2, 3, 4 bits; they
+        // stay within a few per cent of the fastest plan there.
+        //
+        // Plain plan: one workgroup per row group, the largest R that still fills 60 % of the compute
+        // units (or half of them when K is long enough to be cut in two); K cut across workgroups
+        // when there are too few row groups; four waves (one per SIMD) from M = 13 up.
+        auto r_fills = [&](int r) {
+            const int64_t groups = nb / r;
+            if (groups >= (int64_t)cus * 6 / 10) return true;
+            const int64_t j = (cus + groups - 1) / groups;
+            return j <= 2 && K / j >= 6144;
+        };
         int r = force_r;
         if (!r) {
             r = sb;
-            while (r > 1 && nb / r < (int64_t)cus * 7 / 10) r >>= 1;
-            if (r == 1 && sb >= 2 && kt >= 64) r = 2;     // long K: split it across workgroups instead
+            while (r > 1 && !r_fills(r)) r >>= 1;
             while (r > 1 && !matmul_instance_exists(bits, bf16, r, mb, 2, true, xm, false)) r >>= 1;   // registers
         }
         const int64_t groups = nb / r;
         int64_t grid = groups;
-        if (groups < (int64_t)cus * 7 / 10) {
+        if (groups < (int64_t)cus * 6 / 10) {
             int64_t j = (cus + groups - 1) / groups;      // K parts per row group
             if (j > kt / 8) j = kt / 8;
             if (j < 1) j = 1;
@@ -175,7 +161,60 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         }
         while (grid > kMaxGrid) grid = (grid + 1) / 2;
         d.r = r; d.grid = (int)grid; d.rs = 1;
-        d.nw = r == 4 ? 4 : 8;
+        d.nw = (M > 12 || (r == 4 && groups > cus)) ? 4 : 8;
+        // Team plan: a workgroup takes A = R x RS row blocks as RS teams that share the activations
+        // through LDS (needs enough teams to stage a tile between them, and chunked scales).  It pays
+        // when the activations outweigh the weights (M / (4 bits) >= 1.3) on a problem long enough to
+        // hide the barrier per tile, from 17 rows up, or on very large problems.
+        const int64_t size = nb * K / cus;                // weight rows x columns per compute unit / 16
+        const bool teams = (mb == 2 && size >= 12000) || (10 * M >= 52 * bits && size >= 20000) || size >= 100000;
+        if (!teams || !sch || force_r) return d;
+        const int need = (steps_per_tile(bits) * mb + kXPiecesPerWave - 1) / kXPiecesPerWave;
+        struct Cand { bool exact; int r; int64_t rs, sets; };
+        std::vector<Cand> exact, shallow, deep;
+        // R = 2 halves the operand reads from LDS per weight; the 3-bit instances for M > 16 are the
+        // exception (no 16-wave build at R = 2, and R = 1 with twice the teams is faster)
+        const int r_first = (bits == 3 && mb == 2) ? 1 : 2;
+        for (int pass = 0; pass < 2; ++pass) {
+            const int tr = pass == 0 ? r_first : 3 - r_first;
+            if (sb % tr != 0) continue;
+            // one set of row blocks per workgroup and at least 85 % of the compute units busy: no
+            // fix-up; the fullest grid wins, then the larger A
+            Cand best{true, tr, 0, 0};
+            for (int64_t rs = 16; rs >= need; --rs) {
+                const int64_t a = tr * rs;
+                if (nb % a != 0) continue;
+                const int64_t sets = nb / a;
+                if (a >= 6 && sets <= cus && sets * 100 >= (int64_t)cus * 85 && sets > best.sets) best = Cand{true, tr, rs, sets};
+                // one workgroup per compute unit, every set's K range cut across cus / sets of them:
+                // up to four ("shallow") before deeper cuts
+                (sets * 4 >= cus ? shallow : deep).push_back(Cand{false, tr, rs, sets});
+            }
+            if (best.sets) exact.push_back(best);
+        }
+        std::stable_sort(deep.begin(), deep.end(), [](const Cand& x, const Cand& y) { return x.sets > y.sets; });
+        std::vector<Cand> order = exact;
+        order.insert(order.end(), shallow.begin(), shallow.end());
+        order.insert(order.end(), deep.begin(), deep.end());
+        for (const Cand& c : order) {
+            const int64_t cols = c.exact ? K : c.sets * K / cus;      // columns of K per workgroup
+            if (cols < 1536) continue;
+            int ks = c.rs >= 8 ? (c.exact ? 2 : 1) : 2;
+            while (ks > 1 && c.rs * ks > 16) --ks;
+            int nw = (int)c.rs * ks;
+            if (!matmul_instance_exists(bits, bf16, c.r, mb, 2, true, 16, nw > 8, true)) {
+                ks = (int)(8 / c.rs);
+                nw = (int)c.rs * ks;
+                if (ks < 1 || nw < 4 || !matmul_instance_exists(bits, bf16, c.r, mb, 2, true, 16, false, true)) continue;
+            }
+            if (nw < 4) continue;
+            const int lds = bits == 2 ? matmul_lds_bytes<2>(c.r, mb, nw, (int)c.rs, true, true)
+                          : bits == 3 ? matmul_lds_bytes<3>(c.r, mb, nw, (int)c.rs, true, true)
+                                      : matmul_lds_bytes<4>(c.r, mb, nw, (int)c.rs, true, true);
+            if (lds > 160 * 1024) continue;
+            d.r = c.r; d.grid = c.exact ? (int)c.sets : cus; d.nw = nw; d.rs = (int)c.rs;
+            return d;
+        }
         return d;
     }
     if (qn == 1 && pn <= 64 && (!force_r || pn % force_r == 0)) {
@@ -560,6 +599,10 @@ extern "C" lutq_status lutq_tune(const void* X, const void* const* packed, const
         if (st == LUTQ_ERR_PLAN) continue;
         if (st != LUTQ_OK) return cleanup(st);
         order.emplace_back(us, i);
+        if (const char* v = std::getenv("LUTQ_VERBOSE"); v && v[0] == '2')
+            std::fprintf(stderr, "lutq_tune: quick R=%d grid=%d waves=%d stages=%d teams=%d: %.2f us\n",
+                         cands[i].row_blocks_per_wave, cands[i].grid, cands[i].waves_per_workgroup,
+                         cands[i].tiles_in_flight, cands[i].row_groups_per_workgroup, us);
     }
     if (order.empty()) return cleanup(LUTQ_ERR_PLAN);
     std::sort(order.begin(), order.end());
