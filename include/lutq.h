@@ -137,7 +137,8 @@ lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scal
 /* Instance selection by measurement (Section 4.1: the fastest kernel configuration is picked per
  * shape; Section 3.3: how the K range is cut across workgroups is part of that choice).  Times the
  * default plan and the candidate plans that lutq_tune_candidates lists, first with a few launches
- * each, then the eight fastest and the default with `reps` launches, with events on `stream`, and
+ * each, then the eight fastest and the default in three rounds of `reps` launches (the minimum per
+ * plan counts), with events on `stream`, and
  * writes the fastest to *best and, if best_us is not NULL, its microseconds per launch to *best_us.
  *   packed, scales  host arrays of `ring` >= 1 device pointers each: weight sets of the same shape
  *                   (copies of one matrix will do) that successive launches visit in turn, so that
