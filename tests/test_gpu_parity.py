@@ -397,6 +397,15 @@ FULL_SIZE = [
     ("8B gate_up W3 g128 M8 (R = 4, plain activations)", 28672, 4096, 3, 128, "f16", 8),
     ("8B gate_up W3 g64 M32 (R limited by registers)", 28672, 4096, 3, 64, "f16", 32),
     ("8B down W2 g128 M3", 4096, 14336, 2, 128, "bf16", 3),
+    # M > 4: shared-activation team plans (one set per workgroup; K cut across up to four workgroups;
+    # deeper cuts) and the plain plan with four waves
+    ("8B gate_up W4 g128 M32 (4 teams of R = 2, one set per workgroup)", 28672, 4096, 4, 128, "f16", 32),
+    ("70B qkv W4 g64 M32 (5 teams of R = 2, K cut in four)", 10240, 8192, 4, 64, "f16", 32),
+    ("8B down W3 g128 bf16 M32 (8 teams, K cut in eight)", 4096, 14336, 3, 128, "bf16", 32),
+    ("70B o W2 g64 M24 (8 teams)", 8192, 8192, 2, 64, "f16", 24),
+    ("70B qkv W3 g64 M12 (plain, R = 4, 160 workgroups)", 10240, 8192, 3, 64, "f16", 12),
+    ("8B qkv W4 g256 M16 (plain, four waves)", 6144, 4096, 4, 256, "f16", 16),
+    ("70B qkv W3 g64 M1 (one 4-wave workgroup per row block)", 10240, 8192, 3, 64, "f16", 1),
 ]
 
 
