@@ -381,6 +381,50 @@ def test_bad_plan_is_rejected_and_y_untouched(lutq):
     assert (Y == 7.0).all().item()
 
 
+def test_graph_replay_matches_eager(lutq):
+    """The benchmark replays its calls as one HIP graph.  A graph of several calls that share one
+    workspace -- among them plans that cut tiles across workgroups, whose arrival counters must be back
+    at zero for the next replay -- gives on every replay, with eager launches and synchronisations in
+    between, bit for bit what the same calls give when launched directly, and that matches the oracle."""
+    import torch
+    specs = [(1, 256, 2048, 4, "f16", None), (1, 256, 2048, 4, "f16", lutq.Plan(1, 7, 8, 2, 1)),
+             (16, 192, 4096, 3, "f16", lutq.Plan(2, 5, 8, 2, 2)), (32, 128, 1024, 2, "f16", lutq.Plan(1, 3, 8, 2, 8)),
+             (3, 320, 1024, 4, "f16", lutq.Plan(1, 9, 10, 2, 5))]
+    cases = [gen.make_case(500 + i, M, N, K, bits, 64, dtype, "nf") for i, (M, N, K, bits, dtype, _) in enumerate(specs)]
+    devs = [DeviceCase(lutq, c) for c in cases]
+    ws = devs[0].ws
+    outs = [torch.zeros((c.M, c.N), dtype=torch.float16, device="cuda") for c in cases]
+
+    def run_all():
+        for d, c, y, spec in zip(devs, cases, outs, specs):
+            lutq.lutq_matmul(d.X, d.packed, d.S, d.T, c.bits, c.group_size, y, ws, plan=spec[5])
+
+    run_all()
+    torch.cuda.synchronize()
+    eager = [to_bits(y) for y in outs]
+    for y_bits, c in zip(eager, cases):
+        check_y(y_bits, c, "eager")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_all()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_all()
+    for replay in range(4):
+        for y in outs:
+            y.fill_(float("nan"))                        # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for y, e, c in zip(outs, eager, cases):
+            assert np.array_equal(to_bits(y), e), f"replay {replay}: M{c.M} N{c.N} K{c.K} b{c.bits}"
+        assert not ws[:65536].any().item()
+        devs[1].matmul(lutq, plan=specs[1][5])           # an eager call on the same workspace in between
+
+
 FULL_SIZE = [
     # (name, N, K, bits, group, dtype, M) -- BASELINE configs at full size, default launch configuration
     ("8B gate_up W4 g128", 28672, 4096, 4, 128, "f16", 1),
