@@ -380,7 +380,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     // exists, so that two workgroups fit a compute unit
     // M > 4 with enough teams: the activations are staged in LDS once per workgroup instead of being
     // fetched by every team (LUTQ_NO_SHARED_X=1 switches that off, for comparisons)
-    bool xsh = M > 4 && sch && d.stages == 2 && teams_can_share_x(bits, mb, d.rs) && !std::getenv("LUTQ_NO_SHARED_X");
+    bool xsh = M > 4 && sch && teams_can_share_x(bits, mb, d.rs) && !std::getenv("LUTQ_NO_SHARED_X");
     bool wide = d.nw > 8 || (d.nw > 4 && sch && matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, true, xsh));
     if (xsh && !matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, true)) {
         xsh = false;

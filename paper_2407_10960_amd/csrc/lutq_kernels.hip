@@ -36,11 +36,14 @@ hipError_t launch_one(const MatmulParams& p, hipStream_t stream) {
 template <int GROUP, int MB, int R, int XM>
 hipError_t launch_r(int stages, bool sch, bool wide, bool xsh, const MatmulParams& p, hipStream_t stream) {
     if constexpr (XM == 16) {
-        // activations shared through LDS: chunked scales, two tiles in flight
+        // activations shared through LDS: chunked scales
         if (xsh) {
-            if (!sch || stages != 2) return hipErrorInvalidValue;
-            return wide ? launch_one<GROUP, MB, R, 2, true, 16, true, true>(p, stream)
-                        : launch_one<GROUP, MB, R, 2, true, 16, false, true>(p, stream);
+            if (!sch) return hipErrorInvalidValue;
+            if (stages == 2) return wide ? launch_one<GROUP, MB, R, 2, true, 16, true, true>(p, stream)
+                                         : launch_one<GROUP, MB, R, 2, true, 16, false, true>(p, stream);
+            if (stages == 4) return wide ? launch_one<GROUP, MB, R, 4, true, 16, true, true>(p, stream)
+                                         : launch_one<GROUP, MB, R, 4, true, 16, false, true>(p, stream);
+            return hipErrorInvalidValue;
         }
     } else if (xsh) {
         return hipErrorInvalidValue;

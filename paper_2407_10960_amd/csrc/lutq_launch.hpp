@@ -14,7 +14,7 @@ namespace lutq {
 inline bool matmul_instance_exists(int bits, bool bf16, int r, int mb, int stages, bool sch, int xm, bool wide,
                                    bool xsh = false) {
     const bool wt = bf16 && bits != 2;                  // widened table: a larger lookup ring
-    if (xsh && (xm != 16 || !sch || stages != 2)) return false;
+    if (xsh && (xm != 16 || !sch)) return false;
     if (stages != 2 && stages != 4) return false;
     if (!sch) return stages == 2 && !wide;
     if (!wide) {                                        // up to 256 registers; beyond that the K loop would spill
