@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0
 # summarised in profiles/matmul_kernel_llama3_8b_w4g128_m1_hbm_traffic.txt (counters scaled by a copy
 # kernel of known size).  A counter run cannot be made from inside this script; the figure belongs to
 # this exact workload and is reported as measured there.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 28.34e6
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 28.32e6
 LAYERS = 32
 BITS, GROUP, DTYPE, M = 4, 128, "f16", 1
 

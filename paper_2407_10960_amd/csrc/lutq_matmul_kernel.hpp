@@ -254,7 +254,12 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             if constexpr (SCH) {
                 const bool first = in && ((kt % TPC) == 0 || kt == wa);
                 const uint32_t tc = first ? (uint32_t)(kt / TPC) * 16u : kOutOfRange;
-                st.chunk = __builtin_amdgcn_raw_buffer_load_b128(rS, tc + clane, 0, kAuxNone);
+                // seven of eight chunk loads would be out of range: an out-of-range load still costs its
+                // turn in the address unit (as much as the weight load itself), so they are branched
+                // around (the condition is uniform over the wave).  The shared-activation instances keep
+                // the unconditional form: there the extra control flow costs more than it saves.
+                if constexpr (XSH) st.chunk = __builtin_amdgcn_raw_buffer_load_b128(rS, tc + clane, 0, kAuxNone);
+                else if (first) st.chunk = __builtin_amdgcn_raw_buffer_load_b128(rS, tc + clane, 0, kAuxNone);
             } else {
                 const uint32_t ts = in ? (uint32_t)(kt / TPS) * (NS * 2) : kOutOfRange;
 #pragma unroll
