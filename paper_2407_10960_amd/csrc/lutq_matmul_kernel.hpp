@@ -408,14 +408,23 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                 }
             }
         } else {
-            for (int kt = wa; kt < wb; kt += P) {
+            // steady state while a further group of P tiles is left; the last tiles (they are already
+            // in flight) are computed without issuing prefetches beyond the wave's range, which would
+            // be out of range and return nothing but still take their turn in the address unit
+            int kt = wa;
+            for (; kt + P < wb; kt += P) {
 #pragma unroll
                 for (int q = 0; q < P; ++q) {
-                    if (q == 0 || kt + q < wb) compute_stage(st[q], kt + q, 0);
+                    compute_stage(st[q], kt + q, 0);
                     __builtin_amdgcn_sched_barrier(0);
                     load_stage(st[q], kt + q + P);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+            }
+#pragma unroll
+            for (int q = 0; q < P; ++q) {
+                if (kt + q < wb) compute_stage(st[q], kt + q, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
 
