@@ -81,6 +81,8 @@ struct Decomp {
 inline int steps_per_tile(int bits) { return bits == 4 ? 4 : 8; }
 // Activations can be shared through LDS when the teams are enough to stage a tile's pieces between them.
 inline bool teams_can_share_x(int bits, int mb, int rs) { return rs * kXPiecesPerWave >= steps_per_tile(bits) * mb; }
+// pieces of a tile each wave stages: one when there are as many teams as pieces, else two
+inline int x_pieces_per_wave(int bits, int mb, int rs) { return rs >= steps_per_tile(bits) * mb ? 1 : 2; }
 
 bool wide_exists(int bits, bool bf16, int r, int mb, int stages, int xm) {
     return matmul_instance_exists(bits, bf16, r, mb, stages, true, xm, true);
@@ -196,23 +198,34 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         std::vector<Cand> order = exact;
         order.insert(order.end(), shallow.begin(), shallow.end());
         order.insert(order.end(), deep.begin(), deep.end());
-        for (const Cand& c : order) {
+        const int np = steps_per_tile(bits) * mb;         // activation pieces of one tile
+        for (const Cand& c0 : order) {
+            Cand c = c0;
             const int64_t cols = c.exact ? K : c.sets * K / cus;      // columns of K per workgroup
             if (cols < 1536) continue;
-            int ks = c.rs >= 8 ? (c.exact ? 2 : 1) : 2;
-            while (ks > 1 && c.rs * ks > 16) --ks;
-            int nw = (int)c.rs * ks;
-            if (!matmul_instance_exists(bits, bf16, c.r, mb, 2, true, 16, nw > 8, true)) {
-                ks = (int)(8 / c.rs);
-                nw = (int)c.rs * ks;
-                if (ks < 1 || nw < 4 || !matmul_instance_exists(bits, bf16, c.r, mb, 2, true, 16, false, true)) continue;
+            // K cut across workgroups: twice the teams at R = 1 (one piece per wave where there are eight
+            // or more pieces) beat R = 2 (measured, 5-17 %); with eight or more pieces per tile R = 1
+            // runs best with four tiles in flight and one wave per team (3-bit: two tiles)
+            if (!c.exact && np >= 8 && c.r == 2 && 2 * c.rs <= 16) { c.r = 1; c.rs *= 2; }
+            const bool deep = c.r == 1 && np >= 8 && bits != 3;
+            const int xpw = x_pieces_per_wave(bits, mb, (int)c.rs);
+            int ks_first = deep ? 1 : (c.rs >= 8 ? (c.exact ? 2 : 1) : 2);
+            while (ks_first > 1 && c.rs * ks_first > 16) --ks_first;
+            int nw = 0, stages = 2;
+            for (int ks = ks_first; ks >= 1 && !nw; --ks) {          // fewer waves per team if the first choice does not fit
+                const int w = (int)c.rs * ks;
+                if (w < 4) break;
+                for (int st = deep ? 4 : 2; st >= 2 && !nw; st -= 2) {
+                    if (!matmul_instance_exists(bits, bf16, c.r, mb, st, true, 16, w > 8, xpw)) continue;
+                    const int lds = bits == 2 ? matmul_lds_bytes<2>(c.r, mb, w, (int)c.rs, true, true)
+                                  : bits == 3 ? matmul_lds_bytes<3>(c.r, mb, w, (int)c.rs, true, true)
+                                              : matmul_lds_bytes<4>(c.r, mb, w, (int)c.rs, true, true);
+                    if (lds > 160 * 1024) continue;
+                    nw = w; stages = st;
+                }
             }
-            if (nw < 4) continue;
-            const int lds = bits == 2 ? matmul_lds_bytes<2>(c.r, mb, nw, (int)c.rs, true, true)
-                          : bits == 3 ? matmul_lds_bytes<3>(c.r, mb, nw, (int)c.rs, true, true)
-                                      : matmul_lds_bytes<4>(c.r, mb, nw, (int)c.rs, true, true);
-            if (lds > 160 * 1024) continue;
-            d.r = c.r; d.grid = c.exact ? (int)c.sets : cus; d.nw = nw; d.rs = (int)c.rs;
+            if (!nw) continue;
+            d.r = c.r; d.grid = c.exact ? (int)c.sets : cus; d.nw = nw; d.rs = (int)c.rs; d.stages = stages;
             return d;
         }
         return d;
@@ -258,7 +271,7 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
     return d;
 }
 
-typedef hipError_t (*matmul_launcher)(int, int, int, int, bool, int, bool, bool, const MatmulParams&, hipStream_t);
+typedef hipError_t (*matmul_launcher)(int, int, int, int, bool, int, bool, int, const MatmulParams&, hipStream_t);
 typedef hipError_t (*dequant_launcher)(int, const DequantParams&, int, int, hipStream_t);
 
 matmul_launcher pick_matmul(int bits, lutq_dtype dt) {
@@ -319,7 +332,8 @@ namespace {
 struct Prepared {
     MatmulParams p;
     int mb, r, stages, xm;
-    bool sch, wide, xsh;
+    bool sch, wide;
+    int xsh;                  // 0, or activation pieces staged per wave (shared through LDS)
 };
 
 // Validates the arguments of one launch (M <= 32) and fills *out; launches nothing.
@@ -380,10 +394,11 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     // exists, so that two workgroups fit a compute unit
     // M > 4 with enough teams: the activations are staged in LDS once per workgroup instead of being
     // fetched by every team (LUTQ_NO_SHARED_X=1 switches that off, for comparisons)
-    bool xsh = M > 4 && sch && teams_can_share_x(bits, mb, d.rs) && !std::getenv("LUTQ_NO_SHARED_X");
+    int xsh = (M > 4 && sch && teams_can_share_x(bits, mb, d.rs) && !std::getenv("LUTQ_NO_SHARED_X"))
+                  ? x_pieces_per_wave(bits, mb, d.rs) : 0;
     bool wide = d.nw > 8 || (d.nw > 4 && sch && matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, true, xsh));
-    if (xsh && !matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, true)) {
-        xsh = false;
+    if (xsh && !matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, xsh)) {
+        xsh = 0;
         wide = d.nw > 8 || (d.nw > 4 && sch && wide_exists(bits, bf16, r, mb, d.stages, xm));
     }
     if (!matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, xsh)) return LUTQ_ERR_PLAN;
@@ -391,7 +406,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
                   : bits == 3 ? matmul_lds_bytes<3>(r, mb, d.nw, d.rs, sch, xsh)
                               : matmul_lds_bytes<4>(r, mb, d.nw, d.rs, sch, xsh);
     if (xsh && lds_bytes > 160 * 1024) {                  // the buffers do not fit: fetch per team
-        xsh = false;
+        xsh = 0;
         wide = d.nw > 8 || (d.nw > 4 && sch && wide_exists(bits, bf16, r, mb, d.stages, xm));
         if (!matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, false)) return LUTQ_ERR_PLAN;
         lds_bytes = bits == 2 ? matmul_lds_bytes<2>(r, mb, d.nw, d.rs, sch, false)

@@ -14,14 +14,14 @@ namespace lutq {
 
 namespace {
 
-template <int GROUP, int MB, int R, int P, bool SCH, int XM, bool WIDE, bool XSH>
+template <int GROUP, int MB, int R, int P, bool SCH, int XM, bool WIDE, int XSH>
 hipError_t launch_one(const MatmulParams& p, hipStream_t stream) {
     constexpr bool wide_table = Tab<LUTQ_INST_BITS, LUTQ_INST_DT>::WIDE;
     if constexpr (WIDE && !matmul_wide_fits<LUTQ_INST_BITS>(R, MB, P, XM, wide_table, XSH)) {
         return hipErrorInvalidValue;         // would not fit 128 registers: not instantiated
     } else {
         auto kernel = matmul_kernel<LUTQ_INST_BITS, GROUP, MB, R, LUTQ_INST_DT, P, SCH, XM, WIDE, XSH>;
-        const int lds_bytes = matmul_lds_bytes<LUTQ_INST_BITS>(R, MB, p.NW, p.RS, SCH, XSH);
+        const int lds_bytes = matmul_lds_bytes<LUTQ_INST_BITS>(R, MB, p.NW, p.RS, SCH, XSH != 0);
         if (lds_bytes > 64 * 1024) {
             // more than 64 KiB of dynamic LDS has to be enabled once per kernel
             static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -33,34 +33,42 @@ hipError_t launch_one(const MatmulParams& p, hipStream_t stream) {
     }
 }
 
+// xsh: 0 = every wave fetches its own activations; 1 or 2 = activations shared through LDS, that many
+// pieces of a tile staged per wave
+template <int GROUP, int MB, int R, int P, int XSH>
+hipError_t launch_shared(bool wide, const MatmulParams& p, hipStream_t stream) {
+    return wide ? launch_one<GROUP, MB, R, P, true, 16, true, XSH>(p, stream)
+                : launch_one<GROUP, MB, R, P, true, 16, false, XSH>(p, stream);
+}
+
 template <int GROUP, int MB, int R, int XM>
-hipError_t launch_r(int stages, bool sch, bool wide, bool xsh, const MatmulParams& p, hipStream_t stream) {
+hipError_t launch_r(int stages, bool sch, bool wide, int xsh, const MatmulParams& p, hipStream_t stream) {
     if constexpr (XM == 16) {
         // activations shared through LDS: chunked scales
         if (xsh) {
             if (!sch) return hipErrorInvalidValue;
-            if (stages == 2) return wide ? launch_one<GROUP, MB, R, 2, true, 16, true, true>(p, stream)
-                                         : launch_one<GROUP, MB, R, 2, true, 16, false, true>(p, stream);
-            if (stages == 4) return wide ? launch_one<GROUP, MB, R, 4, true, 16, true, true>(p, stream)
-                                         : launch_one<GROUP, MB, R, 4, true, 16, false, true>(p, stream);
+            if (stages == 2 && xsh == 1) return launch_shared<GROUP, MB, R, 2, 1>(wide, p, stream);
+            if (stages == 2 && xsh == 2) return launch_shared<GROUP, MB, R, 2, 2>(wide, p, stream);
+            if (stages == 4 && xsh == 1) return launch_shared<GROUP, MB, R, 4, 1>(wide, p, stream);
+            if (stages == 4 && xsh == 2) return launch_shared<GROUP, MB, R, 4, 2>(wide, p, stream);
             return hipErrorInvalidValue;
         }
     } else if (xsh) {
         return hipErrorInvalidValue;
     }
-    if (!sch) return (!wide && stages == 2) ? launch_one<GROUP, MB, R, 2, false, XM, false, false>(p, stream) : hipErrorInvalidValue;
+    if (!sch) return (!wide && stages == 2) ? launch_one<GROUP, MB, R, 2, false, XM, false, 0>(p, stream) : hipErrorInvalidValue;
     if (wide) {
-        if (stages == 2) return launch_one<GROUP, MB, R, 2, true, XM, true, false>(p, stream);
-        if (stages == 4) return launch_one<GROUP, MB, R, 4, true, XM, true, false>(p, stream);
+        if (stages == 2) return launch_one<GROUP, MB, R, 2, true, XM, true, 0>(p, stream);
+        if (stages == 4) return launch_one<GROUP, MB, R, 4, true, XM, true, 0>(p, stream);
     } else {
-        if (stages == 2) return launch_one<GROUP, MB, R, 2, true, XM, false, false>(p, stream);
-        if (stages == 4) return launch_one<GROUP, MB, R, 4, true, XM, false, false>(p, stream);
+        if (stages == 2) return launch_one<GROUP, MB, R, 2, true, XM, false, 0>(p, stream);
+        if (stages == 4) return launch_one<GROUP, MB, R, 4, true, XM, false, 0>(p, stream);
     }
     return hipErrorInvalidValue;
 }
 
 template <int GROUP>
-hipError_t launch_group(int mb, int r, int stages, bool sch, int xm, bool wide, bool xsh, const MatmulParams& p, hipStream_t stream) {
+hipError_t launch_group(int mb, int r, int stages, bool sch, int xm, bool wide, int xsh, const MatmulParams& p, hipStream_t stream) {
     if (mb == 1 && xm == 4) {
         if (r == 1) return launch_r<GROUP, 1, 1, 4>(stages, sch, wide, xsh, p, stream);
         if (r == 2) return launch_r<GROUP, 1, 2, 4>(stages, sch, wide, xsh, p, stream);
@@ -86,7 +94,7 @@ hipError_t launch_dq(const DequantParams& p, int grid, int lds_bytes, hipStream_
 }  // namespace
 
 hipError_t LUTQ_NAME(launch_matmul_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int r, int stages, bool sch,
-                                                                    int xm, bool wide, bool xsh,
+                                                                    int xm, bool wide, int xsh,
                                                                     const MatmulParams& p, hipStream_t stream) {
     switch (group) {
         case 32: return launch_group<32>(mb, r, stages, sch, xm, wide, xsh, p, stream);

@@ -11,8 +11,9 @@ namespace lutq {
 // Kernel instances that exist.  `wide` instances run up to 16 waves per workgroup within 128
 // registers and exist only where the register estimate fits; the others run up to 8 waves.  The
 // per-tile scale path (K/group not a multiple of 8) exists for 2 tiles in flight, not wide.
+// xsh: 0, or the number of activation pieces a wave stages (1 or 2) in a shared-activation instance
 inline bool matmul_instance_exists(int bits, bool bf16, int r, int mb, int stages, bool sch, int xm, bool wide,
-                                   bool xsh = false) {
+                                   int xsh = 0) {
     const bool wt = bf16 && bits != 2;                  // widened table: a larger lookup ring
     if (xsh && (xm != 16 || !sch)) return false;
     if (stages != 2 && stages != 4) return false;
@@ -28,7 +29,7 @@ inline bool matmul_instance_exists(int bits, bool bf16, int r, int mb, int stage
 
 #define LUTQ_DECLARE_LAUNCHERS(B, DT)                                                               \
     hipError_t launch_matmul_b##B##_##DT(int group, int mb, int r, int stages, bool sch, int xm,     \
-                                         bool wide, bool xsh, const MatmulParams& p,                 \
+                                         bool wide, int xsh, const MatmulParams& p,                  \
                                          hipStream_t stream);                                        \
     hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes, \
                                           hipStream_t stream);

@@ -73,7 +73,7 @@ __device__ __forceinline__ int owner_of(int t, int tq, int tr) {
 // [table, 256-byte entry stride][one partial-sum slot per team][one 1 KiB scale-chunk area per wave]
 __host__ __device__ constexpr int red_bytes(int nreg, int rs) { return nreg * 256 * rs; }
 // Activation pieces: one piece is the B operand of one (K step, 16-row half of M) = 64 lanes x 16 bytes.
-constexpr int kXPiecesPerWave = 2;       // pieces of a tile that one wave stages (shared-activation instances)
+constexpr int kXPiecesPerWave = 2;       // most pieces of a tile that one wave stages (shared-activation instances)
 template <int BITS>
 __host__ __device__ constexpr int x_pieces(int mb) { return Geo<BITS>::STEPS * mb; }
 // offset of the shared activation buffers = end of the other areas
@@ -90,17 +90,17 @@ __host__ __device__ constexpr int matmul_lds_bytes(int r, int mb, int nw, int rs
 // Rough count of the registers live in the K loop (tiles in flight, accumulators, lookup ring,
 // addresses): decides which instances can be held to 128 registers, i.e. four waves per SIMD.
 template <int BITS>
-__host__ __device__ constexpr int matmul_reg_estimate(int r, int mb, int p, int xm, bool wide_table, bool xsh) {
+__host__ __device__ constexpr int matmul_reg_estimate(int r, int mb, int p, int xm, bool wide_table, int xsh) {
     const int wregs = BITS == 3 ? 6 : 4;
     const int xl = Geo<BITS>::STEPS * xm / 16;
     const int na = xm == 16 ? mb : 16 / xm;               // accumulators per row block
     // activations in flight per tile: the wave's own fragments, or its share of the staged pieces
     // (plus two steps' worth of operands read back from LDS)
-    const int xregs = xsh ? kXPiecesPerWave * 4 : xl * mb * 4;
+    const int xregs = xsh ? xsh * 4 : xl * mb * 4;
     return p * (r * wregs + xregs + 4) + (xsh ? 2 * mb * 4 : 0) + r * na * 4 + 46 + (wide_table ? 12 : 0);
 }
 template <int BITS>
-__host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm, bool wide_table, bool xsh) {
+__host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm, bool wide_table, int xsh) {
     return matmul_reg_estimate<BITS>(r, mb, p, xm, wide_table, xsh) <= 124;
 }
 
@@ -127,9 +127,11 @@ __host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm
 // ahead, double buffered, and every wave reads its B operands from there; one workgroup barrier per
 // tile keeps writers and readers apart, and every wave runs the same number of rounds.
 // The number of waves and their arrangement in teams are run-time values.
-template <int BITS, int GROUP, int MB, int R, typename DT, int P, bool SCH, int XM, bool WIDE, bool XSH>
+template <int BITS, int GROUP, int MB, int R, typename DT, int P, bool SCH, int XM, bool WIDE, int XPIECES>
 __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulParams p) {
     static_assert(XM == 16 || (XM == 4 && MB == 1), "packed activation loads exist for M <= 4 only");
+    constexpr bool XSH = XPIECES != 0;       // activations shared through LDS; XPIECES = pieces one wave stages (1 or 2)
+    static_assert(XPIECES >= 0 && XPIECES <= kXPiecesPerWave, "a wave stages one or two pieces");
     static_assert(!XSH || XM == 16, "activations are shared through LDS in the plain layout only");
     using Gm = Geo<BITS>;
     constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
@@ -147,7 +149,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
     constexpr int XL = STEPS / XS;           // activation loads per tile (per 16-row half of M)
     constexpr int NA = XM == 16 ? MB : XS;   // accumulators per row block: M halves, or step positions
     constexpr int NP = STEPS * MB;           // activation pieces (K step, M half) of one tile, 1 KiB each
-    constexpr int XPW = kXPiecesPerWave;     // pieces one wave stages (RS * XPW >= NP is checked on the host)
+    constexpr int XPW = XSH ? XPIECES : 1;   // pieces one wave stages (RS * XPW >= NP is checked on the host)
     constexpr int NX = XSH ? XPW : XL;       // activation loads per tile held in a stage
     constexpr int NXM = XSH ? 1 : MB;
 
