@@ -134,6 +134,20 @@ lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scal
                              void* workspace, size_t workspace_bytes, void* stream,
                              const lutq_plan* plan);
 
+/* Finer-grained tables: one table per output row (Section 2.3: lookup tables obtained at the
+ * output-channel level; Section 5 names flexible tables as what the kernel is for).
+ *        W^[n, k] = round16( T[n][Q[n, k]] * S[n, k / group_size] )
+ *   luts    device, [N, 2^bits] row-major, dtype, 16-byte aligned
+ *   every other argument as in lutq_matmul (scales of 1.0 give tables without group scales).
+ * A workgroup holds the tables of one 16-row block at a time and rebuilds its on-chip copies for
+ * every row block it works on, so each call costs one table build per row block instead of one per
+ * workgroup; the work decomposition is fixed (one row block per workgroup, K split over its waves
+ * and, for few row blocks, over workgroups).  Errors: those of lutq_matmul. */
+lutq_status lutq_matmul_channel(const void* X, const void* packed, const void* scales, const void* luts,
+                                int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                lutq_dtype dtype, void* Y,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 /* Instance selection by measurement (Section 4.1: the fastest kernel configuration is picked per
  * shape; Section 3.3: how the K range is cut across workgroups is part of that choice).  Times the
  * default plan and the candidate plans that lutq_tune_candidates lists, first with a few launches

@@ -272,6 +272,21 @@ def dequant(Q, T_bits, S_bits, group_size: int, dtype: str) -> np.ndarray:
     return from_f64(prod, dtype)
 
 
+def dequant_channel(Q, Tn_bits, S_bits, group_size: int, dtype: str) -> np.ndarray:
+    """One table per output row (Section 2.3: lookup tables at the output-channel level):
+    W^[n,k] = round16( T[n, Q[n,k]] * S[n, k // B] ), Tn_bits of shape [N, 2^b]."""
+    Q = np.asarray(Q)
+    N, K = Q.shape
+    T = to_f64(Tn_bits, dtype)
+    S = to_f64(S_bits, dtype)
+    if T.shape[0] != N or S.shape != (N, K // group_size):
+        raise ValueError("table shape must be [N, 2^b] and scale shape [N, K / group_size]")
+    W = np.empty((N, K), dtype=np.float64)
+    for n in range(N):
+        W[n] = T[n][Q[n]]
+    return from_f64(W * np.repeat(S, group_size, axis=1), dtype)
+
+
 def matmul_f64(X_bits, What_bits, dtype: str) -> np.ndarray:
     """Y[m,n] = sum_k X[m,k] * W^[n,k] in float64; not rounded."""
     X = to_f64(X_bits, dtype)

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     load_library,
     lutq_dequant,
     lutq_matmul,
+    lutq_matmul_channel,
     lutq_pack,
     lutq_packed_bytes,
     lutq_plan_default,

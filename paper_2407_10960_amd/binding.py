@@ -12,7 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "lutq_status_string", "lutq_packed_bytes", "lutq_pack", "lutq_unpack", "lutq_workspace_bytes",
-    "lutq_plan_default", "lutq_matmul", "lutq_matmul_plan", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
+    "lutq_plan_default", "lutq_matmul", "lutq_matmul_plan", "lutq_matmul_channel", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
     "lutq_calib_stream_read", "lutq_calib_copy",
 )
 
@@ -77,6 +77,8 @@ def load_library():
     lib.lutq_matmul_plan.restype = ci
     lib.lutq_matmul_plan.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp,
                                      ctypes.POINTER(_CPlan)]
+    lib.lutq_matmul_channel.restype = ci
+    lib.lutq_matmul_channel.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.lutq_tune.restype = ci
     lib.lutq_tune.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, ci, ci, i64, i64, i64, ci, vp, vp,
                               sz, vp, ci, ctypes.POINTER(_CPlan), ctypes.POINTER(ctypes.c_float)]
@@ -203,6 +205,27 @@ def lutq_matmul(X, packed, scales, lut, bits: int, group_size: int, Y, workspace
     else:
         cp = plan._c()
         _check(lib.lutq_matmul_plan(*args, ctypes.byref(cp)), "lutq_matmul_plan")
+    return Y
+
+
+def lutq_matmul_channel(X, packed, scales, luts, bits: int, group_size: int, Y, workspace, stream=None):
+    """lutq_matmul with one table per output row: luts is [N, 2^bits]."""
+    lib = load_library()
+    for t in (X, packed, scales, luts, Y, workspace):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("lutq_matmul_channel needs contiguous CUDA (HIP) tensors")
+    code = _dtype_code(X)
+    if not (_dtype_code(scales) == code and _dtype_code(luts) == code and _dtype_code(Y) == code):
+        raise TypeError("X, scales, luts and Y must share one dtype")
+    M, K = X.shape
+    N = scales.shape[0]
+    if scales.shape[1] * group_size != K or tuple(Y.shape) != (M, N) or tuple(luts.shape) != (N, 1 << bits):
+        raise ValueError("inconsistent shapes")
+    if packed.numel() != lib.lutq_packed_bytes(N, K, bits, group_size):
+        raise ValueError("packed buffer has the wrong size for (N, K, bits)")
+    _check(lib.lutq_matmul_channel(X.data_ptr(), packed.data_ptr(), scales.data_ptr(), luts.data_ptr(), bits, group_size,
+                                   M, N, K, code, Y.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream)), "lutq_matmul_channel")
     return Y
 
 

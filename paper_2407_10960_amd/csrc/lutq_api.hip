@@ -278,6 +278,11 @@ matmul_launcher pick_matmul(int bits, lutq_dtype dt) {
     if (dt == LUTQ_F16) return bits == 2 ? launch_matmul_b2_F16 : bits == 3 ? launch_matmul_b3_F16 : launch_matmul_b4_F16;
     return bits == 2 ? launch_matmul_b2_BF16 : bits == 3 ? launch_matmul_b3_BF16 : launch_matmul_b4_BF16;
 }
+typedef hipError_t (*rowlut_launcher)(int, int, bool, int, const MatmulParams&, hipStream_t);
+rowlut_launcher pick_rowlut(int bits, lutq_dtype dt) {
+    if (dt == LUTQ_F16) return bits == 2 ? launch_matmul_rowlut_b2_F16 : bits == 3 ? launch_matmul_rowlut_b3_F16 : launch_matmul_rowlut_b4_F16;
+    return bits == 2 ? launch_matmul_rowlut_b2_BF16 : bits == 3 ? launch_matmul_rowlut_b3_BF16 : launch_matmul_rowlut_b4_BF16;
+}
 dequant_launcher pick_dequant(int bits, lutq_dtype dt) {
     if (dt == LUTQ_F16) return bits == 2 ? launch_dequant_b2_F16 : bits == 3 ? launch_dequant_b3_F16 : launch_dequant_b4_F16;
     return bits == 2 ? launch_dequant_b2_BF16 : bits == 3 ? launch_dequant_b3_BF16 : launch_dequant_b4_BF16;
@@ -334,13 +339,14 @@ struct Prepared {
     int mb, r, stages, xm;
     bool sch, wide;
     int xsh;                  // 0, or activation pieces staged per wave (shared through LDS)
+    bool rowlut;              // p.lut holds one table per output row
 };
 
 // Validates the arguments of one launch (M <= 32) and fills *out; launches nothing.
 lutq_status prepare_matmul(const void* X, const void* packed, const void* scales, const void* lut,
                            int bits, int group_size, int64_t M, int64_t N, int64_t K,
                            lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
-                           const lutq_plan* user_plan, Prepared* out) {
+                           const lutq_plan* user_plan, bool rowlut, Prepared* out) {
     if (!X || !packed || !scales || !lut || !Y) return LUTQ_ERR_NULL;
     lutq_status st = check_problem(bits, group_size, N, K);
     if (st != LUTQ_OK) return st;
@@ -348,7 +354,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
     if (!aligned16(X) || !aligned16(packed) || !aligned16(scales) || !aligned16(Y) || !aligned16(workspace))
         return LUTQ_ERR_ALIGN;
-    if ((reinterpret_cast<uintptr_t>(lut) & 1u) != 0) return LUTQ_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(lut) & 1u) != 0 || (rowlut && !aligned16(lut))) return LUTQ_ERR_ALIGN;
     if (!workspace || workspace_bytes < kWorkspaceBytes) return LUTQ_ERR_WORKSPACE;
 
     DeviceInfo di = device_info();
@@ -370,6 +376,20 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         if (user_plan->grid != 0 && (user_plan->grid < 1 || user_plan->grid > kMaxGrid)) return LUTQ_ERR_PLAN;
     }
     Decomp d = default_decomp(bits, bf16, sch, M, N, K, di.cus, force_r);
+    if (rowlut) {
+        // one table per output row: a workgroup holds the tables of one row block at a time, so one
+        // row block per workgroup, its K range split over eight waves, and over several workgroups
+        // when there are fewer row blocks than compute units
+        int64_t grid = nb;
+        if (nb < (int64_t)di.cus * 6 / 10) {
+            int64_t j = (di.cus + nb - 1) / nb;
+            if (j > kt / 4) j = kt / 4;
+            if (j < 1) j = 1;
+            grid = nb * j;
+        }
+        if (grid > kMaxGrid) grid = kMaxGrid;
+        d.r = 1; d.rs = 1; d.nw = 8; d.stages = 2; d.grid = (int)grid;
+    }
     if (user_plan) {
         // a field the caller fixes replaces the default; teams and waves default to one team of the
         // default number of waves once anything about the workgroup's shape is fixed by the caller
@@ -394,7 +414,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     // exists, so that two workgroups fit a compute unit
     // M > 4 with enough teams: the activations are staged in LDS once per workgroup instead of being
     // fetched by every team (LUTQ_NO_SHARED_X=1 switches that off, for comparisons)
-    int xsh = (M > 4 && sch && teams_can_share_x(bits, mb, d.rs) && !std::getenv("LUTQ_NO_SHARED_X"))
+    int xsh = (!rowlut && M > 4 && sch && teams_can_share_x(bits, mb, d.rs) && !std::getenv("LUTQ_NO_SHARED_X"))
                   ? x_pieces_per_wave(bits, mb, d.rs) : 0;
     bool wide = d.nw > 8 || (d.nw > 4 && sch && matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, true, xsh));
     if (xsh && !matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, xsh)) {
@@ -445,13 +465,14 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
                      d.nw, d.rs, p.KS, d.stages, (int)wide, xm, (int)xsh, lds_bytes);
     out->p = p;
     out->mb = mb; out->r = r; out->stages = d.stages; out->xm = xm;
-    out->sch = sch; out->wide = wide; out->xsh = xsh;
+    out->sch = sch; out->wide = wide; out->xsh = xsh; out->rowlut = rowlut;
     return LUTQ_OK;
 }
 
 lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dtype dtype, void* stream) {
-    hipError_t e = pick_matmul(bits, dtype)(group_size, q.mb, q.r, q.stages, q.sch, q.xm, q.wide, q.xsh, q.p,
-                                            static_cast<hipStream_t>(stream));
+    hipError_t e = q.rowlut ? pick_rowlut(bits, dtype)(group_size, q.mb, q.sch, q.xm, q.p, static_cast<hipStream_t>(stream))
+                            : pick_matmul(bits, dtype)(group_size, q.mb, q.r, q.stages, q.sch, q.xm, q.wide, q.xsh, q.p,
+                                                       static_cast<hipStream_t>(stream));
     if (e != hipSuccess && std::getenv("LUTQ_VERBOSE"))
         std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d)\n", hipGetErrorString(e), q.p.G, q.p.NW * 64);
     return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
@@ -459,10 +480,12 @@ lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dt
 
 }  // namespace
 
-extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scales, const void* lut,
-                                        int bits, int group_size, int64_t M, int64_t N, int64_t K,
-                                        lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
-                                        void* stream, const lutq_plan* user_plan) {
+namespace {
+
+lutq_status matmul_sliced(const void* X, const void* packed, const void* scales, const void* lut,
+                          int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                          lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
+                          void* stream, const lutq_plan* user_plan, bool rowlut) {
     if (!X || !Y) return LUTQ_ERR_NULL;
     if (M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
     // More than 32 activation rows: slices of 32 rows, one launch each on the same stream (the
@@ -472,13 +495,13 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
     const size_t xrow = (size_t)K * 2, yrow = (size_t)N * 2;
     if (full > 0) {
         lutq_status st = prepare_matmul(X, packed, scales, lut, bits, group_size, 32, N, K, dtype, Y, workspace,
-                                        workspace_bytes, user_plan, &body);
+                                        workspace_bytes, user_plan, rowlut, &body);
         if (st != LUTQ_OK) return st;
     }
     if (rest > 0) {
         lutq_status st = prepare_matmul(static_cast<const char*>(X) + (size_t)full * 32 * xrow, packed, scales, lut, bits,
                                         group_size, rest, N, K, dtype, static_cast<char*>(Y) + (size_t)full * 32 * yrow,
-                                        workspace, workspace_bytes, user_plan, &tail);
+                                        workspace, workspace_bytes, user_plan, rowlut, &tail);
         if (st != LUTQ_OK) return st;
     }
     for (int64_t i = 0; i < full; ++i) {
@@ -489,6 +512,24 @@ extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const
         if (st != LUTQ_OK) return st;
     }
     return rest > 0 ? launch_prepared(tail, bits, group_size, dtype, stream) : LUTQ_OK;
+}
+
+}  // namespace
+
+extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scales, const void* lut,
+                                        int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                        lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
+                                        void* stream, const lutq_plan* user_plan) {
+    return matmul_sliced(X, packed, scales, lut, bits, group_size, M, N, K, dtype, Y, workspace, workspace_bytes,
+                         stream, user_plan, false);
+}
+
+extern "C" lutq_status lutq_matmul_channel(const void* X, const void* packed, const void* scales, const void* luts,
+                                           int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                           lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
+                                           void* stream) {
+    return matmul_sliced(X, packed, scales, luts, bits, group_size, M, N, K, dtype, Y, workspace, workspace_bytes,
+                         stream, nullptr, true);
 }
 
 extern "C" lutq_status lutq_matmul(const void* X, const void* packed, const void* scales, const void* lut,

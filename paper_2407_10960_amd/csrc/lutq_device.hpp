@@ -156,6 +156,74 @@ __device__ __forceinline__ void build_lut(char* lds, const uint16_t* __restrict_
     lut_build<BITS, DT>(lds, s, log2c, tid, ltpe);
 }
 
+// ---------------------------------------------------------------------------------------
+// One table per output row (finer-grained tables: every output channel has its own 2^b values).
+// A lane only ever looks up indices of one row of a row block (row lane % 16), so its private copy of
+// the table can simply hold that row's table and the lookup code does not change.  The copies of a
+// row block are rebuilt whenever a workgroup moves to another row block: every lane fetches its
+// row's 2^b values (rowlut_fetch, issued before the weight prefetch), then the waves deal the
+// entries between them by their upper index (wave w takes upper indices w, w + nw, w + 2 nw, w + 3 nw;
+// nw >= 4) and each lane writes its own copy of those entries (rowlut_build).  Entry contents and
+// the 256-byte entry stride are those of lut_build.
+// ---------------------------------------------------------------------------------------
+struct RowTab { u32x4 a, b; };           // the row's 2^b 16-bit values, two per word
+
+template <int BITS>
+__device__ __forceinline__ RowTab rowlut_fetch(const uint16_t* __restrict__ T, int64_t row) {
+    RowTab t;
+    t.a = u32x4{0, 0, 0, 0}; t.b = t.a;
+    const uint16_t* src = T + row * (1 << BITS);
+    if constexpr (BITS == 4) {
+        t.a = *reinterpret_cast<const u32x4*>(src);
+        t.b = *reinterpret_cast<const u32x4*>(src + 8);
+    } else if constexpr (BITS == 3) {
+        t.a = *reinterpret_cast<const u32x4*>(src);
+    } else {
+        const u32x2 v = *reinterpret_cast<const u32x2*>(src);
+        t.a.x = v.x; t.a.y = v.y;
+    }
+    return t;
+}
+
+template <int BITS, typename DT>
+__device__ __forceinline__ void rowlut_build(char* lds, const RowTab& t, int wave, int nw, int lane) {
+    auto val = [&](int q) -> uint32_t {                   // value q of the row's table (q is a constant)
+        const uint32_t w = q / 2 < 4 ? t.a[q / 2] : t.b[q / 2 - 4];
+        return (q & 1) ? (w >> 16) : (w & 0xffffu);
+    };
+    const int w1 = wave + nw, w2 = wave + 2 * nw, w3 = wave + 3 * nw;
+    constexpr bool WIDE = Tab<BITS, DT>::WIDE;
+    constexpr int UPPER = BITS == 3 ? 8 : 16;             // upper indices (4-bit: q1; 3-bit: q1; 2-bit: (q3, q2))
+    constexpr int LOWER = BITS == 3 ? 8 : 16;
+#pragma unroll
+    for (int hi = 0; hi < UPPER; ++hi) {
+        if (!(hi == wave || hi == w1 || hi == w2 || hi == w3)) continue;
+#pragma unroll
+        for (int lo = 0; lo < LOWER; ++lo) {
+            if constexpr (BITS == 4) {
+                const int e = lo | (hi << 4);
+                if constexpr (WIDE) {
+                    if (lane < 32) *reinterpret_cast<u32x2*>(lds + e * 256 + lane * 8) = u32x2{val(lo) << 16, val(hi) << 16};
+                } else {
+                    *reinterpret_cast<uint32_t*>(lds + e * 256 + lane * 4) = val(lo) | (val(hi) << 16);
+                }
+            } else if constexpr (BITS == 3) {
+                const int e = (lo & 3) | ((hi & 3) << 2) | ((lo >> 2) << 4) | ((hi >> 2) << 5);
+                if constexpr (WIDE) {
+                    if (lane < 32) *reinterpret_cast<u32x2*>(lds + e * 256 + lane * 8) = u32x2{val(lo) << 16, val(hi) << 16};
+                } else {
+                    *reinterpret_cast<uint32_t*>(lds + e * 256 + lane * 4) = val(lo) | (val(hi) << 16);
+                }
+            } else {
+                const int e = lo | (hi << 4);
+                if (lane < 32)
+                    *reinterpret_cast<u32x2*>(lds + e * 256 + lane * 8) =
+                        u32x2{val(lo & 3) | (val((lo >> 2) & 3) << 16), val(hi & 3) | (val((hi >> 2) & 3) << 16)};
+            }
+        }
+    }
+}
+
 template <int BITS, typename DT>
 __host__ __device__ constexpr int lut_lds_bytes(int log2c) {
     return (Geo<BITS>::ENTRIES * Tab<BITS, DT>::ENTRY_BYTES) << log2c;

@@ -85,6 +85,31 @@ hipError_t launch_group(int mb, int r, int stages, bool sch, int xm, bool wide, 
     return hipErrorInvalidValue;
 }
 
+// One table per output row: R = 1, one team, two tiles in flight; the 128-register build where it fits.
+template <int GROUP, int MB, int XM, bool SCH>
+hipError_t launch_rowlut_one(const MatmulParams& p, hipStream_t stream) {
+    constexpr bool wide_table = Tab<LUTQ_INST_BITS, LUTQ_INST_DT>::WIDE;
+    constexpr bool WIDE = SCH && matmul_wide_fits<LUTQ_INST_BITS>(1, MB, 2, XM, wide_table, 0);
+    auto kernel = matmul_kernel<LUTQ_INST_BITS, GROUP, MB, 1, LUTQ_INST_DT, 2, SCH, XM, WIDE, 0, true>;
+    const int lds_bytes = matmul_lds_bytes<LUTQ_INST_BITS>(1, MB, p.NW, p.RS, SCH, false);
+    if (p.RS != 1 || p.NW > (WIDE ? 16 : 8)) return hipErrorInvalidValue;
+    if (lds_bytes > 64 * 1024) {
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr != hipSuccess) return attr;
+    }
+    hipLaunchKernelGGL(kernel, dim3(p.G), dim3(p.NW * 64), lds_bytes, stream, p);
+    return hipGetLastError();
+}
+
+template <int GROUP>
+hipError_t launch_rowlut(int mb, int xm, bool sch, const MatmulParams& p, hipStream_t stream) {
+    if (mb == 1 && xm == 4) return sch ? launch_rowlut_one<GROUP, 1, 4, true>(p, stream) : launch_rowlut_one<GROUP, 1, 4, false>(p, stream);
+    if (mb == 1 && xm == 16) return sch ? launch_rowlut_one<GROUP, 1, 16, true>(p, stream) : launch_rowlut_one<GROUP, 1, 16, false>(p, stream);
+    if (mb == 2 && xm == 16) return sch ? launch_rowlut_one<GROUP, 2, 16, true>(p, stream) : launch_rowlut_one<GROUP, 2, 16, false>(p, stream);
+    return hipErrorInvalidValue;
+}
+
 template <int GROUP>
 hipError_t launch_dq(const DequantParams& p, int grid, int lds_bytes, hipStream_t stream) {
     hipLaunchKernelGGL((dequant_kernel<LUTQ_INST_BITS, GROUP, LUTQ_INST_DT>), dim3(grid), dim3(256), lds_bytes, stream, p);
@@ -101,6 +126,17 @@ hipError_t LUTQ_NAME(launch_matmul_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, i
         case 64: return launch_group<64>(mb, r, stages, sch, xm, wide, xsh, p, stream);
         case 128: return launch_group<128>(mb, r, stages, sch, xm, wide, xsh, p, stream);
         case 256: return launch_group<256>(mb, r, stages, sch, xm, wide, xsh, p, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t LUTQ_NAME(launch_matmul_rowlut_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, bool sch, int xm,
+                                                                           const MatmulParams& p, hipStream_t stream) {
+    switch (group) {
+        case 32: return launch_rowlut<32>(mb, xm, sch, p, stream);
+        case 64: return launch_rowlut<64>(mb, xm, sch, p, stream);
+        case 128: return launch_rowlut<128>(mb, xm, sch, p, stream);
+        case 256: return launch_rowlut<256>(mb, xm, sch, p, stream);
     }
     return hipErrorInvalidValue;
 }

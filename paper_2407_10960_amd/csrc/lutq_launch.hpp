@@ -31,6 +31,8 @@ inline bool matmul_instance_exists(int bits, bool bf16, int r, int mb, int stage
     hipError_t launch_matmul_b##B##_##DT(int group, int mb, int r, int stages, bool sch, int xm,     \
                                          bool wide, int xsh, const MatmulParams& p,                  \
                                          hipStream_t stream);                                        \
+    hipError_t launch_matmul_rowlut_b##B##_##DT(int group, int mb, bool sch, int xm, const MatmulParams& p, \
+                                                hipStream_t stream);                                 \
     hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes, \
                                           hipStream_t stream);
 

@@ -127,12 +127,13 @@ __host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm
 // ahead, double buffered, and every wave reads its B operands from there; one workgroup barrier per
 // tile keeps writers and readers apart, and every wave runs the same number of rounds.
 // The number of waves and their arrangement in teams are run-time values.
-template <int BITS, int GROUP, int MB, int R, typename DT, int P, bool SCH, int XM, bool WIDE, int XPIECES>
+template <int BITS, int GROUP, int MB, int R, typename DT, int P, bool SCH, int XM, bool WIDE, int XPIECES, bool RLUT = false>
 __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulParams p) {
     static_assert(XM == 16 || (XM == 4 && MB == 1), "packed activation loads exist for M <= 4 only");
     constexpr bool XSH = XPIECES != 0;       // activations shared through LDS; XPIECES = pieces one wave stages (1 or 2)
     static_assert(XPIECES >= 0 && XPIECES <= kXPiecesPerWave, "a wave stages one or two pieces");
     static_assert(!XSH || XM == 16, "activations are shared through LDS in the plain layout only");
+    static_assert(!RLUT || (R == 1 && !XSH), "one table per output row: one row block per workgroup at a time");
     using Gm = Geo<BITS>;
     constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
     constexpr int TPS = GROUP > TK ? GROUP / TK : 1;   // tiles that share one scale (a group longer than a tile)
@@ -173,7 +174,9 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
     float* red = reinterpret_cast<float*>(smem + LUT_BYTES) + team * (NREG * 64);   // this team's slot
     char* sc_lds = smem + LUT_BYTES + red_bytes(NREG, p.RS) + wave * 1024;         // this wave's 64 rows x 16 B
 
-    const LutSeed lut_seed = lut_fetch<BITS>(p.lut, tid, p.lut_ltpe);   // issued before any weight load (see below)
+    // issued before any weight load (see below); with one table per row the table is fetched per row block
+    LutSeed lut_seed{};
+    if constexpr (!RLUT) lut_seed = lut_fetch<BITS>(p.lut, tid, p.lut_ltpe);
     __builtin_amdgcn_sched_barrier(0);
     const LutAddr la = make_lut_addr<BITS, DT>(lut, LOG2C, lane);
     bool lut_ready = false;
@@ -363,6 +366,13 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
 
         // The scheduling barriers keep the loads of different stages in program order, so that the
         // wait before a stage's first use only has to cover that stage's own loads.
+        RowTab rowtab{};
+        if constexpr (RLUT) {
+            // this lane's row of the new row block (one team: rg is the row block); issued before the
+            // tile prefetch so that waiting for it does not wait for the tiles
+            rowtab = rowlut_fetch<BITS>(p.lut, (int64_t)rg * 16 + li);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         Stage st[P];
         u32x4 xfirst[XPW];                              // XSH: this wave's pieces of the segment's first tile
         if constexpr (XSH) {
@@ -377,7 +387,14 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             load_stage(st[q], wa + q);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (!lut_ready) {
+        if constexpr (RLUT) {
+            // every wave has left the K loop of the previous row block (the reduction's barriers lie in
+            // between), so the copies can be overwritten with this row block's tables
+            asm volatile("" : "+v"(rowtab.a), "+v"(rowtab.b));
+            rowlut_build<BITS, DT>(lut, rowtab, wave, p.NW, lane);
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+        } else if (!lut_ready) {
             // first segment: the table is built while the first tiles are in flight (its own reads
             // of T were issued before them, so waiting for T does not wait for the tiles)
             // (the empty statement keeps the wait for T, and the arithmetic on it, from being hoisted

@@ -381,6 +381,55 @@ def test_bad_plan_is_rejected_and_y_untouched(lutq):
     assert (Y == 7.0).all().item()
 
 
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_one_table_per_output_row(lutq, bits, dtype):
+    """lutq_matmul_channel (Section 2.3: tables at the output-channel level) against the oracle: one-hot
+    activations read the dequantised weights back bit for bit, products match for every M class, group
+    sizes with the chunked and the per-tile scale path, row counts that make one workgroup walk several
+    row blocks and K ranges cut across workgroups; identical rows reproduce lutq_matmul exactly."""
+    import torch
+    rng = np.random.default_rng(100 + bits)
+    E = 1 << bits
+    for (N, K, group, Ms) in [(48, 2 * tk(bits), 64, (32,)), (208, 8 * tk(bits), 128, (1, 4, 16, 32)),
+                              (16 * 300, 2048, 32, (2, 40)), (80, 3 * tk(bits), 32, (5,))]:
+        base = gen.make_case(700 + N, 32, N, K, bits, group, dtype, "random_index")
+        Tn = gen.encode16(rng.standard_normal((N, E)), dtype)
+        d = DeviceCase(lutq, base)
+        Td = to_dev(Tn, dtype)
+        What = orc.dequant_channel(base.Q, Tn, base.S, group, dtype)
+        if N <= 64:                                           # exact read-back through the real kernel
+            one = gen.encode16(np.array([1.0]), dtype)[0]
+            for k0 in range(0, K, 32):
+                Xh = np.zeros((32, K), dtype=np.uint16)
+                Xh[np.arange(32), k0 + np.arange(32)] = one
+                Y = torch.full((32, N), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+                lutq.lutq_matmul_channel(to_dev(Xh, dtype), d.packed, d.S, Td, bits, group, Y, d.ws)
+                torch.cuda.synchronize()
+                assert np.array_equal(orc.to_f64(to_bits(Y), dtype), orc.to_f64(What[:, k0:k0 + 32].T, dtype)), (N, K, k0)
+        for M in Ms:
+            X = gen.encode16(rng.standard_normal((M, K)), dtype)
+            Y = torch.full((M, N), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+            lutq.lutq_matmul_channel(to_dev(X, dtype), d.packed, d.S, Td, bits, group, Y, d.ws)
+            torch.cuda.synchronize()
+            Yb = to_bits(Y)
+            Yref = orc.matmul_f64(X, What, dtype)
+            Yf = orc.to_f64(Yb, dtype)
+            what = f"b{bits} {dtype} N{N} K{K} g{group} M{M}"
+            assert np.isfinite(Yf).all(), what
+            assert orc.rel_fro_err(Yf, Yref) <= TOL[dtype], what
+            mag = np.abs(orc.to_f64(X, dtype)) @ np.abs(orc.to_f64(What, dtype)).T
+            assert np.max(np.abs(Yf - Yref) - (0.5 * ulp16(Yref, dtype) * (1 + 1e-9) + 1e-5 * mag)) <= 0, what
+            assert not d.ws[:65536].any().item()
+    # all rows hold the same table: the same numbers as the shared-table kernel under the same plan
+    c = gen.make_case(800 + bits, 3, 128, 4 * tk(bits), bits, 64, dtype, "nf")
+    d = DeviceCase(lutq, c)
+    Y1 = torch.empty((3, 128), dtype=torch_dtype(dtype), device="cuda")
+    lutq.lutq_matmul_channel(d.X, d.packed, d.S, to_dev(np.tile(c.T, (128, 1)), dtype), bits, 64, Y1, d.ws)
+    Y2 = d.matmul(lutq, plan=lutq.Plan(1, 8, 8, 2, 1))
+    assert np.array_equal(to_bits(Y1), to_bits(Y2))
+
+
 def test_graph_replay_matches_eager(lutq):
     """The benchmark replays its calls as one HIP graph.  A graph of several calls that share one
     workspace -- among them plans that cut tiles across workgroups, whose arrival counters must be back

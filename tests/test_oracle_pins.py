@@ -471,3 +471,26 @@ def test_planted_mistake_is_caught(name):
         except AssertionError:
             caught += 1
     assert caught >= 1, f"mutant '{name}' slipped through every pin"
+
+
+# ----------------------------------------------------------------------------
+# pin 9: one table per output row -- reduces to the shared-table path when all rows hold the same
+# table, and matches an entry-by-entry exact-rational evaluation when they differ
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_channel_tables(dtype):
+    rng = np.random.default_rng(11)
+    bits, group, N, K = 3, 32, 5, 64
+    Q = rng.integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+    S = rand16(rng, (N, K // group), dtype, 0.05)
+    T = rand16(rng, (1 << bits,), dtype)
+    same = np.tile(T, (N, 1))
+    assert np.array_equal(orc.dequant_channel(Q, same, S, group, dtype), orc.dequant(Q, T, S, group, dtype))
+    Tn = rand16(rng, (N, 1 << bits), dtype)
+    W = orc.dequant_channel(Q, Tn, S, group, dtype)
+    for n in range(N):
+        for k in range(K):
+            exact = frac_of_bits(int(Tn[n, Q[n, k]]), dtype) * frac_of_bits(int(S[n, k // group]), dtype)
+            assert frac_of_bits(int(W[n, k]), dtype) == round_frac_to_format(exact, dtype), (n, k)
+    with pytest.raises(ValueError):
+        orc.dequant_channel(Q, Tn[:-1], S, group, dtype)
