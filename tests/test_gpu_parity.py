@@ -508,7 +508,7 @@ def test_graph_replay_matches_eager(lutq):
 
 
 FULL_SIZE = [
-    # (name, N, K, bits, group, dtype, M) -- BASELINE configs at full size, default launch configuration
+    # (name, N, K, bits, group, dtype, M) -- the LLaMA-3 layer shapes at full size, default launch configuration
     ("8B gate_up W4 g128", 28672, 4096, 4, 128, "f16", 1),
     ("8B down W4 g128", 4096, 14336, 4, 128, "f16", 16),
     ("8B qkv W3 g64", 6144, 4096, 3, 64, "f16", 32),
@@ -537,7 +537,7 @@ FULL_SIZE = [
 
 @pytest.mark.parametrize("name,N,K,bits,group,dtype,M", FULL_SIZE)
 def test_full_size_sampled_rows(lutq, name, N, K, bits, group, dtype, M):
-    """Full BASELINE sizes in the launch configuration the benchmark times; the oracle recomputes a
+    """Full layer sizes in the launch configuration the benchmark times; the oracle recomputes a
     sample of output columns (all M rows of 192 sampled weight rows, first/last row blocks included)."""
     c = gen.make_case(17, M, N, K, bits, group, dtype, "random_index")
     d = DeviceCase(lutq, c)
