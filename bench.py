@@ -240,6 +240,35 @@ def main():
                             "TFLOPs": 2.0 * M * N * K / t * 1e-12, "dense_fp16_us": td * 1e6, "speedup_vs_dense_fp16": td / t,
                             "stream_read_us": tr * 1e6, "stream_read_GBps": m["packed"].numel() / tr * 1e-9}
         out["per_shape_cold"] = per_shape
+        # the LLaMA-3-70B layer shapes (4-bit, group 64, M = 1; bf16 as in the 70B configuration, fp16 next
+        # to it), each on a ring of weight buffers larger than the caches.  The packed bytes and scales
+        # are random (drawn on the GPU): the kernel's time does not depend on the values, and parity at
+        # these sizes is what the full-size tests check.
+        shapes70 = {"qkv": (10240, 8192), "o": (8192, 8192), "gate_up": (57344, 8192), "down": (8192, 28672)}
+        g70 = 64
+        per70 = {}
+        for tname, tdt in (("bf16", torch.bfloat16), ("f16", torch.float16)):
+            for n, (N, K) in shapes70.items():
+                pb = lutq.lutq_packed_bytes(N, K, BITS, g70)
+                ring = max(2, min(24, int(1.2e9 // pb) + 1))
+                pk = [torch.randint(0, 256, (pb,), dtype=torch.uint8, device="cuda") for _ in range(ring)]
+                S70 = (torch.rand((N, K // g70), device="cuda") * 0.01 + 0.01).to(tdt)
+                T70 = torch.linspace(-1, 1, 1 << BITS, device="cuda").to(tdt)
+                X70 = torch.randn((M, K), device="cuda").to(tdt)
+                Y70 = torch.empty((M, N), dtype=tdt, device="cuda")
+                ws70 = lutq.new_workspace(N, K, BITS, g70)
+
+                def pass70(pk=pk, S70=S70, T70=T70, X70=X70, Y70=Y70, ws70=ws70):
+                    for w in pk:
+                        lutq.lutq_matmul(X70, w, S70, T70, BITS, g70, Y70, ws70)
+                run = capture(pass70).replay if use_graph else pass70
+                warm(torch, run)
+                t = time_region(torch, run, 10) / ring
+                by = gen.algorithmic_bytes(M, N, K, BITS, g70)
+                per70[f"{n}_{tname}"] = {"N": N, "K": K, "us": t * 1e6, "GBps": by / t * 1e-9,
+                                         "frac_of_8TBps": by / t * 1e-9 / HBM_PEAK_GBS}
+                del pk, run
+        out["per_shape_cold_llama3_70b_w4g64_m1"] = per70
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layer0["o"]["case"])
