@@ -123,6 +123,13 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         int ks = 1;
         while ((int64_t)rs * (ks + 1) <= 16 && tiles_per_team / (ks + 1) >= 2 &&
                (rs * ks < 8 || rs * ks * r * 2 < 24)) ++ks;
+        if (rs == 1 && r == 1 && bits == 4) {
+            // one row block per workgroup, its K range split over the waves (measured, 4-bit): eight
+            // waves when the whole row block is 32 KiB or less (launching and joining more waves costs
+            // more than they gain), fourteen when they divide a long K evenly, else twelve
+            if (tiles_per_team <= 32) ks = 8;
+            else if (tiles_per_team >= 96 && tiles_per_team % 14 == 0) ks = 14;
+        }
         int nw = (int)rs * ks;
         if (nw > 8 && !wide_exists(bits, bf16, r, mb, 2, xm)) {          // too many registers for more than 8 waves
             ks = (int)(8 / rs);

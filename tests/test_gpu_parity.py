@@ -515,7 +515,7 @@ FULL_SIZE = [
     ("70B o W3 g64 bf16", 8192, 8192, 3, 64, "bf16", 16),
     ("8192^2 W2 g32", 8192, 8192, 2, 32, "f16", 4),
     # one case per branch of the default work decomposition
-    ("8B o W4 g128 M1 (12 waves split K)", 4096, 4096, 4, 128, "f16", 1),
+    ("8B o W4 g128 M1 (8 waves split K)", 4096, 4096, 4, 128, "f16", 1),
     ("8B qkv W4 g128 M1 (one workgroup per row group)", 6144, 4096, 4, 128, "f16", 1),
     ("70B qkv W4 g64 bf16 M1 (5 teams, every tile split in two)", 10240, 8192, 4, 64, "bf16", 1),
     ("70B o W4 g64 bf16 M1 (R = 2)", 8192, 8192, 4, 64, "bf16", 1),
