@@ -137,8 +137,8 @@ def quantize(W, T_bits, group_size: int, dtype: str):
 # slice so that every load is a power-of-two number of bits)
 # ----------------------------------------------------------------------------
 # N is cut into row blocks of 16, K into tiles of TK (128 for 4-bit, 256 for 2- and 3-bit).
-# Row blocks are grouped into super-blocks of SB = 4 (if N/16 is a multiple of 4, else 2, else 1)
-# consecutive row blocks.  Storage order: super-block, then K tile, then row block inside the
+# Row blocks are grouped into super-blocks of SB consecutive row blocks: SB = 4 if N/16 is a multiple
+# of 4 and not in the range 257..512, else 2 if N/16 is even, else 1.  Storage order: super-block, then K tile, then row block inside the
 # super-block; tile (rb, kt) is tile number ((rb // SB) * (K/TK) + kt) * SB + rb % SB.  (So the SB
 # tiles that cover 16*SB rows x TK columns are adjacent in memory.)  Inside a tile, "lane"
 # l = 16*o + i (i = row inside the block, o = 0..3) owns, for each 32-wide K step t of the tile,
@@ -165,9 +165,11 @@ def packed_bytes(N: int, K: int, bits: int) -> int:
 
 
 def super_block(N: int) -> int:
-    """Row blocks per super-block: 4 if N/16 is a multiple of 4, else 2, else 1."""
+    """Row blocks per super-block: 4 if N/16 is a multiple of 4 and not in 257..512, else 2 if even, else 1."""
     nb = N // 16
-    return 4 if nb % 4 == 0 else 2 if nb % 2 == 0 else 1
+    if nb % 4 == 0 and not (256 < nb <= 512):
+        return 4
+    return 2 if nb % 2 == 0 else 1
 
 
 def _lane_view(Q: np.ndarray, bits: int) -> np.ndarray:

@@ -59,8 +59,8 @@ DeviceInfo device_info() {
     return cache[dev];
 }
 
-// bytes of the replicated table in LDS of lutq_dequant (8 copies)
-inline int super_block(int64_t nb) { return nb % 4 == 0 ? 4 : nb % 2 == 0 ? 2 : 1; }
+// row blocks per super-block of the packed layout (the rule of lutq_pack.cpp)
+inline int super_block(int64_t nb) { return (nb % 4 == 0 && (nb <= 256 || nb > 512)) ? 4 : nb % 2 == 0 ? 2 : 1; }
 // bytes of lutq_dequant's table (log2c copies); entries are 8 bytes for the 2-bit quad table and for the
 // widened bf16 pair tables, else 4
 int lut_bytes(int bits, bool bf16, int log2c) {
@@ -103,7 +103,7 @@ int64_t gcd64(int64_t a, int64_t b) {
 // in flight, and that partial sums leave the workgroup only when the kernel is long enough to hide it.
 //   * N/16 = per x CUs: one workgroup per compute unit, arranged as RS teams x KS waves, per = RS x R.
 //     No output tile is split across workgroups.
-//   * 4-bit, N/16 = (p/q) x CUs with small p, q and at least 96 KiB per compute unit: RS = p row blocks
+//   * 4-bit, N/16 = (p/2) x CUs with small p and at least 96 KiB per compute unit: RS = p row blocks
 //     side by side, one workgroup per compute unit, every super-group's K range cut into q parts
 //     (Stream-K fix-up for every tile, but perfectly balanced).
 //   * otherwise one workgroup of 8 waves per row group, R the largest of 4, 2, 1 that still gives
@@ -173,10 +173,11 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         d.nw = (M > 12 || (r == 4 && groups > cus)) ? 4 : 8;
         // Team plan: a workgroup takes A = R x RS row blocks as RS teams that share the activations
         // through LDS (needs enough teams to stage a tile between them, and chunked scales).  It pays
-        // when the activations outweigh the weights (M / (4 bits) >= 1.3) on a problem long enough to
-        // hide the barrier per tile, from 17 rows up, or on very large problems.
+        // when the activations outweigh the weights (M / (4 bits) >= 1.3, or >= 1 on a larger problem) on
+        // a problem long enough to hide the barrier per tile, from 17 rows up, or on very large problems.
         const int64_t size = nb * K / cus;                // weight rows x columns per compute unit / 16
-        const bool teams = (mb == 2 && size >= 12000) || (10 * M >= 52 * bits && size >= 20000) || size >= 100000;
+        const bool teams = (mb == 2 && size >= 12000) || (10 * M >= 52 * bits && size >= 20000) ||
+                           (M >= 4 * bits && size >= 50000) || size >= 100000;
         if (!teams || !sch || force_r) return d;
         const int need = (steps_per_tile(bits) * mb + kXPiecesPerWave - 1) / kXPiecesPerWave;
         struct Cand { bool exact; int r; int64_t rs, sets; };
@@ -245,6 +246,12 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         if (!force_r) while (r > 2) r >>= 1;              // R <= 2 keeps two tiles in flight within 128 registers
         if (!force_r && r == 2 && per <= 16 && !wide_exists(bits, bf16, 2, mb, 2, xm) && wide_exists(bits, bf16, 1, mb, 2, xm))
             r = 1;                                        // more, narrower teams rather than half the waves
+        // two row blocks per compute unit: two teams of six waves at R = 1 beat eight waves at R = 2 where
+        // the work per weight is heavy (measured: bf16 4-bit 6-9 %, 2-bit at M <= 2 10-18 %); 4-bit fp16
+        // and longer batches keep R = 2
+        if (!force_r && r == 2 && per == 2 && wide_exists(bits, bf16, 1, mb, 2, xm) &&
+            ((bits == 4 && bf16) || (bits == 2 && M <= 2)))
+            r = 1;
         int64_t rs = per / r;
         while (rs > 16 && rs % 2 == 0) { rs /= 2; grid *= 2; }
         const int nw = rs <= 16 ? waves_for(r, rs, kt) : 0;
@@ -252,7 +259,7 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
             d.r = r; d.grid = grid; d.nw = nw; d.rs = (int)rs;
             return d;
         }
-    } else if (!force_r && bits == 4 && qn <= 4 && pn <= 8 && bytes_per_cu >= 96 * 1024 && kt / qn >= 8) {
+    } else if (!force_r && bits == 4 && qn <= 2 && pn <= 8 && bytes_per_cu >= 96 * 1024 && kt / qn >= 8) {
         const int nw = waves_for(1, pn, kt / qn);
         if (nw >= 4 && nw <= 16 && nw % pn == 0) {
             d.r = 1; d.grid = cus; d.nw = nw; d.rs = (int)pn;

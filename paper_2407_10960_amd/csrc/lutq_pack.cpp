@@ -7,7 +7,8 @@
 //
 // Q is [N, K] row-major.  N is cut into row blocks of 16 rows, K into tiles of TK columns
 // (TK = 128 for 4-bit, 256 for 2- and 3-bit).  Row blocks are grouped into super-blocks of SB
-// consecutive row blocks (SB = 4 if N/16 is a multiple of 4, else 2, else 1).  Storage order is
+// consecutive row blocks (SB = 4 if N/16 is a multiple of 4 and not in 257..512, else 2 if N/16 is even,
+// else 1; see super_block below).  Storage order is
 // super-block, then K tile, then row block inside the super-block: tile (rb, kt) starts at byte
 //        (((rb / SB) * K/TK + kt) * SB + rb % SB) * TILE_BYTES,
 // so the SB tiles that cover 16*SB rows x TK columns are adjacent: a wavefront that owns a whole
@@ -45,7 +46,10 @@ namespace {
 
 inline int tile_k(int bits) { return bits == 4 ? 128 : 256; }
 inline int tile_bytes(int bits) { return bits == 3 ? 1536 : 1024; }
-inline int super_block(int64_t nb) { return nb % 4 == 0 ? 4 : nb % 2 == 0 ? 2 : 1; }
+// Between one and two row blocks per compute unit of the 256-CU part (N/16 in 257..512) a workgroup
+// streams two row blocks: with SB = 2 these two are one contiguous run of memory (measured on
+// N = K = 8192, M = 1: 9.96 us with SB = 4, 8.90 us with SB = 2); everywhere else SB = 4 measured best.
+inline int super_block(int64_t nb) { return (nb % 4 == 0 && (nb <= 256 || nb > 512)) ? 4 : nb % 2 == 0 ? 2 : 1; }
 inline int64_t tile_index(int64_t rb, int64_t kt, int64_t KT, int SB) { return ((rb / SB) * KT + kt) * SB + rb % SB; }
 
 lutq_status check_pack_args(int64_t N, int64_t K, int bits, int group_size) {

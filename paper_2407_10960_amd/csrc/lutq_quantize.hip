@@ -239,7 +239,7 @@ extern "C" lutq_status lutq_quantize(const void* W, int w_is_f32, const void* lu
     p.N = (int)N; p.K = (int)K;
     p.KT = (int)(K / tk);
     p.SG = (int)(K / group_size);
-    p.SB = nb % 4 == 0 ? 4 : nb % 2 == 0 ? 2 : 1;
+    p.SB = (nb % 4 == 0 && (nb <= 256 || nb > 512)) ? 4 : nb % 2 == 0 ? 2 : 1;     // the rule of lutq_pack.cpp
     p.upr = (int)(K / uc);
     p.units = nb * (K / uc);
     p.bf16 = dtype == LUTQ_BF16;

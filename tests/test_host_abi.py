@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 
 
 @pytest.mark.parametrize("bits", (2, 3, 4))
-@pytest.mark.parametrize("shape", [(16, 256), (48, 1024), (256, 768)])
+@pytest.mark.parametrize("shape", [(16, 256), (48, 1024), (256, 768), (4096, 256), (4128, 256), (5120, 256), (8192, 256), (8224, 256)])
 def test_pack_matches_oracle_layout_bit_exact(bits, shape):
     N, K = shape
     rng = np.random.default_rng(bits * 100 + N)
