@@ -103,9 +103,20 @@ typedef struct {
                                      must divide N / (16 R) */
 } lutq_plan;
 
-/* Fills *plan with the library's choice for this problem. */
+/* Fills *plan with the library's choice for this problem on the current device. */
 lutq_status lutq_plan_default(int bits, int group_size, int64_t M, int64_t N, int64_t K,
                               lutq_dtype dtype, lutq_plan* plan);
+
+/* The same choice for a device with `compute_units` compute units (1..4096), without touching any
+ * device: host logic only, for planning ahead and for tests.  MI355X has 256. */
+lutq_status lutq_plan_default_for(int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                  lutq_dtype dtype, int compute_units, lutq_plan* plan);
+
+/* Whether lutq_matmul_plan would accept `plan` (NULL = the default plan) for this problem on a device
+ * with `compute_units` compute units: LUTQ_OK, or the status lutq_matmul_plan would return for the
+ * plan and the problem (BITS, GROUP, SHAPE, DTYPE, PLAN).  Host logic only; no device is touched. */
+lutq_status lutq_plan_check(int bits, int group_size, int64_t M, int64_t N, int64_t K, lutq_dtype dtype,
+                            int compute_units, const lutq_plan* plan);
 
 /* Y = X * W^T-dequantised, asynchronous on `stream`.
  *   X       device, [M, K] row-major, dtype

@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     lutq_pack,
     lutq_packed_bytes,
     lutq_plan_default,
+    lutq_plan_default_for,
+    lutq_plan_check,
     lutq_quantize,
     lutq_tune,
     lutq_tune_candidates,

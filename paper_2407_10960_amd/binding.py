@@ -12,7 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "lutq_status_string", "lutq_packed_bytes", "lutq_pack", "lutq_unpack", "lutq_workspace_bytes",
-    "lutq_plan_default", "lutq_matmul", "lutq_matmul_plan", "lutq_matmul_channel", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
+    "lutq_plan_default", "lutq_plan_default_for", "lutq_plan_check", "lutq_matmul", "lutq_matmul_plan", "lutq_matmul_channel", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
     "lutq_calib_stream_read", "lutq_calib_copy",
 )
 
@@ -72,6 +72,10 @@ def load_library():
     lib.lutq_workspace_bytes.argtypes = [i64, i64, ci, ci]
     lib.lutq_plan_default.restype = ci
     lib.lutq_plan_default.argtypes = [ci, ci, i64, i64, i64, ci, ctypes.POINTER(_CPlan)]
+    lib.lutq_plan_default_for.restype = ci
+    lib.lutq_plan_default_for.argtypes = [ci, ci, i64, i64, i64, ci, ci, ctypes.POINTER(_CPlan)]
+    lib.lutq_plan_check.restype = ci
+    lib.lutq_plan_check.argtypes = [ci, ci, i64, i64, i64, ci, ci, ctypes.POINTER(_CPlan)]
     lib.lutq_matmul.restype = ci
     lib.lutq_matmul.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.lutq_matmul_plan.restype = ci
@@ -177,6 +181,24 @@ def lutq_plan_default(bits: int, group_size: int, M: int, N: int, K: int, dtype_
            "lutq_plan_default")
     return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup, cp.tiles_in_flight,
                 cp.row_groups_per_workgroup)
+
+
+def lutq_plan_default_for(bits: int, group_size: int, M: int, N: int, K: int, dtype_code: int = LUTQ_F16,
+                          compute_units: int = 256) -> Plan:
+    """The default plan for a device with that many compute units (host logic, no device needed)."""
+    cp = _CPlan()
+    _check(load_library().lutq_plan_default_for(bits, group_size, M, N, K, dtype_code, compute_units, ctypes.byref(cp)),
+           "lutq_plan_default_for")
+    return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup, cp.tiles_in_flight,
+                cp.row_groups_per_workgroup)
+
+
+def lutq_plan_check(bits: int, group_size: int, M: int, N: int, K: int, dtype_code: int = LUTQ_F16,
+                    compute_units: int = 256, plan: Plan | None = None) -> int:
+    """Status code lutq_matmul_plan would give this plan (None = default) on such a device; 0 = accepted."""
+    cp = plan._c() if plan is not None else None
+    return int(load_library().lutq_plan_check(bits, group_size, M, N, K, dtype_code, compute_units,
+                                              ctypes.byref(cp) if cp is not None else None))
 
 
 def lutq_matmul(X, packed, scales, lut, bits: int, group_size: int, Y, workspace, stream=None,

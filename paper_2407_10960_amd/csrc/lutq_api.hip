@@ -119,16 +119,17 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
     d.stages = 2;                                         // measured: deeper prefetch does not pay at 8-16 waves
     // waves for `rs` teams of `r` row blocks: enough for 24 KiB in flight (r KiB per tile, two tiles
     // per wave), at least 8, at most 16, a multiple of rs, two K tiles or more per wave
+    const int max_nw = sch ? 16 : 8;                      // the per-tile scale path has no 16-wave build
     auto waves_for = [&](int r, int64_t rs, int64_t tiles_per_team) -> int {
         int ks = 1;
-        while ((int64_t)rs * (ks + 1) <= 16 && tiles_per_team / (ks + 1) >= 2 &&
+        while ((int64_t)rs * (ks + 1) <= max_nw && tiles_per_team / (ks + 1) >= 2 &&
                (rs * ks < 8 || rs * ks * r * 2 < 24)) ++ks;
         if (rs == 1 && r == 1 && bits == 4) {
             // one row block per workgroup, its K range split over the waves (measured, 4-bit): eight
             // waves when the whole row block is 32 KiB or less (launching and joining more waves costs
             // more than they gain), fourteen when they divide a long K evenly, else twelve
             if (tiles_per_team <= 32) ks = 8;
-            else if (tiles_per_team >= 96 && tiles_per_team % 14 == 0) ks = 14;
+            else if (tiles_per_team >= 96 && tiles_per_team % 14 == 0 && max_nw >= 14) ks = 14;
         }
         int nw = (int)rs * ks;
         if (nw > 8 && !wide_exists(bits, bf16, r, mb, 2, xm)) {          // too many registers for more than 8 waves
@@ -233,6 +234,7 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
                 }
             }
             if (!nw) continue;
+            if ((c.exact ? c.sets : (int64_t)cus) * c.rs > kMaxGrid) continue;     // partial-sum slots of the workspace
             d.r = c.r; d.grid = c.exact ? (int)c.sets : cus; d.nw = nw; d.rs = (int)c.rs; d.stages = stages;
             return d;
         }
@@ -253,15 +255,15 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
             ((bits == 4 && bf16) || (bits == 2 && M <= 2)))
             r = 1;
         int64_t rs = per / r;
-        while (rs > 16 && rs % 2 == 0) { rs /= 2; grid *= 2; }
-        const int nw = rs <= 16 ? waves_for(r, rs, kt) : 0;
-        if (nw >= 4 && nw <= 16 && (int64_t)grid * rs <= kMaxGrid) {
+        while (rs > max_nw && rs % 2 == 0) { rs /= 2; grid *= 2; }
+        const int nw = rs <= max_nw ? waves_for(r, rs, kt) : 0;
+        if (nw >= 4 && nw <= max_nw && (int64_t)grid * rs <= kMaxGrid) {
             d.r = r; d.grid = grid; d.nw = nw; d.rs = (int)rs;
             return d;
         }
     } else if (!force_r && bits == 4 && qn <= 2 && pn <= 8 && bytes_per_cu >= 96 * 1024 && kt / qn >= 8) {
         const int nw = waves_for(1, pn, kt / qn);
-        if (nw >= 4 && nw <= 16 && nw % pn == 0) {
+        if (nw >= 4 && nw <= max_nw && nw % pn == 0 && (int64_t)cus * pn <= kMaxGrid) {
             d.r = 1; d.grid = cus; d.nw = nw; d.rs = (int)pn;
             return d;
         }
@@ -326,23 +328,33 @@ extern "C" size_t lutq_workspace_bytes(int64_t N, int64_t K, int bits, int group
     return kWorkspaceBytes;
 }
 
-extern "C" lutq_status lutq_plan_default(int bits, int group_size, int64_t M, int64_t N, int64_t K,
-                                         lutq_dtype dtype, lutq_plan* plan) {
+extern "C" lutq_status lutq_plan_default_for(int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                             lutq_dtype dtype, int compute_units, lutq_plan* plan) {
     if (!plan) return LUTQ_ERR_NULL;
     lutq_status st = check_problem(bits, group_size, N, K);
     if (st != LUTQ_OK) return st;
-    if (M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
+    if (M < 1 || M > kMaxRows || compute_units < 1 || compute_units > 4096) return LUTQ_ERR_SHAPE;
     if (M > 32) M = 32;                                   // the plan of the 32-row slices
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
-    DeviceInfo di = device_info();
-    if (!di.ok) return LUTQ_ERR_DEVICE;
-    const Decomp d = default_decomp(bits, dtype == LUTQ_BF16, (K / group_size) % 8 == 0, M, N, K, di.cus, 0);
+    const Decomp d = default_decomp(bits, dtype == LUTQ_BF16, (K / group_size) % 8 == 0, M, N, K, compute_units, 0);
     plan->row_blocks_per_wave = d.r;
     plan->grid = d.grid;
     plan->waves_per_workgroup = d.nw;
     plan->tiles_in_flight = d.stages;
     plan->row_groups_per_workgroup = d.rs;
     return LUTQ_OK;
+}
+
+extern "C" lutq_status lutq_plan_default(int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                         lutq_dtype dtype, lutq_plan* plan) {
+    if (!plan) return LUTQ_ERR_NULL;
+    lutq_status st = check_problem(bits, group_size, N, K);
+    if (st != LUTQ_OK) return st;
+    if (M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
+    if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
+    DeviceInfo di = device_info();
+    if (!di.ok) return LUTQ_ERR_DEVICE;
+    return lutq_plan_default_for(bits, group_size, M, N, K, dtype, di.cus, plan);
 }
 
 namespace {
@@ -360,19 +372,26 @@ struct Prepared {
 lutq_status prepare_matmul(const void* X, const void* packed, const void* scales, const void* lut,
                            int bits, int group_size, int64_t M, int64_t N, int64_t K,
                            lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
-                           const lutq_plan* user_plan, bool rowlut, Prepared* out) {
-    if (!X || !packed || !scales || !lut || !Y) return LUTQ_ERR_NULL;
+                           const lutq_plan* user_plan, bool rowlut, int dry_run_cus, Prepared* out) {
+    // dry_run_cus > 0: only the plan is checked, for a device of that many compute units; no pointer is
+    // looked at and no device is queried
+    const bool dry = dry_run_cus > 0;
+    if (!dry && (!X || !packed || !scales || !lut || !Y)) return LUTQ_ERR_NULL;
     lutq_status st = check_problem(bits, group_size, N, K);
     if (st != LUTQ_OK) return st;
     if (M < 1 || M > 32) return LUTQ_ERR_SHAPE;
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
-    if (!aligned16(X) || !aligned16(packed) || !aligned16(scales) || !aligned16(Y) || !aligned16(workspace))
-        return LUTQ_ERR_ALIGN;
-    if ((reinterpret_cast<uintptr_t>(lut) & 1u) != 0 || (rowlut && !aligned16(lut))) return LUTQ_ERR_ALIGN;
-    if (!workspace || workspace_bytes < kWorkspaceBytes) return LUTQ_ERR_WORKSPACE;
-
-    DeviceInfo di = device_info();
-    if (!di.ok) return LUTQ_ERR_DEVICE;
+    DeviceInfo di;
+    if (dry) {
+        di.cus = dry_run_cus; di.ok = true;
+    } else {
+        if (!aligned16(X) || !aligned16(packed) || !aligned16(scales) || !aligned16(Y) || !aligned16(workspace))
+            return LUTQ_ERR_ALIGN;
+        if ((reinterpret_cast<uintptr_t>(lut) & 1u) != 0 || (rowlut && !aligned16(lut))) return LUTQ_ERR_ALIGN;
+        if (!workspace || workspace_bytes < kWorkspaceBytes) return LUTQ_ERR_WORKSPACE;
+        di = device_info();
+        if (!di.ok) return LUTQ_ERR_DEVICE;
+    }
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1;
     const bool bf16 = dtype == LUTQ_BF16;
@@ -456,7 +475,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     p.lut = static_cast<const uint16_t*>(lut);
     p.Y = static_cast<uint16_t*>(Y);
     p.counters = static_cast<uint32_t*>(workspace);
-    p.slots = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
+    p.slots = dry ? nullptr : reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
     p.packed_bytes = (uint32_t)(N * K * bits / 8);
     p.M = (int)M; p.N = (int)N; p.K = (int)K;
     p.KT = (int)kt;
@@ -509,13 +528,13 @@ lutq_status matmul_sliced(const void* X, const void* packed, const void* scales,
     const size_t xrow = (size_t)K * 2, yrow = (size_t)N * 2;
     if (full > 0) {
         lutq_status st = prepare_matmul(X, packed, scales, lut, bits, group_size, 32, N, K, dtype, Y, workspace,
-                                        workspace_bytes, user_plan, rowlut, &body);
+                                        workspace_bytes, user_plan, rowlut, 0, &body);
         if (st != LUTQ_OK) return st;
     }
     if (rest > 0) {
         lutq_status st = prepare_matmul(static_cast<const char*>(X) + (size_t)full * 32 * xrow, packed, scales, lut, bits,
                                         group_size, rest, N, K, dtype, static_cast<char*>(Y) + (size_t)full * 32 * yrow,
-                                        workspace, workspace_bytes, user_plan, rowlut, &tail);
+                                        workspace, workspace_bytes, user_plan, rowlut, 0, &tail);
         if (st != LUTQ_OK) return st;
     }
     for (int64_t i = 0; i < full; ++i) {
@@ -529,6 +548,19 @@ lutq_status matmul_sliced(const void* X, const void* packed, const void* scales,
 }
 
 }  // namespace
+
+extern "C" lutq_status lutq_plan_check(int bits, int group_size, int64_t M, int64_t N, int64_t K, lutq_dtype dtype,
+                                       int compute_units, const lutq_plan* plan) {
+    if (compute_units < 1 || compute_units > 4096 || M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
+    Prepared q{};
+    for (int64_t m : {M >= 32 ? (int64_t)32 : (int64_t)0, M % 32}) {      // the 32-row slices, then the rest
+        if (m == 0) continue;
+        lutq_status st = prepare_matmul(nullptr, nullptr, nullptr, nullptr, bits, group_size, m, N, K, dtype, nullptr,
+                                        nullptr, 0, plan, false, compute_units, &q);
+        if (st != LUTQ_OK) return st;
+    }
+    return LUTQ_OK;
+}
 
 extern "C" lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scales, const void* lut,
                                         int bits, int group_size, int64_t M, int64_t N, int64_t K,

@@ -134,3 +134,75 @@ def test_product_never_imports_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".cpp", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+
+
+# ----------------------------------------------------------------------------
+# host logic of the default work decomposition (no device needed)
+# ----------------------------------------------------------------------------
+def _sb(nb):
+    return 4 if (nb % 4 == 0 and not (256 < nb <= 512)) else 2 if nb % 2 == 0 else 1
+
+
+def test_default_plans_are_valid_for_random_problems():
+    """Whatever the shape, the default plan respects the documented ranges and divisibility rules, for
+    the 256 compute units of the target and for other device sizes."""
+    rng = np.random.default_rng(3)
+    for i in range(4000):
+        bits = int(rng.choice([2, 3, 4]))
+        tkb = 128 if bits == 4 else 256
+        group = int(rng.choice([32, 64, 128, 256]))
+        nb = int(rng.choice([1, 2, 3, 5, 8, 31, 64, 100, 255, 256, 257, 384, 448, 511, 512, 513, 640, 768, 1024, 1792, 3584,
+                             4096, 5000, 9999, 16384]))
+        kt = int(rng.integers(1, 300))
+        K = tkb * kt
+        if K % group:
+            K *= 2
+        M = int(rng.integers(1, 129))
+        cus = int(rng.choice([256, 256, 256, 304, 64, 8, 1]))
+        dt = int(rng.integers(0, 2))
+        N = 16 * nb
+        if N * K * bits // 8 >= 1 << 31:
+            continue
+        p = lutq.lutq_plan_default_for(bits, group, M, N, K, dt, cus)
+        what = f"b{bits} g{group} M{M} N{N} K{K} cus{cus} dt{dt}: {p}"
+        assert p.row_blocks_per_wave in (1, 2, 4) and _sb(nb) % p.row_blocks_per_wave == 0, what
+        assert 1 <= p.row_groups_per_workgroup <= 16, what
+        assert 4 <= p.waves_per_workgroup <= 16 and p.waves_per_workgroup % p.row_groups_per_workgroup == 0, what
+        assert p.tiles_in_flight in (2, 4), what
+        nrg = nb // p.row_blocks_per_wave
+        assert nrg % p.row_groups_per_workgroup == 0, what
+        assert 1 <= p.grid and p.grid * p.row_groups_per_workgroup <= 4096, what
+        # the library accepts its own default, given explicitly or not (kernel instance exists, LDS fits,
+        # partial-sum slots suffice)
+        assert lutq.lutq_plan_check(bits, group, M, N, K, dt, cus) == 0, what
+        if M <= 32:                                 # (beyond 32 rows an explicit plan must also suit the last slice)
+            assert lutq.lutq_plan_check(bits, group, M, N, K, dt, cus, p) == 0, what
+
+
+def test_default_plans_of_the_llama3_shapes():
+    """The measured choices for the benchmark's shapes on 256 compute units (4-bit, fp16, M = 1): a
+    change here is a change of the benchmark's launch configuration."""
+    want = {(6144, 4096, 128): (1, 384, 8, 2, 1), (4096, 4096, 128): (1, 256, 8, 2, 1),
+            (28672, 4096, 128): (1, 256, 14, 2, 7), (4096, 14336, 128): (1, 256, 14, 2, 1),
+            (10240, 8192, 64): (1, 256, 15, 2, 5), (8192, 8192, 64): (2, 256, 8, 2, 1),
+            (57344, 8192, 64): (2, 256, 14, 2, 7), (8192, 28672, 64): (2, 256, 8, 2, 1)}
+    for (N, K, g), plan in want.items():
+        p = lutq.lutq_plan_default_for(4, g, 1, N, K, 0, 256)
+        assert (p.row_blocks_per_wave, p.grid, p.waves_per_workgroup, p.tiles_in_flight, p.row_groups_per_workgroup) == plan, (N, K, p)
+    assert lutq.lutq_plan_default_for(4, 128, 100, 4096, 4096, 0, 256) == lutq.lutq_plan_default_for(4, 128, 32, 4096, 4096, 0, 256)
+    with pytest.raises(lutq.LutqError):
+        lutq.lutq_plan_default_for(4, 128, 1, 4096, 4096, 0, 0)
+
+
+def test_plan_check_matches_documented_rules():
+    ok = lambda *a, **k: lutq.lutq_plan_check(*a, **k)
+    assert ok(4, 128, 1, 4096, 4096, 0, 256, lutq.Plan(1, 256, 12, 2, 1)) == 0
+    assert ok(4, 128, 1, 4096, 4096, 0, 256, lutq.Plan(0, 4097, 0)) == 10          # grid beyond the slots
+    assert ok(4, 128, 1, 4096, 4096, 0, 256, lutq.Plan(0, 0, 17)) == 10            # more than 16 waves
+    assert ok(4, 128, 1, 4096, 4096, 0, 256, lutq.Plan(1, 0, 8, 2, 3)) == 10       # waves not a multiple of the teams
+    assert ok(4, 128, 32, 4096, 4096, 0, 256, lutq.Plan(1, 0, 16, 2, 1)) == 10     # no 16-wave instance for 32 rows
+    assert ok(4, 128, 36, 4096, 4096, 0, 256, lutq.Plan(1, 0, 16, 2, 1)) == 10     # ... nor for the 32-row slice of 36
+    assert ok(4, 128, 4, 4096, 4096, 0, 256, lutq.Plan(1, 0, 16, 2, 1)) == 0
+    assert ok(4, 128, 1, 8192, 4096, 0, 256, lutq.Plan(4, 0, 4)) == 10             # R = 4 does not divide the super-block of 2
+    assert ok(4, 100, 1, 4096, 4096, 0, 256) == 3 and ok(5, 128, 1, 4096, 4096, 0, 256) == 2
+    assert ok(4, 128, 129, 4096, 4096, 0, 256) == 4 and ok(4, 128, 1, 4096, 4096, 0, 0) == 4
