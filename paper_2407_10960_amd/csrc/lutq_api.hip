@@ -153,7 +153,7 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
             const int64_t groups = nb / r;
             if (groups >= (int64_t)cus * 6 / 10) return true;
             const int64_t j = (cus + groups - 1) / groups;
-            return j <= 2 && K / j >= 6144;
+            return j <= 2 && K / j >= 4096;
         };
         int r = force_r;
         if (!r) {
@@ -163,11 +163,13 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         }
         const int64_t groups = nb / r;
         int64_t grid = groups;
-        if (groups < (int64_t)cus * 6 / 10) {
+        if (groups < (int64_t)cus * 6 / 10 && (int64_t)r * 16 * K * bits / 8 >= 64 * 1024) {   // (a cut must repay its fix-up)
             int64_t j = (cus + groups - 1) / groups;      // K parts per row group
             if (j > kt / 8) j = kt / 8;
             if (j < 1) j = 1;
             grid = groups * j;
+        } else if (groups < cus && K >= 12288) {
+            grid = cus;                                   // long K: every compute unit takes an equal share of the tiles
         }
         while (grid > kMaxGrid) grid = (grid + 1) / 2;
         d.r = r; d.grid = (int)grid; d.rs = 1;
@@ -176,6 +178,7 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         // through LDS (needs enough teams to stage a tile between them, and chunked scales).  It pays
         // when the activations outweigh the weights (M / (4 bits) >= 1.3, or >= 1 on a larger problem) on
         // a problem long enough to hide the barrier per tile, from 17 rows up, or on very large problems.
+        const bool plain_r4_uncut = r == 4 && grid == groups;
         const int64_t size = nb * K / cus;                // weight rows x columns per compute unit / 16
         const bool teams = (mb == 2 && size >= 12000) || (10 * M >= 52 * bits && size >= 20000) ||
                            (M >= 4 * bits && size >= 50000) || size >= 100000;
@@ -189,14 +192,14 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         for (int pass = 0; pass < 2; ++pass) {
             const int tr = pass == 0 ? r_first : 3 - r_first;
             if (sb % tr != 0) continue;
-            // one set of row blocks per workgroup and at least 85 % of the compute units busy: no
+            // one set of row blocks per workgroup and at least 65 % of the compute units busy: no
             // fix-up; the fullest grid wins, then the larger A
             Cand best{true, tr, 0, 0};
             for (int64_t rs = 16; rs >= need; --rs) {
                 const int64_t a = tr * rs;
                 if (nb % a != 0) continue;
                 const int64_t sets = nb / a;
-                if (a >= 6 && sets <= cus && sets * 100 >= (int64_t)cus * 85 && sets > best.sets) best = Cand{true, tr, rs, sets};
+                if (a >= 6 && sets <= cus && sets * 100 >= (int64_t)cus * 65 && sets > best.sets) best = Cand{true, tr, rs, sets};
                 // one workgroup per compute unit, every set's K range cut across cus / sets of them:
                 // up to four ("shallow") before deeper cuts
                 (sets * 4 >= cus ? shallow : deep).push_back(Cand{false, tr, rs, sets});
@@ -211,7 +214,10 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         for (const Cand& c0 : order) {
             Cand c = c0;
             const int64_t cols = c.exact ? K : c.sets * K / cus;      // columns of K per workgroup
-            if (cols < 1536) continue;
+            if (cols < (bits == 4 ? 2048 : 1536)) continue;     // (4-bit: 1536 columns measured 30 % slower than the plain plan)
+            // (a plain plan at R = 4 without a K cut is strong: a team plan with a K cut needs eight row blocks to
+            // beat it, and does not beat it at all when it keeps 70 % of the compute units busy)
+            if (!c.exact && plain_r4_uncut && (c.r * c.rs < 8 || groups * 100 >= (int64_t)cus * 70)) continue;
             // K cut across workgroups: twice the teams at R = 1 (one piece per wave where there are eight
             // or more pieces) beat R = 2 (measured, 5-17 %); with eight or more pieces per tile R = 1
             // runs best with four tiles in flight and one wave per team (3-bit: two tiles)
@@ -268,14 +274,37 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
             return d;
         }
     }
+    if (!force_r && (bits == 4 || (bits == 2 && !bf16)) && nb > 2 * (int64_t)cus) {
+        // 4-bit and fp16 2-bit, row blocks that do not divide over the compute units: measured on shapes outside the
+        // LLaMA-3 set (N/16 = 1376, 1728, 2000, 3696), one workgroup per compute unit or fewer, all
+        // resident at once, beats several smaller ones per compute unit by 20-40 % even at 70 % of the
+        // compute units busy.  A = the smallest divisor of N/16 that leaves at most one workgroup per
+        // compute unit, as R = 2 x A/2 teams or A teams of R = 1.
+        for (int64_t a = (nb + cus - 1) / cus; a <= 32; ++a) {
+            if (nb % a != 0) continue;
+            int r = (a % 2 == 0 && sb % 2 == 0 && (bits == 2 || wide_exists(bits, bf16, 2, mb, 2, xm))) ? 2 : 1;
+            if (a / r > max_nw) { if (r == 1) break; continue; }
+            const int64_t rs = a / r;
+            const int nw = waves_for(r, rs, kt);
+            if (nw >= 4 && nw <= max_nw && (nb / a) * rs <= kMaxGrid) {
+                d.r = r; d.grid = (int)(nb / a); d.nw = nw; d.rs = (int)rs;
+                return d;
+            }
+            break;
+        }
+    }
     // (2- and 3-bit: measured, many small workgroups -- several per compute unit, out of step with
-    // each other -- beat both a larger R and the split above: 70B QKV 3-bit 10.6 us against 12.7 us)
+    // each other -- beat both a larger R and the split above: 70B QKV 3-bit 10.6 us against 12.7 us,
+    // LLaMA-2-13B gate+up 3-bit 15.3 us at R = 1 against 17.6 us at R = 2)
     int r = sb;                                           // R has to divide the layout's super-block
-    while (r > 1 && nb / r < (bits == 4 ? cus : 2 * cus)) r >>= 1;
+    while (r > 1 && (bits != 4 || nb / r < cus)) r >>= 1;
     if (force_r) r = force_r;
     const int64_t groups = nb / r;
     int64_t grid = groups;
-    if (groups < cus) {
+    // K is cut across workgroups only when a row group is long enough to repay the fix-up (three
+    // device-scope round trips, about 2.5 us): N = 1024, K = 4096 runs in 4.3 us on 64 workgroups
+    // against 6.8 us on 256
+    if (groups < cus && (int64_t)r * 16 * K * bits / 8 >= 96 * 1024) {
         int64_t j = (cus + groups - 1) / groups;         // K parts per row group
         if (j > kt / 4) j = kt / 4;                      // keep at least one K tile per wavefront
         if (j < 1) j = 1;
