@@ -8,6 +8,15 @@
 // type; u = W / scale is one IEEE fp64 division; the index is the first c that minimises the fp64
 // value |u - T[c]|; a group whose scale is zero takes u = 0.
 //
+// The minimum is found by scanning all 2^b entries, except for a strictly increasing fp16 table of 8
+// or 16 entries (the NormalFloat tables and sorted learned tables are; with 4 entries the scan is the
+// faster of the two): there a binary search over a copy of the table in LDS brackets u between two neighbours and only their two distances are compared.  This gives
+// the same index as the scan: |u| < 2 and fp16 magnitudes are at most 65504, so a distance
+// is below 2^17 and its fp64 rounding error below 2^-36, while two different fp16 values are at least
+// 2^-24 apart -- rounding keeps the distances to different entries in their exact order, the nearest
+// entry is one of the two neighbours, and a tie between them goes to the lower one, which is the
+// lower index.  bf16 values can be closer together than a rounding error, so bf16 tables are scanned.
+//
 // Work unit: 16 rows x UC columns, UC = max(K tile, group), one wavefront per unit.  Lane l = 16 o + i
 // holds, for every 32-column step t of the unit, the 8 weights W[16 rb + i][col0 + 32 t + 8 o + j] --
 // exactly the 8 indices whose packed bits this lane owns -- so the packed tile is written with one
@@ -66,6 +75,17 @@ __global__ __launch_bounds__(256) void quantize_kernel(const QuantParams p) {
     double T[E];
 #pragma unroll
     for (int c = 0; c < E; ++c) T[c] = (double)widen16(p.lut[c], bf16);
+    __shared__ double Ts[E];
+    bool sorted = !bf16 && BITS >= 3;
+#pragma unroll
+    for (int c = 0; c + 1 < E; ++c) sorted = sorted && T[c] < T[c + 1];
+    if (threadIdx.x < E) {
+        double v = T[0];
+#pragma unroll
+        for (int c = 1; c < E; ++c) v = (int)threadIdx.x == c ? T[c] : v;
+        Ts[threadIdx.x] = v;
+    }
+    __syncthreads();
 
     for (long long unit = (long long)blockIdx.x * 4 + wave; unit < p.units; unit += (long long)gridDim.x * 4) {
         const int rb = (int)(unit / p.upr), uc = (int)(unit % p.upr);
@@ -123,14 +143,24 @@ __global__ __launch_bounds__(256) void quantize_kernel(const QuantParams p) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const double u = sg == 0.0 ? 0.0 : (double)w[t][j] / sg;
-                double best = __builtin_fabs(u - T[0]);
                 uint32_t arg = 0;
+                if (sorted) {                               // (uniform over the launch)
+                    int lower = 0;                          // entries [0, lower) are <= u
 #pragma unroll
-                for (int c = 1; c < E; ++c) {
-                    const double d = __builtin_fabs(u - T[c]);
-                    const bool less = d < best;
-                    best = less ? d : best;
-                    arg = less ? (uint32_t)c : arg;
+                    for (int step = E / 2; step >= 1; step >>= 1)
+                        if (Ts[lower + step - 1] <= u) lower += step;
+                    if (Ts[lower] <= u) lower += 1;
+                    const int lo = lower > 0 ? lower - 1 : 0, hi = lower < E ? lower : E - 1;
+                    arg = __builtin_fabs(u - Ts[hi]) < __builtin_fabs(u - Ts[lo]) ? (uint32_t)hi : (uint32_t)lo;
+                } else {
+                    double best = __builtin_fabs(u - T[0]);
+#pragma unroll
+                    for (int c = 1; c < E; ++c) {
+                        const double d = __builtin_fabs(u - T[c]);
+                        const bool less = d < best;
+                        best = less ? d : best;
+                        arg = less ? (uint32_t)c : arg;
+                    }
                 }
                 word |= arg << (4 * j);
             }

@@ -112,8 +112,8 @@ def test_matmul_matches_oracle(lutq, bits, group, dtype):
 def test_quantize_bit_exact(lutq, bits, group, dtype):
     """The GPU quantiser (Section 3, first equation; absmax group scale of Section 4.1/4.2) against
     the oracle's quantiser followed by the oracle's packer: scales and packed bytes bit for bit, for
-    fp32 and 16-bit weights, a NormalFloat table, an unsorted table with a duplicated entry, a dead
-    group, exact ties, and super-blocks of 1, 2 and 4 row blocks."""
+    fp32 and 16-bit weights, a NormalFloat table, an unsorted table with a duplicated entry, an
+    increasing table that does not reach the normalised weights' range, a dead group, exact ties, and super-blocks of 1, 2 and 4 row blocks."""
     import torch
     rng = np.random.default_rng(17 * bits + group)
     E = 1 << bits
@@ -121,6 +121,8 @@ def test_quantize_bit_exact(lutq, bits, group, dtype):
     t2 = rng.standard_normal(E)
     t2[E - 1] = t2[0]                                           # duplicate: the lower index must win
     tables.append(gen.encode16(t2, dtype))
+    # strictly increasing and short of +-1: normalised weights fall outside the table's range
+    tables.append(gen.encode16(np.sort(rng.uniform(-0.8, 0.7, E)), dtype))
     for N, K in ((48, 512), (96, 768 if group < 256 and bits == 4 else 1024), (128, 256)):
         for ti, T in enumerate(tables):
             W32 = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
