@@ -235,11 +235,56 @@ def main():
             drun = capture(dense_pass).replay if use_graph else dense_pass
             warm(torch, drun)
             td = time_region(torch, drun, 10) / ring
-            del Wd, drun
+            # hot regime: the same weight buffer on every call (what a repetition loop over one matrix
+            # measures: the small shapes then come from the caches, not from HBM)
+            def hot_pass(n=n):
+                for _ in range(LAYERS):
+                    one_call(n, 0)
+            hrun = capture(hot_pass).replay if use_graph else hot_pass
+            warm(torch, hrun)
+            th = time_region(torch, hrun, 10) / LAYERS
             per_shape[n] = {"N": N, "K": K, "us": t * 1e6, "GBps": by / t * 1e-9, "frac_of_8TBps": by / t * 1e-9 / HBM_PEAK_GBS,
                             "TFLOPs": 2.0 * M * N * K / t * 1e-12, "dense_fp16_us": td * 1e6, "speedup_vs_dense_fp16": td / t,
-                            "stream_read_us": tr * 1e6, "stream_read_GBps": m["packed"].numel() / tr * 1e-9}
+                            "stream_read_us": tr * 1e6, "stream_read_GBps": m["packed"].numel() / tr * 1e-9,
+                            "hot_us": th * 1e6, "hot_GBps": by / th * 1e-9}
+            # the other batch sizes of the metric (M = 2..32) on the same cold rings, each beside the dense GEMM
+            by_m = {}
+            for m2 in (2, 4, 8, 16, 32):
+                X2 = torch.randn((m2, K), device="cuda").to(torch.float16)
+                Y2 = torch.empty((m2, N), dtype=torch.float16, device="cuda")
+                Yd2 = torch.empty((m2, N), dtype=torch.float16, device="cuda")
+
+                def m_pass(n=n, X2=X2, Y2=Y2):
+                    for li in range(LAYERS):
+                        lutq.lutq_matmul(X2, layers[li][n]["packed"], layers[li][n]["S"], m["T"], BITS, GROUP, Y2, ws)
+
+                def dense_m_pass(Wd=Wd, X2=X2, Yd2=Yd2):
+                    for w in Wd:
+                        torch.mm(X2, w.t(), out=Yd2)
+                mrun = capture(m_pass).replay if use_graph else m_pass
+                warm(torch, mrun)
+                tm = time_region(torch, mrun, 10) / LAYERS
+                dmrun = capture(dense_m_pass).replay if use_graph else dense_m_pass
+                warm(torch, dmrun)
+                tdm = time_region(torch, dmrun, 10) / ring
+                bm = gen.algorithmic_bytes(m2, N, K, BITS, GROUP)
+                by_m[str(m2)] = {"us": tm * 1e6, "GBps": bm / tm * 1e-9, "frac_of_8TBps": bm / tm * 1e-9 / HBM_PEAK_GBS,
+                                 "TFLOPs": 2.0 * m2 * N * K / tm * 1e-12, "dense_fp16_us": tdm * 1e6,
+                                 "speedup_vs_dense_fp16": tdm / tm}
+                del mrun, dmrun
+            per_shape[n]["by_M"] = by_m
+            del Wd, drun
         out["per_shape_cold"] = per_shape
+        # a chain of dependent launches that do nothing (one workgroup reading 16 bytes): the cost of a
+        # launch itself, part of every call above
+        tiny = torch.zeros(16, dtype=torch.uint8, device="cuda")
+
+        def empty_pass():
+            for _ in range(LAYERS):
+                lutq.calib_stream_read(tiny, 1, sink)
+        erun = capture(empty_pass).replay if use_graph else empty_pass
+        warm(torch, erun)
+        out["empty_launch_us"] = time_region(torch, erun, 10) / LAYERS * 1e6
         # the LLaMA-3-70B layer shapes (4-bit, group 64, M = 1; bf16 as in the 70B configuration, fp16 next
         # to it), each on a ring of weight buffers larger than the caches.  The packed bytes and scales
         # are random (drawn on the GPU): the kernel's time does not depend on the values, and parity at
