@@ -140,20 +140,27 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         return nw;
     };
     if (M > 4) {
-        // More than four activation rows use the plain activation layout: next to its weights every
-        // wave needs the M x TK activations of each tile it works on, as many bytes as the weights of
-        // M / (4 bits) row blocks.  The rules below were fitted to timings of all candidate plans
+        // More than four activation rows: next to its weights every wave needs the M x TK activations
+        // of each tile it works on, as many bytes as the weights of M / (4 bits) row blocks (from nine
+        // rows up the plain layout pads that to 16 or 32 rows; five to eight rows are loaded packed
+        // unless the teams share them through LDS).  The rules below were fitted to timings of all candidate plans
         // (lutq_tune) on the LLaMA-3 8B and 70B layer shapes at M = 8, 16, 32 and 2, 3, 4 bits; they
         // stay within a few per cent of the fastest plan there.
         //
         // Plain plan: one workgroup per row group, the largest R that still fills 60 % of the compute
-        // units (or half of them when K is long enough to be cut in two); K cut across workgroups
+        // units (or, from nine rows up, half of them when K is long enough to be cut in two); K cut across workgroups
         // when there are too few row groups; four waves (one per SIMD) from M = 13 up.
         auto r_fills = [&](int r) {
             const int64_t groups = nb / r;
+            // (2 bits with short K and 3 bits, up to eight rows: four row blocks per wave only on one and a half
+            // row groups per compute unit or more -- 12288x4096 and 15360x5120 at 3 bits, M = 8:
+            // R = 4 11.3 and 14.5 us, R = 2 9.5 and 11.6 us)
+            if (r == 4 && M <= 8 && bits < 4 && (K < 8192 || bits == 3) && groups < (int64_t)cus * 3 / 2) return false;
             if (groups >= (int64_t)cus * 6 / 10) return true;
+            // (up to eight rows load their activations packed, two K steps per load: sharing them
+            // between row blocks then no longer repays a K cut -- 4096x14336 at M = 8: 12.1 -> 10.8 us)
             const int64_t j = (cus + groups - 1) / groups;
-            return j <= 2 && K / j >= 4096;
+            return M > 8 && j <= 2 && K / j >= 4096;
         };
         int r = force_r;
         if (!r) {
@@ -168,12 +175,15 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
             if (j > kt / 8) j = kt / 8;
             if (j < 1) j = 1;
             grid = groups * j;
-        } else if (groups < cus && K >= 12288) {
-            grid = cus;                                   // long K: every compute unit takes an equal share of the tiles
+        } else if (groups < cus && K >= 12288 && M > 8) {
+            // long K: every compute unit takes an equal share of the tiles (not up to eight rows, where
+            // the fix-up of every tile costs more than the idle units: 5120x13824 at M = 8, 160 row
+            // groups: 17.1 us against 15.8 us uncut)
+            grid = cus;
         }
         while (grid > kMaxGrid) grid = (grid + 1) / 2;
         d.r = r; d.grid = (int)grid; d.rs = 1;
-        d.nw = (M > 12 || (r == 4 && groups > cus)) ? 4 : 8;
+        d.nw = (M > 12 || (r == 4 && groups > cus) || (M <= 8 && bits < 4 && groups > cus)) ? 4 : 8;
         // Team plan: a workgroup takes A = R x RS row blocks as RS teams that share the activations
         // through LDS (needs enough teams to stage a tile between them, and chunked scales).  It pays
         // when the activations outweigh the weights (M / (4 bits) >= 1.3, or >= 1 on a larger problem) on
@@ -424,8 +434,9 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1;
     const bool bf16 = dtype == LUTQ_BF16;
-    // M <= 4: four K steps of activations per load, rotated into place (a quarter of the registers)
-    const int xm = (M <= 4) ? 4 : 16;
+    // M <= 4: four K steps of activations per load, rotated into place (a quarter of the registers);
+    // M <= 8: two, unless the plan shares the activations through LDS (decided below)
+    int xm = (M <= 4) ? 4 : 16;
     const bool sch = (K / group_size) % 8 == 0;            // scale rows are 16-byte aligned: chunked scale path
     int force_r = 0;
     if (user_plan) {
@@ -478,9 +489,12 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     // fetched by every team (LUTQ_NO_SHARED_X=1 switches that off, for comparisons)
     int xsh = (!rowlut && M > 4 && sch && teams_can_share_x(bits, mb, d.rs) && !std::getenv("LUTQ_NO_SHARED_X"))
                   ? x_pieces_per_wave(bits, mb, d.rs) : 0;
+    const bool can_pack8 = M > 4 && M <= 8 && !std::getenv("LUTQ_NO_XM8");
+    if (can_pack8 && !xsh) xm = 8;
     bool wide = d.nw > 8 || (d.nw > 4 && sch && matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, true, xsh));
     if (xsh && !matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, xsh)) {
         xsh = 0;
+        if (can_pack8) xm = 8;
         wide = d.nw > 8 || (d.nw > 4 && sch && wide_exists(bits, bf16, r, mb, d.stages, xm));
     }
     if (!matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, xsh)) return LUTQ_ERR_PLAN;
@@ -489,6 +503,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
                               : matmul_lds_bytes<4>(r, mb, d.nw, d.rs, sch, xsh);
     if (xsh && lds_bytes > 160 * 1024) {                  // the buffers do not fit: fetch per team
         xsh = 0;
+        if (can_pack8) xm = 8;
         wide = d.nw > 8 || (d.nw > 4 && sch && wide_exists(bits, bf16, r, mb, d.stages, xm));
         if (!matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, false)) return LUTQ_ERR_PLAN;
         lds_bytes = bits == 2 ? matmul_lds_bytes<2>(r, mb, d.nw, d.rs, sch, false)

@@ -73,6 +73,10 @@ hipError_t launch_group(int mb, int r, int stages, bool sch, int xm, bool wide, 
         if (r == 1) return launch_r<GROUP, 1, 1, 4>(stages, sch, wide, xsh, p, stream);
         if (r == 2) return launch_r<GROUP, 1, 2, 4>(stages, sch, wide, xsh, p, stream);
         if (r == 4) return launch_r<GROUP, 1, 4, 4>(stages, sch, wide, xsh, p, stream);
+    } else if (mb == 1 && xm == 8) {
+        if (r == 1) return launch_r<GROUP, 1, 1, 8>(stages, sch, wide, xsh, p, stream);
+        if (r == 2) return launch_r<GROUP, 1, 2, 8>(stages, sch, wide, xsh, p, stream);
+        if (r == 4) return launch_r<GROUP, 1, 4, 8>(stages, sch, wide, xsh, p, stream);
     } else if (mb == 1 && xm == 16) {
         if (r == 1) return launch_r<GROUP, 1, 1, 16>(stages, sch, wide, xsh, p, stream);
         if (r == 2) return launch_r<GROUP, 1, 2, 16>(stages, sch, wide, xsh, p, stream);
@@ -105,6 +109,7 @@ hipError_t launch_rowlut_one(const MatmulParams& p, hipStream_t stream) {
 template <int GROUP>
 hipError_t launch_rowlut(int mb, int xm, bool sch, const MatmulParams& p, hipStream_t stream) {
     if (mb == 1 && xm == 4) return sch ? launch_rowlut_one<GROUP, 1, 4, true>(p, stream) : launch_rowlut_one<GROUP, 1, 4, false>(p, stream);
+    if (mb == 1 && xm == 8) return sch ? launch_rowlut_one<GROUP, 1, 8, true>(p, stream) : launch_rowlut_one<GROUP, 1, 8, false>(p, stream);
     if (mb == 1 && xm == 16) return sch ? launch_rowlut_one<GROUP, 1, 16, true>(p, stream) : launch_rowlut_one<GROUP, 1, 16, false>(p, stream);
     if (mb == 2 && xm == 16) return sch ? launch_rowlut_one<GROUP, 2, 16, true>(p, stream) : launch_rowlut_one<GROUP, 2, 16, false>(p, stream);
     return hipErrorInvalidValue;

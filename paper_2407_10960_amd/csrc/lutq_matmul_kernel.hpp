@@ -115,7 +115,8 @@ __host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm
 // accumulates into its own registers (the other twelve columns multiply activations of other steps
 // and are never read), and the four accumulators are folded together, with three row rotations, once
 // per output tile.  This cuts the registers that hold activations in flight to a quarter and issues a
-// quarter of the activation loads.
+// quarter of the activation loads.  XM = 8 (M <= 8) is the same with two K steps per load: lane i
+// holds row i % 8 of step i / 8, two accumulators per row block, one rotation.
 // WIDE: the instance is compiled for up to 16 waves per workgroup and therefore at most 128
 // registers (four waves per SIMD, or two 8-wave workgroups with their two 64 KiB tables in the
 // 160 KiB of LDS); otherwise for up to 8 waves and as many registers as it likes.
@@ -129,7 +130,7 @@ __host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm
 // The number of waves and their arrangement in teams are run-time values.
 template <int BITS, int GROUP, int MB, int R, typename DT, int P, bool SCH, int XM, bool WIDE, int XPIECES, bool RLUT = false>
 __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulParams p) {
-    static_assert(XM == 16 || (XM == 4 && MB == 1), "packed activation loads exist for M <= 4 only");
+    static_assert(XM == 16 || ((XM == 4 || XM == 8) && MB == 1), "packed activation loads exist for M <= 8 only");
     constexpr bool XSH = XPIECES != 0;       // activations shared through LDS; XPIECES = pieces one wave stages (1 or 2)
     static_assert(XPIECES >= 0 && XPIECES <= kXPiecesPerWave, "a wave stages one or two pieces");
     static_assert(!XSH || XM == 16, "activations are shared through LDS in the plain layout only");

@@ -313,7 +313,8 @@ def test_team_plans_over_seeded_random_shapes(lutq):
 
 
 @pytest.mark.parametrize("bits,dtype,M,nb,kt", [(4, "f16", 1, 24, 4), (3, "bf16", 8, 24, 3), (2, "f16", 32, 16, 5),
-                                              (4, "bf16", 16, 28, 8), (3, "f16", 3, 12, 6)])
+                                              (4, "bf16", 16, 28, 8), (3, "f16", 3, 12, 6), (4, "f16", 6, 24, 6),
+                                              (2, "bf16", 7, 16, 4)])
 def test_every_tuner_candidate_matches_oracle(lutq, bits, dtype, M, nb, kt):
     """Every plan the tuner may time (Section 4.1: instance selection per shape) is either rejected
     with LUTQ_ERR_PLAN before anything is launched or gives the oracle's result."""
@@ -426,7 +427,7 @@ def test_one_table_per_output_row(lutq, bits, dtype):
     import torch
     rng = np.random.default_rng(100 + bits)
     E = 1 << bits
-    for (N, K, group, Ms) in [(48, 2 * tk(bits), 64, (32,)), (208, 8 * tk(bits), 128, (1, 4, 16, 32)),
+    for (N, K, group, Ms) in [(48, 2 * tk(bits), 64, (32,)), (208, 8 * tk(bits), 128, (1, 4, 7, 16, 32)),
                               (16 * 300, 2048, 32, (2, 40)), (80, 3 * tk(bits), 32, (5,))]:
         base = gen.make_case(700 + N, 32, N, K, bits, group, dtype, "random_index")
         Tn = gen.encode16(rng.standard_normal((N, E)), dtype)
