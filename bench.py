@@ -315,6 +315,51 @@ def main():
                 del pk, run
         out["per_shape_cold_llama3_70b_w4g64_m1"] = per70
 
+    if not args.no_extras:
+        # the entry points beyond the M <= 32 shared-table call, on the gate+up shape (cold rings as above)
+        g = layer0["gate_up"]
+        N, K = g["N"], g["K"]
+        more = {}
+        # one table per output row (Section 2.3: tables at the output-channel level), M = 1
+        Tn = (torch.randn((N, 1 << BITS), device="cuda") * 0.5).to(torch.float16)
+
+        def chan_pass():
+            for li in range(LAYERS):
+                lutq.lutq_matmul_channel(g["X"], layers[li]["gate_up"]["packed"], layers[li]["gate_up"]["S"], Tn,
+                                         BITS, GROUP, Y["gate_up"], ws)
+        run = capture(chan_pass).replay if use_graph else chan_pass
+        warm(torch, run)
+        t = time_region(torch, run, 10) / LAYERS
+        by = gen.algorithmic_bytes(M, N, K, BITS, GROUP) + Tn.numel() * 2
+        more["per_row_tables_m1"] = {"N": N, "K": K, "us": t * 1e6, "GBps": by / t * 1e-9, "frac_of_8TBps": by / t * 1e-9 / HBM_PEAK_GBS}
+        # 33..128 activation rows (slices of 32 rows, one launch each)
+        for m2 in (64, 128):
+            X2 = torch.randn((m2, K), device="cuda").to(torch.float16)
+            Y2 = torch.empty((m2, N), dtype=torch.float16, device="cuda")
+
+            def big_pass(X2=X2, Y2=Y2):
+                for li in range(LAYERS):
+                    lutq.lutq_matmul(X2, layers[li]["gate_up"]["packed"], layers[li]["gate_up"]["S"], g["T"], BITS, GROUP, Y2, ws)
+            run = capture(big_pass).replay if use_graph else big_pass
+            warm(torch, run)
+            t = time_region(torch, run, 5) / LAYERS
+            by = gen.algorithmic_bytes(m2, N, K, BITS, GROUP)
+            more[f"m{m2}"] = {"N": N, "K": K, "us": t * 1e6, "GBps": by / t * 1e-9, "TFLOPs": 2.0 * m2 * N * K / t * 1e-12}
+            del run, X2, Y2
+        # GPU quantiser: dense fp32 weights -> scales + packed indices (reads 4 B, writes b/8 + 2/group B per weight)
+        Wq = torch.randn((N, K), device="cuda") * 0.02
+        Sq = torch.empty((N, K // GROUP), dtype=torch.float16, device="cuda")
+        Pq = torch.empty(lutq.lutq_packed_bytes(N, K, BITS, GROUP), dtype=torch.uint8, device="cuda")
+
+        def quant_pass():
+            lutq.lutq_quantize(Wq, g["T"], BITS, GROUP, Sq, Pq)
+        warm(torch, quant_pass)
+        t = time_region(torch, quant_pass, 10)
+        by = Wq.numel() * 4 + Sq.numel() * 2 + Pq.numel()
+        more["quantize_fp32"] = {"N": N, "K": K, "us": t * 1e6, "GBps": by / t * 1e-9, "Gweights_per_s": N * K / t * 1e-9}
+        del Wq, Sq, Pq
+        out["other_entry_points_llama3_8b_gate_up_w4g128"] = more
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layer0["o"]["case"])
     else:
