@@ -25,6 +25,11 @@
  * each, so the weights are streamed once per slice);
  * N a multiple of 16; K a multiple of the K-tile of the bit width (128 for
  * 4-bit, 256 for 2- and 3-bit) and of group_size; device pointers 16-byte aligned.
+ *
+ * Environment (read once per process, diagnostics only): LUTQ_VERBOSE=1 prints the launch shape
+ * of every call and the tuner's finalists to stderr (2: also the tuner's first-pass times);
+ * LUTQ_NO_SHARED_X=1 / LUTQ_NO_XM8=1 switch off two activation-load variants for comparisons.
+ * None of them changes a result.
  */
 #ifndef LUTQ_H
 #define LUTQ_H

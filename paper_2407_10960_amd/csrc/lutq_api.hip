@@ -84,6 +84,25 @@ inline bool teams_can_share_x(int bits, int mb, int rs) { return rs * kXPiecesPe
 // pieces of a tile each wave stages: one when there are as many teams as pieces, else two
 inline int x_pieces_per_wave(int bits, int mb, int rs) { return rs >= steps_per_tile(bits) * mb ? 1 : 2; }
 
+// Environment switches, read once per process.  LUTQ_VERBOSE=1 prints every launch shape and the tuner's
+// finalists to stderr (2: also the tuner's first-pass times); LUTQ_NO_SHARED_X=1 and LUTQ_NO_XM8=1 switch
+// off the activations shared through LDS and the packed activation loads for M = 5..8 (for comparisons).
+struct EnvSwitches {
+    int verbose;
+    bool no_shared_x, no_xm8;
+};
+const EnvSwitches& env_switches() {
+    static const EnvSwitches e = [] {
+        EnvSwitches v{};
+        const char* s = std::getenv("LUTQ_VERBOSE");
+        v.verbose = !s ? 0 : (s[0] == '2' ? 2 : 1);
+        v.no_shared_x = std::getenv("LUTQ_NO_SHARED_X") != nullptr;
+        v.no_xm8 = std::getenv("LUTQ_NO_XM8") != nullptr;
+        return v;
+    }();
+    return e;
+}
+
 bool wide_exists(int bits, bool bf16, int r, int mb, int stages, int xm) {
     return matmul_instance_exists(bits, bf16, r, mb, stages, true, xm, true);
 }
@@ -487,9 +506,9 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     // exists, so that two workgroups fit a compute unit
     // M > 4 with enough teams: the activations are staged in LDS once per workgroup instead of being
     // fetched by every team (LUTQ_NO_SHARED_X=1 switches that off, for comparisons)
-    int xsh = (!rowlut && M > 4 && sch && teams_can_share_x(bits, mb, d.rs) && !std::getenv("LUTQ_NO_SHARED_X"))
+    int xsh = (!rowlut && M > 4 && sch && teams_can_share_x(bits, mb, d.rs) && !env_switches().no_shared_x)
                   ? x_pieces_per_wave(bits, mb, d.rs) : 0;
-    const bool can_pack8 = M > 4 && M <= 8 && !std::getenv("LUTQ_NO_XM8");
+    const bool can_pack8 = M > 4 && M <= 8 && !env_switches().no_xm8;
     if (can_pack8 && !xsh) xm = 8;
     bool wide = d.nw > 8 || (d.nw > 4 && sch && matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, true, xsh));
     if (xsh && !matmul_instance_exists(bits, bf16, r, mb, d.stages, sch, xm, wide, xsh)) {
@@ -537,7 +556,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     p.kt_magic = p.KT == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KT);
     p.ks_magic = p.KS == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KS);
     p.fast_reduce = (d.nw - d.rs) * (r * mb * 4) * 256 <= (bits == 3 ? 64 : 256) * 256 ? 1 : 0;
-    if (std::getenv("LUTQ_VERBOSE"))
+    if (env_switches().verbose)
         std::fprintf(stderr, "lutq_matmul: R=%d grid=%d waves=%d (teams %d x %d) stages=%d wide=%d xm=%d shared_x=%d lds=%d\n", r, d.grid,
                      d.nw, d.rs, p.KS, d.stages, (int)wide, xm, (int)xsh, lds_bytes);
     out->p = p;
@@ -550,7 +569,7 @@ lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dt
     hipError_t e = q.rowlut ? pick_rowlut(bits, dtype)(group_size, q.mb, q.sch, q.xm, q.p, static_cast<hipStream_t>(stream))
                             : pick_matmul(bits, dtype)(group_size, q.mb, q.r, q.stages, q.sch, q.xm, q.wide, q.xsh, q.p,
                                                        static_cast<hipStream_t>(stream));
-    if (e != hipSuccess && std::getenv("LUTQ_VERBOSE"))
+    if (e != hipSuccess && env_switches().verbose)
         std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d)\n", hipGetErrorString(e), q.p.G, q.p.NW * 64);
     return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
 }
@@ -747,7 +766,7 @@ extern "C" lutq_status lutq_tune(const void* X, const void* const* packed, const
         if (st == LUTQ_ERR_PLAN) continue;
         if (st != LUTQ_OK) return cleanup(st);
         order.emplace_back(us, i);
-        if (const char* v = std::getenv("LUTQ_VERBOSE"); v && v[0] == '2')
+        if (env_switches().verbose == 2)
             std::fprintf(stderr, "lutq_tune: quick R=%d grid=%d waves=%d stages=%d teams=%d: %.2f us\n",
                          cands[i].row_blocks_per_wave, cands[i].grid, cands[i].waves_per_workgroup,
                          cands[i].tiles_in_flight, cands[i].row_groups_per_workgroup, us);
@@ -773,7 +792,7 @@ extern "C" lutq_status lutq_tune(const void* X, const void* const* packed, const
     int best_i = -1;
     for (size_t j = 0; j < fin.size(); ++j) {
         const int i = fin[j];
-        if (std::getenv("LUTQ_VERBOSE"))
+        if (env_switches().verbose)
             std::fprintf(stderr, "lutq_tune: %s R=%d grid=%d waves=%d stages=%d teams=%d: %.2f us\n", i == 0 ? "default" : "candidate",
                          cands[i].row_blocks_per_wave, cands[i].grid, cands[i].waves_per_workgroup,
                          cands[i].tiles_in_flight, cands[i].row_groups_per_workgroup, tmin[j]);
