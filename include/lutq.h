@@ -29,7 +29,7 @@
  * Environment (read once per process, diagnostics only): LUTQ_VERBOSE=1 prints the launch shape
  * of every call and the tuner's finalists to stderr (2: also the tuner's first-pass times);
  * LUTQ_NO_SHARED_X=1 / LUTQ_NO_XM8=1 switch off two activation-load variants for comparisons.
- * None of them changes a result.
+ * They change at most the order of the fp32 summation.
  */
 #ifndef LUTQ_H
 #define LUTQ_H

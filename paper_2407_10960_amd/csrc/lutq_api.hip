@@ -171,15 +171,18 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         // when there are too few row groups; four waves (one per SIMD) from M = 13 up.
         auto r_fills = [&](int r) {
             const int64_t groups = nb / r;
-            // (2 bits with short K and 3 bits, up to eight rows: four row blocks per wave only on one and a half
-            // row groups per compute unit or more -- 12288x4096 and 15360x5120 at 3 bits, M = 8:
-            // R = 4 11.3 and 14.5 us, R = 2 9.5 and 11.6 us)
-            if (r == 4 && M <= 8 && bits < 4 && (K < 8192 || bits == 3) && groups < (int64_t)cus * 3 / 2) return false;
+            // (3 bits below the team plans' M, and 2 bits up to eight rows with a short K: four row blocks
+            // per wave only on one and a half row groups per compute unit or more -- 12288x4096 and
+            // 15360x5120 at 3 bits, M = 8: R = 4 11.3 and 14.5 us, R = 2 9.5 and 11.6 us; M = 12: 12.2 and
+            // 15.2 us against 10.8 and 13.1 us)
+            if (r == 4 && bits < 4 && (bits == 3 ? M <= 15 : (M <= 8 && K < 8192)) && groups < (int64_t)cus * 3 / 2) return false;
             if (groups >= (int64_t)cus * 6 / 10) return true;
             // (up to eight rows load their activations packed, two K steps per load: sharing them
             // between row blocks then no longer repays a K cut -- 4096x14336 at M = 8: 12.1 -> 10.8 us)
             const int64_t j = (cus + groups - 1) / groups;
-            return M > 8 && j <= 2 && K / j >= 4096;
+            // (2 and 3 bits need longer halves: 4096x11008, M = 12, 3 bits: cut 16.5 us, uncut R = 1 11.9 us,
+            // while 4096x14336 is faster cut at every bit width)
+            return M > 8 && j <= 2 && K / j >= (bits == 4 ? 4096 : 6144);
         };
         int r = force_r;
         if (!r) {
@@ -194,22 +197,22 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
             if (j > kt / 8) j = kt / 8;
             if (j < 1) j = 1;
             grid = groups * j;
-        } else if (groups < cus && K >= 12288 && M > 8) {
-            // long K: every compute unit takes an equal share of the tiles (not up to eight rows, where
+        } else if (groups < cus && K >= 12288 && M > 8 && bits == 4) {
+            // long K, 4 bits: every compute unit takes an equal share of the tiles (not up to eight rows, where
             // the fix-up of every tile costs more than the idle units: 5120x13824 at M = 8, 160 row
             // groups: 17.1 us against 15.8 us uncut)
             grid = cus;
         }
         while (grid > kMaxGrid) grid = (grid + 1) / 2;
         d.r = r; d.grid = (int)grid; d.rs = 1;
-        d.nw = (M > 12 || (r == 4 && groups > cus) || (M <= 8 && bits < 4 && groups > cus)) ? 4 : 8;
+        d.nw = (M > 12 || (r == 4 && groups > cus) || (bits < 4 && groups > cus)) ? 4 : 8;
         // Team plan: a workgroup takes A = R x RS row blocks as RS teams that share the activations
         // through LDS (needs enough teams to stage a tile between them, and chunked scales).  It pays
-        // when the activations outweigh the weights (M / (4 bits) >= 1.3, or >= 1 on a larger problem) on
+        // when the activations outweigh the weights (M / (4 bits) >= 1.3 -- 1.0 at 3 bits --, or >= 1 on a larger problem) on
         // a problem long enough to hide the barrier per tile, from 17 rows up, or on very large problems.
         const bool plain_r4_uncut = r == 4 && grid == groups;
         const int64_t size = nb * K / cus;                // weight rows x columns per compute unit / 16
-        const bool teams = (mb == 2 && size >= 12000) || (10 * M >= 52 * bits && size >= 20000) ||
+        const bool teams = (mb == 2 && size >= 12000) || (10 * M >= (bits == 3 ? 40 : 52) * bits && size >= 20000) ||
                            (M >= 4 * bits && size >= 50000) || size >= 100000;
         if (!teams || !sch || force_r) return d;
         const int need = (steps_per_tile(bits) * mb + kXPiecesPerWave - 1) / kXPiecesPerWave;
