@@ -192,13 +192,18 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         }
         const int64_t groups = nb / r;
         int64_t grid = groups;
-        if (groups < (int64_t)cus * 6 / 10 && (int64_t)r * 16 * K * bits / 8 >= 64 * 1024) {   // (a cut must repay its fix-up)
+        // (a cut must repay its fix-up: row groups of 64 KiB or more; from 17 rows up smaller ones too, in two
+        // parts -- 1024x4096 at M = 32: 10.4 -> 9.1 us)
+        const bool big_groups = (int64_t)r * 16 * K * bits / 8 >= 64 * 1024;
+        if (groups < (int64_t)cus * 6 / 10 && (big_groups || M > 16)) {
             int64_t j = (cus + groups - 1) / groups;      // K parts per row group
+            if (!big_groups && j > 2) j = 2;
             if (j > kt / 8) j = kt / 8;
             if (j < 1) j = 1;
             grid = groups * j;
-        } else if (groups < cus && K >= 12288 && M > 8 && bits == 4) {
-            // long K, 4 bits: every compute unit takes an equal share of the tiles (not up to eight rows, where
+        } else if (groups < cus && K >= 12288 && (bits == 4 ? M > 8 : M > 16)) {
+            // long K (2 and 3 bits: from 17 rows up; 5120x13824 at 3 bits: M = 12 19.4 us split, 17.6 us not;
+            // M = 32 29.4 us split, 32.3 us not): every compute unit takes an equal share of the tiles (not up to eight rows, where
             // the fix-up of every tile costs more than the idle units: 5120x13824 at M = 8, 160 row
             // groups: 17.1 us against 15.8 us uncut)
             grid = cus;
@@ -325,6 +330,18 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
             break;
         }
     }
+    if (!force_r && (bits == 4 || (bits == 2 && !bf16)) && nb > cus && nb * 2 < (int64_t)cus * 3 && sb % 2 == 0) {
+        // between one and one and a half row blocks per compute unit (4-bit and fp16 2-bit): pairs of row blocks,
+        // so that every workgroup is resident from the start, as R = 2 or as two teams (5120-row matrices
+        // on 256 compute units, M = 4: 5120x13824 4-bit 15.1 -> 13.2 us, 2-bit 11.5 -> 9.8 us; M = 1, 2: 3-7 %)
+        const int r = (bits == 2 || wide_exists(bits, bf16, 2, mb, 2, xm)) ? 2 : 1;
+        const int64_t rs = 2 / r;
+        const int nw = waves_for(r, rs, kt);
+        if (nw >= 4 && nw <= max_nw) {
+            d.r = r; d.grid = (int)(nb / 2); d.nw = nw; d.rs = (int)rs;
+            return d;
+        }
+    }
     // (2- and 3-bit: measured, many small workgroups -- several per compute unit, out of step with
     // each other -- beat both a larger R and the split above: 70B QKV 3-bit 10.6 us against 12.7 us,
     // LLaMA-2-13B gate+up 3-bit 15.3 us at R = 1 against 17.6 us at R = 2)
@@ -342,9 +359,19 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         if (j < 1) j = 1;
         grid = groups * j;
     }
+    // ... but from two rows (bf16 2-bit) or three (3-bit) up, two or four of them side by side as teams
+    // of one workgroup, as long as that leaves 1.6 workgroups per compute unit (measured at M = 2 and 3 on
+    // N/16 = 960 ... 3696: 32000x4096 bf16 2-bit 18.6 -> 14.5 us, 3-bit 15.5 -> 13.8 us)
+    int rs = 1;
+    if (!force_r && r == 1 && grid == groups && nb <= kMaxGrid &&            // (a partial-sum slot per team and workgroup)
+        ((bits == 3 && M >= 3) || (bits == 2 && bf16 && M >= 2))) {
+        for (int t : {4, 2})
+            if (nb % t == 0 && nb / t >= (int64_t)cus * 16 / 10) { rs = t; break; }
+        grid = groups / rs;
+    }
     while (grid > kMaxGrid) grid = (grid + 1) / 2;
-    d.r = r; d.grid = (int)grid; d.rs = 1;
-    d.nw = (bits == 3 && grid > cus) ? 4 : 8;
+    d.r = r; d.grid = (int)grid; d.rs = rs;
+    d.nw = (bits == 3 && grid * rs > cus) ? 4 : 8;
     return d;
 }
 
