@@ -359,12 +359,12 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         if (j < 1) j = 1;
         grid = groups * j;
     }
-    // ... but from two rows (bf16 2-bit) or three (3-bit) up, two or four of them side by side as teams
-    // of one workgroup, as long as that leaves 1.6 workgroups per compute unit (measured at M = 2 and 3 on
-    // N/16 = 960 ... 3696: 32000x4096 bf16 2-bit 18.6 -> 14.5 us, 3-bit 15.5 -> 13.8 us)
+    // ... but two or four of them side by side as teams of one workgroup, as long as that leaves 1.6
+    // workgroups per compute unit (measured at M = 1, 2, 3 on N/16 = 960 ... 3696: 32000x4096 bf16 2-bit
+    // 18.4 -> 14.3 us at M = 1, 3-bit 15.5 -> 13.8 us at M = 3)
     int rs = 1;
     if (!force_r && r == 1 && grid == groups && nb <= kMaxGrid &&            // (a partial-sum slot per team and workgroup)
-        ((bits == 3 && M >= 3) || (bits == 2 && bf16 && M >= 2))) {
+        (bits == 3 || (bits == 2 && bf16))) {
         for (int t : {4, 2})
             if (nb % t == 0 && nb / t >= (int64_t)cus * 16 / 10) { rs = t; break; }
         grid = groups / rs;
