@@ -217,7 +217,7 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         // a problem long enough to hide the barrier per tile, from 17 rows up, or on very large problems.
         const bool plain_r4_uncut = r == 4 && grid == groups;
         const int64_t size = nb * K / cus;                // weight rows x columns per compute unit / 16
-        const bool teams = (mb == 2 && size >= 12000) || (10 * M >= ((bits == 3 || (bits == 4 && bf16)) ? 40 : 52) * bits && size >= 20000) ||
+        const bool teams = (mb == 2 && size >= ((bf16 && bits == 4 && M <= 24) ? 20000 : 12000)) || (10 * M >= ((bits == 3 || (bits == 4 && bf16)) ? 40 : 52) * bits && size >= 20000) ||
                            (M >= 4 * bits && size >= 50000) || size >= 100000;
         if (!teams || !sch || force_r) return d;
         const int need = (steps_per_tile(bits) * mb + kXPiecesPerWave - 1) / kXPiecesPerWave;
