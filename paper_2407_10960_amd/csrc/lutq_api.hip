@@ -334,7 +334,9 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         // between one and one and a half row blocks per compute unit (4-bit and fp16 2-bit): pairs of row blocks,
         // so that every workgroup is resident from the start, as R = 2 or as two teams (5120-row matrices
         // on 256 compute units, M = 4: 5120x13824 4-bit 15.1 -> 13.2 us, 2-bit 11.5 -> 9.8 us; M = 1, 2: 3-7 %)
-        const int r = (bits == 2 || wide_exists(bits, bf16, 2, mb, 2, xm)) ? 2 : 1;
+        // (a short K as two teams of six waves, a long one as R = 2 on eight waves: 5120x5120 M = 2 7.4 us
+        // at R = 2, 6.3 us as two teams; 5120x13824 is fastest at R = 2)
+        const int r = (K >= 8192 && (bits == 2 || wide_exists(bits, bf16, 2, mb, 2, xm))) ? 2 : 1;
         const int64_t rs = 2 / r;
         const int nw = waves_for(r, rs, kt);
         if (nw >= 4 && nw <= max_nw) {
