@@ -194,6 +194,34 @@ def test_default_plans_of_the_llama3_shapes():
         lutq.lutq_plan_default_for(4, 128, 1, 4096, 4096, 0, 0)
 
 
+def test_default_plans_fitted_by_measurement():
+    """Default plans of settings whose rule was fitted from tuner timings on 256 compute units (one
+    case per rule: packed activation loads for M = 5..8, the 2-/3-bit rules for M = 9..15, small row
+    groups and long K from 17 rows up, pairs of row blocks, joined small workgroups, bf16 team
+    thresholds).  A change here must come with new timings."""
+    want = {
+        (4, 128, 8, 4096, 14336, 0): (1, 256, 8, 2, 1),
+        (3, 128, 8, 12288, 4096, 0): (2, 384, 4, 2, 1),
+        (3, 128, 12, 4096, 11008, 0): (1, 256, 8, 2, 1),
+        (3, 64, 12, 10240, 8192, 0): (1, 256, 10, 2, 10),
+        (2, 128, 12, 5120, 13824, 0): (2, 160, 8, 2, 1),
+        (3, 128, 32, 5120, 13824, 0): (2, 256, 4, 2, 1),
+        (4, 128, 32, 1024, 4096, 0): (1, 128, 4, 2, 1),
+        (4, 128, 4, 5120, 13824, 0): (2, 160, 8, 2, 1),
+        (4, 128, 2, 5120, 5120, 0): (1, 160, 12, 2, 2),
+        (2, 128, 1, 32000, 4096, 1): (1, 500, 8, 2, 4),
+        (3, 128, 3, 22016, 4096, 0): (1, 688, 4, 2, 2),
+        (4, 64, 16, 10240, 8192, 1): (2, 256, 10, 2, 5),
+        (4, 128, 20, 4096, 14336, 1): (2, 256, 4, 2, 1),
+        (4, 128, 8, 28672, 4096, 0): (4, 448, 4, 2, 1),
+        (4, 128, 32, 28672, 4096, 0): (2, 224, 8, 2, 4),
+    }
+    for (bits, g, M, N, K, dt), plan in want.items():
+        p = lutq.lutq_plan_default_for(bits, g, M, N, K, dt, 256)
+        got = (p.row_blocks_per_wave, p.grid, p.waves_per_workgroup, p.tiles_in_flight, p.row_groups_per_workgroup)
+        assert got == plan, (bits, g, M, N, K, dt, p)
+
+
 def test_plan_check_matches_documented_rules():
     ok = lambda *a, **k: lutq.lutq_plan_check(*a, **k)
     assert ok(4, 128, 1, 4096, 4096, 0, 256, lutq.Plan(1, 256, 12, 2, 1)) == 0
