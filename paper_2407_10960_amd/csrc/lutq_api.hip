@@ -189,6 +189,9 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
             r = sb;
             while (r > 1 && !r_fills(r)) r >>= 1;
             while (r > 1 && !matmul_instance_exists(bits, bf16, r, mb, 2, true, xm, false)) r >>= 1;   // registers
+            // (bf16 3-bit, up to eight rows, short K: half as many row blocks per wave while that leaves at
+            // most three row groups per compute unit -- 12288x4096 M = 6 10.2 -> 9.0 us, 5120x5120 9.0 -> 8.0 us)
+            if (bits == 3 && bf16 && M <= 8 && r > 1 && K < 8192 && nb / (r / 2) <= (int64_t)cus * 3) r >>= 1;
         }
         const int64_t groups = nb / r;
         int64_t grid = groups;
@@ -218,7 +221,7 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         const bool plain_r4_uncut = r == 4 && grid == groups;
         const int64_t size = nb * K / cus;                // weight rows x columns per compute unit / 16
         const bool teams = (mb == 2 && size >= ((bf16 && bits == 4 && M <= 24) ? 20000 : 12000)) || (10 * M >= ((bits == 3 || (bits == 4 && bf16)) ? 40 : 52) * bits && size >= 20000) ||
-                           (M >= 4 * bits && size >= 50000) || size >= 100000;
+                           (M > 8 && M >= 4 * bits && size >= 50000) || size >= 100000;
         if (!teams || !sch || force_r) return d;
         const int need = (steps_per_tile(bits) * mb + kXPiecesPerWave - 1) / kXPiecesPerWave;
         struct Cand { bool exact; int r; int64_t rs, sets; };
