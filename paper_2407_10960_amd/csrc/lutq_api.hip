@@ -251,6 +251,8 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         order.insert(order.end(), shallow.begin(), shallow.end());
         order.insert(order.end(), deep.begin(), deep.end());
         const int np = steps_per_tile(bits) * mb;         // activation pieces of one tile
+        Decomp reserve = d;
+        bool have_reserve = false;
         for (const Cand& c0 : order) {
             Cand c = c0;
             const int64_t cols = c.exact ? K : c.sets * K / cus;      // columns of K per workgroup
@@ -281,10 +283,18 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
             }
             if (!nw) continue;
             if ((c.exact ? c.sets : (int64_t)cus) * c.rs > kMaxGrid) continue;     // partial-sum slots of the workspace
-            d.r = c.r; d.grid = c.exact ? (int)c.sets : cus; d.nw = nw; d.rs = (int)c.rs; d.stages = stages;
-            return d;
+            Decomp t = d;
+            t.r = c.r; t.grid = c.exact ? (int)c.sets : cus; t.nw = nw; t.rs = (int)c.rs; t.stages = stages;
+            // a 4-bit candidate that wants four tiles in flight but has no such instance (bf16 beyond eight waves) is
+            // kept in reserve: a later one that has it is faster (70B QKV bf16 M = 28: ten teams, two tiles
+            // 26.4 us; eight teams, four tiles 24.0 us)
+            if (deep && stages == 2 && bits == 4) {
+                if (!have_reserve) { reserve = t; have_reserve = true; }
+                continue;
+            }
+            return t;
         }
-        return d;
+        return have_reserve ? reserve : d;
     }
     if (qn == 1 && pn <= 64 && (!force_r || pn % force_r == 0)) {
         int64_t per = pn;                                 // row blocks per compute unit
