@@ -532,9 +532,18 @@ FULL_SIZE = [
     ("70B qkv W4 g64 M32 (5 teams of R = 2, K cut in four)", 10240, 8192, 4, 64, "f16", 32),
     ("8B down W3 g128 bf16 M32 (8 teams, K cut in eight)", 4096, 14336, 3, 128, "bf16", 32),
     ("70B o W2 g64 M24 (8 teams)", 8192, 8192, 2, 64, "f16", 24),
-    ("70B qkv W3 g64 M12 (plain, R = 4, 160 workgroups)", 10240, 8192, 3, 64, "f16", 12),
+    ("70B qkv W3 g64 M12 (3-bit team plan from 12 rows)", 10240, 8192, 3, 64, "f16", 12),
     ("8B qkv W4 g256 M16 (plain, four waves)", 6144, 4096, 4, 256, "f16", 16),
     ("70B qkv W3 g64 M1 (one 4-wave workgroup per row block)", 10240, 8192, 3, 64, "f16", 1),
+    # branches fitted on shapes outside the LLaMA-3 set
+    ("22016x4096 W3 M3 (small workgroups joined as teams)", 22016, 4096, 3, 128, "f16", 3),
+    ("32000x4096 W2 bf16 M1 (four joined workgroups)", 32000, 4096, 2, 128, "bf16", 1),
+    ("5120x5120 W4 M2 (pairs of row blocks as two teams)", 5120, 5120, 4, 128, "f16", 2),
+    ("5120x13824 W4 M4 (pairs of row blocks, R = 2)", 5120, 13824, 4, 128, "f16", 4),
+    ("4096x11008 W3 M12 (R = 1, no K cut)", 4096, 11008, 3, 128, "f16", 12),
+    ("8B down W4 M8 (packed activation loads for 5..8 rows)", 4096, 14336, 4, 128, "f16", 8),
+    ("1024x4096 W4 M32 (small row groups cut in two)", 1024, 4096, 4, 128, "f16", 32),
+    ("70B qkv W4 g64 bf16 M28 (eight teams, four tiles in flight)", 10240, 8192, 4, 64, "bf16", 28),
 ]
 
 
