@@ -212,6 +212,30 @@ def test_every_batch_size_1_to_32(lutq, bits):
         check_y(Y, c, f"b{bits} M{M}")
 
 
+@pytest.mark.parametrize("bits,dtype", [(4, "f16"), (3, "bf16"), (2, "f16")])
+def test_every_batch_size_1_to_32_at_full_size(lutq, bits, dtype):
+    """Every M from 1 to 32 on a full layer shape (10240 x 8192, group 64: two and a half row blocks per
+    compute unit, so that the default plan changes several times over M -- packed activation loads,
+    plain and team plans, K cuts); the oracle recomputes all M rows of a sample of weight rows."""
+    N, K, group = 10240, 8192, 64
+    base = gen.make_case(23 + bits, 32, N, K, bits, group, dtype, "random_index")
+    d = DeviceCase(lutq, base)
+    rng = np.random.default_rng(bits)
+    rows = np.unique(np.concatenate([np.arange(16), np.arange(N - 16, N), rng.choice(N, 96, replace=False)]))
+    plans = set()
+    for M in range(1, 33):
+        p = lutq.lutq_plan_default(bits, group, M, N, K, 0 if dtype == "f16" else 1)
+        plans.add((p.row_blocks_per_wave, p.grid, p.waves_per_workgroup, p.tiles_in_flight, p.row_groups_per_workgroup))
+        X = base.X[:M].copy()
+        Y = to_bits(d.matmul(lutq, X=to_dev(X, dtype)))
+        assert Y.shape == (M, N)
+        sub = gen.Case(M, len(rows), K, bits, group, dtype, X, base.Q[rows], base.S[rows], base.T)
+        check_y(Y[:, rows], sub, f"b{bits} {dtype} M{M} {p}")
+        assert np.isfinite(orc.to_f64(Y, dtype)).all(), M
+    assert not d.ws[:65536].any().item()
+    assert len(plans) >= 3
+
+
 @pytest.mark.parametrize("bits,dtype", [(4, "f16"), (3, "f16"), (2, "bf16"), (4, "bf16")])
 def test_result_independent_of_work_decomposition(lutq, bits, dtype):
     """Any grid / rows-per-wave / table-copies plan gives the same Y up to fp32 summation order, is
