@@ -287,8 +287,9 @@ def main():
         out["empty_launch_us"] = time_region(torch, erun, 10) / LAYERS * 1e6
         # the LLaMA-3-70B layer shapes (4-bit, group 64, M = 1; bf16 as in the 70B configuration, fp16 next
         # to it), each on a ring of weight buffers larger than the caches.  The packed bytes and scales
-        # are random (drawn on the GPU): the kernel's time does not depend on the values, and parity at
-        # these sizes is what the full-size tests check.
+        # are random (drawn on the GPU): the kernel's time does not depend on the values.  Parity at these
+        # sizes and in these launch configurations is tests/test_gpu_parity.py::test_largest_shapes_sampled_rows
+        # and ::test_full_size_sampled_rows.
         shapes70 = {"qkv": (10240, 8192), "o": (8192, 8192), "gate_up": (57344, 8192), "down": (8192, 28672)}
         g70 = 64
         per70 = {}

@@ -584,3 +584,40 @@ def test_full_size_sampled_rows(lutq, name, N, K, bits, group, dtype, M):
     sub = gen.Case(M, len(rows), K, bits, group, dtype, c.X, c.Q[rows], c.S[rows], c.T)
     check_y(Y[:, rows], sub, name)
     assert np.isfinite(orc.to_f64(Y, dtype)).all()
+
+
+# The LLaMA-3-70B gate+up and down shapes (the largest of the Section 4.1 kernel-benchmark shapes:
+# 224 MiB and 112 MiB of packed 4-bit weights, so the kernel's 32-bit byte offsets are exercised
+# beyond 2^27) and the N = K = 8192, group 32 setting of Figure 4 with an arbitrary sorted table.
+NORTH_STAR_LARGEST = [
+    # (name, N, K, bits, group, dtype, lut, Ms)
+    ("70B gate_up W4 g64 bf16", 57344, 8192, 4, 64, "bf16", "random_index", (1, 16, 32)),
+    ("70B gate_up W4 g64 f16", 57344, 8192, 4, 64, "f16", "random_index", (1, 16, 32)),
+    ("70B gate_up W3 g64 bf16", 57344, 8192, 3, 64, "bf16", "random_index", (1, 16, 32)),
+    ("70B gate_up W3 g64 f16", 57344, 8192, 3, 64, "f16", "random_index", (1, 16, 32)),
+    ("70B down W4 g64 bf16", 8192, 28672, 4, 64, "bf16", "random_index", (1, 16, 32)),
+    ("70B down W4 g64 f16", 8192, 28672, 4, 64, "f16", "random_index", (1, 16, 32)),
+    ("70B down W3 g64 bf16", 8192, 28672, 3, 64, "bf16", "random_index", (1, 16, 32)),
+    ("70B down W3 g64 f16", 8192, 28672, 3, 64, "f16", "random_index", (1, 16, 32)),
+    ("8192^2 W4 g32 learned table", 8192, 8192, 4, 32, "f16", "learned", (1, 2, 4, 8, 16, 32)),
+    ("8192^2 W2 g32 learned table", 8192, 8192, 2, 32, "f16", "learned", (1, 2, 4, 8, 16, 32)),
+]
+
+
+@pytest.mark.parametrize("name,N,K,bits,group,dtype,lut,Ms", NORTH_STAR_LARGEST)
+def test_largest_shapes_sampled_rows(lutq, name, N, K, bits, group, dtype, lut, Ms):
+    """The default launch configuration of every listed M on one weight matrix; the oracle recomputes
+    all M rows of 176 sampled weight rows (the first and the last row block included), and every
+    other output must be finite."""
+    base = gen.make_case(29, max(Ms), N, K, bits, group, dtype, lut)
+    d = DeviceCase(lutq, base)
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([np.arange(16), np.arange(N - 16, N), rng.choice(N, 144, replace=False)]))
+    for M in Ms:
+        X = base.X[:M].copy()
+        Y = to_bits(d.matmul(lutq, X=to_dev(X, dtype)))
+        assert Y.shape == (M, N)
+        assert not d.ws[:65536].any().item()
+        sub = gen.Case(M, len(rows), K, bits, group, dtype, X, base.Q[rows], base.S[rows], base.T)
+        check_y(Y[:, rows], sub, f"{name} M{M}")
+        assert np.isfinite(orc.to_f64(Y, dtype)).all(), f"{name} M{M}"
