@@ -52,7 +52,8 @@ typedef enum {
     LUTQ_ERR_WORKSPACE = 7,    /* workspace missing or smaller than lutq_workspace_bytes() */
     LUTQ_ERR_DTYPE = 8,        /* dtype not LUTQ_F16 / LUTQ_BF16 */
     LUTQ_ERR_DEVICE = 9,       /* a HIP runtime call failed (launch, device query) */
-    LUTQ_ERR_PLAN = 10         /* lutq_plan fields outside their documented ranges */
+    LUTQ_ERR_PLAN = 10,        /* lutq_plan fields outside their documented ranges */
+    LUTQ_ERR_SCRATCH = 11      /* lutq_matmul_static: the launch needs more than the built-in scratch */
 } lutq_status;
 
 typedef enum { LUTQ_F16 = 0, LUTQ_BF16 = 1 } lutq_dtype;
@@ -149,6 +150,26 @@ lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scal
                              lutq_dtype dtype, void* Y,
                              void* workspace, size_t workspace_bytes, void* stream,
                              const lutq_plan* plan);
+
+/* lutq_matmul_plan for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  The arrival counters and
+ * partial sums live in a device array of the library's own, LUTQ_STATIC_SCRATCH_BYTES large (64 KiB of
+ * counters + 16 MiB of partial-sum slots), which every GPU the library runs on holds from the first use
+ * of the library on it until the process ends.  The call allocates nothing and calls no allocating
+ * routine; the first call on a device looks the array's address up once (make that call outside a
+ * graph capture).  Every other argument and the result are those of lutq_matmul_plan (plan may be NULL
+ * for the default decomposition), bit for bit under the same plan.
+ * A launch needs partial-sum slots only when its plan cuts output tiles across workgroups:
+ * grid x row groups per workgroup x 2 slots of R x ceil(M/16) x 1 KiB (M capped at 32).  If that exceeds
+ * the 16 MiB the call returns LUTQ_ERR_SCRATCH before anything is launched (Y untouched); every default
+ * plan of the LLaMA-3 8B/70B shapes fits.
+ * All calls on one GPU share the one array: calls that may overlap on a GPU (different streams) race
+ * on it and must use lutq_matmul with separate workspaces instead.  The counters are returned to zero by
+ * every launch; the slots keep the last call's partial sums and are overwritten before they are read. */
+#define LUTQ_STATIC_SCRATCH_BYTES ((size_t)(64 * 1024 + 16 * 1024 * 1024))
+lutq_status lutq_matmul_static(const void* X, const void* packed, const void* scales, const void* lut,
+                               int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                               lutq_dtype dtype, void* Y, void* stream, const lutq_plan* plan);
 
 /* Finer-grained tables: one table per output row (Section 2.3: lookup tables obtained at the
  * output-channel level; Section 5 names flexible tables as what the kernel is for).

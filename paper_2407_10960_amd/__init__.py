@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     lutq_dequant,
     lutq_matmul,
     lutq_matmul_channel,
+    lutq_matmul_static,
+    STATIC_SCRATCH_BYTES,
     lutq_pack,
     lutq_packed_bytes,
     lutq_plan_default,

@@ -12,7 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "lutq_status_string", "lutq_packed_bytes", "lutq_pack", "lutq_unpack", "lutq_workspace_bytes",
-    "lutq_plan_default", "lutq_plan_default_for", "lutq_plan_check", "lutq_matmul", "lutq_matmul_plan", "lutq_matmul_channel", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
+    "lutq_plan_default", "lutq_plan_default_for", "lutq_plan_check", "lutq_matmul", "lutq_matmul_plan", "lutq_matmul_static", "lutq_matmul_channel", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
     "lutq_calib_stream_read", "lutq_calib_copy",
 )
 
@@ -81,6 +81,8 @@ def load_library():
     lib.lutq_matmul_plan.restype = ci
     lib.lutq_matmul_plan.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp,
                                      ctypes.POINTER(_CPlan)]
+    lib.lutq_matmul_static.restype = ci
+    lib.lutq_matmul_static.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, ctypes.POINTER(_CPlan)]
     lib.lutq_matmul_channel.restype = ci
     lib.lutq_matmul_channel.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.lutq_tune.restype = ci
@@ -227,6 +229,31 @@ def lutq_matmul(X, packed, scales, lut, bits: int, group_size: int, Y, workspace
     else:
         cp = plan._c()
         _check(lib.lutq_matmul_plan(*args, ctypes.byref(cp)), "lutq_matmul_plan")
+    return Y
+
+
+STATIC_SCRATCH_BYTES = 64 * 1024 + 16 * 1024 * 1024
+
+
+def lutq_matmul_static(X, packed, scales, lut, bits: int, group_size: int, Y, stream=None, plan: Plan | None = None):
+    """lutq_matmul on the library's built-in scratch: no workspace argument, nothing is allocated."""
+    lib = load_library()
+    for t in (X, packed, scales, lut, Y):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("lutq_matmul_static needs contiguous CUDA (HIP) tensors")
+    code = _dtype_code(X)
+    if not (_dtype_code(scales) == code and _dtype_code(lut) == code and _dtype_code(Y) == code):
+        raise TypeError("X, scales, lut and Y must share one dtype")
+    M, K = X.shape
+    N = scales.shape[0]
+    if scales.shape[1] * group_size != K or tuple(Y.shape) != (M, N) or lut.numel() != (1 << bits):
+        raise ValueError("inconsistent shapes")
+    if packed.numel() != lib.lutq_packed_bytes(N, K, bits, group_size):
+        raise ValueError("packed buffer has the wrong size for (N, K, bits)")
+    cp = plan._c() if plan is not None else None
+    _check(lib.lutq_matmul_static(X.data_ptr(), packed.data_ptr(), scales.data_ptr(), lut.data_ptr(), bits, group_size,
+                                  M, N, K, code, Y.data_ptr(), _stream_ptr(stream),
+                                  ctypes.byref(cp) if cp is not None else None), "lutq_matmul_static")
     return Y
 
 

@@ -21,6 +21,14 @@ constexpr size_t kCounterBytes = 64 * 1024;                                   //
 constexpr size_t kSlotBytes = (size_t)kSlotFloats * sizeof(float);            // 8 KiB
 constexpr size_t kWorkspaceBytes = kCounterBytes + (size_t)kMaxGrid * 2 * kSlotBytes;
 
+// Scratch of lutq_matmul_static: the same two areas (arrival counters, partial-sum slots) in a device array
+// of the library's own, so that the call needs no workspace from the caller and allocates nothing.  Every
+// device the library runs on holds its own copy from the moment the code object is loaded until the
+// process ends.  Device globals start zeroed, and every launch returns the counters it used to zero, so the
+// counters are zero whenever a launch starts; the slots are overwritten before they are read.
+constexpr size_t kStaticSlotBytes = LUTQ_STATIC_SCRATCH_BYTES - kCounterBytes;
+static __device__ __align__(256) unsigned char scratch[LUTQ_STATIC_SCRATCH_BYTES];
+
 inline int tile_k(int bits) { return bits == 4 ? 128 : 256; }
 
 lutq_status check_problem(int bits, int group_size, int64_t N, int64_t K) {
@@ -422,6 +430,7 @@ extern "C" const char* lutq_status_string(lutq_status s) {
         case LUTQ_ERR_DTYPE: return "dtype must be LUTQ_F16 or LUTQ_BF16";
         case LUTQ_ERR_DEVICE: return "HIP runtime error";
         case LUTQ_ERR_PLAN: return "invalid plan";
+        case LUTQ_ERR_SCRATCH: return "the work decomposition needs more partial-sum scratch than lutq_matmul_static's built-in LUTQ_STATIC_SCRATCH_BYTES";
     }
     return "unknown status";
 }
@@ -475,7 +484,8 @@ struct Prepared {
 lutq_status prepare_matmul(const void* X, const void* packed, const void* scales, const void* lut,
                            int bits, int group_size, int64_t M, int64_t N, int64_t K,
                            lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
-                           const lutq_plan* user_plan, bool rowlut, int dry_run_cus, Prepared* out) {
+                           const lutq_plan* user_plan, bool rowlut, int dry_run_cus, Prepared* out,
+                           bool fitted_workspace = false) {
     // dry_run_cus > 0: only the plan is checked, for a device of that many compute units; no pointer is
     // looked at and no device is queried
     const bool dry = dry_run_cus > 0;
@@ -491,7 +501,8 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         if (!aligned16(X) || !aligned16(packed) || !aligned16(scales) || !aligned16(Y) || !aligned16(workspace))
             return LUTQ_ERR_ALIGN;
         if ((reinterpret_cast<uintptr_t>(lut) & 1u) != 0 || (rowlut && !aligned16(lut))) return LUTQ_ERR_ALIGN;
-        if (!workspace || workspace_bytes < kWorkspaceBytes) return LUTQ_ERR_WORKSPACE;
+        // fitted_workspace: the scratch is checked further down against what this launch really uses
+        if (!workspace || workspace_bytes < (fitted_workspace ? kCounterBytes : kWorkspaceBytes)) return LUTQ_ERR_WORKSPACE;
         di = device_info();
         if (!di.ok) return LUTQ_ERR_DEVICE;
     }
@@ -575,6 +586,12 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
                               : matmul_lds_bytes<4>(r, mb, d.nw, d.rs, sch, false);
     }
     if (lds_bytes > 160 * 1024) return LUTQ_ERR_PLAN;
+    if (fitted_workspace) {
+        // partial sums leave a workgroup only if some range of iterations ends inside an output tile
+        const bool splits = tiles % d.grid != 0 || (tiles / d.grid) % kt != 0;
+        const size_t need = splits ? (size_t)d.grid * 2 * d.rs * slot_floats(r, mb) * sizeof(float) : 0;
+        if (kCounterBytes + need > workspace_bytes) return LUTQ_ERR_SCRATCH;
+    }
 
     MatmulParams p;
     p.X = static_cast<const uint16_t*>(X);
@@ -626,7 +643,7 @@ namespace {
 lutq_status matmul_sliced(const void* X, const void* packed, const void* scales, const void* lut,
                           int bits, int group_size, int64_t M, int64_t N, int64_t K,
                           lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
-                          void* stream, const lutq_plan* user_plan, bool rowlut) {
+                          void* stream, const lutq_plan* user_plan, bool rowlut, bool fitted_workspace = false) {
     if (!X || !Y) return LUTQ_ERR_NULL;
     if (M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
     // More than 32 activation rows: slices of 32 rows, one launch each on the same stream (the
@@ -636,13 +653,13 @@ lutq_status matmul_sliced(const void* X, const void* packed, const void* scales,
     const size_t xrow = (size_t)K * 2, yrow = (size_t)N * 2;
     if (full > 0) {
         lutq_status st = prepare_matmul(X, packed, scales, lut, bits, group_size, 32, N, K, dtype, Y, workspace,
-                                        workspace_bytes, user_plan, rowlut, 0, &body);
+                                        workspace_bytes, user_plan, rowlut, 0, &body, fitted_workspace);
         if (st != LUTQ_OK) return st;
     }
     if (rest > 0) {
         lutq_status st = prepare_matmul(static_cast<const char*>(X) + (size_t)full * 32 * xrow, packed, scales, lut, bits,
                                         group_size, rest, N, K, dtype, static_cast<char*>(Y) + (size_t)full * 32 * yrow,
-                                        workspace, workspace_bytes, user_plan, rowlut, 0, &tail);
+                                        workspace, workspace_bytes, user_plan, rowlut, 0, &tail, fitted_workspace);
         if (st != LUTQ_OK) return st;
     }
     for (int64_t i = 0; i < full; ++i) {
@@ -684,6 +701,37 @@ extern "C" lutq_status lutq_matmul_channel(const void* X, const void* packed, co
                                            void* stream) {
     return matmul_sliced(X, packed, scales, luts, bits, group_size, M, N, K, dtype, Y, workspace, workspace_bytes,
                          stream, nullptr, true);
+}
+
+namespace {
+
+// Device address of this device's copy of `scratch`, looked up once per device with that device current.
+// (In host code the array's name is only a handle for this lookup, never an address to hand to a kernel.)
+lutq_status static_scratch(void** out) {
+    static std::mutex mu;
+    static void* ptr[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LUTQ_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LUTQ_ERR_DEVICE;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return LUTQ_OK;
+}
+
+}  // namespace
+
+extern "C" lutq_status lutq_matmul_static(const void* X, const void* packed, const void* scales, const void* lut,
+                                          int bits, int group_size, int64_t M, int64_t N, int64_t K,
+                                          lutq_dtype dtype, void* Y, void* stream, const lutq_plan* plan) {
+    void* ws = nullptr;
+    const lutq_status st = static_scratch(&ws);
+    if (st != LUTQ_OK) return st;
+    return matmul_sliced(X, packed, scales, lut, bits, group_size, M, N, K, dtype, Y, ws, LUTQ_STATIC_SCRATCH_BYTES,
+                         stream, plan, false, true);
 }
 
 extern "C" lutq_status lutq_matmul(const void* X, const void* packed, const void* scales, const void* lut,

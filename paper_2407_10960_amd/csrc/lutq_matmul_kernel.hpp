@@ -32,7 +32,7 @@ struct MatmulParams {
     const uint16_t* lut;
     uint16_t* Y;              // [M, N]
     uint32_t* counters;       // [NRG], zero on entry, zero on exit
-    float* slots;             // [G][2][RS][SLOT_FLOATS]
+    float* slots;             // [G][2][RS][accumulator registers per lane x 64 lanes]
     uint32_t packed_bytes;
     int M, N, K;
     int KT;                   // K tiles per row block
@@ -49,8 +49,10 @@ struct MatmulParams {
     int fast_reduce;          // the partial sums of all non-leading waves fit in the table area
 };
 
-// Largest partial-sum slot: R = 4 row blocks x 2 M-halves x 4 registers x 64 lanes.
-constexpr int kSlotFloats = 4 * 2 * 4 * 64;
+// A partial-sum slot holds one wave's accumulators: R row blocks x MB halves of M x 4 registers x 64 lanes.
+__host__ __device__ constexpr int slot_floats(int r, int mb) { return r * mb * 4 * 64; }
+// the largest one: R = 4, M > 16
+constexpr int kSlotFloats = slot_floats(4, 2);
 
 // n / d for 0 <= n < 2^31 with m = floor(2^32 / d) (0xffffffff for d = 1) computed on the host: the
 // multiply-high is the quotient or one less, so one correction step makes it exact.  A run-time
@@ -532,7 +534,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                 const int g_first = owner_of(tile0, tq, tr);
                 const int g_last = owner_of(tile0 + p.KT - 1, tq, tr);
                 const int which = (t0 == tbeg) ? 0 : 1;
-                float* slot = p.slots + (((size_t)blockIdx.x * 2 + which) * p.RS + team) * kSlotFloats + lane;
+                float* slot = p.slots + (((size_t)blockIdx.x * 2 + which) * p.RS + team) * slot_floats(R, MB) + lane;
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -559,7 +561,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                     for (int g = g_first; g <= g_last; ++g) {
                         const int gbeg = range_begin(g, tq, tr);
                         const int gw = (div_magic(gbeg, p.kt_magic, p.KT) == sg) ? 0 : 1;   // slot 0 iff sg is g's first super-group
-                        const float* src = p.slots + (((size_t)g * 2 + gw) * p.RS + team) * kSlotFloats + lane;
+                        const float* src = p.slots + (((size_t)g * 2 + gw) * p.RS + team) * slot_floats(R, MB) + lane;
 #pragma unroll
                         for (int r = 0; r < R; ++r)
 #pragma unroll
