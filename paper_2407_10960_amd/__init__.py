@@ -27,5 +27,7 @@ from .binding import (  # noqa: F401
     new_workspace,
     calib_stream_read,
     calib_copy,
+    calib_matmul_trace,
+    TRACE_STAMPS,
     EXPORTED_SYMBOLS,
 )

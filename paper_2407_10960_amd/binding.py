@@ -13,7 +13,7 @@ _LIB = None
 EXPORTED_SYMBOLS = (
     "lutq_status_string", "lutq_packed_bytes", "lutq_pack", "lutq_unpack", "lutq_workspace_bytes",
     "lutq_plan_default", "lutq_plan_default_for", "lutq_plan_check", "lutq_matmul", "lutq_matmul_plan", "lutq_matmul_static", "lutq_matmul_channel", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
-    "lutq_calib_stream_read", "lutq_calib_copy",
+    "lutq_calib_stream_read", "lutq_calib_copy", "lutq_calib_matmul_trace",
 )
 
 LUTQ_F16, LUTQ_BF16 = 0, 1
@@ -28,7 +28,8 @@ class LutqError(RuntimeError):
 class _CPlan(ctypes.Structure):
     _fields_ = [("row_blocks_per_wave", ctypes.c_int), ("grid", ctypes.c_int),
                 ("waves_per_workgroup", ctypes.c_int), ("tiles_in_flight", ctypes.c_int),
-                ("row_groups_per_workgroup", ctypes.c_int)]
+                ("row_groups_per_workgroup", ctypes.c_int), ("scheduling", ctypes.c_int),
+                ("tiles_per_item", ctypes.c_int)]
 
 
 @dataclass
@@ -39,10 +40,12 @@ class Plan:
     waves_per_workgroup: int = 0
     tiles_in_flight: int = 0
     row_groups_per_workgroup: int = 0
+    scheduling: int = 0           # 0 library chooses, 1 static teams, 2 work queue (M <= 4)
+    tiles_per_item: int = 0
 
     def _c(self) -> _CPlan:
         return _CPlan(self.row_blocks_per_wave, self.grid, self.waves_per_workgroup, self.tiles_in_flight,
-                      self.row_groups_per_workgroup)
+                      self.row_groups_per_workgroup, self.scheduling, self.tiles_per_item)
 
 
 def lib_path() -> str:
@@ -99,6 +102,9 @@ def load_library():
     lib.lutq_calib_stream_read.argtypes = [vp, sz, ci, vp, vp]
     lib.lutq_calib_copy.restype = ci
     lib.lutq_calib_copy.argtypes = [vp, vp, sz, ci, vp]
+    lib.lutq_calib_matmul_trace.restype = ci
+    lib.lutq_calib_matmul_trace.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp,
+                                            ctypes.POINTER(_CPlan), vp, sz, ctypes.POINTER(ctypes.c_int)]
     _LIB = lib
     return lib
 
@@ -182,7 +188,7 @@ def lutq_plan_default(bits: int, group_size: int, M: int, N: int, K: int, dtype_
     _check(load_library().lutq_plan_default(bits, group_size, M, N, K, dtype_code, ctypes.byref(cp)),
            "lutq_plan_default")
     return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup, cp.tiles_in_flight,
-                cp.row_groups_per_workgroup)
+                cp.row_groups_per_workgroup, cp.scheduling, cp.tiles_per_item)
 
 
 def lutq_plan_default_for(bits: int, group_size: int, M: int, N: int, K: int, dtype_code: int = LUTQ_F16,
@@ -192,7 +198,7 @@ def lutq_plan_default_for(bits: int, group_size: int, M: int, N: int, K: int, dt
     _check(load_library().lutq_plan_default_for(bits, group_size, M, N, K, dtype_code, compute_units, ctypes.byref(cp)),
            "lutq_plan_default_for")
     return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup, cp.tiles_in_flight,
-                cp.row_groups_per_workgroup)
+                cp.row_groups_per_workgroup, cp.scheduling, cp.tiles_per_item)
 
 
 def lutq_plan_check(bits: int, group_size: int, M: int, N: int, K: int, dtype_code: int = LUTQ_F16,
@@ -287,7 +293,7 @@ def lutq_tune_candidates(bits: int, group_size: int, M: int, N: int, K: int, dty
     _check(lib.lutq_tune_candidates(bits, group_size, M, N, K, dtype_code, arr, n.value, ctypes.byref(n)),
            "lutq_tune_candidates")
     return [Plan(c.row_blocks_per_wave, c.grid, c.waves_per_workgroup, c.tiles_in_flight,
-                 c.row_groups_per_workgroup) for c in arr[:n.value]]
+                 c.row_groups_per_workgroup, c.scheduling, c.tiles_per_item) for c in arr[:n.value]]
 
 
 def lutq_tune(X, packed_ring, scales_ring, lut, bits: int, group_size: int, Y, workspace, stream=None,
@@ -319,7 +325,7 @@ def lutq_tune(X, packed_ring, scales_ring, lut, bits: int, group_size: int, Y, w
                          workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(stream),
                          reps, ctypes.byref(cp), ctypes.byref(us)), "lutq_tune")
     return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup, cp.tiles_in_flight,
-                cp.row_groups_per_workgroup), us.value
+                cp.row_groups_per_workgroup, cp.scheduling, cp.tiles_per_item), us.value
 
 
 def lutq_quantize(W, lut, bits: int, group_size: int, scales_out, packed_out, stream=None):
@@ -371,3 +377,25 @@ def calib_stream_read(src, grid: int, sink, stream=None):
 def calib_copy(src, dst, grid: int, stream=None):
     _check(load_library().lutq_calib_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), grid,
                                           _stream_ptr(stream)), "lutq_calib_copy")
+
+
+TRACE_STAMPS = ("start", "arguments arrived", "first loads issued", "table built", "first tile multiplied",
+                "K loop done", "waves reduced", "outputs stored")
+
+
+def calib_matmul_trace(X, packed, scales, lut, bits: int, group_size: int, Y, workspace, trace, stream=None,
+                       plan: Plan | None = None) -> int:
+    """One launch through the measurement build of the kernel; `trace` is an int64 CUDA tensor that
+    receives [workgroup][16 wave slots][8] device timestamps (10 ns units).  Returns the number of
+    workgroups launched."""
+    lib = load_library()
+    M, K = X.shape
+    N = scales.shape[0]
+    n = ctypes.c_int(0)
+    cp = plan._c() if plan is not None else None
+    _check(lib.lutq_calib_matmul_trace(X.data_ptr(), packed.data_ptr(), scales.data_ptr(), lut.data_ptr(), bits, group_size,
+                                       M, N, K, _dtype_code(X), Y.data_ptr(), workspace.data_ptr(),
+                                       workspace.numel() * workspace.element_size(), _stream_ptr(stream),
+                                       ctypes.byref(cp) if cp is not None else None, trace.data_ptr(),
+                                       trace.numel() * trace.element_size(), ctypes.byref(n)), "lutq_calib_matmul_trace")
+    return n.value

@@ -52,7 +52,7 @@ def build(verbose: bool = False, jobs: int | None = None) -> str:
             objs.append(obj)
             steps.append([hipcc, *HIP_FLAGS, f"-DLUTQ_INST_BITS={bits}", f"-DLUTQ_INST_DT={dt}",
                           "-c", os.path.join(CSRC, "lutq_kernels.hip"), "-o", obj])
-    for src in ("lutq_api.hip", "lutq_calib.hip", "lutq_quantize.hip"):
+    for src in ("lutq_api.hip", "lutq_calib.hip", "lutq_quantize.hip", "lutq_trace.hip"):
         if not os.path.exists(os.path.join(CSRC, src)):
             continue
         obj = os.path.join(BUILD_DIR, src.replace(".hip", ".o"))

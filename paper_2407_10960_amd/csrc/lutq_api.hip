@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "lutq.h"
+#include "lutq_calib.h"
 #include "lutq_launch.hpp"
 
 namespace {
@@ -83,8 +84,54 @@ int ilog2(int v) {
 
 // Everything the launch needs to know about the work decomposition.
 struct Decomp {
-    int r, grid, nw, stages, rs;      // the five plan fields, all chosen
+    int r, grid, nw, stages, rs;      // the first five plan fields, all chosen
+    int queue = 0;                    // work-queue kernel (M <= 4): rs = row groups per workgroup, it = tiles per item
+    int it = 0;
 };
+
+// LDS bytes of a work-queue launch
+int queue_lds_bytes(int bits, int nw, int items, int r) {
+    return bits == 2 ? decode_lds_bytes<2>(nw, items, r) : bits == 3 ? decode_lds_bytes<3>(nw, items, r) : decode_lds_bytes<4>(nw, items, r);
+}
+
+// Work-queue decomposition for M <= 4 (decode_kernel): every workgroup owns `a` row groups of `r` row
+// blocks over the whole of K, one workgroup per compute unit, so no partial sum crosses workgroups and
+// the queue evens out the waves.  Chosen where it measured faster than the team plans (LLaMA-3 8B and 70B
+// shapes, 2/3/4 bits, both dtypes, M = 1 and 4): from eight row blocks per compute unit up at every bit
+// width (2-10 %: 70B gate+up 4-bit fp16 42.3 -> 40.8 us, bf16 49.0 -> 45.3, 3-bit 40.8 -> 39.5, 2-bit 30.9 ->
+// 28.1); with two row blocks per compute unit for 4-bit weights, M <= 2 and a long K (70B down 22.4 -> 21.4
+// us; at 2 and 3 bits, at M = 4 and on the 8192-column O projection the team plans are as fast or faster).
+// Seven row blocks per compute unit (8B gate+up: 12.35 against 12.17 us, and 13.8 against 12.6 us at M = 4,
+// where an odd count rules out two row blocks per wave) and one (no more items than waves, nothing to
+// even out) stay with the teams.
+// Returns false when this problem is left to the team plans (or cannot run on the work-queue kernel).
+bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K, int cus, bool only_if_preferred, Decomp* out) {
+    if (M > 4 || !sch) return false;
+    const int64_t nb = N / 16, kt = K / tile_k(bits);
+    if (nb % cus != 0) return false;
+    const int64_t per = nb / cus;                      // row blocks per workgroup
+    if (only_if_preferred && !(per >= 8 || (per == 2 && bits == 4 && M <= 2 && K >= 16384))) return false;
+    const int sb = super_block(nb);
+    // two row blocks per wave halve the activation and scale-chunk loads per weight; 3-bit tiles (two
+    // bit-slices) run faster one at a time, and two row blocks per compute unit make more items as R = 1
+    const int r = (per >= 4 && bits != 3 && per % 2 == 0 && sb % 2 == 0 && decode_instance_exists(bits, bf16, 2)) ? 2 : 1;
+    const int64_t a = per / r;
+    if (a > 64) return false;
+    // items: at least two tiles (the pipeline depth); as many tiles as still leave every wave about
+    // four items, so that an item's fold and hand-over stay a small part of its work
+    int it = kt % 4 == 0 ? 4 : 2;
+    if (kt % 8 == 0 && a * (kt / 8) >= 64) it = 8;
+    if (kt % it != 0) return false;
+    int64_t items = a * (kt / it);
+    while (queue_lds_bytes(bits, 16, (int)items, r) > 160 * 1024 && kt % (it * 2) == 0) { it *= 2; items = a * (kt / it); }
+    int nw = items >= 16 ? 16 : (int)(items < 4 ? 4 : items);
+    if (queue_lds_bytes(bits, nw, (int)items, r) > 160 * 1024) return false;
+    out->r = r; out->grid = cus; out->nw = nw; out->stages = 2; out->rs = (int)a; out->queue = 1; out->it = it;
+    return true;
+}
+bool default_queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K, int cus, Decomp* out) {
+    return queue_decomp(bits, bf16, sch, M, N, K, cus, true, out);
+}
 
 inline int steps_per_tile(int bits) { return bits == 4 ? 4 : 8; }
 // Activations can be shared through LDS when the teams are enough to stage a tile's pieces between them.
@@ -410,6 +457,11 @@ rowlut_launcher pick_rowlut(int bits, lutq_dtype dt) {
     if (dt == LUTQ_F16) return bits == 2 ? launch_matmul_rowlut_b2_F16 : bits == 3 ? launch_matmul_rowlut_b3_F16 : launch_matmul_rowlut_b4_F16;
     return bits == 2 ? launch_matmul_rowlut_b2_BF16 : bits == 3 ? launch_matmul_rowlut_b3_BF16 : launch_matmul_rowlut_b4_BF16;
 }
+typedef hipError_t (*decode_launcher)(int, int, const DecodeParams&, int, hipStream_t);
+decode_launcher pick_decode(int bits, lutq_dtype dt) {
+    if (dt == LUTQ_F16) return bits == 2 ? launch_decode_b2_F16 : bits == 3 ? launch_decode_b3_F16 : launch_decode_b4_F16;
+    return bits == 2 ? launch_decode_b2_BF16 : bits == 3 ? launch_decode_b3_BF16 : launch_decode_b4_BF16;
+}
 dequant_launcher pick_dequant(int bits, lutq_dtype dt) {
     if (dt == LUTQ_F16) return bits == 2 ? launch_dequant_b2_F16 : bits == 3 ? launch_dequant_b3_F16 : launch_dequant_b4_F16;
     return bits == 2 ? launch_dequant_b2_BF16 : bits == 3 ? launch_dequant_b3_BF16 : launch_dequant_b4_BF16;
@@ -448,12 +500,17 @@ extern "C" lutq_status lutq_plan_default_for(int bits, int group_size, int64_t M
     if (M < 1 || M > kMaxRows || compute_units < 1 || compute_units > 4096) return LUTQ_ERR_SHAPE;
     if (M > 32) M = 32;                                   // the plan of the 32-row slices
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
-    const Decomp d = default_decomp(bits, dtype == LUTQ_BF16, (K / group_size) % 8 == 0, M, N, K, compute_units, 0);
+    const bool sch = (K / group_size) % 8 == 0;
+    Decomp d;
+    if (!default_queue_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, &d))
+        d = default_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, 0);
     plan->row_blocks_per_wave = d.r;
     plan->grid = d.grid;
     plan->waves_per_workgroup = d.nw;
     plan->tiles_in_flight = d.stages;
     plan->row_groups_per_workgroup = d.rs;
+    plan->scheduling = d.queue ? LUTQ_SCHED_QUEUE : LUTQ_SCHED_TEAMS;
+    plan->tiles_per_item = d.it;
     return LUTQ_OK;
 }
 
@@ -478,7 +535,65 @@ struct Prepared {
     bool sch, wide;
     int xsh;                  // 0, or activation pieces staged per wave (shared through LDS)
     bool rowlut;              // p.lut holds one table per output row
+    bool queue;               // work-queue kernel: dp and queue_lds instead of p
+    DecodeParams dp;
+    int queue_lds;
 };
+
+// Validates a work-queue launch (M <= 4) and fills out->dp.  `d` holds the decomposition: r, rs = row
+// groups per workgroup, nw, stages, it.
+lutq_status prepare_queue(const void* X, const void* packed, const void* scales, const void* lut, int bits,
+                          int group_size, int64_t M, int64_t N, int64_t K, bool bf16, void* Y, const Decomp& d, Prepared* out) {
+    const int64_t nb = N / 16, kt = K / tile_k(bits);
+    if (M > 4 || (K / group_size) % 8 != 0) return LUTQ_ERR_PLAN;
+    if (!decode_instance_exists(bits, bf16, d.r) || super_block(nb) % d.r != 0) return LUTQ_ERR_PLAN;
+    const int64_t nrg = nb / d.r;
+    if (d.rs < 1 || d.rs > 64 || nrg % d.rs != 0 || d.grid != nrg / d.rs) return LUTQ_ERR_PLAN;
+    if (d.nw < 4 || d.nw > 16 || d.stages != 2) return LUTQ_ERR_PLAN;
+    if (d.it < d.stages || d.it % d.stages != 0 || kt % d.it != 0) return LUTQ_ERR_PLAN;
+    const int64_t items = (int64_t)d.rs * (kt / d.it);
+    if (items > 4096) return LUTQ_ERR_PLAN;
+    const int lds = queue_lds_bytes(bits, d.nw, (int)items, d.r);
+    if (lds > 160 * 1024) return LUTQ_ERR_PLAN;
+    DecodeParams q{};
+    q.X = static_cast<const uint16_t*>(X);
+    q.packed = static_cast<const uint8_t*>(packed);
+    q.scales = static_cast<const uint16_t*>(scales);
+    q.lut = static_cast<const uint16_t*>(lut);
+    q.Y = static_cast<uint16_t*>(Y);
+    q.packed_bytes = (uint32_t)(N * K * bits / 8);
+    q.scale_bytes = (uint32_t)(N * (K / group_size) * 2);
+    q.x_bytes = (uint32_t)(M * K * 2);
+    q.M = (int)M; q.N = (int)N; q.K = (int)K;
+    q.SG2 = (int)(K / group_size) * 2;
+    q.SBL = ilog2(super_block(nb));
+    const uint32_t tile_bytes = bits == 3 ? 1536u : 1024u;
+    q.tile_stride = tile_bytes << q.SBL;
+    q.sblock_bytes = (uint32_t)kt * q.tile_stride;
+    q.A = d.rs; q.C = (int)(kt / d.it); q.IT = d.it; q.NW = d.nw;
+    q.a_magic = q.A == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)q.A);
+    q.lut_ltpe = bits == 2 ? lut_log2_threads_per_row<2>(d.nw * 64)
+               : bits == 3 ? lut_log2_threads_per_row<3>(d.nw * 64) : lut_log2_threads_per_row<4>(d.nw * 64);
+    q.slot_off = bits == 2 ? decode_slot_off<2>(d.nw) : bits == 3 ? decode_slot_off<3>(d.nw) : decode_slot_off<4>(d.nw);
+    // final reduction: as many groups of items per output as there are threads for them (the group sums
+    // are parked in the table's area: at most 4 KiB)
+    const int outputs = q.A * d.r * 64;
+    int ng = (d.nw * 64) / outputs;
+    if (ng > (q.C + 3) / 4) ng = (q.C + 3) / 4;           // groups of four items or more: fewer are not worth a barrier
+    if (ng < 1) ng = 1;
+    q.GL = (q.C + ng - 1) / ng;
+    q.NG = (q.C + q.GL - 1) / q.GL;
+    q.o_magic = (uint32_t)((1ull << 32) / (uint64_t)outputs);
+    q.trace = nullptr;
+    if (env_switches().verbose)
+        std::fprintf(stderr, "lutq_matmul: work queue R=%d grid=%d waves=%d row groups per workgroup=%d tiles per item=%d items=%d lds=%d\n",
+                     d.r, d.grid, d.nw, d.rs, d.it, (int)items, lds);
+    out->queue = true;
+    out->dp = q;
+    out->queue_lds = lds;
+    out->r = d.r;
+    return LUTQ_OK;
+}
 
 // Validates the arguments of one launch (M <= 32) and fills *out; launches nothing.
 lutq_status prepare_matmul(const void* X, const void* packed, const void* scales, const void* lut,
@@ -522,6 +637,38 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         if (force_r != 0 && ((force_r != 1 && force_r != 2 && force_r != 4) || super_block(nb) % force_r != 0))
             return LUTQ_ERR_PLAN;
         if (user_plan->grid != 0 && (user_plan->grid < 1 || user_plan->grid > kMaxGrid)) return LUTQ_ERR_PLAN;
+    }
+    out->queue = false;
+    if (!rowlut) {
+        // the work-queue kernel: asked for by the plan, or the default for M <= 4 where it applies
+        // (an explicit plan without a scheduling field keeps meaning the static teams it describes)
+        const bool plan_is_empty = !user_plan || (user_plan->row_blocks_per_wave == 0 && user_plan->grid == 0 &&
+                                                  user_plan->waves_per_workgroup == 0 && user_plan->tiles_in_flight == 0 &&
+                                                  user_plan->row_groups_per_workgroup == 0 && user_plan->tiles_per_item == 0);
+        const int sched = user_plan ? user_plan->scheduling : 0;
+        if (sched < 0 || sched > LUTQ_SCHED_QUEUE) return LUTQ_ERR_PLAN;
+        Decomp q;
+        if (sched == LUTQ_SCHED_QUEUE) {
+            // the fields the plan leaves open: one workgroup per compute unit where the row blocks divide
+            // evenly, else one workgroup of 16 waves per row block with items of two tiles
+            const bool have_default = queue_decomp(bits, bf16, sch, M, N, K, di.cus, false, &q);
+            if (!have_default) {
+                q.r = 1; q.rs = 1; q.nw = 16; q.stages = 2; q.it = 2; q.queue = 1;
+            }
+            if (user_plan->row_blocks_per_wave) q.r = user_plan->row_blocks_per_wave;
+            if (q.r != 1 && q.r != 2) return LUTQ_ERR_PLAN;
+            if (user_plan->row_groups_per_workgroup) q.rs = user_plan->row_groups_per_workgroup;
+            else if (user_plan->row_blocks_per_wave && have_default) q.rs = (int)(nb / di.cus / q.r);
+            if (q.rs < 1 || nb % ((int64_t)q.r * q.rs) != 0) return LUTQ_ERR_PLAN;
+            q.grid = (int)(nb / q.r / q.rs);
+            if (user_plan->grid && user_plan->grid != q.grid) return LUTQ_ERR_PLAN;
+            if (user_plan->waves_per_workgroup) q.nw = user_plan->waves_per_workgroup;
+            if (user_plan->tiles_in_flight) q.stages = user_plan->tiles_in_flight;
+            if (user_plan->tiles_per_item) q.it = user_plan->tiles_per_item;
+            return prepare_queue(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out);
+        }
+        if (sched == 0 && plan_is_empty && default_queue_decomp(bits, bf16, sch, M, N, K, di.cus, &q))
+            return prepare_queue(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out);
     }
     Decomp d = default_decomp(bits, bf16, sch, M, N, K, di.cus, force_r);
     if (rowlut) {
@@ -618,6 +765,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     p.kt_magic = p.KT == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KT);
     p.ks_magic = p.KS == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)p.KS);
     p.fast_reduce = (d.nw - d.rs) * (r * mb * 4) * 256 <= (bits == 3 ? 64 : 256) * 256 ? 1 : 0;
+    p.trace = nullptr;
     if (env_switches().verbose)
         std::fprintf(stderr, "lutq_matmul: R=%d grid=%d waves=%d (teams %d x %d) stages=%d wide=%d xm=%d shared_x=%d lds=%d\n", r, d.grid,
                      d.nw, d.rs, p.KS, d.stages, (int)wide, xm, (int)xsh, lds_bytes);
@@ -628,6 +776,10 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
 }
 
 lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dtype dtype, void* stream) {
+    if (q.queue) {
+        const hipError_t e = pick_decode(bits, dtype)(group_size, q.r, q.dp, q.queue_lds, static_cast<hipStream_t>(stream));
+        return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
+    }
     hipError_t e = q.rowlut ? pick_rowlut(bits, dtype)(group_size, q.mb, q.sch, q.xm, q.p, static_cast<hipStream_t>(stream))
                             : pick_matmul(bits, dtype)(group_size, q.mb, q.r, q.stages, q.sch, q.xm, q.wide, q.xsh, q.p,
                                                        static_cast<hipStream_t>(stream));
@@ -741,6 +893,38 @@ extern "C" lutq_status lutq_matmul(const void* X, const void* packed, const void
                             workspace_bytes, stream, nullptr);
 }
 
+extern "C" int lutq_calib_matmul_trace(const void* X, const void* packed, const void* scales, const void* lut,
+                                       int bits, int group_size, int64_t M, int64_t N, int64_t K, int dtype,
+                                       void* Y, void* workspace, size_t workspace_bytes, void* stream,
+                                       const lutq_plan* plan, void* trace, size_t trace_bytes, int* workgroups) {
+    if (!trace || !workgroups) return LUTQ_ERR_NULL;
+    if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
+    Prepared q{};
+    lutq_status st = prepare_matmul(X, packed, scales, lut, bits, group_size, M, N, K, (lutq_dtype)dtype, Y, workspace,
+                                    workspace_bytes, plan, false, 0, &q);
+    if (st != LUTQ_OK) return st;
+    if (q.queue) {
+        if (bits != 4 || (group_size != 64 && group_size != 128)) return LUTQ_ERR_PLAN;
+        const int groups = (int)((N / 16) / (q.r * q.dp.A));
+        if (trace_bytes < (size_t)groups * kTraceWaves * kTraceStamps * sizeof(unsigned long long) || (reinterpret_cast<uintptr_t>(trace) & 7u))
+            return LUTQ_ERR_WORKSPACE;
+        q.dp.trace = static_cast<unsigned long long*>(trace);
+        *workgroups = groups;
+        const hipError_t e = launch_decode_trace(dtype == LUTQ_BF16, group_size, q.r, q.dp, q.queue_lds, static_cast<hipStream_t>(stream));
+        return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
+    }
+    // measurement builds exist for the instances the M <= 4 plans of 4-bit weights use
+    if (bits != 4 || q.mb != 1 || q.xm != 4 || !q.sch || !q.wide || q.stages != 2 || q.xsh || q.r > 2 ||
+        (group_size != 64 && group_size != 128))
+        return LUTQ_ERR_PLAN;
+    if (trace_bytes < (size_t)q.p.G * kTraceWaves * kTraceStamps * sizeof(unsigned long long) || (reinterpret_cast<uintptr_t>(trace) & 7u))
+        return LUTQ_ERR_WORKSPACE;
+    q.p.trace = static_cast<unsigned long long*>(trace);
+    *workgroups = q.p.G;
+    const hipError_t e = launch_matmul_trace(dtype == LUTQ_BF16, group_size, q.r, q.p, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
+}
+
 namespace {
 
 // Candidate work decompositions of lutq_tune: the default plan first, then every combination of row
@@ -751,9 +935,34 @@ namespace {
 std::vector<lutq_plan> tune_candidates(int bits, int group_size, int64_t M, int64_t N, int64_t K, lutq_dtype dtype,
                                        int cus) {
     std::vector<lutq_plan> out;
+    auto push_unique = [&](const lutq_plan& c) {
+        for (const lutq_plan& o : out)
+            if (o.row_blocks_per_wave == c.row_blocks_per_wave && o.grid == c.grid &&
+                o.waves_per_workgroup == c.waves_per_workgroup && o.tiles_in_flight == c.tiles_in_flight &&
+                o.row_groups_per_workgroup == c.row_groups_per_workgroup && o.scheduling == c.scheduling &&
+                o.tiles_per_item == c.tiles_per_item)
+                return;
+        out.push_back(c);
+    };
     lutq_plan def;
     if (lutq_plan_default(bits, group_size, M, N, K, dtype, &def) == LUTQ_OK) out.push_back(def);
     const int64_t nb = N / 16, kt = K / tile_k(bits);
+    if (M <= 4 && (K / group_size) % 8 == 0) {
+        // work-queue plans: row blocks per workgroup = every divisor of N/16 that leaves between half a
+        // workgroup and four per compute unit, as R = 1 or 2, 8 to 16 waves, items of 2, 4, 8 tiles
+        for (int64_t per = 1; per <= 64; ++per) {
+            if (nb % per != 0) continue;
+            const int64_t g = nb / per;
+            if (g * 2 < cus || g > 4 * (int64_t)cus) continue;
+            for (int r : {1, 2}) {
+                if (per % r != 0 || super_block(nb) % r != 0) continue;
+                for (int nw : {8, 12, 16})
+                    for (int it : {2, 4, 8})
+                        if (kt % it == 0)
+                            push_unique(lutq_plan{r, (int)g, nw, 2, (int)(per / r), LUTQ_SCHED_QUEUE, it});
+            }
+        }
+    }
     for (int r : {1, 2, 4}) {
         if (super_block(nb) % r != 0) continue;
         const int64_t nrg = nb / r;
@@ -769,14 +978,7 @@ std::vector<lutq_plan> tune_candidates(int bits, int group_size, int64_t M, int6
                     if (g < 1 || g > tiles || g * rs > kMaxGrid) continue;
                     if (gi > 0 && g == sets) continue;
                     for (int stages : {2, 4}) {
-                        const lutq_plan c{r, (int)g, nw, stages, rs};
-                        bool dup = false;
-                        for (const lutq_plan& o : out)
-                            dup = dup || (o.row_blocks_per_wave == c.row_blocks_per_wave && o.grid == c.grid &&
-                                          o.waves_per_workgroup == c.waves_per_workgroup &&
-                                          o.tiles_in_flight == c.tiles_in_flight &&
-                                          o.row_groups_per_workgroup == c.row_groups_per_workgroup);
-                        if (!dup) out.push_back(c);
+                        push_unique(lutq_plan{r, (int)g, nw, stages, rs, LUTQ_SCHED_TEAMS, 0});
                     }
                 }
             }

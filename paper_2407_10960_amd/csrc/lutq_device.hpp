@@ -95,10 +95,9 @@ __device__ __forceinline__ void load_wfrag(WFrag<BITS>& f, rsrc_t packed, uint32
 // as 128-bit stores (lut_build).  The 16-byte chunk a lane starts with is skewed by its row number,
 // so that the lanes of one store instruction, whose rows are 256 bytes apart, hit different banks.
 // The two halves are separate so that the caller can issue the reads of T first, then its weight
-// prefetch, and only then wait for T: lut_fetch returns the raw loaded values and does no arithmetic
-// on them.  lut_build is called by all `nthreads` threads; the caller synchronises after it.
+// prefetch, and only then wait for T: lut_fetch returns the loaded words untouched.  lut_build is called by all `nthreads` threads; the caller synchronises after it.
 // ---------------------------------------------------------------------------------------
-struct LutSeed { uint32_t v[4]; };     // raw 16-bit table values of this thread's row
+struct LutSeed { uint32_t w[4]; };      // the aligned 32-bit words that hold this thread's table values
 
 // log2 of the threads that share one row (the fused kernel gets it from the host)
 template <int BITS>
@@ -107,24 +106,43 @@ __host__ __device__ constexpr int lut_log2_threads_per_row(int nthreads) {
     return t >= 16 ? 4 : t >= 8 ? 3 : t >= 4 ? 2 : t >= 2 ? 1 : 0;
 }
 
+// The table indices (up to four) that entry e of the vectorised table is made of.
+template <int BITS>
+__device__ __forceinline__ void entry_indices(int e, int q[4]) {
+    if constexpr (BITS == 4) {
+        q[0] = e & 15; q[1] = (e >> 4) & 15; q[2] = 0; q[3] = 0;
+    } else if constexpr (BITS == 3) {
+        q[0] = (e & 3) | (((e >> 4) & 1) << 2);
+        q[1] = ((e >> 2) & 3) | (((e >> 5) & 1) << 2);
+        q[2] = 0; q[3] = 0;
+    } else {
+        q[0] = e & 3; q[1] = (e >> 2) & 3; q[2] = (e >> 4) & 3; q[3] = (e >> 6) & 3;
+    }
+}
+
+// lut_fetch returns what it loaded untouched -- whole aligned 32-bit words, so that not even a zero
+// extension follows the loads: any instruction on the loaded values would make the compiler wait for
+// them right there, in front of the weight prefetch.  T needs 2-byte alignment only: the word that
+// holds T[q] is word (q + mis) / 2 of the aligned address at or below T, mis = 1 if T starts in the
+// upper half of a word; lut_build picks the half.
 template <int BITS>
 __device__ __forceinline__ LutSeed lut_fetch(const uint16_t* __restrict__ T, int tid, int ltpe) {
     const int e = (tid >> ltpe) & (Geo<BITS>::ENTRIES - 1);
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(T);
+    typedef __attribute__((address_space(1))) const uint32_t global_cu32;
+    global_cu32* words = reinterpret_cast<global_cu32*>(addr & ~(uintptr_t)3);
+    const int mis = (int)(addr >> 1) & 1;
+    int q[4];
+    entry_indices<BITS>(e, q);
     LutSeed s;
-    if constexpr (BITS == 4) {
-        s.v[0] = T[e & 15]; s.v[1] = T[(e >> 4) & 15]; s.v[2] = 0; s.v[3] = 0;
-    } else if constexpr (BITS == 3) {
-        const int q0 = (e & 3) | (((e >> 4) & 1) << 2);
-        const int q1 = ((e >> 2) & 3) | (((e >> 5) & 1) << 2);
-        s.v[0] = T[q0]; s.v[1] = T[q1]; s.v[2] = 0; s.v[3] = 0;
-    } else {
-        s.v[0] = T[e & 3]; s.v[1] = T[(e >> 2) & 3]; s.v[2] = T[(e >> 4) & 3]; s.v[3] = T[(e >> 6) & 3];
-    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s.w[i] = (BITS == 2 || i < 2) ? words[(q[i] + mis) >> 1] : 0u;
     return s;
 }
 
+// mis: 1 if the table's first value sits in the upper half of word 0 (a pointer that is not 4-byte aligned)
 template <int BITS, typename DT>
-__device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int log2c, int tid, int ltpe) {
+__device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int mis, int log2c, int tid, int ltpe) {
     using Gm = Geo<BITS>;
     constexpr int ESH = Tab<BITS, DT>::ENTRY_BYTES == 8 ? 3 : 2;
     const int stride = 1 << (log2c + ESH);                        // bytes of one row
@@ -133,12 +151,17 @@ __device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int lo
     const int e = tid >> ltpe, part = tid & (tpe - 1);
     const int per = chunks / tpe > 0 ? chunks / tpe : 1;          // chunks written by this thread
     if (e >= Gm::ENTRIES || part * per >= chunks) return;
+    int q[4];
+    entry_indices<BITS>(e, q);
+    uint32_t val[4];                                              // the 16-bit table values of this row
+#pragma unroll
+    for (int i = 0; i < 4; ++i) val[i] = ((q[i] + mis) & 1) ? (seed.w[i] >> 16) : (seed.w[i] & 0xffffu);
     u32x4 v;
     if constexpr (Tab<BITS, DT>::WIDE) {          // {T[q0], T[q1]} as fp32
-        v.x = seed.v[0] << 16; v.y = seed.v[1] << 16; v.z = v.x; v.w = v.y;
+        v.x = val[0] << 16; v.y = val[1] << 16; v.z = v.x; v.w = v.y;
     } else {
-        v.x = seed.v[0] | (seed.v[1] << 16);
-        if constexpr (Gm::ENTRY_BYTES == 8) { v.y = seed.v[2] | (seed.v[3] << 16); v.z = v.x; v.w = v.y; }
+        v.x = val[0] | (val[1] << 16);
+        if constexpr (Gm::ENTRY_BYTES == 8) { v.y = val[2] | (val[3] << 16); v.z = v.x; v.w = v.y; }
         else { v.y = v.x; v.z = v.x; v.w = v.x; }
     }
     char* row = lds + (size_t)e * stride;
@@ -153,7 +176,7 @@ template <int BITS, typename DT>
 __device__ __forceinline__ void build_lut(char* lds, const uint16_t* __restrict__ T, int log2c, int tid, int nthreads) {
     const int ltpe = lut_log2_threads_per_row<BITS>(nthreads);
     const LutSeed s = lut_fetch<BITS>(T, tid, ltpe);
-    lut_build<BITS, DT>(lds, s, log2c, tid, ltpe);
+    lut_build<BITS, DT>(lds, s, (int)(reinterpret_cast<uintptr_t>(T) >> 1) & 1, log2c, tid, ltpe);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -115,6 +115,30 @@ hipError_t launch_rowlut(int mb, int xm, bool sch, const MatmulParams& p, hipStr
     return hipErrorInvalidValue;
 }
 
+// Work-queue kernel for M <= 4: two tiles in flight, R = 1 or 2.
+template <int GROUP, int R>
+hipError_t launch_decode_one(const DecodeParams& p, int lds_bytes, hipStream_t stream) {
+    if constexpr (!decode_instance_exists(LUTQ_INST_BITS, Tab<LUTQ_INST_BITS, LUTQ_INST_DT>::WIDE, R)) {
+        return hipErrorInvalidValue;
+    } else {
+    auto kernel = decode_kernel<LUTQ_INST_BITS, GROUP, R, LUTQ_INST_DT, 2>;
+    if (lds_bytes > 64 * 1024) {
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr != hipSuccess) return attr;
+    }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)((p.N / 16) / (R * p.A))), dim3(p.NW * 64), lds_bytes, stream, p);
+    return hipGetLastError();
+    }
+}
+
+template <int GROUP>
+hipError_t launch_decode_group(int r, const DecodeParams& p, int lds_bytes, hipStream_t stream) {
+    if (r == 1) return launch_decode_one<GROUP, 1>(p, lds_bytes, stream);
+    if (r == 2) return launch_decode_one<GROUP, 2>(p, lds_bytes, stream);
+    return hipErrorInvalidValue;
+}
+
 template <int GROUP>
 hipError_t launch_dq(const DequantParams& p, int grid, int lds_bytes, hipStream_t stream) {
     hipLaunchKernelGGL((dequant_kernel<LUTQ_INST_BITS, GROUP, LUTQ_INST_DT>), dim3(grid), dim3(256), lds_bytes, stream, p);
@@ -142,6 +166,17 @@ hipError_t LUTQ_NAME(launch_matmul_rowlut_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int g
         case 64: return launch_rowlut<64>(mb, xm, sch, p, stream);
         case 128: return launch_rowlut<128>(mb, xm, sch, p, stream);
         case 256: return launch_rowlut<256>(mb, xm, sch, p, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t LUTQ_NAME(launch_decode_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int r, const DecodeParams& p, int lds_bytes,
+                                                                    hipStream_t stream) {
+    switch (group) {
+        case 32: return launch_decode_group<32>(r, p, lds_bytes, stream);
+        case 64: return launch_decode_group<64>(r, p, lds_bytes, stream);
+        case 128: return launch_decode_group<128>(r, p, lds_bytes, stream);
+        case 256: return launch_decode_group<256>(r, p, lds_bytes, stream);
     }
     return hipErrorInvalidValue;
 }

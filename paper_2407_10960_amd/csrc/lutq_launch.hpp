@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include "lutq_matmul_kernel.hpp"
+#include "lutq_decode_kernel.hpp"
 
 namespace lutq {
 
@@ -34,7 +35,16 @@ inline bool matmul_instance_exists(int bits, bool bf16, int r, int mb, int stage
     hipError_t launch_matmul_rowlut_b##B##_##DT(int group, int mb, bool sch, int xm, const MatmulParams& p, \
                                                 hipStream_t stream);                                 \
     hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes, \
-                                          hipStream_t stream);
+                                          hipStream_t stream);                                       \
+    hipError_t launch_decode_b##B##_##DT(int group, int r, const DecodeParams& p, int lds_bytes,     \
+                                         hipStream_t stream);
+
+// Measurement builds (phase timestamps, see TraceStamp) of the 4-bit instances that serve M <= 4 under the
+// default plans: group 64 or 128, R = 1 or 2, two tiles in flight, chunked scales, 128-register build.
+// Defined in lutq_trace.hip.
+hipError_t launch_matmul_trace(bool bf16, int group, int r, const MatmulParams& p, hipStream_t stream);
+// the same for the work-queue kernel (decode_kernel): 4-bit, group 64 or 128, R = 1 or 2
+hipError_t launch_decode_trace(bool bf16, int group, int r, const DecodeParams& p, int lds_bytes, hipStream_t stream);
 
 LUTQ_DECLARE_LAUNCHERS(2, F16)
 LUTQ_DECLARE_LAUNCHERS(3, F16)

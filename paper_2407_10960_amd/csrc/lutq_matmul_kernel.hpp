@@ -21,6 +21,8 @@
 //     another workgroup, so the kernel cannot deadlock whatever the number of resident workgroups.
 #pragma once
 
+#include <type_traits>
+
 #include "lutq_device.hpp"
 
 namespace lutq {
@@ -47,6 +49,23 @@ struct MatmulParams {
     int lut_ltpe;             // log2 of the threads that build one table row together
     int xbuf_off;             // LDS byte offset of the shared activation buffers (XSH instances)
     int fast_reduce;          // the partial sums of all non-leading waves fit in the table area
+    unsigned long long* trace;   // TRACE instances only: [G][kTraceWaves][kTraceStamps] device timestamps (else unused)
+};
+
+// Phase timestamps of the TRACE instances (measurement builds of a few instances, launched only by
+// lutq_calib_matmul_trace): the constant 100 MHz device clock, read by every wave at these points of
+// its first segment.
+constexpr int kTraceWaves = 16;        // slots per workgroup (a workgroup has at most 16 waves)
+enum TraceStamp {
+    kTraceStart = 0,       // first instruction of the wave
+    kTraceArgs = 1,        // kernel arguments have arrived in scalar registers
+    kTraceIssued = 2,      // addresses computed, table values requested, first tiles requested
+    kTraceTable = 3,       // table built, workgroup barrier passed
+    kTraceFirstTile = 4,   // first tile of weights has arrived and is multiplied
+    kTraceLoopDone = 5,    // K loop finished
+    kTraceReduced = 6,     // waves of the team reduced through LDS
+    kTraceEnd = 7,         // outputs stored (or partial sums handed over)
+    kTraceStamps = 8
 };
 
 // A partial-sum slot holds one wave's accumulators: R row blocks x MB halves of M x 4 registers x 64 lanes.
@@ -130,7 +149,8 @@ __host__ __device__ constexpr bool matmul_wide_fits(int r, int mb, int p, int xm
 // ahead, double buffered, and every wave reads its B operands from there; one workgroup barrier per
 // tile keeps writers and readers apart, and every wave runs the same number of rounds.
 // The number of waves and their arrangement in teams are run-time values.
-template <int BITS, int GROUP, int MB, int R, typename DT, int P, bool SCH, int XM, bool WIDE, int XPIECES, bool RLUT = false>
+template <int BITS, int GROUP, int MB, int R, typename DT, int P, bool SCH, int XM, bool WIDE, int XPIECES, bool RLUT = false,
+          bool TRACE = false>
 __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulParams p) {
     static_assert(XM == 16 || ((XM == 4 || XM == 8) && MB == 1), "packed activation loads exist for M <= 8 only");
     constexpr bool XSH = XPIECES != 0;       // activations shared through LDS; XPIECES = pieces one wave stages (1 or 2)
@@ -157,12 +177,24 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
     constexpr int NX = XSH ? XPW : XL;       // activation loads per tile held in a stage
     constexpr int NXM = XSH ? 1 : MB;
 
+    unsigned long long tr[kTraceStamps];
+    auto stamp = [&](int i) {
+        if constexpr (TRACE) {
+            if (tr[i] == 0) tr[i] = wall_clock64();
+        }
+    };
+    if constexpr (TRACE) {
+#pragma unroll
+        for (int i = 0; i < kTraceStamps; ++i) tr[i] = 0;
+        stamp(kTraceStart);
+    }
     // Every scalar of the parameter block is used in the entry block, so that the argument segment
     // is fetched with one round trip instead of one per basic block that first needs a field.
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.counters), "s"(p.slots));
     asm volatile("" ::"s"(p.packed_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.KT), "s"(p.NRG), "s"(p.G), "s"(p.TQ),
                  "s"(p.TR), "s"(p.SG), "s"(p.SBL), "s"(p.NW), "s"(p.KS), "s"(p.RS), "s"(p.fast_reduce),
                  "s"(p.kt_magic), "s"(p.ks_magic), "s"(p.lut_ltpe), "s"(p.xbuf_off));
+    stamp(kTraceArgs);
 
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
@@ -253,7 +285,11 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                                              : kOutOfRange;                              // chunk mode
 
         // Loads of tile kt; kt >= wb turns every offset out of range (zeros, no traffic).
-        auto load_stage = [&](Stage& st, int kt) {
+        // (`prologue`: the loads that fill the pipeline before the table is built.  There the scale-chunk
+        // load is issued unconditionally, so that the number of loads between the table fetch and the
+        // wait for it is the same on every path and the wait counts exactly the table's two loads
+        // instead of, conservatively, the first tile as well.)
+        auto load_stage = [&](Stage& st, int kt, auto prologue) {
             const bool in = kt < wb;
             const uint32_t tw = in ? wrow + (uint32_t)kt * tile_stride : kOutOfRange;
             const uint32_t tx = in ? (uint32_t)kt * (TK * 2) : kOutOfRange;
@@ -267,7 +303,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                 // around (the condition is uniform over the wave).  The shared-activation instances keep
                 // the unconditional form: there the extra control flow costs more than it saves.
                 if constexpr (XSH) st.chunk = __builtin_amdgcn_raw_buffer_load_b128(rS, tc + clane, 0, kAuxNone);
-                else if (first) st.chunk = __builtin_amdgcn_raw_buffer_load_b128(rS, tc + clane, 0, kAuxNone);
+                else if (decltype(prologue)::value || first) st.chunk = __builtin_amdgcn_raw_buffer_load_b128(rS, tc + clane, 0, kAuxNone);
             } else {
                 const uint32_t ts = in ? (uint32_t)(kt / TPS) * (NS * 2) : kOutOfRange;
 #pragma unroll
@@ -387,9 +423,10 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
         }
 #pragma unroll
         for (int q = 0; q < P; ++q) {
-            load_stage(st[q], wa + q);
+            load_stage(st[q], wa + q, std::true_type{});
             __builtin_amdgcn_sched_barrier(0);
         }
+        stamp(kTraceIssued);
         if constexpr (RLUT) {
             // every wave has left the K loop of the previous row block (the reduction's barriers lie in
             // between), so the copies can be overwritten with this row block's tables
@@ -403,12 +440,13 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             // (the empty statement keeps the wait for T, and the arithmetic on it, from being hoisted
             // out of the segment loop to a point before the prefetch)
             LutSeed seed = lut_seed;
-            asm volatile("" : "+v"(seed.v[0]), "+v"(seed.v[1]), "+v"(seed.v[2]), "+v"(seed.v[3]));
-            lut_build<BITS, DT>(lut, seed, LOG2C, tid, p.lut_ltpe);
+            asm volatile("" : "+v"(seed.w[0]), "+v"(seed.w[1]), "+v"(seed.w[2]), "+v"(seed.w[3]));
+            lut_build<BITS, DT>(lut, seed, (int)(reinterpret_cast<uintptr_t>(p.lut) >> 1) & 1, LOG2C, tid, p.lut_ltpe);
             if constexpr (!XSH) __syncthreads();
             lut_ready = true;
             __builtin_amdgcn_sched_barrier(0);
         }
+        stamp(kTraceTable);
         if constexpr (XSH) {
             // first tile's pieces into buffer 0 (every reader of the previous segment has passed its
             // last barrier); the barrier also publishes the table
@@ -425,7 +463,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                     compute_stage(st[q], wa + it + q, it + q);
                     __syncthreads();
                     __builtin_amdgcn_sched_barrier(0);
-                    load_stage(st[q], wa + it + q + P);
+                    load_stage(st[q], wa + it + q + P, std::false_type{});
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -439,7 +477,8 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
                 for (int q = 0; q < P; ++q) {
                     compute_stage(st[q], kt + q, 0);
                     __builtin_amdgcn_sched_barrier(0);
-                    load_stage(st[q], kt + q + P);
+                    stamp(kTraceFirstTile);
+                    load_stage(st[q], kt + q + P, std::false_type{});
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -447,8 +486,10 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             for (int q = 0; q < P; ++q) {
                 if (kt + q < wb) compute_stage(st[q], kt + q, 0);
                 __builtin_amdgcn_sched_barrier(0);
+                stamp(kTraceFirstTile);
             }
         }
+        stamp(kTraceLoopDone);
 
         if constexpr (XM != 16) {
             // fold the step positions: columns 4 j .. 4 j + 3 of accumulator j move to columns 0 .. 3
@@ -516,6 +557,7 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             }
         }
 
+        stamp(kTraceReduced);
         // ---- emit: whole output tile -> Y; otherwise the Stream-K fix-up ----
         // Partial sums and counters are moved with device-scope (agent) atomic loads/stores, which
         // bypass the per-XCD L2 for coherence.  No device-scope fence is used: on this multi-die part
@@ -590,6 +632,15 @@ __global__ __launch_bounds__(WIDE ? 1024 : 512) void matmul_kernel(const MatmulP
             }
         }
         t0 += rem;
+    }
+    if constexpr (TRACE) {
+        __builtin_amdgcn_s_waitcnt(0);                       // the stores of Y have been acknowledged
+        stamp(kTraceEnd);
+        if (p.trace && lane == 0) {
+            unsigned long long* o = p.trace + ((size_t)blockIdx.x * kTraceWaves + wave) * kTraceStamps;
+#pragma unroll
+            for (int i = 0; i < kTraceStamps; ++i) o[i] = tr[i];
+        }
     }
 }
 

@@ -621,3 +621,58 @@ def test_largest_shapes_sampled_rows(lutq, name, N, K, bits, group, dtype, lut, 
         sub = gen.Case(M, len(rows), K, bits, group, dtype, X, base.Q[rows], base.S[rows], base.T)
         check_y(Y[:, rows], sub, f"{name} M{M}")
         assert np.isfinite(orc.to_f64(Y, dtype)).all(), f"{name} M{M}"
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_work_queue_plans_match_oracle(lutq, bits, dtype):
+    """The work-queue kernel for M <= 4 (items of K tiles dealt to the waves by a counter; partial sums
+    per item, added in K order): every M, group sizes with one to sixteen tiles per scale chunk, one and
+    two row blocks per wave, one to several row groups per workgroup, fewer items than waves and many
+    more, against the oracle; bit-reproducible; the library's own choice where it applies."""
+    Q = 2                                                   # LUTQ_SCHED_QUEUE
+    for (N, K, group, lut) in [(64, 8 * tk(bits), 128, "nf"), (192, 16 * tk(bits), 64, "learned"),
+                               (96, 8 * tk(bits), 32, "random_index"), (128, 16 * tk(bits), 256, "nf")]:
+        nb = N // 16
+        for M in (1, 2, 3, 4):
+            c = gen.make_case(400 + M, M, N, K, bits, group, dtype, lut)
+            d = DeviceCase(lutq, c)
+            plans = [lutq.Plan(1, 0, 16, 2, 1, Q, 2), lutq.Plan(1, 0, 4, 2, nb, Q, 4), lutq.Plan(1, 0, 12, 2, nb // 2, Q, 8),
+                     lutq.Plan(1, 0, 7, 2, 1, Q, 4), lutq.Plan(0, 0, 0, 0, 0, Q, 0)]
+            if not (bits == 3 and dtype == "bf16"):
+                plans += [lutq.Plan(2, 0, 16, 2, 1, Q, 2), lutq.Plan(2, 0, 9, 2, nb // 2, Q, 4)]
+            for plan in plans:
+                Y1 = to_bits(d.matmul(lutq, plan=plan))
+                Y2 = to_bits(d.matmul(lutq, plan=plan))
+                assert np.array_equal(Y1, Y2), f"{plan} is not reproducible"
+                check_y(Y1, c, f"b{bits} {dtype} g{group} M{M} N{N} K{K} {plan}")
+            # what does not fit the kernel is refused before anything is launched
+            for bad in (lutq.Plan(4, 0, 16, 2, 1, Q, 2), lutq.Plan(1, 0, 16, 2, 1, Q, 3), lutq.Plan(1, 0, 16, 2, 5, Q, 2),
+                        lutq.Plan(1, 7, 16, 2, 1, Q, 2), lutq.Plan(1, 0, 17, 2, 1, Q, 2), lutq.Plan(1, 0, 16, 4, 1, Q, 4)):
+                with pytest.raises(lutq.LutqError) as e:
+                    d.matmul(lutq, plan=bad)
+                assert e.value.code == 10, bad
+    c = gen.make_case(9, 5, 64, 8 * tk(bits), bits, 64, dtype, "nf")            # five rows: no work queue
+    with pytest.raises(lutq.LutqError):
+        DeviceCase(lutq, c).matmul(lutq, plan=lutq.Plan(1, 0, 16, 2, 1, Q, 2))
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_table_pointer_in_the_upper_half_of_a_word(lutq, bits, dtype):
+    """The kernels fetch the table as aligned 32-bit words; a table that starts in the upper half of a
+    word (a pointer that is only 2-byte aligned) must give the same bits, in the work-queue kernel and
+    under team plans."""
+    import torch
+    for (M, N, K, group, plan) in [(1, 128, 8 * tk(bits), 64, None), (3, 64, 8 * tk(bits), 128, lutq.Plan(1, 0, 8, 2, 2, 2, 4)),
+                                   (4, 96, 4 * tk(bits), 32, lutq.Plan(1, 5, 8, 2, 1)), (17, 160, 4 * tk(bits), 64, None)]:
+        c = gen.make_case(600 + M, M, N, K, bits, group, dtype, "learned")
+        d = DeviceCase(lutq, c)
+        want = to_bits(d.matmul(lutq, plan=plan))
+        check_y(want, c, f"b{bits} {dtype} M{M} {plan}")
+        pad = torch.zeros(1 + (1 << bits), dtype=d.T.dtype, device="cuda")
+        pad[1:] = d.T
+        Y = torch.full((M, N), float("nan"), dtype=d.X.dtype, device="cuda")
+        lutq.lutq_matmul(d.X, d.packed, d.S, pad[1:], bits, group, Y, d.ws, plan=plan)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_bits(Y), want), (bits, dtype, M, plan)

@@ -166,12 +166,18 @@ def test_default_plans_are_valid_for_random_problems():
         p = lutq.lutq_plan_default_for(bits, group, M, N, K, dt, cus)
         what = f"b{bits} g{group} M{M} N{N} K{K} cus{cus} dt{dt}: {p}"
         assert p.row_blocks_per_wave in (1, 2, 4) and _sb(nb) % p.row_blocks_per_wave == 0, what
-        assert 1 <= p.row_groups_per_workgroup <= 16, what
-        assert 4 <= p.waves_per_workgroup <= 16 and p.waves_per_workgroup % p.row_groups_per_workgroup == 0, what
-        assert p.tiles_in_flight in (2, 4), what
+        assert 4 <= p.waves_per_workgroup <= 16 and p.tiles_in_flight in (2, 4), what
         nrg = nb // p.row_blocks_per_wave
         assert nrg % p.row_groups_per_workgroup == 0, what
-        assert 1 <= p.grid and p.grid * p.row_groups_per_workgroup <= 4096, what
+        if p.scheduling == 2:                       # work queue: M <= 4, whole row groups per workgroup
+            assert M <= 4 and p.row_blocks_per_wave <= 2 and 1 <= p.row_groups_per_workgroup <= 64, what
+            assert p.grid * p.row_groups_per_workgroup == nrg and p.tiles_in_flight == 2, what
+            assert p.tiles_per_item % 2 == 0 and (K // tkb) % p.tiles_per_item == 0, what
+        else:
+            assert p.scheduling == 1 and p.tiles_per_item == 0, what
+            assert 1 <= p.row_groups_per_workgroup <= 16, what
+            assert p.waves_per_workgroup % p.row_groups_per_workgroup == 0, what
+            assert 1 <= p.grid and p.grid * p.row_groups_per_workgroup <= 4096, what
         # the library accepts its own default, given explicitly or not (kernel instance exists, LDS fits,
         # partial-sum slots suffice)
         assert lutq.lutq_plan_check(bits, group, M, N, K, dt, cus) == 0, what
@@ -182,13 +188,15 @@ def test_default_plans_are_valid_for_random_problems():
 def test_default_plans_of_the_llama3_shapes():
     """The measured choices for the benchmark's shapes on 256 compute units (4-bit, fp16, M = 1): a
     change here is a change of the benchmark's launch configuration."""
-    want = {(6144, 4096, 128): (1, 384, 8, 2, 1), (4096, 4096, 128): (1, 256, 8, 2, 1),
-            (28672, 4096, 128): (1, 256, 14, 2, 7), (4096, 14336, 128): (1, 256, 14, 2, 1),
-            (10240, 8192, 64): (1, 256, 15, 2, 5), (8192, 8192, 64): (2, 256, 8, 2, 1),
-            (57344, 8192, 64): (2, 256, 14, 2, 7), (8192, 28672, 64): (2, 256, 8, 2, 1)}
+    want = {(6144, 4096, 128): (1, 384, 8, 2, 1, 1, 0), (4096, 4096, 128): (1, 256, 8, 2, 1, 1, 0),
+            (28672, 4096, 128): (1, 256, 14, 2, 7, 1, 0), (4096, 14336, 128): (1, 256, 14, 2, 1, 1, 0),
+            (10240, 8192, 64): (1, 256, 15, 2, 5, 1, 0), (8192, 8192, 64): (2, 256, 8, 2, 1, 1, 0),
+            # the two largest: the work-queue kernel (one workgroup per compute unit, items of four K tiles)
+            (57344, 8192, 64): (2, 256, 16, 2, 7, 2, 4), (8192, 28672, 64): (1, 256, 16, 2, 2, 2, 4)}
     for (N, K, g), plan in want.items():
         p = lutq.lutq_plan_default_for(4, g, 1, N, K, 0, 256)
-        assert (p.row_blocks_per_wave, p.grid, p.waves_per_workgroup, p.tiles_in_flight, p.row_groups_per_workgroup) == plan, (N, K, p)
+        assert (p.row_blocks_per_wave, p.grid, p.waves_per_workgroup, p.tiles_in_flight, p.row_groups_per_workgroup,
+                p.scheduling, p.tiles_per_item) == plan, (N, K, p)
     assert lutq.lutq_plan_default_for(4, 128, 100, 4096, 4096, 0, 256) == lutq.lutq_plan_default_for(4, 128, 32, 4096, 4096, 0, 256)
     with pytest.raises(lutq.LutqError):
         lutq.lutq_plan_default_for(4, 128, 1, 4096, 4096, 0, 0)

@@ -17,10 +17,12 @@ def _both(lutq, c, plan):
     d = DeviceCase(lutq, c)
     want = to_bits(d.matmul(lutq, plan=plan))
     Y = torch.full((c.M, c.N), float("nan"), dtype=d.X.dtype, device="cuda")
+    import gc
+    gc.collect()
     before = torch.cuda.memory_allocated()
     lutq.lutq_matmul_static(d.X, d.packed, d.S, d.T, c.bits, c.group_size, Y, plan=plan)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_allocated() <= before          # nothing was allocated through torch either
     return to_bits(Y), want
 
 
