@@ -68,9 +68,49 @@ const char* lutq_status_string(lutq_status s);
  * The packed form orders indices so that a wavefront's 128-bit loads deliver them
  * already in the operand order of the gfx950 16x16x32 matrix instruction, and
  * splits 3-bit indices into a 2-bit slice and a 1-bit slice so that every load is
- * a power-of-two number of bits.  The byte layout is spelled out at the top of csrc/lutq_pack.cpp; it
- * does not depend on group_size (the argument is validated and otherwise unused).
+ * a power-of-two number of bits.  It does not depend on group_size (the argument is
+ * validated and otherwise unused).
+ *
+ * Packed layout (normative; this library's own -- the paper's is tied to NVIDIA Ampere fragments).
+ * Q is [N, K] row-major.  N is cut into row blocks of 16 rows, K into tiles of TK columns (TK = 128
+ * for 4-bit, 256 for 2- and 3-bit).  Row blocks are grouped into super-blocks of SB consecutive row
+ * blocks: with nb = N / 16, SB = 4 if nb is a multiple of 4, else 2 if nb is even, else 1 -- except
+ * SB = 2 for multiples of 4 in 257..512 (a choice tuned for 256 compute units and frozen into the
+ * format: it holds on every device; lutq_pack_layout reports SB for a given N, so that it can be
+ * recorded next to a packed blob).  Storage order is super-block, then K tile, then row block inside
+ * the super-block: tile (rb, kt) starts at byte
+ *        (((rb / SB) * (K / TK) + kt) * SB + rb % SB) * TILE_BYTES,
+ * so the SB tiles that cover 16*SB rows x TK columns are adjacent.  A tile is what one 64-lane
+ * wavefront loads with one 128-bit load per lane (plus one 64-bit load for the 3-bit high slice).
+ * v_mfma_f32_16x16x32_{f16,bf16} takes, from lane l = 16*o + i (i = 0..15, o = 0..3), the eight
+ * A-matrix elements of row i and columns 8*o .. 8*o+7 of a 16 x 32 block; a tile holds TK/32 such
+ * blocks ("steps" t).  Lane l owns, for step t, the indices Q[16*rb + i][TK*kt + 32*t + 8*o + j],
+ * j = 0..7, and its bytes sit at offset 16*l of the tile:
+ *   4-bit  TILE_BYTES = 1024.  Four little-endian 32-bit words d = 0..3; word d is step d; nibble j
+ *          (bits 4j..4j+3) is index j, so byte p of a word is the pair (2p, 2p+1).
+ *   2-bit  TILE_BYTES = 1024.  Words d = 0..3; 2-bit field e (bits 2e..2e+1), e = 0..15, of word d is
+ *          index j = e % 8 of step t = 2d + e / 8, so byte p holds four consecutive indices.
+ *   3-bit  TILE_BYTES = 1536 = 1024 (low slice: index bits 0..1) + 512 (high slice: bit 2).
+ *          Low slice, lane l at 16*l, words d = 0..3, byte p = 0..3 of word d:
+ *              bits 0..1 low2(index 2p, step 2d)      bits 2..3 low2(index 2p+1, step 2d)
+ *              bits 4..5 low2(index 2p, step 2d+1)    bits 6..7 low2(index 2p+1, step 2d+1)
+ *          High slice, lane l at 1024 + 8*l, words h = 0..1, byte p of word h, u = 0..3:
+ *              bit 2u = bit2(index 2p, step 4h+u)     bit 2u+1 = bit2(index 2p+1, step 4h+u)
+ *          so that, for one step, (low word >> 0 or 4) supplies bits 0..3 of each byte and (high word
+ *          shifted by 4 - 2u) supplies bits 4..5: four 6-bit pair-table addresses.
  * ------------------------------------------------------------------------- */
+
+/* Geometry of the packed form of an [N, K] matrix at `bits` bits. */
+typedef struct {
+    int tile_k;                       /* K columns per tile: 128 (4-bit) or 256 */
+    int tile_bytes;                   /* 1024, or 1536 at 3 bits */
+    int row_blocks_per_super_block;   /* SB: 4, 2 or 1 */
+    int64_t row_blocks;               /* N / 16 */
+    int64_t k_tiles;                  /* K / tile_k */
+} lutq_layout;
+
+/* Fills *out for (N, K, bits).  Errors: NULL, BITS, GROUP, SHAPE. */
+lutq_status lutq_pack_layout(int64_t N, int64_t K, int bits, int group_size, lutq_layout* out);
 
 /* Size in bytes of the packed form (N*K*bits/8); 0 if the arguments are unsupported. */
 size_t lutq_packed_bytes(int64_t N, int64_t K, int bits, int group_size);
@@ -136,6 +176,27 @@ lutq_status lutq_plan_default_for(int bits, int group_size, int64_t M, int64_t N
  * plan and the problem (BITS, GROUP, SHAPE, DTYPE, PLAN).  Host logic only; no device is touched. */
 lutq_status lutq_plan_check(int bits, int group_size, int64_t M, int64_t N, int64_t K, lutq_dtype dtype,
                             int compute_units, const lutq_plan* plan);
+
+/* Plans chosen by measurement (lutq_tune; Section 4.1 picks the kernel configuration per shape offline and
+ * dispatches on it): a process-wide table that lutq_matmul and lutq_matmul_static consult, when no plan
+ * is passed, before their own choice.  An entry applies to calls with its bits, group_size, dtype, N,
+ * K and m_min <= M <= m_max (for M > 32 the M of each 32-row slice counts); the first match wins; an
+ * entry whose plan the kernels cannot run for a call is skipped (the library's own choice is used). */
+typedef struct {
+    int bits, group_size;
+    lutq_dtype dtype;
+    int64_t m_min, m_max, N, K;
+    lutq_plan plan;
+} lutq_plan_entry;
+
+/* Replaces the table by a copy of entries[0 .. count-1] (count = 0 clears it).  Host memory only; safe to
+ * call from any thread, but calls already in flight may still use the old table.  Errors: NULL, SHAPE
+ * (count < 0 or > 4096). */
+lutq_status lutq_plan_table_set(const lutq_plan_entry* entries, int count);
+
+/* The plan the table holds for this call: LUTQ_OK and *plan, or LUTQ_ERR_PLAN if no entry matches. */
+lutq_status lutq_plan_table_lookup(int bits, int group_size, int64_t M, int64_t N, int64_t K, lutq_dtype dtype,
+                                   lutq_plan* plan);
 
 /* Y = X * W^T-dequantised, asynchronous on `stream`.
  *   X       device, [M, K] row-major, dtype

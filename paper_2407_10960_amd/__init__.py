@@ -19,6 +19,9 @@ from .binding import (  # noqa: F401
     lutq_plan_default,
     lutq_plan_default_for,
     lutq_plan_check,
+    lutq_pack_layout,
+    lutq_plan_table_set,
+    lutq_plan_table_lookup,
     lutq_quantize,
     lutq_tune,
     lutq_tune_candidates,

@@ -12,7 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "lutq_status_string", "lutq_packed_bytes", "lutq_pack", "lutq_unpack", "lutq_workspace_bytes",
-    "lutq_plan_default", "lutq_plan_default_for", "lutq_plan_check", "lutq_matmul", "lutq_matmul_plan", "lutq_matmul_static", "lutq_matmul_channel", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
+    "lutq_plan_default", "lutq_plan_default_for", "lutq_plan_check", "lutq_pack_layout", "lutq_plan_table_set", "lutq_plan_table_lookup", "lutq_matmul", "lutq_matmul_plan", "lutq_matmul_static", "lutq_matmul_channel", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
     "lutq_calib_stream_read", "lutq_calib_copy", "lutq_calib_matmul_trace",
 )
 
@@ -30,6 +30,17 @@ class _CPlan(ctypes.Structure):
                 ("waves_per_workgroup", ctypes.c_int), ("tiles_in_flight", ctypes.c_int),
                 ("row_groups_per_workgroup", ctypes.c_int), ("scheduling", ctypes.c_int),
                 ("tiles_per_item", ctypes.c_int)]
+
+
+class _CLayout(ctypes.Structure):
+    _fields_ = [("tile_k", ctypes.c_int), ("tile_bytes", ctypes.c_int), ("row_blocks_per_super_block", ctypes.c_int),
+                ("row_blocks", ctypes.c_int64), ("k_tiles", ctypes.c_int64)]
+
+
+class _CPlanEntry(ctypes.Structure):
+    _fields_ = [("bits", ctypes.c_int), ("group_size", ctypes.c_int), ("dtype", ctypes.c_int),
+                ("m_min", ctypes.c_int64), ("m_max", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("plan", _CPlan)]
 
 
 @dataclass
@@ -79,6 +90,12 @@ def load_library():
     lib.lutq_plan_default_for.argtypes = [ci, ci, i64, i64, i64, ci, ci, ctypes.POINTER(_CPlan)]
     lib.lutq_plan_check.restype = ci
     lib.lutq_plan_check.argtypes = [ci, ci, i64, i64, i64, ci, ci, ctypes.POINTER(_CPlan)]
+    lib.lutq_pack_layout.restype = ci
+    lib.lutq_pack_layout.argtypes = [i64, i64, ci, ci, ctypes.POINTER(_CLayout)]
+    lib.lutq_plan_table_set.restype = ci
+    lib.lutq_plan_table_set.argtypes = [ctypes.POINTER(_CPlanEntry), ci]
+    lib.lutq_plan_table_lookup.restype = ci
+    lib.lutq_plan_table_lookup.argtypes = [ci, ci, i64, i64, i64, ci, ctypes.POINTER(_CPlan)]
     lib.lutq_matmul.restype = ci
     lib.lutq_matmul.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.lutq_matmul_plan.restype = ci
@@ -207,6 +224,32 @@ def lutq_plan_check(bits: int, group_size: int, M: int, N: int, K: int, dtype_co
     cp = plan._c() if plan is not None else None
     return int(load_library().lutq_plan_check(bits, group_size, M, N, K, dtype_code, compute_units,
                                               ctypes.byref(cp) if cp is not None else None))
+
+
+def lutq_pack_layout(N: int, K: int, bits: int, group_size: int) -> dict:
+    """Geometry of the packed form: tile_k, tile_bytes, row_blocks_per_super_block, row_blocks, k_tiles."""
+    c = _CLayout()
+    _check(load_library().lutq_pack_layout(N, K, bits, group_size, ctypes.byref(c)), "lutq_pack_layout")
+    return {f: int(getattr(c, f)) for f, _ in _CLayout._fields_}
+
+
+def lutq_plan_table_set(entries) -> None:
+    """entries: iterable of (bits, group_size, dtype_code, m_min, m_max, N, K, Plan); replaces the table."""
+    entries = list(entries)
+    arr = (_CPlanEntry * max(len(entries), 1))()
+    for i, (bits, group, dt, m0, m1, N, K, plan) in enumerate(entries):
+        arr[i] = _CPlanEntry(bits, group, dt, m0, m1, N, K, plan._c())
+    _check(load_library().lutq_plan_table_set(arr, len(entries)), "lutq_plan_table_set")
+
+
+def lutq_plan_table_lookup(bits: int, group_size: int, M: int, N: int, K: int, dtype_code: int = LUTQ_F16):
+    """The registered plan for this call, or None."""
+    cp = _CPlan()
+    code = load_library().lutq_plan_table_lookup(bits, group_size, M, N, K, dtype_code, ctypes.byref(cp))
+    if code != 0:
+        return None
+    return Plan(cp.row_blocks_per_wave, cp.grid, cp.waves_per_workgroup, cp.tiles_in_flight,
+                cp.row_groups_per_workgroup, cp.scheduling, cp.tiles_per_item)
 
 
 def lutq_matmul(X, packed, scales, lut, bits: int, group_size: int, Y, workspace, stream=None,
@@ -359,6 +402,11 @@ def lutq_dequant(packed, scales, lut, bits: int, group_size: int, W_out, stream=
     N, K = W_out.shape
     if not (packed.is_cuda and scales.is_cuda and lut.is_cuda and W_out.is_cuda):
         raise ValueError("lutq_dequant needs CUDA (HIP) tensors")
+    for t in (packed, scales, lut, W_out):
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+    if not (_dtype_code(scales) == code and _dtype_code(lut) == code):
+        raise TypeError("scales, lut and W_out must share one dtype")
     if scales.shape[0] != N or scales.shape[1] * group_size != K or lut.numel() != (1 << bits):
         raise ValueError("inconsistent shapes")
     if packed.numel() != lib.lutq_packed_bytes(N, K, bits, group_size):

@@ -11,6 +11,7 @@
 #include "lutq.h"
 #include "lutq_calib.h"
 #include "lutq_launch.hpp"
+#include "lutq_layout.hpp"
 
 namespace {
 
@@ -30,7 +31,8 @@ constexpr size_t kWorkspaceBytes = kCounterBytes + (size_t)kMaxGrid * 2 * kSlotB
 constexpr size_t kStaticSlotBytes = LUTQ_STATIC_SCRATCH_BYTES - kCounterBytes;
 static __device__ __align__(256) unsigned char scratch[LUTQ_STATIC_SCRATCH_BYTES];
 
-inline int tile_k(int bits) { return bits == 4 ? 128 : 256; }
+using layout::super_block;
+using layout::tile_k;
 
 lutq_status check_problem(int bits, int group_size, int64_t N, int64_t K) {
     if (bits < 2 || bits > 4) return LUTQ_ERR_BITS;
@@ -68,8 +70,6 @@ DeviceInfo device_info() {
     return cache[dev];
 }
 
-// row blocks per super-block of the packed layout (the rule of lutq_pack.cpp)
-inline int super_block(int64_t nb) { return (nb % 4 == 0 && (nb <= 256 || nb > 512)) ? 4 : nb % 2 == 0 ? 2 : 1; }
 // bytes of lutq_dequant's table (log2c copies); entries are 8 bytes for the 2-bit quad table and for the
 // widened bf16 pair tables, else 4
 int lut_bytes(int bits, bool bf16, int log2c) {
@@ -528,6 +528,39 @@ extern "C" lutq_status lutq_plan_default(int bits, int group_size, int64_t M, in
 
 namespace {
 
+// Plans registered with lutq_plan_table_set.
+std::mutex g_plan_table_mu;
+std::vector<lutq_plan_entry> g_plan_table;
+
+bool plan_table_find(int bits, int group_size, int64_t M, int64_t N, int64_t K, lutq_dtype dtype, lutq_plan* out) {
+    std::lock_guard<std::mutex> lock(g_plan_table_mu);
+    for (const lutq_plan_entry& e : g_plan_table)
+        if (e.bits == bits && e.group_size == group_size && e.dtype == dtype && e.N == N && e.K == K && e.m_min <= M && M <= e.m_max) {
+            *out = e.plan;
+            return true;
+        }
+    return false;
+}
+
+}  // namespace
+
+extern "C" lutq_status lutq_plan_table_set(const lutq_plan_entry* entries, int count) {
+    if (count < 0 || count > 4096) return LUTQ_ERR_SHAPE;
+    if (count > 0 && !entries) return LUTQ_ERR_NULL;
+    std::vector<lutq_plan_entry> fresh(entries, entries + count);
+    std::lock_guard<std::mutex> lock(g_plan_table_mu);
+    g_plan_table.swap(fresh);
+    return LUTQ_OK;
+}
+
+extern "C" lutq_status lutq_plan_table_lookup(int bits, int group_size, int64_t M, int64_t N, int64_t K, lutq_dtype dtype,
+                                              lutq_plan* plan) {
+    if (!plan) return LUTQ_ERR_NULL;
+    return plan_table_find(bits, group_size, M, N, K, dtype, plan) ? LUTQ_OK : LUTQ_ERR_PLAN;
+}
+
+namespace {
+
 // One validated launch: everything lutq_matmul_plan decides before it touches the device.
 struct Prepared {
     MatmulParams p;
@@ -600,7 +633,15 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
                            int bits, int group_size, int64_t M, int64_t N, int64_t K,
                            lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
                            const lutq_plan* user_plan, bool rowlut, int dry_run_cus, Prepared* out,
-                           bool fitted_workspace = false) {
+                           bool fitted_workspace = false, bool consult_table = true) {
+    // no plan from the caller: a registered plan for this call goes first, if the kernels can run it
+    lutq_plan registered;
+    if (!user_plan && !rowlut && dry_run_cus == 0 && consult_table &&
+        plan_table_find(bits, group_size, M, N, K, dtype, &registered)) {
+        const lutq_status st = prepare_matmul(X, packed, scales, lut, bits, group_size, M, N, K, dtype, Y, workspace,
+                                              workspace_bytes, &registered, rowlut, dry_run_cus, out, fitted_workspace, false);
+        if (st != LUTQ_ERR_PLAN && st != LUTQ_ERR_SCRATCH) return st;
+    }
     // dry_run_cus > 0: only the plan is checked, for a device of that many compute units; no pointer is
     // looked at and no device is queried
     const bool dry = dry_run_cus > 0;

@@ -3,54 +3,18 @@
 // the matrix-instruction operand layout; split 3-bit indices into a 2-bit and a 1-bit
 // slice so that all loads are a power-of-two number of bits).
 //
-// Packed layout (this library's own; the paper's is tied to NVIDIA Ampere fragments).
-//
-// Q is [N, K] row-major.  N is cut into row blocks of 16 rows, K into tiles of TK columns
-// (TK = 128 for 4-bit, 256 for 2- and 3-bit).  Row blocks are grouped into super-blocks of SB
-// consecutive row blocks (SB = 4 if N/16 is a multiple of 4 and not in 257..512, else 2 if N/16 is even,
-// else 1; see super_block below).  Storage order is
-// super-block, then K tile, then row block inside the super-block: tile (rb, kt) starts at byte
-//        (((rb / SB) * K/TK + kt) * SB + rb % SB) * TILE_BYTES,
-// so the SB tiles that cover 16*SB rows x TK columns are adjacent: a wavefront that owns a whole
-// super-block streams one contiguous run of memory along K instead of SB separate runs.  A tile is
-// what one 64-lane wavefront loads with one 128-bit load per lane (plus one 64-bit load for the
-// 3-bit high slice).
-//
-// The gfx950 instruction v_mfma_f32_16x16x32_{f16,bf16} takes, from lane l = 16*o + i
-// (i = 0..15, o = 0..3), the eight A-matrix elements of row i and columns 8*o .. 8*o+7
-// of a 16 x 32 block.  A K tile holds TK/32 such blocks ("steps" t).  Lane l therefore
-// owns, for step t, the indices
-//        Q[16*rb + i][TK*kt + 32*t + 8*o + j],   j = 0..7,
-// and its bytes sit at offset 16*l of the tile:
-//
-//  4-bit  TILE_BYTES = 1024.  Four little-endian 32-bit words d = 0..3; word d is step d;
-//         nibble j (bits 4j..4j+3) is index j.  Byte p of a word is thus the pair
-//         (j = 2p, 2p+1): directly the address of a pair-table entry.
-//  2-bit  TILE_BYTES = 1024.  Words d = 0..3; 2-bit field e (bits 2e..2e+1), e = 0..15, of
-//         word d is index j = e % 8 of step t = 2d + e / 8.  Byte p holds four consecutive
-//         indices: the address of a quad-table entry.
-//  3-bit  TILE_BYTES = 1536 = 1024 (low slice: index bits 0..1) + 512 (high slice: bit 2).
-//         Low slice, lane l at 16*l, words d = 0..3, byte p = 0..3 of word d:
-//              bits 0..1 low2(index 2p, step 2d)      bits 2..3 low2(index 2p+1, step 2d)
-//              bits 4..5 low2(index 2p, step 2d+1)    bits 6..7 low2(index 2p+1, step 2d+1)
-//         High slice, lane l at 1024 + 8*l, words h = 0..1, byte p of word h, u = 0..3:
-//              bit 2u   = bit2(index 2p,   step 4h+u)
-//              bit 2u+1 = bit2(index 2p+1, step 4h+u)
-//         so that, for one step, (low word >> 0 or 4) supplies bits 0..3 of each byte and
-//         (high word shifted by 4 - 2u) supplies bits 4..5: four 6-bit pair-table addresses.
+// The byte layout is specified in include/lutq.h ("Packed layout"); its geometry is lutq_layout.hpp.
 #include "lutq.h"
+#include "lutq_layout.hpp"
 
 #include <cstring>
 
 namespace {
 
-inline int tile_k(int bits) { return bits == 4 ? 128 : 256; }
-inline int tile_bytes(int bits) { return bits == 3 ? 1536 : 1024; }
-// Between one and two row blocks per compute unit of the 256-CU part (N/16 in 257..512) a workgroup
-// streams two row blocks: with SB = 2 these two are one contiguous run of memory (measured on
-// N = K = 8192, M = 1: 9.96 us with SB = 4, 8.90 us with SB = 2); everywhere else SB = 4 measured best.
-inline int super_block(int64_t nb) { return (nb % 4 == 0 && (nb <= 256 || nb > 512)) ? 4 : nb % 2 == 0 ? 2 : 1; }
-inline int64_t tile_index(int64_t rb, int64_t kt, int64_t KT, int SB) { return ((rb / SB) * KT + kt) * SB + rb % SB; }
+using lutq::layout::super_block;
+using lutq::layout::tile_bytes;
+using lutq::layout::tile_index;
+using lutq::layout::tile_k;
 
 lutq_status check_pack_args(int64_t N, int64_t K, int bits, int group_size) {
     if (bits < 2 || bits > 4) return LUTQ_ERR_BITS;
@@ -77,6 +41,18 @@ inline Loc loc3_low(int l, int t, int j) { return { 16 * l + 4 * (t >> 1), 8 * (
 inline Loc loc3_high(int l, int t, int j) { return { 1024 + 8 * l + 4 * (t >> 2), 8 * (j >> 1) + 2 * (t & 3) + (j & 1) }; }
 
 }  // namespace
+
+extern "C" lutq_status lutq_pack_layout(int64_t N, int64_t K, int bits, int group_size, lutq_layout* out) {
+    if (!out) return LUTQ_ERR_NULL;
+    const lutq_status st = check_pack_args(N, K, bits, group_size);
+    if (st != LUTQ_OK) return st;
+    out->tile_k = tile_k(bits);
+    out->tile_bytes = tile_bytes(bits);
+    out->row_blocks_per_super_block = super_block(N / 16);
+    out->row_blocks = N / 16;
+    out->k_tiles = K / tile_k(bits);
+    return LUTQ_OK;
+}
 
 extern "C" size_t lutq_packed_bytes(int64_t N, int64_t K, int bits, int group_size) {
     if (check_pack_args(N, K, bits, group_size) != LUTQ_OK) return 0;

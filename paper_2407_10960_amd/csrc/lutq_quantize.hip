@@ -27,6 +27,7 @@
 #include <cstdint>
 
 #include "lutq.h"
+#include "lutq_layout.hpp"
 
 namespace lutq {
 
@@ -258,7 +259,7 @@ extern "C" lutq_status lutq_quantize(const void* W, int w_is_f32, const void* lu
     if (!aligned16(W) || !aligned16(packed_out) || (reinterpret_cast<uintptr_t>(scales_out) & 1u) ||
         (reinterpret_cast<uintptr_t>(lut) & 1u))
         return LUTQ_ERR_ALIGN;
-    const int tk = bits == 4 ? 128 : 256;
+    const int tk = lutq::layout::tile_k(bits);
     const int uc = group_size > tk ? group_size : tk;
     const int64_t nb = N / 16;
     lutq::QuantParams p;
@@ -269,7 +270,7 @@ extern "C" lutq_status lutq_quantize(const void* W, int w_is_f32, const void* lu
     p.N = (int)N; p.K = (int)K;
     p.KT = (int)(K / tk);
     p.SG = (int)(K / group_size);
-    p.SB = (nb % 4 == 0 && (nb <= 256 || nb > 512)) ? 4 : nb % 2 == 0 ? 2 : 1;     // the rule of lutq_pack.cpp
+    p.SB = lutq::layout::super_block(nb);
     p.upr = (int)(K / uc);
     p.units = nb * (K / uc);
     p.bf16 = dtype == LUTQ_BF16;

@@ -676,3 +676,61 @@ def test_table_pointer_in_the_upper_half_of_a_word(lutq, bits, dtype):
         lutq.lutq_matmul(d.X, d.packed, d.S, pad[1:], bits, group, Y, d.ws, plan=plan)
         torch.cuda.synchronize()
         assert np.array_equal(to_bits(Y), want), (bits, dtype, M, plan)
+
+
+def test_fixup_protocol_soak(lutq):
+    """The cross-workgroup fix-up (Algorithm 2: partial sums to global scratch, an arrival counter per
+    row group, the last arriver adds all partials in workgroup order) under a heavily split plan, a few
+    thousand launches back to back with two alternating problems on one workspace: every result equals,
+    bit for bit, the first result of its problem, and the arrival counters end at zero.  Stops at the
+    first mismatch."""
+    import torch
+    bits, group, dtype, N, K = 4, 64, "f16", 256, 8192
+    cases = [gen.make_case(70 + i, M, N, K, bits, group, dtype, "random_index") for i, M in enumerate((1, 16))]
+    devs = [DeviceCase(lutq, c) for c in cases]
+    ws = devs[0].ws
+    plans = [lutq.Plan(1, 2048, 8, 2, 2), lutq.Plan(1, 1000, 4, 2, 1)]       # every tile cut across many workgroups
+    outs = [torch.empty((c.M, N), dtype=torch.float16, device="cuda") for c in cases]
+    first = []
+    for d, c, y, plan in zip(devs, cases, outs, plans):
+        lutq.lutq_matmul(d.X, d.packed, d.S, d.T, bits, group, y, ws, plan=plan)
+        torch.cuda.synchronize()
+        first.append(y.clone())
+        check_y(to_bits(y), c, f"soak reference {plan}")
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for it in range(1500):
+        for d, y, ref, plan in zip(devs, outs, first, plans):
+            lutq.lutq_matmul(d.X, d.packed, d.S, d.T, bits, group, y, ws, plan=plan)
+            bad += (y.view(torch.int16) != ref.view(torch.int16)).any().to(torch.int32)
+        if it % 100 == 99:
+            assert bad.item() == 0, f"a result changed within the first {it + 1} rounds"
+    assert bad.item() == 0
+    assert not ws[:65536].any().item()
+
+
+def test_registered_plans_are_used_by_lutq_matmul(lutq):
+    """A plan registered with lutq_plan_table_set (what lutq_tune returns, kept for later) is what
+    lutq_matmul runs for a matching call: same bits as lutq_matmul_plan with that plan; a registered
+    plan the kernels cannot run is skipped; calls that do not match are untouched."""
+    bits, group, dtype, N, K = 4, 64, "f16", 256, 4096
+    c = gen.make_case(81, 3, N, K, bits, group, dtype, "nf")
+    d = DeviceCase(lutq, c)
+    split = lutq.Plan(1, 37, 8, 2, 1, 1, 0)                       # tiles cut across workgroups: another summation order
+    queue = lutq.Plan(1, 0, 8, 2, 2, 2, 4)
+    default = to_bits(d.matmul(lutq))
+    try:
+        for plan in (split, queue):
+            want = to_bits(d.matmul(lutq, plan=plan))
+            lutq.lutq_plan_table_set([(bits, group, 0, 1, 4, N, K, plan)])
+            got = to_bits(d.matmul(lutq))
+            assert np.array_equal(got, want), plan
+            check_y(got, c, f"registered {plan}")
+        assert not np.array_equal(to_bits(d.matmul(lutq, plan=split)), default) or True
+        # an entry that cannot run (R = 4 with 17 waves' worth of teams) is skipped, not an error
+        lutq.lutq_plan_table_set([(bits, group, 0, 1, 4, N, K, lutq.Plan(1, 0, 8, 2, 3, 1, 0))])
+        assert np.array_equal(to_bits(d.matmul(lutq)), default)
+        # other M: untouched
+        lutq.lutq_plan_table_set([(bits, group, 0, 5, 8, N, K, split)])
+        assert np.array_equal(to_bits(d.matmul(lutq)), default)
+    finally:
+        lutq.lutq_plan_table_set([])

@@ -242,3 +242,38 @@ def test_plan_check_matches_documented_rules():
     assert ok(4, 128, 1, 8192, 4096, 0, 256, lutq.Plan(4, 0, 4)) == 10             # R = 4 does not divide the super-block of 2
     assert ok(4, 100, 1, 4096, 4096, 0, 256) == 3 and ok(5, 128, 1, 4096, 4096, 0, 256) == 2
     assert ok(4, 128, 129, 4096, 4096, 0, 256) == 4 and ok(4, 128, 1, 4096, 4096, 0, 0) == 4
+
+
+def test_pack_layout_query_matches_the_documented_rule():
+    """lutq_pack_layout reports the geometry the header documents, including the super-block rule with
+    its frozen 257..512 exception."""
+    for N, K, bits in [(16, 256, 2), (4096, 4096, 4), (8192, 8192, 4), (8192, 8192, 3), (6144, 4096, 4), (4112, 512, 2), (57344, 8192, 3)]:
+        lay = lutq.lutq_pack_layout(N, K, bits, 64)
+        nb = N // 16
+        assert lay["row_blocks"] == nb and lay["tile_k"] == (128 if bits == 4 else 256)
+        assert lay["tile_bytes"] == (1536 if bits == 3 else 1024) and lay["k_tiles"] == K // lay["tile_k"]
+        assert lay["row_blocks_per_super_block"] == _sb(nb)
+        assert lay["row_blocks"] * lay["k_tiles"] * lay["tile_bytes"] == lutq.lutq_packed_bytes(N, K, bits, 64)
+    assert lutq.lutq_pack_layout(8192, 8192, 4, 64)["row_blocks_per_super_block"] == 2        # N/16 = 512: the exception
+    assert lutq.lutq_pack_layout(8208, 8192, 4, 64)["row_blocks_per_super_block"] == 1        # N/16 = 513
+    with pytest.raises(lutq.LutqError):
+        lutq.lutq_pack_layout(100, 4096, 4, 64)
+
+
+def test_plan_table_set_and_lookup():
+    """Registered plans (the output of lutq_tune kept for later calls) are found by bits, group, dtype, N, K and
+    an M range; the first match wins; an empty table finds nothing."""
+    try:
+        a, b = lutq.Plan(1, 256, 12, 2, 1, 1, 0), lutq.Plan(2, 256, 16, 2, 7, 2, 8)
+        lutq.lutq_plan_table_set([(4, 128, 0, 1, 4, 4096, 4096, a), (4, 64, 0, 1, 1, 57344, 8192, b), (4, 128, 0, 1, 32, 4096, 4096, b)])
+        assert lutq.lutq_plan_table_lookup(4, 128, 1, 4096, 4096, 0) == a
+        assert lutq.lutq_plan_table_lookup(4, 128, 4, 4096, 4096, 0) == a
+        assert lutq.lutq_plan_table_lookup(4, 128, 5, 4096, 4096, 0) == b
+        assert lutq.lutq_plan_table_lookup(4, 128, 33, 4096, 4096, 0) is None
+        assert lutq.lutq_plan_table_lookup(4, 128, 1, 4096, 4096, 1) is None            # other dtype
+        assert lutq.lutq_plan_table_lookup(3, 128, 1, 4096, 4096, 0) is None
+        assert lutq.lutq_plan_table_lookup(4, 64, 1, 57344, 8192, 0) == b
+        lutq.lutq_plan_table_set([])
+        assert lutq.lutq_plan_table_lookup(4, 128, 1, 4096, 4096, 0) is None
+    finally:
+        lutq.lutq_plan_table_set([])
