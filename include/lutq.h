@@ -150,11 +150,14 @@ typedef struct {
     int scheduling;           /* how a workgroup's work is dealt to its wavefronts: 0 = library chooses,
                                  LUTQ_SCHED_TEAMS (1) = the static teams described above,
                                  LUTQ_SCHED_QUEUE (2) = a work queue (M <= 4 and K / group_size a multiple of 8
-                                 only): the workgroup owns row_groups_per_workgroup (1..64) row groups over the
-                                 whole of K, cut into items of tiles_per_item K tiles that its wavefronts take
-                                 one after the other from a counter; grid is then N / (16 R) /
-                                 row_groups_per_workgroup (0 or exactly that), R is 1 or 2, waves_per_workgroup
-                                 4..16 with no relation to the row groups, tiles_in_flight 2 */
+                                 only): a workgroup owns whole row groups over the whole of K, cut into items of
+                                 tiles_per_item K tiles that its wavefronts take one after the other from a
+                                 counter.  The N / (16 R) row groups are dealt to `grid` workgroups as evenly
+                                 as whole row groups allow: row_groups_per_workgroup (1..64) = the whole part of
+                                 row groups / grid, the first workgroups one more.  Give grid (then
+                                 row_groups_per_workgroup is 0 or that quotient) or row_groups_per_workgroup
+                                 (a divisor of the row groups); R is 1 or 2, waves_per_workgroup 4..16 with
+                                 no relation to the row groups, tiles_in_flight 2 */
     int tiles_per_item;       /* LUTQ_SCHED_QUEUE: K tiles (128 columns at 4 bits, 256 at 2 and 3) per item:
                                  0, or a multiple of tiles_in_flight that divides the K tiles of a row */
 } lutq_plan;

@@ -108,23 +108,33 @@ int queue_lds_bytes(int bits, int nw, int items, int r) {
 bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K, int cus, bool only_if_preferred, Decomp* out) {
     if (M > 4 || !sch) return false;
     const int64_t nb = N / 16, kt = K / tile_k(bits);
-    if (nb % cus != 0) return false;
-    const int64_t per = nb / cus;                      // row blocks per workgroup
-    if (only_if_preferred && !(per >= 8 || (per == 2 && bits == 4 && M <= 2 && K >= 16384))) return false;
+    const int64_t per = nb / cus;                      // row blocks per workgroup (the first nb % cus get one more)
+    const bool even = nb % cus == 0;
+    if (per < 1 || per >= 64) return false;
+    // Row blocks that do not divide over the compute units (4-bit, M <= 2; measured against the team plans,
+    // which then cut every tile across two workgroups or leave compute units idle): 2.5 per compute unit
+    // (70B QKV: 12.2 -> 11.4 us, bf16 13.3 -> 12.6) and more than four (LLaMA-2-7B gate+up, 5.4 per compute
+    // unit: 12.0 -> 11.1 us; 13B gate+up, 6.75: 15.3 us either way).  With 1.5 (8B QKV) or 3.75 (13B QKV) per
+    // compute unit, at 3 bits and at M = 4 the team plans are as fast or faster.
+    const bool uneven_preferred = bits == 4 && M <= 2 && ((nb * 2) % cus == 0 ? per >= 2 : per >= 4);
+    // One row block per compute unit with a short K (4-bit, at most eight items of four tiles: 8B O 4.52 -> 4.38
+    // us at M = 1, 4.72 -> 4.57 at M = 4): one item per wave, so the queue is never used, but the short set-up
+    // of this kernel shows.  A longer K (8B down) is faster with the teams' even static split.
+    const bool short_k = even && per == 1 && bits == 4 && kt % 4 == 0 && kt / 4 <= 8;
+    if (only_if_preferred && !(even ? (per >= 8 || short_k || (per == 2 && bits == 4 && M <= 2 && K >= 16384)) : uneven_preferred)) return false;
     const int sb = super_block(nb);
     // two row blocks per wave halve the activation and scale-chunk loads per weight; 3-bit tiles (two
     // bit-slices) run faster one at a time, and two row blocks per compute unit make more items as R = 1
-    const int r = (per >= 4 && bits != 3 && per % 2 == 0 && sb % 2 == 0 && decode_instance_exists(bits, bf16, 2)) ? 2 : 1;
-    const int64_t a = per / r;
-    if (a > 64) return false;
-    // items: at least two tiles (the pipeline depth); as many tiles as still leave every wave about
-    // four items, so that an item's fold and hand-over stay a small part of its work
+    const int r = (even && per >= 4 && bits != 3 && per % 2 == 0 && sb % 2 == 0 && decode_instance_exists(bits, bf16, 2)) ? 2 : 1;
+    const int64_t a = per / r, amax = a + (even ? 0 : 1);
+    // items: at least two tiles (the pipeline depth); four where K allows, eight when that still leaves
+    // every wave about four items, so that an item's fold and hand-over stay a small part of its work
     int it = kt % 4 == 0 ? 4 : 2;
     if (kt % 8 == 0 && a * (kt / 8) >= 64) it = 8;
     if (kt % it != 0) return false;
-    int64_t items = a * (kt / it);
-    while (queue_lds_bytes(bits, 16, (int)items, r) > 160 * 1024 && kt % (it * 2) == 0) { it *= 2; items = a * (kt / it); }
-    int nw = items >= 16 ? 16 : (int)(items < 4 ? 4 : items);
+    int64_t items = amax * (kt / it);
+    while (queue_lds_bytes(bits, 16, (int)items, r) > 160 * 1024 && kt % (it * 2) == 0) { it *= 2; items = amax * (kt / it); }
+    int nw = items >= 16 ? (amax <= 3 && !even ? 12 : 16) : (int)(items < 4 ? 4 : items);
     if (queue_lds_bytes(bits, nw, (int)items, r) > 160 * 1024) return false;
     out->r = r; out->grid = cus; out->nw = nw; out->stages = 2; out->rs = (int)a; out->queue = 1; out->it = it;
     return true;
@@ -581,10 +591,14 @@ lutq_status prepare_queue(const void* X, const void* packed, const void* scales,
     if (M > 4 || (K / group_size) % 8 != 0) return LUTQ_ERR_PLAN;
     if (!decode_instance_exists(bits, bf16, d.r) || super_block(nb) % d.r != 0) return LUTQ_ERR_PLAN;
     const int64_t nrg = nb / d.r;
-    if (d.rs < 1 || d.rs > 64 || nrg % d.rs != 0 || d.grid != nrg / d.rs) return LUTQ_ERR_PLAN;
+    // the row groups are dealt to the workgroups as evenly as whole row groups allow: rs each, one more
+    // in the first nrg - rs * grid workgroups
+    if (d.grid < 1 || d.grid > kMaxGrid || d.rs < 1 || d.rs > 64 || d.rs != nrg / d.grid) return LUTQ_ERR_PLAN;
+    const int extra = (int)(nrg - (int64_t)d.rs * d.grid);
     if (d.nw < 4 || d.nw > 16 || d.stages != 2) return LUTQ_ERR_PLAN;
     if (d.it < d.stages || d.it % d.stages != 0 || kt % d.it != 0) return LUTQ_ERR_PLAN;
-    const int64_t items = (int64_t)d.rs * (kt / d.it);
+    const int amax = d.rs + (extra ? 1 : 0);
+    const int64_t items = (int64_t)amax * (kt / d.it);
     if (items > 4096) return LUTQ_ERR_PLAN;
     const int lds = queue_lds_bytes(bits, d.nw, (int)items, d.r);
     if (lds > 160 * 1024) return LUTQ_ERR_PLAN;
@@ -603,20 +617,22 @@ lutq_status prepare_queue(const void* X, const void* packed, const void* scales,
     const uint32_t tile_bytes = bits == 3 ? 1536u : 1024u;
     q.tile_stride = tile_bytes << q.SBL;
     q.sblock_bytes = (uint32_t)kt * q.tile_stride;
-    q.A = d.rs; q.C = (int)(kt / d.it); q.IT = d.it; q.NW = d.nw;
+    q.A = d.rs; q.extra = extra; q.C = (int)(kt / d.it); q.IT = d.it; q.NW = d.nw; q.G = d.grid;
     q.a_magic = q.A == 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)q.A);
+    q.a1_magic = (uint32_t)((1ull << 32) / (uint64_t)(q.A + 1));
     q.lut_ltpe = bits == 2 ? lut_log2_threads_per_row<2>(d.nw * 64)
                : bits == 3 ? lut_log2_threads_per_row<3>(d.nw * 64) : lut_log2_threads_per_row<4>(d.nw * 64);
     q.slot_off = bits == 2 ? decode_slot_off<2>(d.nw) : bits == 3 ? decode_slot_off<3>(d.nw) : decode_slot_off<4>(d.nw);
     // final reduction: as many groups of items per output as there are threads for them (the group sums
     // are parked in the table's area: at most 4 KiB)
-    const int outputs = q.A * d.r * 64;
-    int ng = (d.nw * 64) / outputs;
-    if (ng > (q.C + 3) / 4) ng = (q.C + 3) / 4;           // groups of four items or more: fewer are not worth a barrier
+    const int outputs = q.A * d.r * 64, outputs_max = amax * d.r * 64;
+    int ng = (d.nw * 64) / outputs_max;
+    if (ng > q.C / 8) ng = q.C / 8;                       // groups of eight items or more: fewer are not worth a barrier
     if (ng < 1) ng = 1;
     q.GL = (q.C + ng - 1) / ng;
     q.NG = (q.C + q.GL - 1) / q.GL;
     q.o_magic = (uint32_t)((1ull << 32) / (uint64_t)outputs);
+    q.o1_magic = (uint32_t)((1ull << 32) / (uint64_t)(outputs + d.r * 64));
     q.trace = nullptr;
     if (env_switches().verbose)
         std::fprintf(stderr, "lutq_matmul: work queue R=%d grid=%d waves=%d row groups per workgroup=%d tiles per item=%d items=%d lds=%d\n",
@@ -698,11 +714,20 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
             }
             if (user_plan->row_blocks_per_wave) q.r = user_plan->row_blocks_per_wave;
             if (q.r != 1 && q.r != 2) return LUTQ_ERR_PLAN;
-            if (user_plan->row_groups_per_workgroup) q.rs = user_plan->row_groups_per_workgroup;
-            else if (user_plan->row_blocks_per_wave && have_default) q.rs = (int)(nb / di.cus / q.r);
-            if (q.rs < 1 || nb % ((int64_t)q.r * q.rs) != 0) return LUTQ_ERR_PLAN;
-            q.grid = (int)(nb / q.r / q.rs);
-            if (user_plan->grid && user_plan->grid != q.grid) return LUTQ_ERR_PLAN;
+            if (nb % q.r != 0) return LUTQ_ERR_PLAN;
+            const int64_t nrg = nb / q.r;
+            // grid and row groups per workgroup: either fixes the other (row groups per workgroup = the
+            // whole part of row groups / grid; a grid derived from them has to come out even)
+            if (user_plan->grid) {
+                q.grid = user_plan->grid;
+                q.rs = (int)(nrg / q.grid);
+                if (user_plan->row_groups_per_workgroup && user_plan->row_groups_per_workgroup != q.rs) return LUTQ_ERR_PLAN;
+            } else {
+                if (user_plan->row_groups_per_workgroup) q.rs = user_plan->row_groups_per_workgroup;
+                else if (user_plan->row_blocks_per_wave && have_default) q.rs = (int)(nrg / di.cus);
+                if (q.rs < 1 || nrg % q.rs != 0) return LUTQ_ERR_PLAN;
+                q.grid = (int)(nrg / q.rs);
+            }
             if (user_plan->waves_per_workgroup) q.nw = user_plan->waves_per_workgroup;
             if (user_plan->tiles_in_flight) q.stages = user_plan->tiles_in_flight;
             if (user_plan->tiles_per_item) q.it = user_plan->tiles_per_item;
@@ -946,7 +971,7 @@ extern "C" int lutq_calib_matmul_trace(const void* X, const void* packed, const 
     if (st != LUTQ_OK) return st;
     if (q.queue) {
         if (bits != 4 || (group_size != 64 && group_size != 128)) return LUTQ_ERR_PLAN;
-        const int groups = (int)((N / 16) / (q.r * q.dp.A));
+        const int groups = q.dp.G;
         if (trace_bytes < (size_t)groups * kTraceWaves * kTraceStamps * sizeof(unsigned long long) || (reinterpret_cast<uintptr_t>(trace) & 7u))
             return LUTQ_ERR_WORKSPACE;
         q.dp.trace = static_cast<unsigned long long*>(trace);
@@ -989,6 +1014,13 @@ std::vector<lutq_plan> tune_candidates(int bits, int group_size, int64_t M, int6
     if (lutq_plan_default(bits, group_size, M, N, K, dtype, &def) == LUTQ_OK) out.push_back(def);
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     if (M <= 4 && (K / group_size) % 8 == 0) {
+        // work-queue plans with uneven shares: one workgroup per compute unit (or per two), R = 1
+        if (nb % cus != 0 && nb > cus)
+            for (int g : {cus, cus / 2})
+                if (g >= 1 && nb / g <= 64)
+                    for (int nw : {8, 12, 16})
+                        for (int it : {2, 4, 8})
+                            if (kt % it == 0) push_unique(lutq_plan{1, g, nw, 2, (int)(nb / g), LUTQ_SCHED_QUEUE, it});
         // work-queue plans: row blocks per workgroup = every divisor of N/16 that leaves between half a
         // workgroup and four per compute unit, as R = 1 or 2, 8 to 16 waves, items of 2, 4, 8 tiles
         for (int64_t per = 1; per <= 64; ++per) {

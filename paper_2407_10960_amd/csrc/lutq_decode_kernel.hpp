@@ -6,7 +6,9 @@
 // concern, here inside a workgroup instead of across them):
 //
 //   * A workgroup owns A consecutive row groups (a row group = R 16-row blocks) over the whole of K and
-//     nothing else, so no partial sum ever leaves it (no cross-workgroup fix-up).
+//     nothing else, so no partial sum ever leaves it (no cross-workgroup fix-up).  Where the row groups
+//     do not divide over the workgroups the first `extra` workgroups own A + 1: better a few compute
+//     units with one more row group than every output tile cut in two and put together again.
 //   * Its work is cut into items: (row group a, IT consecutive K tiles).  Wave w starts with item w;
 //     whenever a wave finishes an item it takes the next one from a counter in LDS.  A wave that the
 //     hardware favours (the issue arbiter serves old waves first, and 14 waves do not divide over 4
@@ -42,15 +44,19 @@ struct DecodeParams {
     int SBL;                  // log2 of the row blocks per super-block of the packed layout (R divides it)
     uint32_t tile_stride;     // packed bytes from K tile kt to kt + 1 of one row block (tile bytes << SBL)
     uint32_t sblock_bytes;    // packed bytes of one super-block
-    int A;                    // row groups per workgroup
+    int A;                    // row groups per workgroup ...
+    int extra;                // ... plus one more in workgroups 0 .. extra - 1
     int C;                    // items per row group (K tiles per row block = C * IT)
     int IT;                   // K tiles per item, a multiple of the pipeline depth
     int NW;                   // waves per workgroup
+    int G;                    // workgroups
     uint32_t a_magic;         // floor(2^32 / A) (0xffffffff for A = 1), see div_magic
+    uint32_t a1_magic;        // the same for A + 1
     int lut_ltpe;             // log2 of the threads that build one table row together
     int slot_off;             // LDS byte offset of the item slots
     int NG, GL;               // final reduction: NG groups of GL consecutive items per output (NG * GL >= C)
     uint32_t o_magic;         // floor(2^32 / (A * R * 64))
+    uint32_t o1_magic;        // floor(2^32 / ((A + 1) * R * 64))
     unsigned long long* trace;   // TRACE instances only
 };
 
@@ -96,7 +102,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.packed_bytes), "s"(p.scale_bytes),
                  "s"(p.x_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.SG2), "s"(p.SBL), "s"(p.tile_stride), "s"(p.sblock_bytes),
                  "s"(p.A), "s"(p.C), "s"(p.IT), "s"(p.NW), "s"(p.a_magic), "s"(p.lut_ltpe), "s"(p.slot_off), "s"(p.NG), "s"(p.GL),
-                 "s"(p.o_magic));
+                 "s"(p.o_magic), "s"(p.extra), "s"(p.a1_magic), "s"(p.o1_magic));
     stamp(kTraceArgs);
 
     extern __shared__ __align__(16) char smem[];
@@ -123,8 +129,11 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     const uint32_t wlane = 16u * lane;
     // scale chunks: lane l < 16 R fetches 16 bytes of row l of the row group
     const uint32_t clane = lane < 16 * R ? (uint32_t)lane * (uint32_t)p.SG2 : kOutOfRange;
-    const int nitems = p.A * p.C;
-    const int rg0 = (int)blockIdx.x * p.A;             // first row group of this workgroup
+    const bool big = (int)blockIdx.x < p.extra;        // this workgroup owns one row group more
+    const int A = p.A + (big ? 1 : 0);
+    const uint32_t a_magic = big ? p.a1_magic : p.a_magic;
+    const int nitems = A * p.C;
+    const int rg0 = (int)blockIdx.x * p.A + ((int)blockIdx.x < p.extra ? (int)blockIdx.x : p.extra);   // first row group
 
     // the queue hands out items NW, NW + 1, ...: items 0 .. NW - 1 are the waves' first ones
     if (tid == 0) *queue = (uint32_t)p.NW;
@@ -143,8 +152,8 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     struct Item { uint32_t wbase, sbase, xbase; int kt0; };
     auto locate = [&](int item) -> Item {
         Item it;
-        const int c = div_magic(item, p.a_magic, p.A);    // items are numbered K-major: item = c * A + a
-        const int a = item - c * p.A;
+        const int c = div_magic(item, a_magic, A);        // items are numbered K-major: item = c * A + a
+        const int a = item - c * A;
         const int rb0 = (rg0 + a) * R;
         const bool in = item < nitems;
         it.kt0 = c * p.IT;
@@ -304,11 +313,12 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     // at float o of the slots of items c A + a.  The items of an output are cut into NG groups of GL
     // consecutive ones (both fixed by the launch, not by the timing); thread (g, o) adds group g in K
     // order, then thread o adds the group sums in order: the same tree on every run.
-    const int outputs = p.A * R * 64;
+    const int outputs = A * R * 64;
+    const uint32_t o_magic = big ? p.o1_magic : p.o_magic;
     float* gsum = reinterpret_cast<float*>(lut);        // the table is no longer needed
     if (p.NG > 1) {
         for (int idx = tid; idx < outputs * p.NG; idx += p.NW * 64) {
-            const int g = div_magic(idx, p.o_magic, outputs);
+            const int g = div_magic(idx, o_magic, outputs);
             const int o = idx - g * outputs;
             const int c0 = g * p.GL, c1 = (c0 + p.GL < p.C) ? c0 + p.GL : p.C;
             const float* src = slots + o;

@@ -37,7 +37,7 @@ hipError_t launch_decode_traced(const DecodeParams& p, int lds_bytes, hipStream_
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (attr != hipSuccess) return attr;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)((p.N / 16) / (R * p.A))), dim3(p.NW * 64), lds_bytes, stream, p);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)p.G), dim3(p.NW * 64), lds_bytes, stream, p);
     return hipGetLastError();
 }
 

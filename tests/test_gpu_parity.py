@@ -638,7 +638,9 @@ def test_work_queue_plans_match_oracle(lutq, bits, dtype):
             c = gen.make_case(400 + M, M, N, K, bits, group, dtype, lut)
             d = DeviceCase(lutq, c)
             plans = [lutq.Plan(1, 0, 16, 2, 1, Q, 2), lutq.Plan(1, 0, 4, 2, nb, Q, 4), lutq.Plan(1, 0, 12, 2, nb // 2, Q, 8),
-                     lutq.Plan(1, 0, 7, 2, 1, Q, 4), lutq.Plan(0, 0, 0, 0, 0, Q, 0)]
+                     lutq.Plan(1, 0, 7, 2, 1, Q, 4), lutq.Plan(0, 0, 0, 0, 0, Q, 0),
+                     # row blocks that do not divide over the workgroups: the first ones take one more
+                     lutq.Plan(1, nb - 1, 8, 2, 0, Q, 2), lutq.Plan(1, 3, 16, 2, 0, Q, 4), lutq.Plan(1, (nb + 1) // 2 + 1, 5, 2, 1, Q, 2)]
             if not (bits == 3 and dtype == "bf16"):
                 plans += [lutq.Plan(2, 0, 16, 2, 1, Q, 2), lutq.Plan(2, 0, 9, 2, nb // 2, Q, 4)]
             for plan in plans:
@@ -648,7 +650,8 @@ def test_work_queue_plans_match_oracle(lutq, bits, dtype):
                 check_y(Y1, c, f"b{bits} {dtype} g{group} M{M} N{N} K{K} {plan}")
             # what does not fit the kernel is refused before anything is launched
             for bad in (lutq.Plan(4, 0, 16, 2, 1, Q, 2), lutq.Plan(1, 0, 16, 2, 1, Q, 3), lutq.Plan(1, 0, 16, 2, 5, Q, 2),
-                        lutq.Plan(1, 7, 16, 2, 1, Q, 2), lutq.Plan(1, 0, 17, 2, 1, Q, 2), lutq.Plan(1, 0, 16, 4, 1, Q, 4)):
+                        lutq.Plan(1, 3, 16, 2, nb, Q, 2), lutq.Plan(1, nb + 1, 16, 2, 0, Q, 2), lutq.Plan(1, 0, 17, 2, 1, Q, 2),
+                        lutq.Plan(1, 0, 16, 4, 1, Q, 4)):
                 with pytest.raises(lutq.LutqError) as e:
                     d.matmul(lutq, plan=bad)
                 assert e.value.code == 10, bad
