@@ -158,12 +158,21 @@ typedef struct {
                                  row_groups_per_workgroup is 0 or that quotient) or row_groups_per_workgroup
                                  (a divisor of the row groups); R is 1 or 2, waves_per_workgroup 4..16 with
                                  no relation to the row groups, tiles_in_flight 2 */
+                              /* LUTQ_SCHED_ROWS (3) = activation-stationary (5 <= M <= 32): `grid` workgroups own
+                                 whole 16-row blocks over the whole of K, dealt as evenly as whole row blocks
+                                 allow (row_groups_per_workgroup = the whole part of N / 16 / grid, 0 or that
+                                 value; at most 64); the wavefronts (waves_per_workgroup 4..16, as many as the
+                                 instance's registers allow) split K, hold a K tile's activations in registers
+                                 and stream the weights of row_blocks_per_wave (4 or 8) row blocks past them
+                                 side by side, in as many passes as the workgroup's row blocks need;
+                                 tiles_in_flight 2 */
     int tiles_per_item;       /* LUTQ_SCHED_QUEUE: K tiles (128 columns at 4 bits, 256 at 2 and 3) per item:
                                  0, or a multiple of tiles_in_flight that divides the K tiles of a row */
 } lutq_plan;
 
 #define LUTQ_SCHED_TEAMS 1
 #define LUTQ_SCHED_QUEUE 2
+#define LUTQ_SCHED_ROWS 3
 
 /* Fills *plan with the library's choice for this problem on the current device. */
 lutq_status lutq_plan_default(int bits, int group_size, int64_t M, int64_t N, int64_t K,

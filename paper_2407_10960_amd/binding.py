@@ -51,7 +51,8 @@ class Plan:
     waves_per_workgroup: int = 0
     tiles_in_flight: int = 0
     row_groups_per_workgroup: int = 0
-    scheduling: int = 0           # 0 library chooses, 1 static teams, 2 work queue (M <= 4)
+    scheduling: int = 0           # 0 library chooses, 1 static teams, 2 work queue (M <= 4), 3 row streaming
+                                  # (row_blocks_per_wave = 4 or 8 row blocks side by side, whole row blocks per workgroup)
     tiles_per_item: int = 0
 
     def _c(self) -> _CPlan:

@@ -87,7 +87,66 @@ struct Decomp {
     int r, grid, nw, stages, rs;      // the first five plan fields, all chosen
     int queue = 0;                    // work-queue kernel (M <= 4): rs = row groups per workgroup, it = tiles per item
     int it = 0;
+    int rows = 0;                     // row-streaming kernel: r = row blocks side by side, rs = row blocks per workgroup
 };
+
+int rows_table_bytes(int bits) { return bits == 2 ? lut_row_table_bytes<2>() : bits == 3 ? lut_row_table_bytes<3>() : lut_row_table_bytes<4>(); }
+// waves the row-streaming instance (bits, dtype, M half count, row blocks side by side) is compiled for; 0 = none
+int rows_instance_waves(int bits, bool bf16, int mb, int amax) {
+    const bool wide = bf16 ? (bits == 2 ? Tab<2, BF16>::WIDE : bits == 3 ? Tab<3, BF16>::WIDE : Tab<4, BF16>::WIDE)
+                           : (bits == 2 ? Tab<2, F16>::WIDE : bits == 3 ? Tab<3, F16>::WIDE : Tab<4, F16>::WIDE);
+    return (amax == 4 || amax == 8) ? rows_max_waves(bits, mb, amax, wide) : 0;
+}
+
+// Row-streaming decomposition (rows_kernel): one workgroup per compute unit (per row block where there
+// are fewer), whole row blocks each, eight row blocks side by side where the instance exists, as many
+// waves as it was compiled for (no more than K tiles).
+// LDS offset of the row-streaming kernel's reduction slots (behind the table and the scales of `side` row
+// blocks), and how many row blocks one round of the reduction can hold (0: the launch does not fit)
+int rows_red_off(int bits, int side, int sg2) { return rows_table_bytes(bits) + side * 16 * (sg2 + 16); }
+int rows_blocks_per_round(int bits, int side, int sg2, int mb, int nw) {
+    const int room = 160 * 1024 - rows_red_off(bits, side, sg2);
+    return room <= 0 ? 0 : room / (mb * nw * 1024);
+}
+
+bool rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int group_size, int cus, Decomp* out) {
+    const int64_t nb = N / 16, kt = K / tile_k(bits);
+    const int mb = M > 16 ? 2 : 1;
+    const int grid = (int)(nb < cus ? nb : cus);
+    const int64_t per = nb / grid;
+    if (per > 64) return false;
+    int amax = per + (nb % grid ? 1 : 0) > 4 ? 8 : 4;
+    int nw = rows_instance_waves(bits, bf16, mb, amax);
+    if (nw == 0) { amax = 4; nw = rows_instance_waves(bits, bf16, mb, amax); }
+    if (nw == 0) return false;
+    if (nw > kt) nw = (int)(kt < 4 ? 4 : kt);
+    if (rows_blocks_per_round(bits, amax, (int)(K / group_size) * 2, mb, nw) < 1) return false;
+    out->r = amax; out->grid = grid; out->nw = nw; out->stages = 2; out->rs = (int)per; out->queue = 0; out->it = 0; out->rows = 1;
+    return true;
+}
+
+// Where the row-streaming kernel is the default (M >= 5).  Measured against the team plans on the gate+up and
+// QKV shapes of LLaMA-2-7B/13B and LLaMA-3-8B/70B, M = 8, 16, 24, 32, fp16 and bf16, MI355X:
+//   * 4 bits, five to eight row blocks per compute unit (one pass), M > 8: 3-10 % faster where the row blocks
+//     do not divide over the compute units (7B gate+up M = 16: 15.8 -> 14.2 us, bf16 18.1 -> 16.3; 13B: 20.5 ->
+//     18.9); where they do (8B gate+up) 1-4 % in bf16 (M = 16: 18.4 -> 17.8 us) and within the noise of either
+//     in fp16, which stays with the teams.  With more (70B gate+up, fourteen: two passes, each with its own
+//     ramp and reduction) the teams are faster, and at M <= 8 they are as fast.
+//   * 3 bits, the same shapes, 8 < M <= 16: 6-19 % (13B gate+up 20.5 -> 17.8 us, bf16 24.3 -> 19.7).
+//   * 4 bits, two to four row blocks per compute unit that do not divide (QKV shapes), M <= 16, bf16 M <= 24:
+//     70B QKV M = 8 14.2 -> 13.3 us, M = 16 17.5 -> 16.2, bf16 M = 24 23.2 -> 20.4; beyond that the teams win.
+bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int group_size, int cus, Decomp* out) {
+    if (M < 5 || ((K / group_size) * 2) % 16 != 0) return false;
+    const int64_t nb = N / 16;
+    if (nb < cus) return false;
+    const int64_t per = nb / cus;
+    const bool uneven = nb % cus != 0;
+    const int64_t amax = per + (uneven ? 1 : 0);
+    bool take = false;
+    if (bits == 4) take = (per >= 5 && amax <= 8 && M > 8 && (uneven || bf16)) || (uneven && per >= 2 && amax <= 4 && M <= (bf16 ? 24 : 16));
+    else if (bits == 3) take = per >= 5 && amax <= 8 && M > 8 && M <= 16;
+    return take && rows_decomp(bits, bf16, M, N, K, group_size, cus, out);
+}
 
 // LDS bytes of a work-queue launch
 int queue_lds_bytes(int bits, int nw, int items, int r) {
@@ -472,6 +531,11 @@ decode_launcher pick_decode(int bits, lutq_dtype dt) {
     if (dt == LUTQ_F16) return bits == 2 ? launch_decode_b2_F16 : bits == 3 ? launch_decode_b3_F16 : launch_decode_b4_F16;
     return bits == 2 ? launch_decode_b2_BF16 : bits == 3 ? launch_decode_b3_BF16 : launch_decode_b4_BF16;
 }
+typedef hipError_t (*rows_launcher)(int, int, int, const RowsParams&, int, hipStream_t);
+rows_launcher pick_rows(int bits, lutq_dtype dt) {
+    if (dt == LUTQ_F16) return bits == 2 ? launch_rows_b2_F16 : bits == 3 ? launch_rows_b3_F16 : launch_rows_b4_F16;
+    return bits == 2 ? launch_rows_b2_BF16 : bits == 3 ? launch_rows_b3_BF16 : launch_rows_b4_BF16;
+}
 dequant_launcher pick_dequant(int bits, lutq_dtype dt) {
     if (dt == LUTQ_F16) return bits == 2 ? launch_dequant_b2_F16 : bits == 3 ? launch_dequant_b3_F16 : launch_dequant_b4_F16;
     return bits == 2 ? launch_dequant_b2_BF16 : bits == 3 ? launch_dequant_b3_BF16 : launch_dequant_b4_BF16;
@@ -512,14 +576,15 @@ extern "C" lutq_status lutq_plan_default_for(int bits, int group_size, int64_t M
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
     const bool sch = (K / group_size) % 8 == 0;
     Decomp d;
-    if (!default_queue_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, &d))
+    if (!default_queue_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, &d) &&
+        !default_rows_decomp(bits, dtype == LUTQ_BF16, M, N, K, group_size, compute_units, &d))
         d = default_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, 0);
     plan->row_blocks_per_wave = d.r;
     plan->grid = d.grid;
     plan->waves_per_workgroup = d.nw;
     plan->tiles_in_flight = d.stages;
     plan->row_groups_per_workgroup = d.rs;
-    plan->scheduling = d.queue ? LUTQ_SCHED_QUEUE : LUTQ_SCHED_TEAMS;
+    plan->scheduling = d.rows ? LUTQ_SCHED_ROWS : d.queue ? LUTQ_SCHED_QUEUE : LUTQ_SCHED_TEAMS;
     plan->tiles_per_item = d.it;
     return LUTQ_OK;
 }
@@ -581,7 +646,68 @@ struct Prepared {
     bool queue;               // work-queue kernel: dp and queue_lds instead of p
     DecodeParams dp;
     int queue_lds;
+    bool rows;                // row-streaming kernel: rp, rows_lds, r = row blocks side by side
+    RowsParams rp;
+    int rows_lds;
 };
+
+// Validates a row-streaming launch and fills out->rp.  `d`: r = row blocks side by side (4 or 8), grid,
+// nw, rs = row blocks per workgroup (the whole part of row blocks / grid).
+lutq_status prepare_rows(const void* X, const void* packed, const void* scales, const void* lut, int bits,
+                         int group_size, int64_t M, int64_t N, int64_t K, bool bf16, void* Y, const Decomp& d, Prepared* out) {
+    const int64_t nb = N / 16, kt = K / tile_k(bits);
+    const int mb = M > 16 ? 2 : 1;
+    const int max_waves = rows_instance_waves(bits, bf16, mb, d.r);
+    if (max_waves == 0 || d.nw < 4 || d.nw > max_waves || d.stages != 2) return LUTQ_ERR_PLAN;
+    if (d.grid < 1 || d.grid > kMaxGrid || d.grid > nb || d.rs < 1 || d.rs > 64 || d.rs != nb / d.grid) return LUTQ_ERR_PLAN;
+    const int extra = (int)(nb - (int64_t)d.rs * d.grid);
+    const int amax = d.rs + (extra ? 1 : 0);
+    // the scales of a pass's row blocks are staged in LDS in 16-byte units
+    const int sg2 = (int)(K / group_size) * 2;
+    if (sg2 % 16 != 0) return LUTQ_ERR_PLAN;
+    const int srow = sg2 + 16;
+    const int red_off = rows_red_off(bits, d.r, sg2);
+    // rounds of the final reduction: as many row blocks at a time as LDS holds beside the table and the scales
+    int rpr = rows_blocks_per_round(bits, d.r, sg2, mb, d.nw);
+    if (rpr > d.r) rpr = d.r;
+    if (rpr > amax) rpr = amax;
+    if (rpr < 1) return LUTQ_ERR_PLAN;
+    const int lds = red_off + rpr * mb * d.nw * 1024;
+    RowsParams q{};
+    q.X = static_cast<const uint16_t*>(X);
+    q.packed = static_cast<const uint8_t*>(packed);
+    q.scales = static_cast<const uint16_t*>(scales);
+    q.lut = static_cast<const uint16_t*>(lut);
+    q.Y = static_cast<uint16_t*>(Y);
+    q.packed_bytes = (uint32_t)(N * K * bits / 8);
+    q.scale_bytes = (uint32_t)(N * (K / group_size) * 2);
+    q.x_bytes = (uint32_t)(M * K * 2);
+    q.M = (int)M; q.N = (int)N; q.K = (int)K; q.KT = (int)kt;
+    q.SG2 = (int)(K / group_size) * 2;
+    q.SBL = ilog2(super_block(nb));
+    const uint32_t tile_bytes = bits == 3 ? 1536u : 1024u;
+    q.tile_stride = tile_bytes << q.SBL;
+    q.sblock_bytes = (uint32_t)kt * q.tile_stride;
+    q.A = d.rs; q.extra = extra; q.NW = d.nw; q.G = d.grid;
+    q.TQ = (int)(kt / d.nw); q.TR = (int)(kt % d.nw);
+    q.RPR = rpr;
+    q.s_units = sg2 / 16;
+    q.s_magic = (uint32_t)((1ull << 32) / (uint64_t)q.s_units + 1);
+    q.SROW = srow;
+    q.red_off = red_off;
+    q.lut_ltpe = bits == 2 ? lut_log2_threads_per_row<2>(d.nw * 64)
+               : bits == 3 ? lut_log2_threads_per_row<3>(d.nw * 64) : lut_log2_threads_per_row<4>(d.nw * 64);
+    if (env_switches().verbose)
+        std::fprintf(stderr, "lutq_matmul: row streaming, %d row blocks side by side, grid=%d waves=%d row blocks per workgroup=%d (+1 in %d) reduce %d per round lds=%d\n",
+                     d.r, d.grid, d.nw, d.rs, extra, rpr, lds);
+    out->queue = false;
+    out->rows = true;
+    out->rp = q;
+    out->rows_lds = lds;
+    out->r = d.r;
+    out->mb = mb;
+    return LUTQ_OK;
+}
 
 // Validates a work-queue launch (M <= 4) and fills out->dp.  `d` holds the decomposition: r, rs = row
 // groups per workgroup, nw, stages, it.
@@ -689,13 +815,16 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     if (user_plan) {
         const int w = user_plan->waves_per_workgroup, f = user_plan->tiles_in_flight;
         const int t = user_plan->row_groups_per_workgroup;
-        if ((w != 0 && (w < 4 || w > 16)) || (f != 0 && f != 2 && f != 4) || t < 0 || t > 16) return LUTQ_ERR_PLAN;
+        const bool teams = user_plan->scheduling == 0 || user_plan->scheduling == LUTQ_SCHED_TEAMS;
+        if ((w != 0 && (w < 4 || w > 16)) || (f != 0 && f != 2 && f != 4) || t < 0 || t > (teams ? 16 : 64)) return LUTQ_ERR_PLAN;
         force_r = user_plan->row_blocks_per_wave;
-        if (force_r != 0 && ((force_r != 1 && force_r != 2 && force_r != 4) || super_block(nb) % force_r != 0))
+        if (teams && force_r != 0 && ((force_r != 1 && force_r != 2 && force_r != 4) || super_block(nb) % force_r != 0))
             return LUTQ_ERR_PLAN;
         if (user_plan->grid != 0 && (user_plan->grid < 1 || user_plan->grid > kMaxGrid)) return LUTQ_ERR_PLAN;
     }
     out->queue = false;
+    out->rows = false;
+    if (rowlut && user_plan && user_plan->scheduling > LUTQ_SCHED_TEAMS) return LUTQ_ERR_PLAN;
     if (!rowlut) {
         // the work-queue kernel: asked for by the plan, or the default for M <= 4 where it applies
         // (an explicit plan without a scheduling field keeps meaning the static teams it describes)
@@ -703,8 +832,29 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
                                                   user_plan->waves_per_workgroup == 0 && user_plan->tiles_in_flight == 0 &&
                                                   user_plan->row_groups_per_workgroup == 0 && user_plan->tiles_per_item == 0);
         const int sched = user_plan ? user_plan->scheduling : 0;
-        if (sched < 0 || sched > LUTQ_SCHED_QUEUE) return LUTQ_ERR_PLAN;
+        if (sched < 0 || sched > LUTQ_SCHED_ROWS) return LUTQ_ERR_PLAN;
         Decomp q;
+        if (sched == LUTQ_SCHED_ROWS) {
+            if (user_plan->tiles_per_item != 0) return LUTQ_ERR_PLAN;
+            const bool have_default = rows_decomp(bits, bf16, M, N, K, group_size, di.cus, &q);
+            if (!have_default) { q.r = 4; q.grid = (int)(nb < di.cus ? nb : di.cus); q.nw = 8; q.stages = 2; }
+            if (user_plan->row_blocks_per_wave) {
+                q.r = user_plan->row_blocks_per_wave;
+                const int w = rows_instance_waves(bits, bf16, mb, q.r);
+                if (!user_plan->waves_per_workgroup && w) q.nw = (int)(w > kt ? (kt < 4 ? 4 : kt) : w);
+            }
+            if (user_plan->grid) q.grid = user_plan->grid;
+            else if (user_plan->row_groups_per_workgroup) {
+                if (nb % user_plan->row_groups_per_workgroup != 0) return LUTQ_ERR_PLAN;
+                q.grid = (int)(nb / user_plan->row_groups_per_workgroup);
+            }
+            if (q.grid < 1 || q.grid > nb) return LUTQ_ERR_PLAN;
+            q.rs = (int)(nb / q.grid);
+            if (user_plan->row_groups_per_workgroup && user_plan->row_groups_per_workgroup != q.rs) return LUTQ_ERR_PLAN;
+            if (user_plan->waves_per_workgroup) q.nw = user_plan->waves_per_workgroup;
+            if (user_plan->tiles_in_flight) q.stages = user_plan->tiles_in_flight;
+            return prepare_rows(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out);
+        }
         if (sched == LUTQ_SCHED_QUEUE) {
             // the fields the plan leaves open: one workgroup per compute unit where the row blocks divide
             // evenly, else one workgroup of 16 waves per row block with items of two tiles
@@ -735,6 +885,8 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         }
         if (sched == 0 && plan_is_empty && default_queue_decomp(bits, bf16, sch, M, N, K, di.cus, &q))
             return prepare_queue(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out);
+        if (sched == 0 && plan_is_empty && default_rows_decomp(bits, bf16, M, N, K, group_size, di.cus, &q))
+            return prepare_rows(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out);
     }
     Decomp d = default_decomp(bits, bf16, sch, M, N, K, di.cus, force_r);
     if (rowlut) {
@@ -842,6 +994,10 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
 }
 
 lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dtype dtype, void* stream) {
+    if (q.rows) {
+        const hipError_t e = pick_rows(bits, dtype)(group_size, q.mb, q.r, q.rp, q.rows_lds, static_cast<hipStream_t>(stream));
+        return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
+    }
     if (q.queue) {
         const hipError_t e = pick_decode(bits, dtype)(group_size, q.r, q.dp, q.queue_lds, static_cast<hipStream_t>(stream));
         return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
@@ -884,6 +1040,8 @@ lutq_status matmul_sliced(const void* X, const void* packed, const void* scales,
         Prepared q = body;
         q.p.X = reinterpret_cast<const uint16_t*>(static_cast<const char*>(X) + (size_t)i * 32 * xrow);
         q.p.Y = reinterpret_cast<uint16_t*>(static_cast<char*>(Y) + (size_t)i * 32 * yrow);
+        q.rp.X = q.p.X;
+        q.rp.Y = q.p.Y;
         lutq_status st = launch_prepared(q, bits, group_size, dtype, stream);
         if (st != LUTQ_OK) return st;
     }
@@ -1033,6 +1191,20 @@ std::vector<lutq_plan> tune_candidates(int bits, int group_size, int64_t M, int6
                     for (int it : {2, 4, 8})
                         if (kt % it == 0)
                             push_unique(lutq_plan{r, (int)g, nw, 2, (int)(per / r), LUTQ_SCHED_QUEUE, it});
+            }
+        }
+    }
+    if (M > 4 && ((K / group_size) * 2) % 16 == 0 && nb >= cus / 2) {
+        // row-streaming plans: one workgroup per compute unit (or two, or one per two), four and eight row blocks
+        // side by side, all the waves the instance allows and eight
+        const int mbh = M > 16 ? 2 : 1;
+        for (int g : {cus, 2 * cus, cus / 2}) {
+            if (g < 1 || g > nb || nb / g > 64) continue;
+            for (int side : {4, 8}) {
+                const int w = rows_instance_waves(bits, dtype == LUTQ_BF16, mbh, side);
+                if (w == 0) continue;
+                for (int nw : {w, 8})
+                    if (nw <= w) push_unique(lutq_plan{side, g, nw, 2, (int)(nb / g), LUTQ_SCHED_ROWS, 0});
             }
         }
     }

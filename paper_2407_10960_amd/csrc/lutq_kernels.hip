@@ -139,6 +139,34 @@ hipError_t launch_decode_group(int r, const DecodeParams& p, int lds_bytes, hipS
     return hipErrorInvalidValue;
 }
 
+// Row-streaming kernel for 5..32 activation rows: MB halves of M, AMAX = 4 or 8 row blocks side by side.
+template <int GROUP, int MB, int AMAX>
+hipError_t launch_rows_one(const RowsParams& p, int lds_bytes, hipStream_t stream) {
+    constexpr int max_waves = rows_max_waves(LUTQ_INST_BITS, MB, AMAX, Tab<LUTQ_INST_BITS, LUTQ_INST_DT>::WIDE);
+    if constexpr (max_waves == 0) {
+        return hipErrorInvalidValue;
+    } else {
+        if (p.NW > max_waves) return hipErrorInvalidValue;
+        auto kernel = rows_kernel<LUTQ_INST_BITS, GROUP, MB, LUTQ_INST_DT, AMAX>;
+        if (lds_bytes > 64 * 1024) {
+            static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (attr != hipSuccess) return attr;
+        }
+        hipLaunchKernelGGL(kernel, dim3((unsigned)p.G), dim3(p.NW * 64), lds_bytes, stream, p);
+        return hipGetLastError();
+    }
+}
+
+template <int GROUP>
+hipError_t launch_rows_group(int mb, int amax, const RowsParams& p, int lds_bytes, hipStream_t stream) {
+    if (mb == 1 && amax == 4) return launch_rows_one<GROUP, 1, 4>(p, lds_bytes, stream);
+    if (mb == 1 && amax == 8) return launch_rows_one<GROUP, 1, 8>(p, lds_bytes, stream);
+    if (mb == 2 && amax == 4) return launch_rows_one<GROUP, 2, 4>(p, lds_bytes, stream);
+    if (mb == 2 && amax == 8) return launch_rows_one<GROUP, 2, 8>(p, lds_bytes, stream);
+    return hipErrorInvalidValue;
+}
+
 template <int GROUP>
 hipError_t launch_dq(const DequantParams& p, int grid, int lds_bytes, hipStream_t stream) {
     hipLaunchKernelGGL((dequant_kernel<LUTQ_INST_BITS, GROUP, LUTQ_INST_DT>), dim3(grid), dim3(256), lds_bytes, stream, p);
@@ -177,6 +205,17 @@ hipError_t LUTQ_NAME(launch_decode_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, i
         case 64: return launch_decode_group<64>(r, p, lds_bytes, stream);
         case 128: return launch_decode_group<128>(r, p, lds_bytes, stream);
         case 256: return launch_decode_group<256>(r, p, lds_bytes, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t LUTQ_NAME(launch_rows_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int amax, const RowsParams& p, int lds_bytes,
+                                                                  hipStream_t stream) {
+    switch (group) {
+        case 32: return launch_rows_group<32>(mb, amax, p, lds_bytes, stream);
+        case 64: return launch_rows_group<64>(mb, amax, p, lds_bytes, stream);
+        case 128: return launch_rows_group<128>(mb, amax, p, lds_bytes, stream);
+        case 256: return launch_rows_group<256>(mb, amax, p, lds_bytes, stream);
     }
     return hipErrorInvalidValue;
 }

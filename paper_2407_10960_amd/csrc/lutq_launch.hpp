@@ -6,6 +6,7 @@
 
 #include "lutq_matmul_kernel.hpp"
 #include "lutq_decode_kernel.hpp"
+#include "lutq_rows_kernel.hpp"
 
 namespace lutq {
 
@@ -37,7 +38,9 @@ inline bool matmul_instance_exists(int bits, bool bf16, int r, int mb, int stage
     hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes, \
                                           hipStream_t stream);                                       \
     hipError_t launch_decode_b##B##_##DT(int group, int r, const DecodeParams& p, int lds_bytes,     \
-                                         hipStream_t stream);
+                                         hipStream_t stream);                                        \
+    hipError_t launch_rows_b##B##_##DT(int group, int mb, int amax, const RowsParams& p, int lds_bytes, \
+                                       hipStream_t stream);
 
 // Measurement builds (phase timestamps, see TraceStamp) of the 4-bit instances that serve M <= 4 under the
 // default plans: group 64 or 128, R = 1 or 2, two tiles in flight, chunked scales, 128-register build.

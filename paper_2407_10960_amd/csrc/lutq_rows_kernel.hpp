@@ -1,0 +1,292 @@
+// The fused kernel for 5 to 32 activation rows on matrices with several row blocks per compute unit.
+//
+// What is computed is that of matmul_kernel (Algorithm 1 of the paper).  The loop nest is turned round:
+// from five rows up the activations are as large a stream as the weights (M x 128 x 2 bytes per 1 KiB
+// weight tile at 4 bits: one to eight times the weights for M = 4 .. 32), so this kernel holds the
+// activations still and streams weights past them:
+//
+//   * A workgroup owns A consecutive 16-row blocks over the whole of K (the first `extra` workgroups one
+//     more), nothing else: no partial sum leaves it.
+//   * Its waves split K.  For each of its K tiles a wave loads the tile's activations once -- all M rows,
+//     as B operands of the matrix instruction, into registers -- and then walks the workgroup's row
+//     blocks: one 1 KiB weight tile per row block, dequantised through the table and multiplied into
+//     that row block's accumulators.  Up to AMAX row blocks are accumulated side by side (AMAX x MB x 4
+//     registers); a workgroup with more walks them in passes of AMAX.
+//   * So an activation fragment is fetched once per AMAX weight tiles instead of once per tile or per
+//     pair of tiles, no activation goes through LDS, and there is no barrier inside the K loop: the waves
+//     run out of step and cover each other's memory and table-lookup latencies.
+//   * After a pass the waves' accumulators are added in wave order through LDS, a few row blocks per
+//     round, and written out: bit-reproducible.
+//
+//   * The scales of a pass's row blocks (consecutive rows: one contiguous range) are copied into LDS when
+//     the pass begins, 16 bytes per lane, and read from there per (tile, row block): a 2- to 16-byte read
+//     per lane from global memory would touch sixteen cache lines per instruction for one line's worth of
+//     weights.
+#pragma once
+
+#include "lutq_matmul_kernel.hpp"
+
+namespace lutq {
+
+struct RowsParams {
+    const uint16_t* X;        // [M, K]
+    const uint8_t* packed;
+    const uint16_t* scales;   // [N, SG]
+    const uint16_t* lut;
+    uint16_t* Y;              // [M, N]
+    uint32_t packed_bytes, scale_bytes, x_bytes;
+    int M, N, K;
+    int KT;                   // K tiles per row block
+    int SG2;                  // bytes of one row of scales
+    int SBL;                  // log2 of the row blocks per super-block of the packed layout
+    uint32_t tile_stride;     // packed bytes from K tile kt to kt + 1 of one row block
+    uint32_t sblock_bytes;    // packed bytes of one super-block
+    int A, extra;             // row blocks per workgroup; workgroups 0 .. extra - 1 own one more
+    int NW;                   // waves per workgroup
+    int TQ, TR;               // KT = TQ * NW + TR: wave w owns TQ (+1 if w < TR) consecutive K tiles
+    int RPR;                  // row blocks reduced per round (RPR * MB * NW KiB of LDS)
+    int s_units;              // 16-byte units per row of scales (SG2 / 16)
+    uint32_t s_magic;         // 2^32 / s_units + 1 (unused when s_units == 1)
+    int SROW;                 // bytes from row to row of the scales in LDS (SG2 + 16: sixteen rows, sixteen banks)
+    int red_off;              // LDS offset of the reduction slots
+    int lut_ltpe;             // log2 of the threads that build one table row together
+    int G;                    // workgroups
+};
+
+// LDS of one launch: [table, 256-byte entry stride][scales of AMAX x 16 rows, SROW bytes each][RPR x MB x NW slots of 1 KiB]
+
+// Registers: AMAX x MB x 4 accumulators + STEPS x MB x 4 activation operands + four weight tiles in flight
+// (eight at 4 bits with eight row blocks side by side: five registers each), the lookup ring and addresses
+// (about 84 at 4 bits, 108 and 116 at 2 and 3 bits with their eight steps per tile, 28 more with a widened
+// bf16 table).  The estimate decides how many waves an instance is compiled for (4-bit fp16, M > 16: 152
+// registers and twelve waves with four row blocks side by side, 221 and eight waves with eight; M <= 16
+// with eight: 153 and twelve waves); 0 = no such instance.
+__host__ __device__ constexpr int rows_tiles_in_flight(int bits, int amax) { return bits == 4 && amax == 8 ? 8 : 4; }
+__host__ __device__ constexpr int rows_max_waves(int bits, int mb, int amax, bool wide_table) {
+    const int steps = bits == 4 ? 4 : 8;
+    const int regs = amax * mb * 4 + steps * mb * 4 + (bits == 4 ? 84 : bits == 3 ? 116 : 108) + (wide_table ? 28 : 0)
+                   + 5 * (rows_tiles_in_flight(bits, amax) - 4);
+    return regs <= 128 ? 16 : regs <= 168 ? 12 : regs <= 240 ? 8 : 0;
+}
+
+template <int BITS, int GROUP, int MB, typename DT, int AMAX>
+__global__ __launch_bounds__(64 * (rows_max_waves(BITS, MB, AMAX, Tab<BITS, DT>::WIDE) > 0 ? rows_max_waves(BITS, MB, AMAX, Tab<BITS, DT>::WIDE) : 4))
+void rows_kernel(const RowsParams p) {
+    using Gm = Geo<BITS>;
+    constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
+    constexpr int TPS = GROUP > TK ? GROUP / TK : 1;   // tiles that share one scale
+    constexpr int NS = GROUP > TK ? 1 : TK / GROUP;    // scales per tile per row
+    constexpr int SPG = GROUP / 32;                    // steps per group
+    constexpr int LOG2C = perm_log2_copies<BITS, DT>();
+    constexpr int LUT_BYTES = lut_row_table_bytes<BITS>();
+    constexpr int D = 4;                               // steps whose table reads are in flight ahead of their use
+    static_assert(STEPS % D == 0, "the ring of table reads runs on from one tile into the next");
+    constexpr int NST = rows_tiles_in_flight(BITS, AMAX);   // weight tiles (and their scales) in flight per wave
+    static_assert(AMAX % NST == 0, "the row blocks of a pass are walked in rounds of the pipeline's stages");
+
+    asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.packed_bytes), "s"(p.scale_bytes),
+                 "s"(p.x_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.KT), "s"(p.SG2), "s"(p.SBL), "s"(p.tile_stride),
+                 "s"(p.sblock_bytes), "s"(p.A), "s"(p.extra), "s"(p.NW), "s"(p.TQ), "s"(p.TR), "s"(p.RPR), "s"(p.lut_ltpe),
+                 "s"(p.s_units), "s"(p.s_magic), "s"(p.SROW), "s"(p.red_off));
+
+    extern __shared__ __align__(16) char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15;                // row inside a 16-row block (A side) / activation row (B side)
+    const int lo = lane >> 4;                // K octet
+    char* lut = smem;
+    char* sc = smem + LUT_BYTES;
+    char* red = smem + p.red_off;
+
+    const LutSeed lut_seed = lut_fetch<BITS>(p.lut, tid, p.lut_ltpe);
+    __builtin_amdgcn_sched_barrier(0);
+    const LutAddr la = make_lut_addr<BITS, DT>(lut, LOG2C, lane);
+    const rsrc_t rW = make_rsrc(p.packed, p.packed_bytes);
+    const rsrc_t rS = make_rsrc(p.scales, p.scale_bytes);
+    const rsrc_t rX = make_rsrc(p.X, p.x_bytes);
+
+    // this workgroup's row blocks and this wave's K tiles
+    const bool big = (int)blockIdx.x < p.extra;
+    const int nrb = p.A + (big ? 1 : 0);
+    const int rb_first = (int)blockIdx.x * p.A + ((int)blockIdx.x < p.extra ? (int)blockIdx.x : p.extra);
+    const int ka = wave * p.TQ + (wave < p.TR ? wave : p.TR);
+    const int kb = ka + p.TQ + (wave < p.TR ? 1 : 0);
+
+    // activation rows m >= M lie beyond the X buffer and read as zero
+    uint32_t xlane[MB];
+    bool valid[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int m = li + 16 * mb;
+        valid[mb] = m < p.M;
+        xlane[mb] = ((uint32_t)m * (uint32_t)p.K + 8u * (uint32_t)lo) * 2u;
+    }
+    const uint32_t wlane = 16u * lane;
+    (void)wlane;
+    const uint32_t slane = (uint32_t)li * (uint32_t)p.SROW;
+
+    struct Stage {
+        WFrag<BITS> w;
+        ScaleWords<NS> s;
+    };
+    // Slot (kt, a) of pass p0, a = 0 .. AMAX - 1: weight tile and scales of row block rb_first + p0 + a - skip,
+    // where skip = AMAX - (row blocks of the pass): a short pass leaves its FIRST slots empty, so that the
+    // last slot, which also fetches the next tile's activations, always holds a row block.  Every slot
+    // issues the same loads, in range or not (out of range: zeros, no memory traffic), and no load sits
+    // under a branch: the waits on the load counter then name exactly the tile they need and leave the
+    // younger ones in flight.
+    auto load_w = [&](Stage& st, int p0, int skip, int kt, int a) {
+        const bool in = a >= skip && kt < kb;
+        const int rb = rb_first + p0 + a - skip;
+        const uint32_t tw = (uint32_t)(rb >> p.SBL) * p.sblock_bytes + (uint32_t)(rb & ((1 << p.SBL) - 1)) * TILE_BYTES
+                          + (uint32_t)kt * p.tile_stride;
+        load_wfrag<BITS>(st.w, rW, in ? tw : kOutOfRange, lane);
+    };
+    // the slot's scales, from the pass's copy in LDS (an empty slot reads the first row's)
+    auto load_s = [&](Stage& st, int skip, int kt, int a) {
+        const bool in = a >= skip && kt < kb;
+        const uint32_t ts = (uint32_t)(a - skip) * 16u * (uint32_t)p.SROW + slane + (uint32_t)(kt / TPS) * (NS * 2);
+        lds_load_scales<NS>(st.s, sc + (in ? ts : 0u));
+    };
+    auto load_slot = [&](Stage& st, int p0, int skip, int kt, int a) {
+        load_w(st, p0, skip, kt, a);
+        load_s(st, skip, kt, a);
+    };
+
+    bool lut_ready = false;
+    for (int p0 = 0; p0 < nrb; p0 += AMAX) {
+        const int na = nrb - p0 < AMAX ? nrb - p0 : AMAX;      // row blocks of this pass
+        const int skip = AMAX - na;                             // empty slots at the head of every K tile
+        f32x4 acc[AMAX][MB];
+#pragma unroll
+        for (int a = 0; a < AMAX; ++a)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) acc[a][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        Stage st[NST];
+#pragma unroll
+        for (int a = 0; a < NST; ++a) {
+            load_w(st[a], p0, skip, ka, a);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        u32x4 bx[STEPS][MB];
+        auto load_x_step = [&](int kt, int s) {
+            const uint32_t tx = kt < kb ? (uint32_t)kt * (TK * 2) : kOutOfRange;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                bx[s][mb] = __builtin_amdgcn_raw_buffer_load_b128(rX, tx + xlane[mb] + 64u * s, 0, kAuxNone);
+        };
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) load_x_step(ka, s);
+        __builtin_amdgcn_sched_barrier(0);
+        {
+            // The pass's scales: rows (rb_first + p0) * 16 onwards, na * 16 rows of SG2 bytes, one contiguous
+            // range.  (Every wave is past the previous pass's K loop: its reduction began with a barrier.)
+            const int units = na * 16 * p.s_units;
+            const uint32_t gbase = (uint32_t)(rb_first + p0) * 16u * (uint32_t)p.SG2;
+            for (int i = tid; i < units; i += p.NW * 64) {
+                const int row = p.s_units == 1 ? i : (int)__umulhi((uint32_t)i, p.s_magic);
+                const int col = i - row * p.s_units;
+                const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rS, gbase + 16u * (uint32_t)i, 0, kAuxNone);
+                *reinterpret_cast<u32x4*>(sc + (size_t)row * p.SROW + 16 * col) = v;
+            }
+        }
+        if (!lut_ready) {
+            // the table is built while the first tiles are in flight (its own reads were issued before them)
+            LutSeed seed = lut_seed;
+            asm volatile("" : "+v"(seed.w[0]), "+v"(seed.w[1]), "+v"(seed.w[2]), "+v"(seed.w[3]));
+            lut_build<BITS, DT>(lut, seed, (int)(reinterpret_cast<uintptr_t>(p.lut) >> 1) & 1, LOG2C, tid, p.lut_ltpe);
+            lut_ready = true;
+        }
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int a = 0; a < NST; ++a) load_s(st[a], skip, ka, a);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // The table reads run D steps ahead of their use, across slots: when a slot begins, those of its
+        // first D steps are already under way (issued by the slot before it, or here for the first).
+        Raw<BITS, DT> raw[D];
+#pragma unroll
+        for (int s = 0; s < D; ++s) raw[s] = lookup_step<BITS, DT, true>(st[0].w, s, la);
+        __builtin_amdgcn_sched_barrier(0);
+
+        for (int kt = ka; kt < kb; ++kt) {
+#pragma unroll
+            for (int a = 0; a < AMAX; ++a) {
+                {
+                    Stage& cur = st[a % NST];
+                    const Stage& nxt = st[(a + 1) % NST];
+                    if (a == AMAX - 1 || a >= skip) {
+                        // dequantise the tile step by step and multiply it into row block a's accumulators
+                        u32x4 aop[2];
+#pragma unroll
+                        for (int s = 0; s <= STEPS; ++s) {
+                            if (s < STEPS) {
+                                const ScaleReg<DT> sc = scale_of<DT, NS>(cur.s, s / SPG);
+                                aop[s & 1] = scale4<BITS, DT>(raw[s % D], sc);
+                                __builtin_amdgcn_sched_barrier(0);
+                                raw[s % D] = s + D < STEPS ? lookup_step<BITS, DT, true>(cur.w, s + D, la)
+                                                           : lookup_step<BITS, DT, true>(nxt.w, s + D - STEPS, la);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                            if (s > 0) {
+#pragma unroll
+                                for (int mb = 0; mb < MB; ++mb)
+                                    acc[a][mb] = mfma16x16x32<DT>(aop[(s - 1) & 1], bx[s - 1][mb], acc[a][mb]);
+                                __builtin_amdgcn_sched_barrier(0);
+                                // the tile's last row block: this step's activations have had their last
+                                // use, the next tile's take their registers
+                                if (a == AMAX - 1) {
+                                    load_x_step(kt + 1, s - 1);
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
+                            }
+                        }
+                    } else {
+                        // an empty slot: only the next slot's first table reads
+#pragma unroll
+                        for (int s = 0; s < D; ++s) raw[s] = lookup_step<BITS, DT, true>(nxt.w, s, la);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    // the slot NST ahead: further along this K tile, or among the first ones of the next
+                    const bool here = a + NST < AMAX;
+                    load_slot(cur, p0, skip, here ? kt : kt + 1, here ? a + NST : a + NST - AMAX);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+
+        // ---- add the waves' sums in wave order, RPR row blocks per round, and store ----
+        for (int a0 = 0; a0 < na; a0 += p.RPR) {   // a0: first row block (of the pass) of this round
+            __syncthreads();                       // the previous round's readers are done
+#pragma unroll
+            for (int a = 0; a < AMAX; ++a) {
+                const int rbp = a - skip;          // slot a holds row block rbp of the pass
+                if (rbp >= a0 && rbp < a0 + p.RPR) {
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+                        *reinterpret_cast<f32x4*>(red + ((size_t)(((rbp - a0) * MB + mb) * p.NW + wave) * 64 + lane) * 16) = acc[a][mb];
+                }
+            }
+            __syncthreads();
+            const int nr = na - a0 < p.RPR ? na - a0 : p.RPR;
+            for (int task = wave; task < nr * MB; task += p.NW) {       // task = (row block of the round, M half); one wave each
+                const int al = task / MB, mb = task - al * MB;
+                f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+                const char* src = red + ((size_t)(task * p.NW) * 64 + lane) * 16;
+#pragma unroll 4
+                for (int w = 0; w < p.NW; ++w) sum += *reinterpret_cast<const f32x4*>(src + (size_t)w * 1024);
+                const int m = li + 16 * mb;
+                if (m < p.M) {
+                    const int n = (rb_first + p0 + a0 + al) * 16 + 4 * lo;
+                    *reinterpret_cast<u32x2*>(p.Y + (size_t)m * p.N + n) = pack4<DT>(sum);
+                }
+            }
+        }
+        (void)valid;
+    }
+}
+
+}  // namespace lutq

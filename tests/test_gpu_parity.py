@@ -660,6 +660,63 @@ def test_work_queue_plans_match_oracle(lutq, bits, dtype):
         DeviceCase(lutq, c).matmul(lutq, plan=lutq.Plan(1, 0, 16, 2, 1, Q, 2))
 
 
+def rows_waves(lutq, bits, dtype, M, N, K, group, side):
+    """Waves the row-streaming instance with `side` row blocks side by side accepts (found through
+    lutq_plan_check: 16, 12 or 8; 0 = no such instance)."""
+    for w in (16, 12, 8):
+        if lutq.lutq_plan_check(bits, group, M, N, K, 0 if dtype == "f16" else 1, 256, lutq.Plan(side, 0, w, 2, 0, 3, 0)) == 0:
+            return w
+    return 0
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_row_streaming_plans_match_oracle(lutq, bits, dtype):
+    """The activation-stationary kernel (the waves of a workgroup split K, hold a tile's activations in
+    registers and stream the weights of four or eight row blocks past them; sums added in wave order):
+    M on both sides of 16, every group size, one to many row blocks per workgroup (several passes, a
+    ragged last pass, uneven shares), more waves than K tiles, several rounds of the final reduction;
+    against the oracle; bit-reproducible."""
+    RW = 3                                                  # LUTQ_SCHED_ROWS
+    for (N, K, group, lut) in [(64, 8 * tk(bits), 128, "nf"), (336, 20 * tk(bits), 64, "learned"),
+                               (96, 4 * tk(bits), 32, "random_index"), (208, 16 * tk(bits), 256, "nf")]:
+        nb = N // 16
+        for M in (1, 5, 8, 13, 16, 17, 24, 31, 32):
+            c = gen.make_case(700 + M, M, N, K, bits, group, dtype, lut)
+            d = DeviceCase(lutq, c)
+            plans = [lutq.Plan(0, 0, 0, 0, 0, RW, 0)]
+            for side in (4, 8):
+                w = rows_waves(lutq, bits, dtype, M, N, K, group, side)
+                if w == 0:
+                    with pytest.raises(lutq.LutqError) as e:
+                        d.matmul(lutq, plan=lutq.Plan(side, 0, 8, 2, 0, RW, 0))
+                    assert e.value.code == 10
+                    continue
+                plans += [lutq.Plan(side, 1, w, 2, 0, RW, 0),              # one workgroup walks every row block
+                          lutq.Plan(side, nb, 4, 2, 1, RW, 0),             # one row block per workgroup
+                          lutq.Plan(side, 2, w, 2, 0, RW, 0), lutq.Plan(side, 3, 5, 2, 0, RW, 0),
+                          lutq.Plan(side, nb - 1, 7, 2, 1, RW, 0)]
+                bad = [lutq.Plan(side, 0, w + 1, 2, 0, RW, 0), lutq.Plan(side, nb + 1, 4, 2, 0, RW, 0),
+                       lutq.Plan(side, 2, 4, 2, 1, RW, 0), lutq.Plan(side, 0, 4, 4, 0, RW, 0), lutq.Plan(side, 0, 4, 2, 0, RW, 2)]
+                for b in bad:
+                    with pytest.raises(lutq.LutqError) as e:
+                        d.matmul(lutq, plan=b)
+                    assert e.value.code == 10, b
+            for plan in plans:
+                Y1 = to_bits(d.matmul(lutq, plan=plan))
+                Y2 = to_bits(d.matmul(lutq, plan=plan))
+                assert np.array_equal(Y1, Y2), f"{plan} is not reproducible"
+                check_y(Y1, c, f"b{bits} {dtype} g{group} M{M} N{N} K{K} {plan}")
+    for side in (2, 16):
+        with pytest.raises(lutq.LutqError):
+            d.matmul(lutq, plan=lutq.Plan(side, 0, 8, 2, 0, RW, 0))
+    # rows of scales that are not whole 16-byte units are left to the other kernels
+    c = gen.make_case(9, 8, 64, 3 * tk(bits), bits, 32 if bits == 4 else 64, dtype, "nf")
+    with pytest.raises(lutq.LutqError) as e:
+        DeviceCase(lutq, c).matmul(lutq, plan=lutq.Plan(4, 0, 4, 2, 0, RW, 0))
+    assert e.value.code == 10
+
+
 @pytest.mark.parametrize("bits", BITS)
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_table_pointer_in_the_upper_half_of_a_word(lutq, bits, dtype):

@@ -165,8 +165,16 @@ def test_default_plans_are_valid_for_random_problems():
             continue
         p = lutq.lutq_plan_default_for(bits, group, M, N, K, dt, cus)
         what = f"b{bits} g{group} M{M} N{N} K{K} cus{cus} dt{dt}: {p}"
-        assert p.row_blocks_per_wave in (1, 2, 4) and _sb(nb) % p.row_blocks_per_wave == 0, what
         assert 4 <= p.waves_per_workgroup <= 16 and p.tiles_in_flight in (2, 4), what
+        if p.scheduling == 3:                       # row streaming: M >= 5, whole row blocks per workgroup
+            assert M >= 5 and p.row_blocks_per_wave in (4, 8) and p.tiles_in_flight == 2 and p.tiles_per_item == 0, what
+            assert 1 <= p.grid <= nb and p.row_groups_per_workgroup == nb // p.grid <= 64, what
+            assert (K // group * 2) % 16 == 0, what
+            assert lutq.lutq_plan_check(bits, group, M, N, K, dt, cus) == 0, what
+            if M <= 32:
+                assert lutq.lutq_plan_check(bits, group, M, N, K, dt, cus, p) == 0, what
+            continue
+        assert p.row_blocks_per_wave in (1, 2, 4) and _sb(nb) % p.row_blocks_per_wave == 0, what
         nrg = nb // p.row_blocks_per_wave
         assert nrg % p.row_groups_per_workgroup == 0, what
         if p.scheduling == 2:                       # work queue: M <= 4, whole row groups per workgroup
@@ -219,15 +227,23 @@ def test_default_plans_fitted_by_measurement():
         (4, 128, 2, 5120, 5120, 0): (1, 160, 12, 2, 2),
         (2, 128, 1, 32000, 4096, 1): (1, 500, 8, 2, 4),
         (3, 128, 3, 22016, 4096, 0): (1, 688, 4, 2, 2),
-        (4, 64, 16, 10240, 8192, 1): (2, 256, 10, 2, 5),
+        (4, 64, 32, 10240, 8192, 1): (1, 256, 8, 4, 8),
+        # row streaming (scheduling 3): row blocks that do not divide over the compute units, and one pass of
+        # five to eight row blocks per compute unit from nine rows up
+        (4, 64, 16, 10240, 8192, 1): (4, 256, 12, 2, 2, 3),
+        (4, 128, 16, 22016, 4096, 0): (8, 256, 12, 2, 5, 3),
+        (3, 128, 16, 28672, 4096, 1): (8, 256, 8, 2, 7, 3),
+        (3, 128, 24, 28672, 4096, 0): (1, 224, 16, 2, 8, 1),
         (4, 128, 20, 4096, 14336, 1): (2, 256, 4, 2, 1),
         (4, 128, 8, 28672, 4096, 0): (4, 448, 4, 2, 1),
         (4, 128, 32, 28672, 4096, 0): (2, 224, 8, 2, 4),
+        (4, 128, 32, 28672, 4096, 1): (8, 256, 8, 2, 7, 3),
+        (4, 64, 32, 57344, 8192, 0): (2, 256, 14, 2, 7, 1),
     }
     for (bits, g, M, N, K, dt), plan in want.items():
         p = lutq.lutq_plan_default_for(bits, g, M, N, K, dt, 256)
-        got = (p.row_blocks_per_wave, p.grid, p.waves_per_workgroup, p.tiles_in_flight, p.row_groups_per_workgroup)
-        assert got == plan, (bits, g, M, N, K, dt, p)
+        got = (p.row_blocks_per_wave, p.grid, p.waves_per_workgroup, p.tiles_in_flight, p.row_groups_per_workgroup, p.scheduling)
+        assert got == (plan if len(plan) == 6 else plan + (1,)), (bits, g, M, N, K, dt, p)
 
 
 def test_plan_check_matches_documented_rules():
