@@ -198,6 +198,40 @@ bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K
     out->r = r; out->grid = cus; out->nw = nw; out->stages = 2; out->rs = (int)a; out->queue = 1; out->it = it;
     return true;
 }
+// Work-queue kernel with one table per output row (M <= 4): the sixteen-copy tables of all of a workgroup's row
+// blocks are resident at once, so the number of row blocks per workgroup is what LDS holds (4-bit fp16: eight
+// at 16 KiB each); one workgroup per compute unit where that fits, else the smallest multiple of the compute
+// units that does (the workgroups of one unit then run one after the other), one workgroup per row block when
+// there are fewer than two per unit.
+int rowlut16_table_bytes(int bits, bool bf16) {
+    return bf16 ? (bits == 2 ? rowlut16_bytes<2, BF16>() : bits == 3 ? rowlut16_bytes<3, BF16>() : rowlut16_bytes<4, BF16>())
+                : (bits == 2 ? rowlut16_bytes<2, F16>() : bits == 3 ? rowlut16_bytes<3, F16>() : rowlut16_bytes<4, F16>());
+}
+int rowlut16_stage(int bits) { return 16 * (1 << bits) * 2; }
+int rowlut_queue_lds(int bits, bool bf16, int amax, int nw, int items) {
+    const int slots = items * 256, stage = amax * rowlut16_stage(bits);
+    return amax * rowlut16_table_bytes(bits, bf16) + 256 + nw * 1024 + (slots > stage ? slots : stage);
+}
+bool rowlut_queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K, int cus, Decomp* out) {
+    if (M > 4 || !sch) return false;
+    const int64_t nb = N / 16, kt = K / tile_k(bits);
+    const int it = kt % 4 == 0 ? 4 : 2;
+    if (kt % it != 0) return false;
+    for (int mult = 1; mult <= 16; ++mult) {
+        const int64_t grid = nb < 2 * (int64_t)cus ? nb : (int64_t)cus * mult;
+        if (grid > nb || grid > kMaxGrid) return false;
+        const int64_t a = nb / grid, amax = a + (nb % grid ? 1 : 0);
+        const int64_t items = amax * (kt / it);
+        const int nw = items >= 16 ? 16 : (int)(items < 4 ? 4 : items);
+        if (items <= 4096 && amax * (rowlut16_stage(bits) / 4) <= 2 * nw * 64 &&
+            rowlut_queue_lds(bits, bf16, (int)amax, nw, (int)items) <= 160 * 1024) {
+            out->r = 1; out->grid = (int)grid; out->nw = nw; out->stages = 2; out->rs = (int)a; out->queue = 1; out->it = it;
+            return true;
+        }
+        if (nb < 2 * (int64_t)cus) return false;
+    }
+    return false;
+}
 bool default_queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K, int cus, Decomp* out) {
     return queue_decomp(bits, bf16, sch, M, N, K, cus, true, out);
 }
@@ -526,7 +560,7 @@ rowlut_launcher pick_rowlut(int bits, lutq_dtype dt) {
     if (dt == LUTQ_F16) return bits == 2 ? launch_matmul_rowlut_b2_F16 : bits == 3 ? launch_matmul_rowlut_b3_F16 : launch_matmul_rowlut_b4_F16;
     return bits == 2 ? launch_matmul_rowlut_b2_BF16 : bits == 3 ? launch_matmul_rowlut_b3_BF16 : launch_matmul_rowlut_b4_BF16;
 }
-typedef hipError_t (*decode_launcher)(int, int, const DecodeParams&, int, hipStream_t);
+typedef hipError_t (*decode_launcher)(int, int, bool, const DecodeParams&, int, hipStream_t);
 decode_launcher pick_decode(int bits, lutq_dtype dt) {
     if (dt == LUTQ_F16) return bits == 2 ? launch_decode_b2_F16 : bits == 3 ? launch_decode_b3_F16 : launch_decode_b4_F16;
     return bits == 2 ? launch_decode_b2_BF16 : bits == 3 ? launch_decode_b3_BF16 : launch_decode_b4_BF16;
@@ -644,6 +678,7 @@ struct Prepared {
     int xsh;                  // 0, or activation pieces staged per wave (shared through LDS)
     bool rowlut;              // p.lut holds one table per output row
     bool queue;               // work-queue kernel: dp and queue_lds instead of p
+    bool queue_rowlut;        // ... with one table per output row
     DecodeParams dp;
     int queue_lds;
     bool rows;                // row-streaming kernel: rp, rows_lds, r = row blocks side by side
@@ -712,10 +747,11 @@ lutq_status prepare_rows(const void* X, const void* packed, const void* scales, 
 // Validates a work-queue launch (M <= 4) and fills out->dp.  `d` holds the decomposition: r, rs = row
 // groups per workgroup, nw, stages, it.
 lutq_status prepare_queue(const void* X, const void* packed, const void* scales, const void* lut, int bits,
-                          int group_size, int64_t M, int64_t N, int64_t K, bool bf16, void* Y, const Decomp& d, Prepared* out) {
+                          int group_size, int64_t M, int64_t N, int64_t K, bool bf16, void* Y, const Decomp& d, Prepared* out,
+                          bool rowlut = false) {
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     if (M > 4 || (K / group_size) % 8 != 0) return LUTQ_ERR_PLAN;
-    if (!decode_instance_exists(bits, bf16, d.r) || super_block(nb) % d.r != 0) return LUTQ_ERR_PLAN;
+    if (!decode_instance_exists(bits, bf16, d.r) || super_block(nb) % d.r != 0 || (rowlut && d.r != 1)) return LUTQ_ERR_PLAN;
     const int64_t nrg = nb / d.r;
     // the row groups are dealt to the workgroups as evenly as whole row groups allow: rs each, one more
     // in the first nrg - rs * grid workgroups
@@ -726,7 +762,8 @@ lutq_status prepare_queue(const void* X, const void* packed, const void* scales,
     const int amax = d.rs + (extra ? 1 : 0);
     const int64_t items = (int64_t)amax * (kt / d.it);
     if (items > 4096) return LUTQ_ERR_PLAN;
-    const int lds = queue_lds_bytes(bits, d.nw, (int)items, d.r);
+    if (rowlut && amax * (rowlut16_stage(bits) / 4) > 2 * d.nw * 64) return LUTQ_ERR_PLAN;   // raw tables: two words per thread
+    const int lds = rowlut ? rowlut_queue_lds(bits, bf16, amax, d.nw, (int)items) : queue_lds_bytes(bits, d.nw, (int)items, d.r);
     if (lds > 160 * 1024) return LUTQ_ERR_PLAN;
     DecodeParams q{};
     q.X = static_cast<const uint16_t*>(X);
@@ -749,6 +786,11 @@ lutq_status prepare_queue(const void* X, const void* packed, const void* scales,
     q.lut_ltpe = bits == 2 ? lut_log2_threads_per_row<2>(d.nw * 64)
                : bits == 3 ? lut_log2_threads_per_row<3>(d.nw * 64) : lut_log2_threads_per_row<4>(d.nw * 64);
     q.slot_off = bits == 2 ? decode_slot_off<2>(d.nw) : bits == 3 ? decode_slot_off<3>(d.nw) : decode_slot_off<4>(d.nw);
+    q.tab_total = 0;
+    if (rowlut) {
+        q.tab_total = amax * rowlut16_table_bytes(bits, bf16);
+        q.slot_off = q.tab_total + 256 + d.nw * 1024;
+    }
     // final reduction: as many groups of items per output as there are threads for them (the group sums
     // are parked in the table's area: at most 4 KiB)
     const int outputs = q.A * d.r * 64, outputs_max = amax * d.r * 64;
@@ -764,6 +806,7 @@ lutq_status prepare_queue(const void* X, const void* packed, const void* scales,
         std::fprintf(stderr, "lutq_matmul: work queue R=%d grid=%d waves=%d row groups per workgroup=%d tiles per item=%d items=%d lds=%d\n",
                      d.r, d.grid, d.nw, d.rs, d.it, (int)items, lds);
     out->queue = true;
+    out->queue_rowlut = rowlut;
     out->dp = q;
     out->queue_lds = lds;
     out->r = d.r;
@@ -823,8 +866,19 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         if (user_plan->grid != 0 && (user_plan->grid < 1 || user_plan->grid > kMaxGrid)) return LUTQ_ERR_PLAN;
     }
     out->queue = false;
+    out->queue_rowlut = false;
     out->rows = false;
     if (rowlut && user_plan && user_plan->scheduling > LUTQ_SCHED_TEAMS) return LUTQ_ERR_PLAN;
+    if (rowlut && !user_plan) {
+        // one table per output row, M <= 4: the work-queue kernel with all of a workgroup's tables resident
+        Decomp q;
+        if (rowlut_queue_decomp(bits, bf16, sch, M, N, K, di.cus, &q)) {
+            const lutq_status qs = prepare_queue(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out, true);
+            if (qs == LUTQ_OK) return qs;
+            out->queue = false;
+            out->queue_rowlut = false;
+        }
+    }
     if (!rowlut) {
         // the work-queue kernel: asked for by the plan, or the default for M <= 4 where it applies
         // (an explicit plan without a scheduling field keeps meaning the static teams it describes)
@@ -999,7 +1053,7 @@ lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dt
         return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
     }
     if (q.queue) {
-        const hipError_t e = pick_decode(bits, dtype)(group_size, q.r, q.dp, q.queue_lds, static_cast<hipStream_t>(stream));
+        const hipError_t e = pick_decode(bits, dtype)(group_size, q.r, q.queue_rowlut, q.dp, q.queue_lds, static_cast<hipStream_t>(stream));
         return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
     }
     hipError_t e = q.rowlut ? pick_rowlut(bits, dtype)(group_size, q.mb, q.sch, q.xm, q.p, static_cast<hipStream_t>(stream))

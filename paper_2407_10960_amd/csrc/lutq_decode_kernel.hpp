@@ -24,6 +24,13 @@
 //
 // Activations use the packed layout for M <= 4 (one 128-bit load covers four 32-wide K steps: lane i
 // holds row i % 4 of step i / 4; four accumulators folded by three row rotations per item).
+//
+// RLUT (one table per output row, Section 2.3's tables at the output-channel level): the four lanes that
+// work on a row share one copy of that row's table, so a row block's tables are 16 copies (16 KiB at 4
+// bits) instead of 64, and the tables of ALL the workgroup's row blocks are built once, before the K
+// loop: a launch then costs what the shared-table launch costs plus the larger build and one more
+// instruction per lookup (the entry stride is no longer the 256 bytes that one byte permute addresses;
+// two lanes of a row that read different entries can meet in a bank).
 #pragma once
 
 #include <type_traits>
@@ -57,6 +64,7 @@ struct DecodeParams {
     int NG, GL;               // final reduction: NG groups of GL consecutive items per output (NG * GL >= C)
     uint32_t o_magic;         // floor(2^32 / (A * R * 64))
     uint32_t o1_magic;        // floor(2^32 / ((A + 1) * R * 64))
+    int tab_total;            // RLUT: LDS bytes of all the row blocks' tables (the other areas follow)
     unsigned long long* trace;   // TRACE instances only
 };
 
@@ -75,8 +83,71 @@ __host__ __device__ constexpr bool decode_instance_exists(int bits, bool bf16, i
     return (r == 1 || r == 2) && !(bits == 3 && bf16 && r == 2);
 }
 
-template <int BITS, int GROUP, int R, typename DT, int P, bool TRACE = false>
+// ---------------------------------------------------------------------------------------
+// Per-row tables, sixteen copies: the table of row c of a row block is copy c (log2 copies = 4), so
+// lane l reads copy l % 16 = its row, with the generic (shift + add) entry address.
+// ---------------------------------------------------------------------------------------
+template <int BITS, typename DT>
+__host__ __device__ constexpr int rowlut16_bytes() { return lut_lds_bytes<BITS, DT>(4); }
+// bytes of one row block's raw tables (16 rows x 2^b 16-bit values), staged in LDS for the build
+template <int BITS>
+__host__ __device__ constexpr int rowlut16_stage_bytes() { return 16 * (1 << BITS) * 2; }
+
+// Builds the tables of `nrb` row blocks at `tables` (rowlut16_bytes apart) from their raw rows at `stage`
+// (both LDS).  Thread (row block a, row c, lower index lo) reads the row's 2^b values once and writes the
+// entries (lo, hi) for every upper index hi: the lanes of one store cover rows c = 0..15 (one entry's
+// sixteen copies, contiguous) of four consecutive entries, so stores do not conflict.
+template <int BITS, typename DT>
+__device__ __forceinline__ void rowlut16_build(char* tables, const char* stage, int nrb, int tid, int nthreads) {
+    constexpr int E = 1 << BITS;
+    constexpr int LOWN = BITS == 3 ? 8 : 16, LOWL = BITS == 3 ? 3 : 4;
+    constexpr bool WIDE = Tab<BITS, DT>::WIDE;
+    constexpr int EB = Tab<BITS, DT>::ENTRY_BYTES;
+    constexpr int SH = 4 + (EB == 8 ? 3 : 2);
+    const int combos = nrb * 16 * LOWN;
+    for (int idx = tid; idx < combos; idx += nthreads) {
+        const int c = idx & 15, lo = (idx >> 4) & (LOWN - 1), a = idx >> (4 + LOWL);
+        const char* row = stage + (size_t)(a * 16 + c) * (E * 2);
+        uint32_t t[8] = {0, 0, 0, 0, 0, 0, 0, 0};               // the row's values, two per word
+        if constexpr (BITS == 4) {
+            const u32x4 v0 = *reinterpret_cast<const u32x4*>(row), v1 = *reinterpret_cast<const u32x4*>(row + 16);
+            t[0] = v0.x; t[1] = v0.y; t[2] = v0.z; t[3] = v0.w; t[4] = v1.x; t[5] = v1.y; t[6] = v1.z; t[7] = v1.w;
+        } else if constexpr (BITS == 3) {
+            const u32x4 v0 = *reinterpret_cast<const u32x4*>(row);
+            t[0] = v0.x; t[1] = v0.y; t[2] = v0.z; t[3] = v0.w;
+        } else {
+            const u32x2 v0 = *reinterpret_cast<const u32x2*>(row);
+            t[0] = v0.x; t[1] = v0.y;
+        }
+        auto val = [&](int q) -> uint32_t { return (q & 1) ? (t[q >> 1] >> 16) : (t[q >> 1] & 0xffffu); };   // q is a constant
+        const uint16_t* rowv = reinterpret_cast<const uint16_t*>(row);
+        uint32_t first;                                         // the part of the entry that lo decides
+        int e_lo;
+        if constexpr (BITS == 2) {
+            first = (uint32_t)rowv[lo & 3] | ((uint32_t)rowv[lo >> 2] << 16);
+            e_lo = lo;
+        } else {
+            first = rowv[lo];
+            e_lo = BITS == 3 ? ((lo & 3) | ((lo >> 2) << 4)) : lo;
+        }
+        char* dst = tables + (size_t)a * rowlut16_bytes<BITS, DT>() + ((size_t)e_lo << SH) + c * EB;
+#pragma unroll
+        for (int hi = 0; hi < LOWN; ++hi) {
+            const int e_hi = BITS == 3 ? (((hi & 3) << 2) | ((hi >> 2) << 5)) : (hi << 4);
+            if constexpr (BITS == 2) {
+                *reinterpret_cast<u32x2*>(dst + (e_hi << SH)) = u32x2{first, val(hi & 3) | (val(hi >> 2) << 16)};
+            } else if constexpr (WIDE) {
+                *reinterpret_cast<u32x2*>(dst + (e_hi << SH)) = u32x2{first << 16, val(hi) << 16};
+            } else {
+                *reinterpret_cast<uint32_t*>(dst + (e_hi << SH)) = first | (val(hi) << 16);
+            }
+        }
+    }
+}
+
+template <int BITS, int GROUP, int R, typename DT, int P, bool TRACE = false, bool RLUT = false>
 __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
+    static_assert(!RLUT || R == 1, "per-row tables: one row block per row group");
     using Gm = Geo<BITS>;
     constexpr int TK = Gm::TK, STEPS = Gm::STEPS, TILE_BYTES = Gm::TILE_BYTES;
     constexpr int TPS = GROUP > TK ? GROUP / TK : 1;   // tiles that share one scale
@@ -102,7 +173,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.packed_bytes), "s"(p.scale_bytes),
                  "s"(p.x_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.SG2), "s"(p.SBL), "s"(p.tile_stride), "s"(p.sblock_bytes),
                  "s"(p.A), "s"(p.C), "s"(p.IT), "s"(p.NW), "s"(p.a_magic), "s"(p.lut_ltpe), "s"(p.slot_off), "s"(p.NG), "s"(p.GL),
-                 "s"(p.o_magic), "s"(p.extra), "s"(p.a1_magic), "s"(p.o1_magic));
+                 "s"(p.o_magic), "s"(p.extra), "s"(p.a1_magic), "s"(p.o1_magic), "s"(p.tab_total));
     stamp(kTraceArgs);
 
     extern __shared__ __align__(16) char smem[];
@@ -111,13 +182,33 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15;                // row inside a 16-row block (A side)
     char* lut = smem;
-    uint32_t* queue = reinterpret_cast<uint32_t*>(smem + lut_row_table_bytes<BITS>());
-    char* sc_lds = smem + decode_scale_off<BITS>() + wave * 1024;
+    const int table_bytes = RLUT ? p.tab_total : lut_row_table_bytes<BITS>();
+    uint32_t* queue = reinterpret_cast<uint32_t*>(smem + table_bytes);
+    char* sc_lds = smem + table_bytes + 256 + wave * 1024;
     float* slots = reinterpret_cast<float*>(smem + p.slot_off);
 
-    const LutSeed lut_seed = lut_fetch<BITS>(p.lut, tid, p.lut_ltpe);
+    const bool big = (int)blockIdx.x < p.extra;        // this workgroup owns one row group more
+    const int A = p.A + (big ? 1 : 0);
+    const int rg0 = (int)blockIdx.x * p.A + ((int)blockIdx.x < p.extra ? (int)blockIdx.x : p.extra);   // first row group
+
+    // the table's values are asked for first: they are needed first
+    LutSeed lut_seed{};
+    uint32_t rowtab_raw[2] = {0, 0};
+    if constexpr (RLUT) {
+        // the raw tables of the workgroup's rows (consecutive rows: one contiguous range), two words per thread
+        const rsrc_t rT = make_rsrc(p.lut, (uint32_t)p.N * (uint32_t)((1 << BITS) * 2));
+        const int words = A * (rowlut16_stage_bytes<BITS>() / 4);
+        const uint32_t tbase = (uint32_t)rg0 * (uint32_t)rowlut16_stage_bytes<BITS>();
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int i = tid + k * p.NW * 64;
+            rowtab_raw[k] = __builtin_amdgcn_raw_buffer_load_b32(rT, i < words ? tbase + 4u * (uint32_t)i : kOutOfRange, 0, kAuxNone);
+        }
+    } else {
+        lut_seed = lut_fetch<BITS>(p.lut, tid, p.lut_ltpe);
+    }
     __builtin_amdgcn_sched_barrier(0);
-    const LutAddr la = make_lut_addr<BITS, DT>(lut, LOG2C, lane);
+    const LutAddr la = make_lut_addr<BITS, DT>(lut, RLUT ? 4 : LOG2C, lane);
 
     const rsrc_t rW = make_rsrc(p.packed, p.packed_bytes);
     const rsrc_t rS = make_rsrc(p.scales, p.scale_bytes);
@@ -129,11 +220,8 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     const uint32_t wlane = 16u * lane;
     // scale chunks: lane l < 16 R fetches 16 bytes of row l of the row group
     const uint32_t clane = lane < 16 * R ? (uint32_t)lane * (uint32_t)p.SG2 : kOutOfRange;
-    const bool big = (int)blockIdx.x < p.extra;        // this workgroup owns one row group more
-    const int A = p.A + (big ? 1 : 0);
     const uint32_t a_magic = big ? p.a1_magic : p.a_magic;
     const int nitems = A * p.C;
-    const int rg0 = (int)blockIdx.x * p.A + ((int)blockIdx.x < p.extra ? (int)blockIdx.x : p.extra);   // first row group
 
     // the queue hands out items NW, NW + 1, ...: items 0 .. NW - 1 are the waves' first ones
     if (tid == 0) *queue = (uint32_t)p.NW;
@@ -149,7 +237,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     // (an item beyond the last one gets bases of exactly 2 GiB: every offset formed from them stays out
     // of range without wrapping, and no branch is needed -- with a branch the compiler duplicates the
     // loads on both paths and then waits for all outstanding loads where the paths join)
-    struct Item { uint32_t wbase, sbase, xbase; int kt0; };
+    struct Item { uint32_t wbase, sbase, xbase; int kt0; uint32_t tab; };   // tab (RLUT): LDS offset of the row block's tables
     auto locate = [&](int item) -> Item {
         Item it;
         const int c = div_magic(item, a_magic, A);        // items are numbered K-major: item = c * A + a
@@ -162,6 +250,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
         it.wbase = in ? wb : kOutOfRange;
         it.sbase = in ? (uint32_t)rb0 * 16u * (uint32_t)p.SG2 : kOutOfRange;
         it.xbase = in ? (uint32_t)it.kt0 * (TK * 2) : kOutOfRange;
+        it.tab = RLUT && in ? (uint32_t)a * (uint32_t)rowlut16_bytes<BITS, DT>() : 0u;
         return it;
     };
     // loads of tile j of an item (K tile kt0 + j); an item beyond the last one has out-of-range bases.
@@ -192,7 +281,10 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     };
 
     f32x4 acc[R][4];
-    auto compute_stage = [&](const Stage& st, int kt, int j) {
+    auto compute_stage = [&](const Stage& st, int kt, int j, uint32_t tab) {
+        LutAddr la_item = la;
+        if constexpr (RLUT) la_item.lane_base += tab;
+        constexpr bool PERM = !RLUT;
         ScaleWords<NS> sw[R];
         if ((kt % TPC) == 0 || j == 0) {
             // a new chunk: every lane parks its row's 8 scales in LDS, then each lane picks the scales
@@ -206,7 +298,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
         for (int r = 0; r < R; ++r) lds_load_scales<NS>(sw[r], src + 256 * r);
         Raw<BITS, DT> raw[D];
 #pragma unroll
-        for (int u = 0; u < D; ++u) raw[u] = lookup_step<BITS, DT, true>(st.w[u % R], u / R, la);
+        for (int u = 0; u < D; ++u) raw[u] = lookup_step<BITS, DT, PERM>(st.w[u % R], u / R, la_item);
         __builtin_amdgcn_sched_barrier(0);
         u32x4 a[2];
 #pragma unroll
@@ -217,7 +309,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
                 a[u & 1] = scale4<BITS, DT>(raw[u % D], sc);
                 __builtin_amdgcn_sched_barrier(0);
                 if (u + D < U) {
-                    raw[u % D] = lookup_step<BITS, DT, true>(st.w[(u + D) % R], (u + D) / R, la);
+                    raw[u % D] = lookup_step<BITS, DT, PERM>(st.w[(u + D) % R], (u + D) / R, la_item);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -243,7 +335,21 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
         __builtin_amdgcn_sched_barrier(0);
     }
     stamp(kTraceIssued);
-    {
+    if constexpr (RLUT) {
+        // the raw tables go to LDS -- into the item slots' area, which nothing uses before the K loop -- and
+        // the copies are built from there, while the first tiles are in flight
+        const int words = A * (rowlut16_stage_bytes<BITS>() / 4);
+        char* stage = reinterpret_cast<char*>(slots);
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int i = tid + k * p.NW * 64;
+            if (i < words) *reinterpret_cast<uint32_t*>(stage + 4 * i) = rowtab_raw[k];
+        }
+        __syncthreads();
+        rowlut16_build<BITS, DT>(lut, stage, A, tid, p.NW * 64);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+    } else {
         // the table is built while the first tiles are in flight (its own reads were issued before them)
         LutSeed seed = lut_seed;
         asm volatile("" : "+v"(seed.w[0]), "+v"(seed.w[1]), "+v"(seed.w[2]), "+v"(seed.w[3]));
@@ -271,7 +377,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
         for (; j + P < p.IT; j += P) {
 #pragma unroll
             for (int q = 0; q < P; ++q) {
-                compute_stage(st[q], cur.kt0 + j + q, j + q);
+                compute_stage(st[q], cur.kt0 + j + q, j + q, cur.tab);
                 __builtin_amdgcn_sched_barrier(0);
                 stamp(kTraceFirstTile);
                 load_stage(st[q], cur, j + q + P);
@@ -285,7 +391,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
         const Item nxt = locate(next);
 #pragma unroll
         for (int q = 0; q < P; ++q) {
-            compute_stage(st[q], cur.kt0 + j + q, j + q);
+            compute_stage(st[q], cur.kt0 + j + q, j + q, cur.tab);
             __builtin_amdgcn_sched_barrier(0);
             stamp(kTraceFirstTile);
             load_stage(st[q], nxt, q);

@@ -115,13 +115,13 @@ hipError_t launch_rowlut(int mb, int xm, bool sch, const MatmulParams& p, hipStr
     return hipErrorInvalidValue;
 }
 
-// Work-queue kernel for M <= 4: two tiles in flight, R = 1 or 2.
-template <int GROUP, int R>
+// Work-queue kernel for M <= 4: two tiles in flight, R = 1 or 2; RLUT: one table per output row (R = 1).
+template <int GROUP, int R, bool RLUT = false>
 hipError_t launch_decode_one(const DecodeParams& p, int lds_bytes, hipStream_t stream) {
     if constexpr (!decode_instance_exists(LUTQ_INST_BITS, Tab<LUTQ_INST_BITS, LUTQ_INST_DT>::WIDE, R)) {
         return hipErrorInvalidValue;
     } else {
-    auto kernel = decode_kernel<LUTQ_INST_BITS, GROUP, R, LUTQ_INST_DT, 2>;
+    auto kernel = decode_kernel<LUTQ_INST_BITS, GROUP, R, LUTQ_INST_DT, 2, false, RLUT>;
     if (lds_bytes > 64 * 1024) {
         static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -133,7 +133,8 @@ hipError_t launch_decode_one(const DecodeParams& p, int lds_bytes, hipStream_t s
 }
 
 template <int GROUP>
-hipError_t launch_decode_group(int r, const DecodeParams& p, int lds_bytes, hipStream_t stream) {
+hipError_t launch_decode_group(int r, bool rowlut, const DecodeParams& p, int lds_bytes, hipStream_t stream) {
+    if (rowlut) return r == 1 ? launch_decode_one<GROUP, 1, true>(p, lds_bytes, stream) : hipErrorInvalidValue;
     if (r == 1) return launch_decode_one<GROUP, 1>(p, lds_bytes, stream);
     if (r == 2) return launch_decode_one<GROUP, 2>(p, lds_bytes, stream);
     return hipErrorInvalidValue;
@@ -198,13 +199,13 @@ hipError_t LUTQ_NAME(launch_matmul_rowlut_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int g
     return hipErrorInvalidValue;
 }
 
-hipError_t LUTQ_NAME(launch_decode_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int r, const DecodeParams& p, int lds_bytes,
+hipError_t LUTQ_NAME(launch_decode_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int r, bool rowlut, const DecodeParams& p, int lds_bytes,
                                                                     hipStream_t stream) {
     switch (group) {
-        case 32: return launch_decode_group<32>(r, p, lds_bytes, stream);
-        case 64: return launch_decode_group<64>(r, p, lds_bytes, stream);
-        case 128: return launch_decode_group<128>(r, p, lds_bytes, stream);
-        case 256: return launch_decode_group<256>(r, p, lds_bytes, stream);
+        case 32: return launch_decode_group<32>(r, rowlut, p, lds_bytes, stream);
+        case 64: return launch_decode_group<64>(r, rowlut, p, lds_bytes, stream);
+        case 128: return launch_decode_group<128>(r, rowlut, p, lds_bytes, stream);
+        case 256: return launch_decode_group<256>(r, rowlut, p, lds_bytes, stream);
     }
     return hipErrorInvalidValue;
 }

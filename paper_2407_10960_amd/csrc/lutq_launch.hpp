@@ -37,7 +37,7 @@ inline bool matmul_instance_exists(int bits, bool bf16, int r, int mb, int stage
                                                 hipStream_t stream);                                 \
     hipError_t launch_dequant_b##B##_##DT(int group, const DequantParams& p, int grid, int lds_bytes, \
                                           hipStream_t stream);                                       \
-    hipError_t launch_decode_b##B##_##DT(int group, int r, const DecodeParams& p, int lds_bytes,     \
+    hipError_t launch_decode_b##B##_##DT(int group, int r, bool rowlut, const DecodeParams& p, int lds_bytes, \
                                          hipStream_t stream);                                        \
     hipError_t launch_rows_b##B##_##DT(int group, int mb, int amax, const RowsParams& p, int lds_bytes, \
                                        hipStream_t stream);

@@ -447,12 +447,15 @@ def test_one_table_per_output_row(lutq, bits, dtype):
     """lutq_matmul_channel (Section 2.3: tables at the output-channel level) against the oracle: one-hot
     activations read the dequantised weights back bit for bit, products match for every M class, group
     sizes with the chunked and the per-tile scale path, row counts that make one workgroup walk several
-    row blocks and K ranges cut across workgroups; identical rows reproduce lutq_matmul exactly."""
+    row blocks and K ranges cut across workgroups, and for M <= 4 (the work-queue kernel with the tables of
+    all of a workgroup's row blocks resident) one to eight row blocks per workgroup in even and uneven
+    shares; identical rows reproduce lutq_matmul exactly."""
     import torch
     rng = np.random.default_rng(100 + bits)
     E = 1 << bits
     for (N, K, group, Ms) in [(48, 2 * tk(bits), 64, (32,)), (208, 8 * tk(bits), 128, (1, 4, 7, 16, 32)),
-                              (16 * 300, 2048, 32, (2, 40)), (80, 3 * tk(bits), 32, (5,))]:
+                              (16 * 300, 2048, 32, (2, 40)), (80, 3 * tk(bits), 32, (5,)),
+                              (16 * 600, 1024, 64, (1, 3)), (16 * 1800, 4 * tk(bits), 64, (4,)), (64, 3 * tk(bits), 32, (2,))]:
         base = gen.make_case(700 + N, 32, N, K, bits, group, dtype, "random_index")
         Tn = gen.encode16(rng.standard_normal((N, E)), dtype)
         d = DeviceCase(lutq, base)
@@ -485,6 +488,12 @@ def test_one_table_per_output_row(lutq, bits, dtype):
     c = gen.make_case(800 + bits, 3, 128, 4 * tk(bits), bits, 64, dtype, "nf")
     d = DeviceCase(lutq, c)
     Y1 = torch.empty((3, 128), dtype=torch_dtype(dtype), device="cuda")
+    lutq.lutq_matmul_channel(d.X, d.packed, d.S, to_dev(np.tile(c.T, (128, 1)), dtype), bits, 64, Y1, d.ws)
+    Y2 = d.matmul(lutq, plan=lutq.Plan(1, 8, 4, 2, 1, 2, 4))      # the work queue's shape for this problem
+    assert np.array_equal(to_bits(Y1), to_bits(Y2))
+    c = gen.make_case(810 + bits, 9, 128, 4 * tk(bits), bits, 64, dtype, "nf")
+    d = DeviceCase(lutq, c)
+    Y1 = torch.empty((9, 128), dtype=torch_dtype(dtype), device="cuda")
     lutq.lutq_matmul_channel(d.X, d.packed, d.S, to_dev(np.tile(c.T, (128, 1)), dtype), bits, 64, Y1, d.ws)
     Y2 = d.matmul(lutq, plan=lutq.Plan(1, 8, 8, 2, 1))
     assert np.array_equal(to_bits(Y1), to_bits(Y2))
