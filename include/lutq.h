@@ -262,10 +262,12 @@ lutq_status lutq_matmul_static(const void* X, const void* packed, const void* sc
  *        W^[n, k] = round16( T[n][Q[n, k]] * S[n, k / group_size] )
  *   luts    device, [N, 2^bits] row-major, dtype, 16-byte aligned
  *   every other argument as in lutq_matmul (scales of 1.0 give tables without group scales).
- * A workgroup holds the tables of one 16-row block at a time and rebuilds its on-chip copies for
- * every row block it works on, so each call costs one table build per row block instead of one per
- * workgroup; the work decomposition is fixed (one row block per workgroup, K split over its waves
- * and, for few row blocks, over workgroups).  Errors: those of lutq_matmul. */
+ * M <= 4 with K / group_size a multiple of 8: the work-queue kernel with the tables of all of a
+ * workgroup's row blocks built once and resident (sixteen copies per row block: the four lanes that
+ * work on a row share one).  Otherwise a workgroup holds the tables of one 16-row block at a time and
+ * rebuilds its on-chip copies for every row block it works on (one row block per workgroup, K split
+ * over its waves and, for few row blocks, over workgroups).  The work decomposition is the library's
+ * in both cases.  Errors: those of lutq_matmul. */
 lutq_status lutq_matmul_channel(const void* X, const void* packed, const void* scales, const void* luts,
                                 int bits, int group_size, int64_t M, int64_t N, int64_t K,
                                 lutq_dtype dtype, void* Y,
