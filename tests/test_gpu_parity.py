@@ -551,9 +551,9 @@ FULL_SIZE = [
     ("70B o W3 g64 bf16", 8192, 8192, 3, 64, "bf16", 16),
     ("8192^2 W2 g32", 8192, 8192, 2, 32, "f16", 4),
     # one case per branch of the default work decomposition
-    ("8B o W4 g128 M1 (8 waves split K)", 4096, 4096, 4, 128, "f16", 1),
+    ("8B o W4 g128 M1 (work queue, one item per wave)", 4096, 4096, 4, 128, "f16", 1),
     ("8B qkv W4 g128 M1 (one workgroup per row group)", 6144, 4096, 4, 128, "f16", 1),
-    ("70B qkv W4 g64 bf16 M1 (5 teams, every tile split in two)", 10240, 8192, 4, 64, "bf16", 1),
+    ("70B qkv W4 g64 bf16 M1 (work queue, uneven shares of 2 and 3 row blocks)", 10240, 8192, 4, 64, "bf16", 1),
     ("70B o W4 g64 bf16 M1 (R = 2)", 8192, 8192, 4, 64, "bf16", 1),
     ("8B gate_up W3 g128 M1 (7 teams x 2)", 28672, 4096, 3, 128, "f16", 1),
     ("8B gate_up W3 g128 M8 (R = 4, plain activations)", 28672, 4096, 3, 128, "f16", 8),
@@ -577,6 +577,11 @@ FULL_SIZE = [
     ("8B down W4 M8 (packed activation loads for 5..8 rows)", 4096, 14336, 4, 128, "f16", 8),
     ("1024x4096 W4 M32 (small row groups cut in two)", 1024, 4096, 4, 128, "f16", 32),
     ("70B qkv W4 g64 bf16 M28 (eight teams, four tiles in flight)", 10240, 8192, 4, 64, "bf16", 28),
+    # the row-streaming kernel where it is the default
+    ("70B qkv W4 g64 M16 (row streaming, shares of 2 and 3 row blocks, four side by side)", 10240, 8192, 4, 64, "f16", 16),
+    ("8B gate_up W3 g128 bf16 M16 (row streaming, eight side by side)", 28672, 4096, 3, 128, "bf16", 16),
+    ("8B gate_up W4 g128 bf16 M32 (row streaming, more than 16 rows)", 28672, 4096, 4, 128, "bf16", 32),
+    ("22016x4096 W4 M24 (row streaming, shares of 5 and 6 row blocks)", 22016, 4096, 4, 128, "f16", 24),
 ]
 
 
