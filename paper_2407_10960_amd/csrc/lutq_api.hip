@@ -145,7 +145,8 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
     bool take = false;
     if (bits == 4) take = (per >= 5 && amax <= 8 && M > 8 && (uneven || bf16)) || (uneven && per >= 2 && amax <= 4 && M <= (bf16 ? 24 : 16));
     else if (bits == 3) take = per >= 5 && amax <= 8 && M > 8 && M <= 16;
-    return take && rows_decomp(bits, bf16, M, N, K, group_size, cus, out);
+    // (only where one pass covers the workgroup's row blocks: a second pass costs more than the teams)
+    return take && rows_decomp(bits, bf16, M, N, K, group_size, cus, out) && out->r >= amax;
 }
 
 // LDS bytes of a work-queue launch

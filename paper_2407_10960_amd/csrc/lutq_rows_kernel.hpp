@@ -24,6 +24,8 @@
 //     weights.
 #pragma once
 
+#include <type_traits>
+
 #include "lutq_matmul_kernel.hpp"
 
 namespace lutq {
@@ -61,11 +63,16 @@ struct RowsParams {
 // bf16 table).  The estimate decides how many waves an instance is compiled for (4-bit fp16, M > 16: 152
 // registers and twelve waves with four row blocks side by side, 221 and eight waves with eight; M <= 16
 // with eight: 153 and twelve waves); 0 = no such instance.
-__host__ __device__ constexpr int rows_tiles_in_flight(int bits, int amax) { return bits == 4 && amax == 8 ? 8 : 4; }
+__host__ __device__ constexpr int rows_tiles_in_flight(int bits, int amax) { return 4; }   // (eight measured no faster)
+// The activations of the next K tile are fetched a whole tile ahead into a second set of registers where that
+// measured faster (4-bit fp16 beyond sixteen rows: 8B gate+up M = 32 21.9 -> 20.8 us); elsewhere the second set
+// costs waves (twelve -> eight) or the instance, and the next tile's activations are fetched step by step
+// during the tile's last row block instead.
+__host__ __device__ constexpr bool rows_x_double(int bits, int mb, bool wide_table) { return bits == 4 && mb == 2 && !wide_table; }
 __host__ __device__ constexpr int rows_max_waves(int bits, int mb, int amax, bool wide_table) {
     const int steps = bits == 4 ? 4 : 8;
     const int regs = amax * mb * 4 + steps * mb * 4 + (bits == 4 ? 84 : bits == 3 ? 116 : 108) + (wide_table ? 28 : 0)
-                   + 5 * (rows_tiles_in_flight(bits, amax) - 4);
+                   + (bits == 4 && amax == 8 ? 20 : 0) + (rows_x_double(bits, mb, wide_table) ? steps * mb * 4 + 8 : 0);
     return regs <= 128 ? 16 : regs <= 168 ? 12 : regs <= 240 ? 8 : 0;
 }
 
@@ -82,6 +89,7 @@ void rows_kernel(const RowsParams p) {
     constexpr int D = 4;                               // steps whose table reads are in flight ahead of their use
     static_assert(STEPS % D == 0, "the ring of table reads runs on from one tile into the next");
     constexpr int NST = rows_tiles_in_flight(BITS, AMAX);   // weight tiles (and their scales) in flight per wave
+    constexpr bool XDB = rows_x_double(BITS, MB, Tab<BITS, DT>::WIDE);
     static_assert(AMAX % NST == 0, "the row blocks of a pass are walked in rounds of the pipeline's stages");
 
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.packed_bytes), "s"(p.scale_bytes),
@@ -131,8 +139,7 @@ void rows_kernel(const RowsParams p) {
         ScaleWords<NS> s;
     };
     // Slot (kt, a) of pass p0, a = 0 .. AMAX - 1: weight tile and scales of row block rb_first + p0 + a - skip,
-    // where skip = AMAX - (row blocks of the pass): a short pass leaves its FIRST slots empty, so that the
-    // last slot, which also fetches the next tile's activations, always holds a row block.  Every slot
+    // where skip = AMAX - (row blocks of the pass): a short pass leaves its first slots empty.  Every slot
     // issues the same loads, in range or not (out of range: zeros, no memory traffic), and no load sits
     // under a branch: the waits on the load counter then name exactly the tile they need and leave the
     // younger ones in flight.
@@ -170,15 +177,20 @@ void rows_kernel(const RowsParams p) {
             load_w(st[a], p0, skip, ka, a);
             __builtin_amdgcn_sched_barrier(0);
         }
-        u32x4 bx[STEPS][MB];
-        auto load_x_step = [&](int kt, int s) {
+        // Activations of two K tiles: the one being multiplied and the next one, asked for a whole tile ahead.  (A
+        // load covers sixteen rows 2K bytes apart -- sixteen requests to one L2 channel -- and takes its time.)
+        u32x4 bx[XDB ? 2 : 1][STEPS][MB];
+        auto load_x_step = [&](auto buf, int kt, int s) {
             const uint32_t tx = kt < kb ? (uint32_t)kt * (TK * 2) : kOutOfRange;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
-                bx[s][mb] = __builtin_amdgcn_raw_buffer_load_b128(rX, tx + xlane[mb] + 64u * s, 0, kAuxNone);
+                bx[decltype(buf)::value][s][mb] = __builtin_amdgcn_raw_buffer_load_b128(rX, tx + xlane[mb] + 64u * s, 0, kAuxNone);
         };
+        auto load_x = [&](auto buf, int kt) {
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) load_x_step(ka, s);
+            for (int s = 0; s < STEPS; ++s) load_x_step(buf, kt, s);
+        };
+        load_x(std::integral_constant<int, 0>{}, ka);
         __builtin_amdgcn_sched_barrier(0);
         {
             // The pass's scales: rows (rb_first + p0) * 16 onwards, na * 16 rows of SG2 bytes, one contiguous
@@ -212,50 +224,67 @@ void rows_kernel(const RowsParams p) {
         for (int s = 0; s < D; ++s) raw[s] = lookup_step<BITS, DT, true>(st[0].w, s, la);
         __builtin_amdgcn_sched_barrier(0);
 
-        for (int kt = ka; kt < kb; ++kt) {
+        // One K tile: buf = which set of bx holds its activations.  With two sets a tile beyond the wave's range
+        // (the second of a pair when the wave owns an odd number) issues the same loads, out of range, and
+        // multiplies nothing.  With one set the tile's last slot always multiplies (an empty pass slot there would
+        // be a row block of zeros: the pass's empty slots are its first ones), because the next tile's activations
+        // are fetched inside it, step by step as this tile's have had their last use.
+        auto tile = [&](auto buf, int kt) {
+            constexpr int B = decltype(buf)::value;
+            if constexpr (XDB) {
+                load_x(std::integral_constant<int, B ^ 1>{}, kt + 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const bool live = !XDB || kt < kb;
 #pragma unroll
             for (int a = 0; a < AMAX; ++a) {
-                {
-                    Stage& cur = st[a % NST];
-                    const Stage& nxt = st[(a + 1) % NST];
-                    if (a == AMAX - 1 || a >= skip) {
-                        // dequantise the tile step by step and multiply it into row block a's accumulators
-                        u32x4 aop[2];
+                Stage& cur = st[a % NST];
+                const Stage& nxt = st[(a + 1) % NST];
+                if ((!XDB && a == AMAX - 1) || (live && a >= skip)) {
+                    // dequantise the tile step by step and multiply it into row block a's accumulators
+                    u32x4 aop[2];
 #pragma unroll
-                        for (int s = 0; s <= STEPS; ++s) {
-                            if (s < STEPS) {
-                                const ScaleReg<DT> sc = scale_of<DT, NS>(cur.s, s / SPG);
-                                aop[s & 1] = scale4<BITS, DT>(raw[s % D], sc);
-                                __builtin_amdgcn_sched_barrier(0);
-                                raw[s % D] = s + D < STEPS ? lookup_step<BITS, DT, true>(cur.w, s + D, la)
-                                                           : lookup_step<BITS, DT, true>(nxt.w, s + D - STEPS, la);
-                                __builtin_amdgcn_sched_barrier(0);
-                            }
-                            if (s > 0) {
+                    for (int s = 0; s <= STEPS; ++s) {
+                        if (s < STEPS) {
+                            const ScaleReg<DT> sc = scale_of<DT, NS>(cur.s, s / SPG);
+                            aop[s & 1] = scale4<BITS, DT>(raw[s % D], sc);
+                            __builtin_amdgcn_sched_barrier(0);
+                            raw[s % D] = s + D < STEPS ? lookup_step<BITS, DT, true>(cur.w, s + D, la)
+                                                       : lookup_step<BITS, DT, true>(nxt.w, s + D - STEPS, la);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if (s > 0) {
 #pragma unroll
-                                for (int mb = 0; mb < MB; ++mb)
-                                    acc[a][mb] = mfma16x16x32<DT>(aop[(s - 1) & 1], bx[s - 1][mb], acc[a][mb]);
-                                __builtin_amdgcn_sched_barrier(0);
-                                // the tile's last row block: this step's activations have had their last
-                                // use, the next tile's take their registers
+                            for (int mb = 0; mb < MB; ++mb)
+                                acc[a][mb] = mfma16x16x32<DT>(aop[(s - 1) & 1], bx[B][s - 1][mb], acc[a][mb]);
+                            __builtin_amdgcn_sched_barrier(0);
+                            if constexpr (!XDB) {
                                 if (a == AMAX - 1) {
-                                    load_x_step(kt + 1, s - 1);
+                                    load_x_step(std::integral_constant<int, 0>{}, kt + 1, s - 1);
                                     __builtin_amdgcn_sched_barrier(0);
                                 }
                             }
                         }
-                    } else {
-                        // an empty slot: only the next slot's first table reads
-#pragma unroll
-                        for (int s = 0; s < D; ++s) raw[s] = lookup_step<BITS, DT, true>(nxt.w, s, la);
-                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    // the slot NST ahead: further along this K tile, or among the first ones of the next
-                    const bool here = a + NST < AMAX;
-                    load_slot(cur, p0, skip, here ? kt : kt + 1, here ? a + NST : a + NST - AMAX);
+                } else {
+                    // an empty slot: only the next slot's first table reads
+#pragma unroll
+                    for (int s = 0; s < D; ++s) raw[s] = lookup_step<BITS, DT, true>(nxt.w, s, la);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                // the slot NST ahead: further along this K tile, or among the first ones of the next
+                const bool here = a + NST < AMAX;
+                load_slot(cur, p0, skip, here ? kt : kt + 1, here ? a + NST : a + NST - AMAX);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        };
+        if constexpr (XDB) {
+            for (int kt = ka; kt < kb; kt += 2) {
+                tile(std::integral_constant<int, 0>{}, kt);
+                tile(std::integral_constant<int, 1>{}, kt + 1);
+            }
+        } else {
+            for (int kt = ka; kt < kb; ++kt) tile(std::integral_constant<int, 0>{}, kt);
         }
 
         // ---- add the waves' sums in wave order, RPR row blocks per round, and store ----

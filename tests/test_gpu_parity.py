@@ -699,6 +699,12 @@ def test_row_streaming_plans_match_oracle(lutq, bits, dtype):
             c = gen.make_case(700 + M, M, N, K, bits, group, dtype, lut)
             d = DeviceCase(lutq, c)
             plans = [lutq.Plan(0, 0, 0, 0, 0, RW, 0)]
+            if not any(rows_waves(lutq, bits, dtype, M, N, K, group, side) for side in (4, 8)):
+                # no instance for this bit width, dtype and M (the registers do not hold it): refused
+                with pytest.raises(lutq.LutqError) as e:
+                    d.matmul(lutq, plan=plans[0])
+                assert e.value.code == 10
+                continue
             for side in (4, 8):
                 w = rows_waves(lutq, bits, dtype, M, N, K, group, side)
                 if w == 0:
