@@ -264,7 +264,8 @@ lutq_status lutq_matmul_static(const void* X, const void* packed, const void* sc
  *   every other argument as in lutq_matmul (scales of 1.0 give tables without group scales).
  * M <= 4 with K / group_size a multiple of 8: the work-queue kernel with the tables of all of a
  * workgroup's row blocks built once and resident (sixteen copies per row block: the four lanes that
- * work on a row share one).  Otherwise a workgroup holds the tables of one 16-row block at a time and
+ * work on a row share one).  5 <= M <= 32 with at least two row blocks per compute unit: the row-streaming
+ * kernel with the tables of four row blocks at a time.  Otherwise a workgroup holds the tables of one 16-row block at a time and
  * rebuilds its on-chip copies for every row block it works on (one row block per workgroup, K split
  * over its waves and, for few row blocks, over workgroups).  The work decomposition is the library's
  * in both cases.  Errors: those of lutq_matmul. */

@@ -103,9 +103,14 @@ int rows_instance_waves(int bits, bool bf16, int mb, int amax) {
 // waves as it was compiled for (no more than K tiles).
 // LDS offset of the row-streaming kernel's reduction slots (behind the table and the scales of `side` row
 // blocks), and how many row blocks one round of the reduction can hold (0: the launch does not fit)
-int rows_red_off(int bits, int side, int sg2) { return rows_table_bytes(bits) + side * 16 * (sg2 + 16); }
-int rows_blocks_per_round(int bits, int side, int sg2, int mb, int nw) {
-    const int room = 160 * 1024 - rows_red_off(bits, side, sg2);
+// (tab16 > 0: one table per output row -- `side` sixteen-copy tables of tab16 bytes and their raw rows instead of
+// the shared table)
+int rows_red_off(int bits, int side, int sg2, int tab16 = 0) {
+    const int tables = tab16 > 0 ? side * (tab16 + 16 * (1 << bits) * 2) : rows_table_bytes(bits);
+    return tables + side * 16 * (sg2 + 16);
+}
+int rows_blocks_per_round(int bits, int side, int sg2, int mb, int nw, int tab16 = 0) {
+    const int room = 160 * 1024 - rows_red_off(bits, side, sg2, tab16);
     return room <= 0 ? 0 : room / (mb * nw * 1024);
 }
 
@@ -566,7 +571,7 @@ decode_launcher pick_decode(int bits, lutq_dtype dt) {
     if (dt == LUTQ_F16) return bits == 2 ? launch_decode_b2_F16 : bits == 3 ? launch_decode_b3_F16 : launch_decode_b4_F16;
     return bits == 2 ? launch_decode_b2_BF16 : bits == 3 ? launch_decode_b3_BF16 : launch_decode_b4_BF16;
 }
-typedef hipError_t (*rows_launcher)(int, int, int, const RowsParams&, int, hipStream_t);
+typedef hipError_t (*rows_launcher)(int, int, int, bool, const RowsParams&, int, hipStream_t);
 rows_launcher pick_rows(int bits, lutq_dtype dt) {
     if (dt == LUTQ_F16) return bits == 2 ? launch_rows_b2_F16 : bits == 3 ? launch_rows_b3_F16 : launch_rows_b4_F16;
     return bits == 2 ? launch_rows_b2_BF16 : bits == 3 ? launch_rows_b3_BF16 : launch_rows_b4_BF16;
@@ -683,6 +688,7 @@ struct Prepared {
     DecodeParams dp;
     int queue_lds;
     bool rows;                // row-streaming kernel: rp, rows_lds, r = row blocks side by side
+    bool rows_rowlut;         // ... with one table per output row
     RowsParams rp;
     int rows_lds;
 };
@@ -690,7 +696,8 @@ struct Prepared {
 // Validates a row-streaming launch and fills out->rp.  `d`: r = row blocks side by side (4 or 8), grid,
 // nw, rs = row blocks per workgroup (the whole part of row blocks / grid).
 lutq_status prepare_rows(const void* X, const void* packed, const void* scales, const void* lut, int bits,
-                         int group_size, int64_t M, int64_t N, int64_t K, bool bf16, void* Y, const Decomp& d, Prepared* out) {
+                         int group_size, int64_t M, int64_t N, int64_t K, bool bf16, void* Y, const Decomp& d, Prepared* out,
+                         bool rowlut = false) {
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1;
     const int max_waves = rows_instance_waves(bits, bf16, mb, d.r);
@@ -702,9 +709,11 @@ lutq_status prepare_rows(const void* X, const void* packed, const void* scales, 
     const int sg2 = (int)(K / group_size) * 2;
     if (sg2 % 16 != 0) return LUTQ_ERR_PLAN;
     const int srow = sg2 + 16;
-    const int red_off = rows_red_off(bits, d.r, sg2);
+    if (rowlut && d.r != 4) return LUTQ_ERR_PLAN;           // per-row tables: four row blocks side by side
+    const int tab16 = rowlut ? rowlut16_table_bytes(bits, bf16) : 0;
+    const int red_off = rows_red_off(bits, d.r, sg2, tab16);
     // rounds of the final reduction: as many row blocks at a time as LDS holds beside the table and the scales
-    int rpr = rows_blocks_per_round(bits, d.r, sg2, mb, d.nw);
+    int rpr = rows_blocks_per_round(bits, d.r, sg2, mb, d.nw, tab16);
     if (rpr > d.r) rpr = d.r;
     if (rpr > amax) rpr = amax;
     if (rpr < 1) return LUTQ_ERR_PLAN;
@@ -731,6 +740,7 @@ lutq_status prepare_rows(const void* X, const void* packed, const void* scales, 
     q.s_magic = (uint32_t)((1ull << 32) / (uint64_t)q.s_units + 1);
     q.SROW = srow;
     q.red_off = red_off;
+    q.tab_total = d.r * tab16;
     q.lut_ltpe = bits == 2 ? lut_log2_threads_per_row<2>(d.nw * 64)
                : bits == 3 ? lut_log2_threads_per_row<3>(d.nw * 64) : lut_log2_threads_per_row<4>(d.nw * 64);
     if (env_switches().verbose)
@@ -738,6 +748,7 @@ lutq_status prepare_rows(const void* X, const void* packed, const void* scales, 
                      d.r, d.grid, d.nw, d.rs, extra, rpr, lds);
     out->queue = false;
     out->rows = true;
+    out->rows_rowlut = rowlut;
     out->rp = q;
     out->rows_lds = lds;
     out->r = d.r;
@@ -869,7 +880,25 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
     out->queue = false;
     out->queue_rowlut = false;
     out->rows = false;
+    out->rows_rowlut = false;
     if (rowlut && user_plan && user_plan->scheduling > LUTQ_SCHED_TEAMS) return LUTQ_ERR_PLAN;
+    if (rowlut && !user_plan && M > 4 && nb >= 2 * (int64_t)di.cus && ((K / group_size) * 2) % 16 == 0) {
+        // one table per output row, 5..32 rows, at least two row blocks per compute unit: the row-streaming
+        // kernel with the tables of four row blocks at a time (the teams' per-row-table kernel holds one row
+        // block's and fetches the activations again for every row block)
+        const int grid = di.cus;
+        const int64_t per = nb / grid;
+        int nw = rows_instance_waves(bits, bf16, mb, 4);
+        if (nw > kt) nw = (int)(kt < 4 ? 4 : kt);
+        if (per <= 64 && nw >= 4 && rows_blocks_per_round(bits, 4, (int)(K / group_size) * 2, mb, nw, rowlut16_table_bytes(bits, bf16)) >= 1) {
+            Decomp q;
+            q.r = 4; q.grid = grid; q.nw = nw; q.stages = 2; q.rs = (int)per; q.queue = 0; q.it = 0; q.rows = 1;
+            const lutq_status qs = prepare_rows(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out, true);
+            if (qs == LUTQ_OK) return qs;
+            out->rows = false;
+            out->rows_rowlut = false;
+        }
+    }
     if (rowlut && !user_plan) {
         // one table per output row, M <= 4: the work-queue kernel with all of a workgroup's tables resident
         Decomp q;
@@ -1050,7 +1079,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
 
 lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dtype dtype, void* stream) {
     if (q.rows) {
-        const hipError_t e = pick_rows(bits, dtype)(group_size, q.mb, q.r, q.rp, q.rows_lds, static_cast<hipStream_t>(stream));
+        const hipError_t e = pick_rows(bits, dtype)(group_size, q.mb, q.r, q.rows_rowlut, q.rp, q.rows_lds, static_cast<hipStream_t>(stream));
         return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
     }
     if (q.queue) {

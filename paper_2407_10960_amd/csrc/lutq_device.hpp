@@ -256,6 +256,69 @@ template <int BITS, typename DT>
 __host__ __device__ constexpr int perm_log2_copies() {
     return Tab<BITS, DT>::ENTRY_BYTES == 8 ? 5 : 6;
 }
+
+// ---------------------------------------------------------------------------------------
+// Per-row tables, sixteen copies: the table of row c of a row block is copy c (log2 copies = 4), so
+// lane l reads copy l % 16 = its row, with the generic (shift + add) entry address.
+// ---------------------------------------------------------------------------------------
+template <int BITS, typename DT>
+__host__ __device__ constexpr int rowlut16_bytes() { return lut_lds_bytes<BITS, DT>(4); }
+// bytes of one row block's raw tables (16 rows x 2^b 16-bit values), staged in LDS for the build
+template <int BITS>
+__host__ __device__ constexpr int rowlut16_stage_bytes() { return 16 * (1 << BITS) * 2; }
+
+// Builds the tables of `nrb` row blocks at `tables` (rowlut16_bytes apart) from their raw rows at `stage`
+// (both LDS).  Thread (row block a, row c, lower index lo) reads the row's 2^b values once and writes the
+// entries (lo, hi) for every upper index hi: the lanes of one store cover rows c = 0..15 (one entry's
+// sixteen copies, contiguous) of four consecutive entries, so stores do not conflict.
+template <int BITS, typename DT>
+__device__ __forceinline__ void rowlut16_build(char* tables, const char* stage, int nrb, int tid, int nthreads) {
+    constexpr int E = 1 << BITS;
+    constexpr int LOWN = BITS == 3 ? 8 : 16, LOWL = BITS == 3 ? 3 : 4;
+    constexpr bool WIDE = Tab<BITS, DT>::WIDE;
+    constexpr int EB = Tab<BITS, DT>::ENTRY_BYTES;
+    constexpr int SH = 4 + (EB == 8 ? 3 : 2);
+    const int combos = nrb * 16 * LOWN;
+    for (int idx = tid; idx < combos; idx += nthreads) {
+        const int c = idx & 15, lo = (idx >> 4) & (LOWN - 1), a = idx >> (4 + LOWL);
+        const char* row = stage + (size_t)(a * 16 + c) * (E * 2);
+        uint32_t t[8] = {0, 0, 0, 0, 0, 0, 0, 0};               // the row's values, two per word
+        if constexpr (BITS == 4) {
+            const u32x4 v0 = *reinterpret_cast<const u32x4*>(row), v1 = *reinterpret_cast<const u32x4*>(row + 16);
+            t[0] = v0.x; t[1] = v0.y; t[2] = v0.z; t[3] = v0.w; t[4] = v1.x; t[5] = v1.y; t[6] = v1.z; t[7] = v1.w;
+        } else if constexpr (BITS == 3) {
+            const u32x4 v0 = *reinterpret_cast<const u32x4*>(row);
+            t[0] = v0.x; t[1] = v0.y; t[2] = v0.z; t[3] = v0.w;
+        } else {
+            const u32x2 v0 = *reinterpret_cast<const u32x2*>(row);
+            t[0] = v0.x; t[1] = v0.y;
+        }
+        auto val = [&](int q) -> uint32_t { return (q & 1) ? (t[q >> 1] >> 16) : (t[q >> 1] & 0xffffu); };   // q is a constant
+        const uint16_t* rowv = reinterpret_cast<const uint16_t*>(row);
+        uint32_t first;                                         // the part of the entry that lo decides
+        int e_lo;
+        if constexpr (BITS == 2) {
+            first = (uint32_t)rowv[lo & 3] | ((uint32_t)rowv[lo >> 2] << 16);
+            e_lo = lo;
+        } else {
+            first = rowv[lo];
+            e_lo = BITS == 3 ? ((lo & 3) | ((lo >> 2) << 4)) : lo;
+        }
+        char* dst = tables + (size_t)a * rowlut16_bytes<BITS, DT>() + ((size_t)e_lo << SH) + c * EB;
+#pragma unroll
+        for (int hi = 0; hi < LOWN; ++hi) {
+            const int e_hi = BITS == 3 ? (((hi & 3) << 2) | ((hi >> 2) << 5)) : (hi << 4);
+            if constexpr (BITS == 2) {
+                *reinterpret_cast<u32x2*>(dst + (e_hi << SH)) = u32x2{first, val(hi & 3) | (val(hi >> 2) << 16)};
+            } else if constexpr (WIDE) {
+                *reinterpret_cast<u32x2*>(dst + (e_hi << SH)) = u32x2{first << 16, val(hi) << 16};
+            } else {
+                *reinterpret_cast<uint32_t*>(dst + (e_hi << SH)) = first | (val(hi) << 16);
+            }
+        }
+    }
+}
+
 // bytes of the fused kernel's table: every entry is one 256-byte row, whatever it holds
 template <int BITS>
 __host__ __device__ constexpr int lut_row_table_bytes() { return Geo<BITS>::ENTRIES * 256; }

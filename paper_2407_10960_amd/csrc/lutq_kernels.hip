@@ -141,14 +141,14 @@ hipError_t launch_decode_group(int r, bool rowlut, const DecodeParams& p, int ld
 }
 
 // Row-streaming kernel for 5..32 activation rows: MB halves of M, AMAX = 4 or 8 row blocks side by side.
-template <int GROUP, int MB, int AMAX>
+template <int GROUP, int MB, int AMAX, bool RLUT = false>
 hipError_t launch_rows_one(const RowsParams& p, int lds_bytes, hipStream_t stream) {
     constexpr int max_waves = rows_max_waves(LUTQ_INST_BITS, MB, AMAX, Tab<LUTQ_INST_BITS, LUTQ_INST_DT>::WIDE);
     if constexpr (max_waves == 0) {
         return hipErrorInvalidValue;
     } else {
         if (p.NW > max_waves) return hipErrorInvalidValue;
-        auto kernel = rows_kernel<LUTQ_INST_BITS, GROUP, MB, LUTQ_INST_DT, AMAX>;
+        auto kernel = rows_kernel<LUTQ_INST_BITS, GROUP, MB, LUTQ_INST_DT, AMAX, RLUT>;
         if (lds_bytes > 64 * 1024) {
             static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -160,7 +160,12 @@ hipError_t launch_rows_one(const RowsParams& p, int lds_bytes, hipStream_t strea
 }
 
 template <int GROUP>
-hipError_t launch_rows_group(int mb, int amax, const RowsParams& p, int lds_bytes, hipStream_t stream) {
+hipError_t launch_rows_group(int mb, int amax, bool rowlut, const RowsParams& p, int lds_bytes, hipStream_t stream) {
+    if (rowlut) {                    // one table per output row: four row blocks side by side
+        if (mb == 1 && amax == 4) return launch_rows_one<GROUP, 1, 4, true>(p, lds_bytes, stream);
+        if (mb == 2 && amax == 4) return launch_rows_one<GROUP, 2, 4, true>(p, lds_bytes, stream);
+        return hipErrorInvalidValue;
+    }
     if (mb == 1 && amax == 4) return launch_rows_one<GROUP, 1, 4>(p, lds_bytes, stream);
     if (mb == 1 && amax == 8) return launch_rows_one<GROUP, 1, 8>(p, lds_bytes, stream);
     if (mb == 2 && amax == 4) return launch_rows_one<GROUP, 2, 4>(p, lds_bytes, stream);
@@ -210,13 +215,13 @@ hipError_t LUTQ_NAME(launch_decode_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, i
     return hipErrorInvalidValue;
 }
 
-hipError_t LUTQ_NAME(launch_rows_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int amax, const RowsParams& p, int lds_bytes,
+hipError_t LUTQ_NAME(launch_rows_b, LUTQ_INST_BITS, LUTQ_INST_DT)(int group, int mb, int amax, bool rowlut, const RowsParams& p, int lds_bytes,
                                                                   hipStream_t stream) {
     switch (group) {
-        case 32: return launch_rows_group<32>(mb, amax, p, lds_bytes, stream);
-        case 64: return launch_rows_group<64>(mb, amax, p, lds_bytes, stream);
-        case 128: return launch_rows_group<128>(mb, amax, p, lds_bytes, stream);
-        case 256: return launch_rows_group<256>(mb, amax, p, lds_bytes, stream);
+        case 32: return launch_rows_group<32>(mb, amax, rowlut, p, lds_bytes, stream);
+        case 64: return launch_rows_group<64>(mb, amax, rowlut, p, lds_bytes, stream);
+        case 128: return launch_rows_group<128>(mb, amax, rowlut, p, lds_bytes, stream);
+        case 256: return launch_rows_group<256>(mb, amax, rowlut, p, lds_bytes, stream);
     }
     return hipErrorInvalidValue;
 }

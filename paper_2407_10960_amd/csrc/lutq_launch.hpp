@@ -39,7 +39,7 @@ inline bool matmul_instance_exists(int bits, bool bf16, int r, int mb, int stage
                                           hipStream_t stream);                                       \
     hipError_t launch_decode_b##B##_##DT(int group, int r, bool rowlut, const DecodeParams& p, int lds_bytes, \
                                          hipStream_t stream);                                        \
-    hipError_t launch_rows_b##B##_##DT(int group, int mb, int amax, const RowsParams& p, int lds_bytes, \
+    hipError_t launch_rows_b##B##_##DT(int group, int mb, int amax, bool rowlut, const RowsParams& p, int lds_bytes, \
                                        hipStream_t stream);
 
 // Measurement builds (phase timestamps, see TraceStamp) of the 4-bit instances that serve M <= 4 under the

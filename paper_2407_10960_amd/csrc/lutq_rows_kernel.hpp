@@ -51,11 +51,13 @@ struct RowsParams {
     uint32_t s_magic;         // 2^32 / s_units + 1 (unused when s_units == 1)
     int SROW;                 // bytes from row to row of the scales in LDS (SG2 + 16: sixteen rows, sixteen banks)
     int red_off;              // LDS offset of the reduction slots
+    int tab_total;            // RLUT: LDS bytes of the pass's per-row tables (AMAX x sixteen copies); the scales follow
     int lut_ltpe;             // log2 of the threads that build one table row together
     int G;                    // workgroups
 };
 
 // LDS of one launch: [table, 256-byte entry stride][scales of AMAX x 16 rows, SROW bytes each][RPR x MB x NW slots of 1 KiB]
+// RLUT: [AMAX tables of sixteen copies][scales][raw tables of AMAX row blocks][slots]
 
 // Registers: AMAX x MB x 4 accumulators + STEPS x MB x 4 activation operands + four weight tiles in flight
 // (eight at 4 bits with eight row blocks side by side: five registers each), the lookup ring and addresses
@@ -76,7 +78,10 @@ __host__ __device__ constexpr int rows_max_waves(int bits, int mb, int amax, boo
     return regs <= 128 ? 16 : regs <= 168 ? 12 : regs <= 240 ? 8 : 0;
 }
 
-template <int BITS, int GROUP, int MB, typename DT, int AMAX>
+// RLUT: one table per output row (p.lut = [N, 2^bits]).  The tables of the pass's row blocks are built when the
+// pass begins, sixteen copies per row block (the four lanes of a row share one; rowlut16_build), and slot a reads
+// the copies of its own row block with the generic entry address.
+template <int BITS, int GROUP, int MB, typename DT, int AMAX, bool RLUT = false>
 __global__ __launch_bounds__(64 * (rows_max_waves(BITS, MB, AMAX, Tab<BITS, DT>::WIDE) > 0 ? rows_max_waves(BITS, MB, AMAX, Tab<BITS, DT>::WIDE) : 4))
 void rows_kernel(const RowsParams p) {
     using Gm = Geo<BITS>;
@@ -95,7 +100,7 @@ void rows_kernel(const RowsParams p) {
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.packed_bytes), "s"(p.scale_bytes),
                  "s"(p.x_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.KT), "s"(p.SG2), "s"(p.SBL), "s"(p.tile_stride),
                  "s"(p.sblock_bytes), "s"(p.A), "s"(p.extra), "s"(p.NW), "s"(p.TQ), "s"(p.TR), "s"(p.RPR), "s"(p.lut_ltpe),
-                 "s"(p.s_units), "s"(p.s_magic), "s"(p.SROW), "s"(p.red_off));
+                 "s"(p.s_units), "s"(p.s_magic), "s"(p.SROW), "s"(p.red_off), "s"(p.tab_total));
 
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
@@ -104,12 +109,21 @@ void rows_kernel(const RowsParams p) {
     const int li = lane & 15;                // row inside a 16-row block (A side) / activation row (B side)
     const int lo = lane >> 4;                // K octet
     char* lut = smem;
-    char* sc = smem + LUT_BYTES;
+    char* sc = smem + (RLUT ? p.tab_total : LUT_BYTES);
     char* red = smem + p.red_off;
+    constexpr bool PERM = !RLUT;             // the one-instruction entry address needs 256-byte entries
+    constexpr int TB16 = rowlut16_bytes<BITS, DT>();
 
-    const LutSeed lut_seed = lut_fetch<BITS>(p.lut, tid, p.lut_ltpe);
+    LutSeed lut_seed{};
+    if constexpr (!RLUT) lut_seed = lut_fetch<BITS>(p.lut, tid, p.lut_ltpe);
     __builtin_amdgcn_sched_barrier(0);
-    const LutAddr la = make_lut_addr<BITS, DT>(lut, LOG2C, lane);
+    const LutAddr la = make_lut_addr<BITS, DT>(lut, RLUT ? 4 : LOG2C, lane);
+    // table of slot a (RLUT): the pass's row block a - skip; an empty slot reads the first one's
+    auto la_of = [&](int a, int skip) {
+        LutAddr r = la;
+        if constexpr (RLUT) r.lane_base += (uint32_t)(a > skip ? a - skip : 0) * (uint32_t)TB16;
+        return r;
+    };
     const rsrc_t rW = make_rsrc(p.packed, p.packed_bytes);
     const rsrc_t rS = make_rsrc(p.scales, p.scale_bytes);
     const rsrc_t rX = make_rsrc(p.X, p.x_bytes);
@@ -204,7 +218,20 @@ void rows_kernel(const RowsParams p) {
                 *reinterpret_cast<u32x4*>(sc + (size_t)row * p.SROW + 16 * col) = v;
             }
         }
-        if (!lut_ready) {
+        if constexpr (RLUT) {
+            // the raw tables of the pass's rows (one contiguous range) are staged in an area of their own in front
+            // of the reduction slots (those may still be read by a slower wave of the previous pass), and the
+            // sixteen-copy tables are built from there (nobody reads tables after a pass's K loop, which every wave
+            // has left: the reduction began with a barrier)
+            const rsrc_t rT = make_rsrc(p.lut, (uint32_t)p.N * (uint32_t)((1 << BITS) * 2));
+            char* stage = red - AMAX * rowlut16_stage_bytes<BITS>();
+            const int words = na * (rowlut16_stage_bytes<BITS>() / 4);
+            const uint32_t tbase = (uint32_t)(rb_first + p0) * (uint32_t)rowlut16_stage_bytes<BITS>();
+            for (int i = tid; i < words; i += p.NW * 64)
+                *reinterpret_cast<uint32_t*>(stage + 4 * i) = __builtin_amdgcn_raw_buffer_load_b32(rT, tbase + 4u * (uint32_t)i, 0, kAuxNone);
+            __syncthreads();
+            rowlut16_build<BITS, DT>(lut, stage, na, tid, p.NW * 64);
+        } else if (!lut_ready) {
             // the table is built while the first tiles are in flight (its own reads were issued before them)
             LutSeed seed = lut_seed;
             asm volatile("" : "+v"(seed.w[0]), "+v"(seed.w[1]), "+v"(seed.w[2]), "+v"(seed.w[3]));
@@ -221,7 +248,7 @@ void rows_kernel(const RowsParams p) {
         // first D steps are already under way (issued by the slot before it, or here for the first).
         Raw<BITS, DT> raw[D];
 #pragma unroll
-        for (int s = 0; s < D; ++s) raw[s] = lookup_step<BITS, DT, true>(st[0].w, s, la);
+        for (int s = 0; s < D; ++s) raw[s] = lookup_step<BITS, DT, PERM>(st[0].w, s, la_of(0, skip));
         __builtin_amdgcn_sched_barrier(0);
 
         // One K tile: buf = which set of bx holds its activations.  With two sets a tile beyond the wave's range
@@ -240,6 +267,7 @@ void rows_kernel(const RowsParams p) {
             for (int a = 0; a < AMAX; ++a) {
                 Stage& cur = st[a % NST];
                 const Stage& nxt = st[(a + 1) % NST];
+                const LutAddr la_cur = la_of(a, skip), la_nxt = la_of((a + 1) % AMAX, skip);
                 if ((!XDB && a == AMAX - 1) || (live && a >= skip)) {
                     // dequantise the tile step by step and multiply it into row block a's accumulators
                     u32x4 aop[2];
@@ -249,8 +277,8 @@ void rows_kernel(const RowsParams p) {
                             const ScaleReg<DT> sc = scale_of<DT, NS>(cur.s, s / SPG);
                             aop[s & 1] = scale4<BITS, DT>(raw[s % D], sc);
                             __builtin_amdgcn_sched_barrier(0);
-                            raw[s % D] = s + D < STEPS ? lookup_step<BITS, DT, true>(cur.w, s + D, la)
-                                                       : lookup_step<BITS, DT, true>(nxt.w, s + D - STEPS, la);
+                            raw[s % D] = s + D < STEPS ? lookup_step<BITS, DT, PERM>(cur.w, s + D, la_cur)
+                                                       : lookup_step<BITS, DT, PERM>(nxt.w, s + D - STEPS, la_nxt);
                             __builtin_amdgcn_sched_barrier(0);
                         }
                         if (s > 0) {
@@ -269,7 +297,7 @@ void rows_kernel(const RowsParams p) {
                 } else {
                     // an empty slot: only the next slot's first table reads
 #pragma unroll
-                    for (int s = 0; s < D; ++s) raw[s] = lookup_step<BITS, DT, true>(nxt.w, s, la);
+                    for (int s = 0; s < D; ++s) raw[s] = lookup_step<BITS, DT, PERM>(nxt.w, s, la_nxt);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 // the slot NST ahead: further along this K tile, or among the first ones of the next

@@ -449,13 +449,14 @@ def test_one_table_per_output_row(lutq, bits, dtype):
     sizes with the chunked and the per-tile scale path, row counts that make one workgroup walk several
     row blocks and K ranges cut across workgroups, and for M <= 4 (the work-queue kernel with the tables of
     all of a workgroup's row blocks resident) one to eight row blocks per workgroup in even and uneven
-    shares; identical rows reproduce lutq_matmul exactly."""
+    shares, and from five rows up with at least two row blocks per compute unit the row-streaming kernel
+    with four row blocks' tables per pass; identical rows reproduce lutq_matmul exactly."""
     import torch
     rng = np.random.default_rng(100 + bits)
     E = 1 << bits
     for (N, K, group, Ms) in [(48, 2 * tk(bits), 64, (32,)), (208, 8 * tk(bits), 128, (1, 4, 7, 16, 32)),
                               (16 * 300, 2048, 32, (2, 40)), (80, 3 * tk(bits), 32, (5,)),
-                              (16 * 600, 1024, 64, (1, 3)), (16 * 1800, 4 * tk(bits), 64, (4,)), (64, 3 * tk(bits), 32, (2,))]:
+                              (16 * 600, 1024, 64, (1, 3, 9, 20)), (16 * 1800, 4 * tk(bits), 64, (4, 16, 32)), (64, 3 * tk(bits), 32, (2,))]:
         base = gen.make_case(700 + N, 32, N, K, bits, group, dtype, "random_index")
         Tn = gen.encode16(rng.standard_normal((N, E)), dtype)
         d = DeviceCase(lutq, base)
