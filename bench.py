@@ -381,6 +381,14 @@ def main():
         by = gen.algorithmic_bytes(M, N, K, BITS, GROUP) + Tn.numel() * 2
         more["per_row_tables_m1"] = {"us": r2(t * 1e6), "frac_of_8TBps": round(by / t * 1e-9 / HBM_PEAK_GBS, 3),
                                      "over_shared_table": r2(t * 1e6 / per_shape["gate_up"]["us"])}
+        # ... and at M = 16 (the row-streaming kernel with four row blocks' tables per pass)
+        X16 = torch.randn((16, K), device="cuda").to(torch.float16)
+        Y16 = torch.empty((16, N), dtype=torch.float16, device="cuda")
+        t = timer.per_call(lambda: [lutq.lutq_matmul_channel(X16, layers[li]["gate_up"]["packed"], layers[li]["gate_up"]["S"], Tn,
+                                                             BITS, GROUP, Y16, ws) for li in range(LAYERS)], LAYERS)
+        t16 = per_shape["gate_up"]["by_M"].get("16", {}).get("us")
+        more["per_row_tables_m16"] = {"us": r2(t * 1e6), "over_shared_table": r2(t * 1e6 / t16) if t16 else None}
+        del X16, Y16
         # 33..128 activation rows
         dense = Dense(torch, N, K, torch.float16)
         for m2 in (64, 128):

@@ -134,8 +134,8 @@ bool rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int group
 // QKV shapes of LLaMA-2-7B/13B and LLaMA-3-8B/70B, M = 8, 16, 24, 32, fp16 and bf16, MI355X:
 //   * 4 bits, five to eight row blocks per compute unit (one pass), M > 8: 3-10 % faster where the row blocks
 //     do not divide over the compute units (7B gate+up M = 16: 15.8 -> 14.2 us, bf16 18.1 -> 16.3; 13B: 20.5 ->
-//     18.9); where they do (8B gate+up) 1-4 % in bf16 (M = 16: 18.4 -> 17.8 us) and within the noise of either
-//     in fp16, which stays with the teams.  With more (70B gate+up, fourteen: two passes, each with its own
+//     18.9); where they do (8B gate+up) 1-6 % in bf16 (M = 16: 18.4 -> 17.3 us), 1.5 % in fp16 up to sixteen rows
+//     (16.0 -> 15.7, 16.5 -> 16.2 us in two runs) and within the noise of either beyond, which stays with the teams.  With more (70B gate+up, fourteen: two passes, each with its own
 //     ramp and reduction) the teams are faster, and at M <= 8 they are as fast.
 //   * 3 bits, the same shapes, 8 < M <= 16: 6-19 % (13B gate+up 20.5 -> 17.8 us, bf16 24.3 -> 19.7).
 //   * 4 bits, two to four row blocks per compute unit that do not divide (QKV shapes), M <= 16, bf16 M <= 24:
@@ -148,7 +148,7 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
     const bool uneven = nb % cus != 0;
     const int64_t amax = per + (uneven ? 1 : 0);
     bool take = false;
-    if (bits == 4) take = (per >= 5 && amax <= 8 && M > 8 && (uneven || bf16)) || (uneven && per >= 2 && amax <= 4 && M <= (bf16 ? 24 : 16));
+    if (bits == 4) take = (per >= 5 && amax <= 8 && M > 8 && (uneven || bf16 || M <= 16)) || (uneven && per >= 2 && amax <= 4 && M <= (bf16 ? 24 : 16));
     else if (bits == 3) take = per >= 5 && amax <= 8 && M > 8 && M <= 16;
     // (only where one pass covers the workgroup's row blocks: a second pass costs more than the teams)
     return take && rows_decomp(bits, bf16, M, N, K, group_size, cus, out) && out->r >= amax;
