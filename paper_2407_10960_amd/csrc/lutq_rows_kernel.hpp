@@ -59,13 +59,13 @@ struct RowsParams {
 // LDS of one launch: [table, 256-byte entry stride][scales of AMAX x 16 rows, SROW bytes each][RPR x MB x NW slots of 1 KiB]
 // RLUT: [AMAX tables of sixteen copies][scales][raw tables of AMAX row blocks][slots]
 
-// Registers: AMAX x MB x 4 accumulators + STEPS x MB x 4 activation operands + four weight tiles in flight
-// (eight at 4 bits with eight row blocks side by side: five registers each), the lookup ring and addresses
-// (about 84 at 4 bits, 108 and 116 at 2 and 3 bits with their eight steps per tile, 28 more with a widened
-// bf16 table).  The estimate decides how many waves an instance is compiled for (4-bit fp16, M > 16: 152
-// registers and twelve waves with four row blocks side by side, 221 and eight waves with eight; M <= 16
-// with eight: 153 and twelve waves); 0 = no such instance.
-__host__ __device__ constexpr int rows_tiles_in_flight(int bits, int amax) { return 4; }   // (eight measured no faster)
+// Registers: AMAX x MB x 4 accumulators + STEPS x MB x 4 activation operands (twice that where two tiles' are
+// held) + four weight tiles in flight, the lookup ring and addresses (about 84 at 4 bits, 108 and 116 at 2 and
+// 3 bits with their eight steps per tile, 28 more with a widened bf16 table, 20 more at 4 bits with eight row
+// blocks side by side).  The estimate decides how many waves an instance is compiled for (4-bit fp16: M <= 16
+// with four / eight row blocks side by side 114 / 149 registers, sixteen / twelve waves; M > 16 191 / 241,
+// eight waves); 0 = no such instance (the registers do not hold it without spilling).
+__host__ __device__ constexpr int rows_tiles_in_flight(int, int) { return 4; }   // (eight measured no faster)
 // The activations of the next K tile are fetched a whole tile ahead into a second set of registers where that
 // measured faster (4-bit fp16 beyond sixteen rows: 8B gate+up M = 32 21.9 -> 20.8 us); elsewhere the second set
 // costs waves (twelve -> eight) or the instance, and the next tile's activations are fetched step by step
