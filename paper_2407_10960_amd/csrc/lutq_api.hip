@@ -186,7 +186,11 @@ bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K
     // us at M = 1, 4.72 -> 4.57 at M = 4): one item per wave, so the queue is never used, but the short set-up
     // of this kernel shows.  A longer K (8B down) is faster with the teams' even static split.
     const bool short_k = even && per == 1 && bits == 4 && kt % 4 == 0 && kt / 4 <= 8;
-    if (only_if_preferred && !(even ? (per >= 8 || short_k || (per == 2 && bits == 4 && M <= 2 && K >= 16384)) : uneven_preferred)) return false;
+    // Four to seven row blocks per compute unit at 2 and 3 bits, twelve waves (8B gate+up, seven: 3-bit 13.2 -> 12.1 us,
+    // bf16 15.1 -> 13.8, 2-bit 9.7 -> 9.0, M = 4 14.5 -> 13.8; with fourteen or sixteen waves the queue loses to the
+    // teams here, and at 4 bits the two are equal: 12.5 against 12.3 us).
+    const bool few_bits_mid = even && per >= 4 && per < 8 && bits < 4;
+    if (only_if_preferred && !(even ? (per >= 8 || short_k || few_bits_mid || (per == 2 && bits == 4 && M <= 2 && K >= 16384)) : uneven_preferred)) return false;
     const int sb = super_block(nb);
     // two row blocks per wave halve the activation and scale-chunk loads per weight; 3-bit tiles (two
     // bit-slices) run faster one at a time, and two row blocks per compute unit make more items as R = 1
@@ -199,7 +203,7 @@ bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K
     if (kt % it != 0) return false;
     int64_t items = amax * (kt / it);
     while (queue_lds_bytes(bits, 16, (int)items, r) > 160 * 1024 && kt % (it * 2) == 0) { it *= 2; items = amax * (kt / it); }
-    int nw = items >= 16 ? (amax <= 3 && !even ? 12 : 16) : (int)(items < 4 ? 4 : items);
+    int nw = items >= 16 ? ((amax <= 3 && !even) || few_bits_mid ? 12 : 16) : (int)(items < 4 ? 4 : items);
     if (queue_lds_bytes(bits, nw, (int)items, r) > 160 * 1024) return false;
     out->r = r; out->grid = cus; out->nw = nw; out->stages = 2; out->rs = (int)a; out->queue = 1; out->it = it;
     return true;

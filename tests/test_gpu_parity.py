@@ -556,7 +556,7 @@ FULL_SIZE = [
     ("8B qkv W4 g128 M1 (one workgroup per row group)", 6144, 4096, 4, 128, "f16", 1),
     ("70B qkv W4 g64 bf16 M1 (work queue, uneven shares of 2 and 3 row blocks)", 10240, 8192, 4, 64, "bf16", 1),
     ("70B o W4 g64 bf16 M1 (R = 2)", 8192, 8192, 4, 64, "bf16", 1),
-    ("8B gate_up W3 g128 M1 (7 teams x 2)", 28672, 4096, 3, 128, "f16", 1),
+    ("8B gate_up W3 g128 M1 (work queue, twelve waves)", 28672, 4096, 3, 128, "f16", 1),
     ("8B gate_up W3 g128 M8 (R = 4, plain activations)", 28672, 4096, 3, 128, "f16", 8),
     ("8B gate_up W3 g64 M32 (R limited by registers)", 28672, 4096, 3, 64, "f16", 32),
     ("8B down W2 g128 M3", 4096, 14336, 2, 128, "bf16", 3),
@@ -583,6 +583,8 @@ FULL_SIZE = [
     ("8B gate_up W3 g128 bf16 M16 (row streaming, eight side by side)", 28672, 4096, 3, 128, "bf16", 16),
     ("8B gate_up W4 g128 bf16 M32 (row streaming, more than 16 rows)", 28672, 4096, 4, 128, "bf16", 32),
     ("22016x4096 W4 M24 (row streaming, shares of 5 and 6 row blocks)", 22016, 4096, 4, 128, "f16", 24),
+    ("8B gate_up W4 g128 M16 (row streaming, twelve waves, eight side by side)", 28672, 4096, 4, 128, "f16", 16),
+    ("22016x4096 W4 M32 (row streaming, two tiles' activations in registers)", 22016, 4096, 4, 128, "f16", 32),
 ]
 
 

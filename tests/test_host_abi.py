@@ -237,6 +237,9 @@ def test_default_plans_fitted_by_measurement():
         (4, 128, 20, 4096, 14336, 1): (2, 256, 4, 2, 1),
         (4, 128, 8, 28672, 4096, 0): (4, 448, 4, 2, 1),
         (4, 128, 32, 28672, 4096, 0): (2, 224, 8, 2, 4),
+        # work queue with twelve waves: seven row blocks per compute unit at 2 and 3 bits
+        (3, 128, 1, 28672, 4096, 0): (1, 256, 12, 2, 7, 2),
+        (2, 128, 4, 28672, 4096, 1): (1, 256, 12, 2, 7, 2),
         (4, 128, 16, 28672, 4096, 0): (8, 256, 12, 2, 7, 3),
         (4, 128, 32, 28672, 4096, 1): (8, 256, 8, 2, 7, 3),
         (4, 64, 32, 57344, 8192, 0): (2, 256, 14, 2, 7, 1),
