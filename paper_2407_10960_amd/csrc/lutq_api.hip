@@ -189,8 +189,13 @@ bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K
     // Four to seven row blocks per compute unit at 2 and 3 bits, twelve waves (8B gate+up, seven: 3-bit 13.2 -> 12.1 us,
     // bf16 15.1 -> 13.8, 2-bit 9.7 -> 9.0, M = 4 14.5 -> 13.8; with fourteen or sixteen waves the queue loses to the
     // teams here, and at 4 bits the two are equal: 12.5 against 12.3 us).
-    const bool few_bits_mid = even && per >= 4 && per < 8 && bits < 4;
-    if (only_if_preferred && !(even ? (per >= 8 || short_k || few_bits_mid || (per == 2 && bits == 4 && M <= 2 && K >= 16384)) : uneven_preferred)) return false;
+    // At 4 bits the same up to two rows and in bf16 (M = 1 12.8 -> 12.4 us, M = 2 13.2 -> 12.6, bf16 15.4 -> 14.4; fp16 M = 4
+    // equal).
+    const bool few_bits_mid = even && per >= 4 && per < 8 && (bits < 4 || M <= 2 || bf16);
+    // Two row blocks per compute unit at 2 bits, and at 3 bits up to two rows, twelve waves (N = K = 8192 group 32, 2-bit:
+    // M = 1 7.3 -> 7.1 us, M = 2 7.8 -> 7.3, M = 4 9.0 -> 8.3, bf16 9.5 -> 9.1; 70B O 3-bit bf16 9.9 -> 9.3; sixteen waves: 7.8).
+    const bool few_bits_two = even && per == 2 && (bits == 2 || (bits == 3 && M <= 2)) && kt % 4 == 0;
+    if (only_if_preferred && !(even ? (per >= 8 || short_k || few_bits_mid || few_bits_two || (per == 2 && bits == 4 && M <= 2 && K >= 16384)) : uneven_preferred)) return false;
     const int sb = super_block(nb);
     // two row blocks per wave halve the activation and scale-chunk loads per weight; 3-bit tiles (two
     // bit-slices) run faster one at a time, and two row blocks per compute unit make more items as R = 1
@@ -199,11 +204,11 @@ bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K
     // items: at least two tiles (the pipeline depth); four where K allows, eight when that still leaves
     // every wave about four items, so that an item's fold and hand-over stay a small part of its work
     int it = kt % 4 == 0 ? 4 : 2;
-    if (kt % 8 == 0 && a * (kt / 8) >= 64) it = 8;
+    if (kt % 8 == 0 && a * (kt / 8) >= 64 && !few_bits_two) it = 8;
     if (kt % it != 0) return false;
     int64_t items = amax * (kt / it);
     while (queue_lds_bytes(bits, 16, (int)items, r) > 160 * 1024 && kt % (it * 2) == 0) { it *= 2; items = amax * (kt / it); }
-    int nw = items >= 16 ? ((amax <= 3 && !even) || few_bits_mid ? 12 : 16) : (int)(items < 4 ? 4 : items);
+    int nw = items >= 16 ? ((amax <= 3 && !even) || few_bits_mid || few_bits_two ? 12 : 16) : (int)(items < 4 ? 4 : items);
     if (queue_lds_bytes(bits, nw, (int)items, r) > 160 * 1024) return false;
     out->r = r; out->grid = cus; out->nw = nw; out->stages = 2; out->rs = (int)a; out->queue = 1; out->it = it;
     return true;
@@ -296,7 +301,7 @@ int64_t gcd64(int64_t a, int64_t b) {
 //   * otherwise one workgroup of 8 waves per row group, R the largest of 4, 2, 1 that still gives
 //     every compute unit a row group; only when N is too small even for that is K split across
 //     workgroups, with the fix-up.
-Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K, int cus, int force_r) {
+Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K, int cus, int force_r, int group_size) {
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1, xm = M <= 4 ? 4 : 16;
     const int sb = super_block(nb);
@@ -381,7 +386,23 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         }
         while (grid > kMaxGrid) grid = (grid + 1) / 2;
         d.r = r; d.grid = (int)grid; d.rs = 1;
-        d.nw = (M > 12 || (r == 4 && groups > cus) || (bits < 4 && groups > cus)) ? 4 : 8;
+        // (2 and 3 bits, up to eight rows, exactly one row group per compute unit: four waves too -- 8192^2 2-bit M = 8 11.6 -> 9.8 us,
+        // 8B O and down 3-bit M = 8 2-3 %)
+        d.nw = (M > 12 || (r == 4 && groups > cus) || (bits < 4 && (groups > cus || (groups == cus && M <= 8)))) ? 4 : 8;
+        // The waves of a workgroup split its K tiles evenly (a row group's, or its part of them where K is cut evenly
+        // across workgroups); a split that also falls on the 16-byte chunks of scales (8 scales = tpc tiles) saves every
+        // wave a chunk load it uses half of: where the default count does not divide that way and seven, six or five
+        // waves do, take those (8B down, 112 tiles, chunks of 8: M = 16, K cut in two, four waves 14.0-14.3 us, seven
+        // 13.4-13.6; M = 8 uncut, eight waves 11.1 us, seven 10.7).
+        if (sch && M <= 16 && grid % groups == 0 && kt % (grid / groups) == 0 && group_size > 0) {
+            const int tk = tile_k(bits);
+            const int64_t tpc = group_size >= tk ? 8 * (int64_t)(group_size / tk) : 8 / (tk / group_size);
+            const int64_t wg_tiles = kt / (grid / groups);
+            auto aligned = [&](int w) { return wg_tiles % w == 0 && tpc > 0 && (wg_tiles / w) % tpc == 0; };
+            if (!aligned(d.nw))
+                for (int w : {7, 6, 5})
+                    if (aligned(w)) { d.nw = w; break; }
+        }
         // Team plan: a workgroup takes A = R x RS row blocks as RS teams that share the activations
         // through LDS (needs enough teams to stage a tile between them, and chunked scales).  It pays
         // when the activations outweigh the weights (M / (4 bits) >= 1.3 -- 1.0 at 3 bits --, or >= 1 on a larger problem) on
@@ -476,8 +497,8 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
         // the work per weight is heavy (measured: bf16 4-bit 6-9 %, 2-bit at M <= 2 10-18 %); 4-bit fp16
         // and longer batches keep R = 2
         if (!force_r && r == 2 && per == 2 && wide_exists(bits, bf16, 1, mb, 2, xm) &&
-            ((bits == 4 && bf16) || (bits == 2 && M <= 2)))
-            r = 1;
+            ((bits == 4 && bf16) || (bits == 2 && M <= 2) || (bits == 4 && group_size == 32 && M <= 2)))
+            r = 1;                                        // (group 32, a scale per 32 weights: 8192^2 M = 1 9.6 -> 9.0-9.1 us)
         int64_t rs = per / r;
         while (rs > max_nw && rs % 2 == 0) { rs /= 2; grid *= 2; }
         const int nw = rs <= max_nw ? waves_for(r, rs, kt) : 0;
@@ -622,7 +643,7 @@ extern "C" lutq_status lutq_plan_default_for(int bits, int group_size, int64_t M
     Decomp d;
     if (!default_queue_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, &d) &&
         !default_rows_decomp(bits, dtype == LUTQ_BF16, M, N, K, group_size, compute_units, &d))
-        d = default_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, 0);
+        d = default_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, 0, group_size);
     plan->row_blocks_per_wave = d.r;
     plan->grid = d.grid;
     plan->waves_per_workgroup = d.nw;
@@ -976,7 +997,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         if (sched == 0 && plan_is_empty && default_rows_decomp(bits, bf16, M, N, K, group_size, di.cus, &q))
             return prepare_rows(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out);
     }
-    Decomp d = default_decomp(bits, bf16, sch, M, N, K, di.cus, force_r);
+    Decomp d = default_decomp(bits, bf16, sch, M, N, K, di.cus, force_r, group_size);
     if (rowlut) {
         // one table per output row: a workgroup holds the tables of one row block at a time, so one
         // row block per workgroup, its K range split over eight waves, and over several workgroups
