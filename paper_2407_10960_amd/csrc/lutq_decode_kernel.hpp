@@ -65,6 +65,7 @@ struct DecodeParams {
     uint32_t o_magic;         // floor(2^32 / (A * R * 64))
     uint32_t o1_magic;        // floor(2^32 / ((A + 1) * R * 64))
     int tab_total;            // RLUT: LDS bytes of all the row blocks' tables (the other areas follow)
+    int NB;                   // waves 0 .. NB - 1 build the shared table; the others wait for it before their first loads
     unsigned long long* trace;   // TRACE instances only
 };
 
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.packed_bytes), "s"(p.scale_bytes),
                  "s"(p.x_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.SG2), "s"(p.SBL), "s"(p.tile_stride), "s"(p.sblock_bytes),
                  "s"(p.A), "s"(p.C), "s"(p.IT), "s"(p.NW), "s"(p.a_magic), "s"(p.lut_ltpe), "s"(p.slot_off), "s"(p.NG), "s"(p.GL),
-                 "s"(p.o_magic), "s"(p.extra), "s"(p.a1_magic), "s"(p.o1_magic), "s"(p.tab_total));
+                 "s"(p.o_magic), "s"(p.extra), "s"(p.a1_magic), "s"(p.o1_magic), "s"(p.tab_total), "s"(p.NB));
     stamp(kTraceArgs);
 
     extern __shared__ __align__(16) char smem[];
@@ -128,6 +129,14 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
     const bool big = (int)blockIdx.x < p.extra;        // this workgroup owns one row group more
     const int A = p.A + (big ? 1 : 0);
     const int rg0 = (int)blockIdx.x * p.A + ((int)blockIdx.x < p.extra ? (int)blockIdx.x : p.extra);   // first row group
+
+    // Sixteen waves' first loads queue up in the compute unit's address unit, and the table is not complete before
+    // the last wave has got its loads out and joined the build: with sixteen waves only the first NB = 8 build
+    // the table, and the others meet them at the barrier BEFORE they ask for anything.  The builders' loads then go
+    // out unhindered, the table stands earlier, and the later waves start from a built table.  (Every wave passes
+    // the one barrier exactly once, here or after the build.)
+    const bool builder = RLUT || wave < p.NB;
+    if (!builder) __syncthreads();
 
     // the table's values are asked for first: they are needed first
     LutSeed lut_seed{};
@@ -287,7 +296,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeParams p) {
         rowlut16_build<BITS, DT>(lut, stage, A, tid, p.NW * 64);
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
-    } else {
+    } else if (builder) {
         // the table is built while the first tiles are in flight (its own reads were issued before them)
         LutSeed seed = lut_seed;
         asm volatile("" : "+v"(seed.w[0]), "+v"(seed.w[1]), "+v"(seed.w[2]), "+v"(seed.w[3]));
