@@ -247,8 +247,9 @@ lutq_status lutq_matmul_plan(const void* X, const void* packed, const void* scal
  * for the default decomposition), bit for bit under the same plan.
  * A launch needs partial-sum slots only when its plan cuts output tiles across workgroups:
  * grid x row groups per workgroup x 2 slots of R x ceil(M/16) x 1 KiB (M capped at 32).  If that exceeds
- * the 16 MiB the call returns LUTQ_ERR_SCRATCH before anything is launched (Y untouched); every default
- * plan of the LLaMA-3 8B/70B shapes fits.
+ * the 16 MiB, a call with a plan returns LUTQ_ERR_SCRATCH before anything is launched (Y untouched), and a
+ * call without one takes the library's choice among the decompositions that need little scratch (of the
+ * LLaMA-3 8B/70B shapes only 70B gate+up in bf16 beyond sixteen rows does not fit with its first choice).
  * All calls on one GPU share the one array: calls that may overlap on a GPU (different streams) race
  * on it and must use lutq_matmul with separate workspaces instead.  The counters are returned to zero by
  * every launch; the slots keep the last call's partial sums and are overwritten before they are read. */

@@ -301,7 +301,8 @@ int64_t gcd64(int64_t a, int64_t b) {
 //   * otherwise one workgroup of 8 waves per row group, R the largest of 4, 2, 1 that still gives
 //     every compute unit a row group; only when N is too small even for that is K split across
 //     workgroups, with the fix-up.
-Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K, int cus, int force_r, int group_size) {
+Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K, int cus, int force_r, int group_size,
+                      bool small_scratch = false) {
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1, xm = M <= 4 ? 4 : 16;
     const int sb = super_block(nb);
@@ -471,6 +472,22 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
                 }
             }
             if (!nw) continue;
+            // One set per workgroup that only gets one wave per team and fewer than eight waves (bf16 4-bit beyond
+            // sixteen rows: no 128-register build for two pieces per wave): twice the teams, one piece per wave, every
+            // set's K range cut in two, where that fits (70B gate+up bf16, M = 20..32: seven waves 75.7 us, fourteen 70.3)
+            // (not for a caller with little scratch: every tile's partial sums go through it)
+            if (!small_scratch && c.exact && nw < 8 && c.sets == cus && 2 * c.rs <= 16 && nb % (c.r * c.rs * 2) == 0 && K / 2 >= 2048 &&
+                (int64_t)cus * c.rs * 2 <= kMaxGrid) {
+                const int w2 = (int)c.rs * 2, xpw2 = x_pieces_per_wave(bits, mb, w2);
+                const int lds2 = bits == 2 ? matmul_lds_bytes<2>(c.r, mb, w2, w2, true, true)
+                               : bits == 3 ? matmul_lds_bytes<3>(c.r, mb, w2, w2, true, true)
+                                           : matmul_lds_bytes<4>(c.r, mb, w2, w2, true, true);
+                if (matmul_instance_exists(bits, bf16, c.r, mb, 2, true, 16, w2 > 8, xpw2) && lds2 <= 160 * 1024) {
+                    Decomp t = d;
+                    t.r = c.r; t.grid = cus; t.nw = w2; t.rs = w2; t.stages = 2;
+                    return t;
+                }
+            }
             if ((c.exact ? c.sets : (int64_t)cus) * c.rs > kMaxGrid) continue;     // partial-sum slots of the workspace
             Decomp t = d;
             t.r = c.r; t.grid = c.exact ? (int)c.sets : cus; t.nw = nw; t.rs = (int)c.rs; t.stages = stages;
@@ -859,7 +876,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
                            int bits, int group_size, int64_t M, int64_t N, int64_t K,
                            lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
                            const lutq_plan* user_plan, bool rowlut, int dry_run_cus, Prepared* out,
-                           bool fitted_workspace = false, bool consult_table = true) {
+                           bool fitted_workspace = false, bool consult_table = true, bool small_scratch = false) {
     // no plan from the caller: a registered plan for this call goes first, if the kernels can run it
     lutq_plan registered;
     if (!user_plan && !rowlut && dry_run_cus == 0 && consult_table &&
@@ -1001,7 +1018,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         if (sched == 0 && plan_is_empty && default_rows_decomp(bits, bf16, M, N, K, group_size, di.cus, &q))
             return prepare_rows(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out);
     }
-    Decomp d = default_decomp(bits, bf16, sch, M, N, K, di.cus, force_r, group_size);
+    Decomp d = default_decomp(bits, bf16, sch, M, N, K, di.cus, force_r, group_size, small_scratch);
     if (rowlut) {
         // one table per output row: a workgroup holds the tables of one row block at a time, so one
         // row block per workgroup, its K range split over eight waves, and over several workgroups
@@ -1068,7 +1085,13 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         // partial sums leave a workgroup only if some range of iterations ends inside an output tile
         const bool splits = tiles % d.grid != 0 || (tiles / d.grid) % kt != 0;
         const size_t need = splits ? (size_t)d.grid * 2 * d.rs * slot_floats(r, mb) * sizeof(float) : 0;
-        if (kCounterBytes + need > workspace_bytes) return LUTQ_ERR_SCRATCH;
+        if (kCounterBytes + need > workspace_bytes) {
+            // the library's own choice does not fit the caller's scratch: once more with the plans that need little
+            if (!user_plan && !small_scratch)
+                return prepare_matmul(X, packed, scales, lut, bits, group_size, M, N, K, dtype, Y, workspace, workspace_bytes,
+                                      user_plan, rowlut, dry_run_cus, out, fitted_workspace, false, true);
+            return LUTQ_ERR_SCRATCH;
+        }
     }
 
     MatmulParams p;

@@ -66,3 +66,24 @@ def test_static_scratch_rejects_what_does_not_fit(lutq):
     lutq.lutq_matmul_static(big.X, big.packed, big.S, big.T, bits, 128, Y, plan=lutq.Plan(4, 64, 4, 2, 1))
     torch.cuda.synchronize()
     assert np.array_equal(to_bits(Y), to_bits(big.matmul(lutq, plan=lutq.Plan(4, 64, 4, 2, 1))))
+
+
+def test_static_scratch_falls_back_to_a_default_that_fits(lutq):
+    """Where the library's own plan would need more partial-sum scratch than the built-in array holds (70B
+    gate+up, bf16, M = 32: fourteen teams with every tile cut in two, 28 MiB of slots), the call without a
+    plan takes the library's low-scratch choice instead of failing: the same bits as that plan on a
+    workspace (seven teams, no cut), while the plan that does not fit is refused when asked for by name."""
+    import torch
+    M, N, K, bits, group = 32, 57344, 8192, 4, 64
+    small = gen.make_case(5, M, 64, K, bits, group, "bf16", "random_index")
+    c = gen.Case(M, N, K, bits, group, "bf16", small.X, np.tile(small.Q, (N // 64, 1)), np.tile(small.S, (N // 64, 1)), small.T)
+    d = DeviceCase(lutq, c)
+    assert lutq.lutq_plan_default(bits, group, M, N, K, 1).row_groups_per_workgroup == 14
+    Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lutq.lutq_matmul_static(d.X, d.packed, d.S, d.T, bits, group, Y)
+    torch.cuda.synchronize()
+    want = to_bits(d.matmul(lutq, plan=lutq.Plan(2, 256, 7, 2, 7)))
+    assert np.array_equal(to_bits(Y), want)
+    with pytest.raises(lutq.LutqError) as e:
+        lutq.lutq_matmul_static(d.X, d.packed, d.S, d.T, bits, group, Y, plan=lutq.Plan(2, 256, 14, 2, 14))
+    assert e.value.code == 11
