@@ -148,8 +148,13 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
     const bool uneven = nb % cus != 0;
     const int64_t amax = per + (uneven ? 1 : 0);
     bool take = false;
-    if (bits == 4) take = (per >= 5 && amax <= 8 && M > 8 && (uneven || bf16 || M <= 16)) || (uneven && per >= 2 && amax <= 4 && M <= (bf16 ? 24 : 16));
-    else if (bits == 3) take = per >= 5 && amax <= 8 && M > 8 && M <= 16;
+    // Three to four row blocks per compute unit (QKV of LLaMA-2-7B and 13B, not in the benchmark), 3-bit or bf16, up
+    // to 24 rows: 7B QKV bf16 M = 16 12.1 -> 9.9 us, 3-bit M = 16 11.7 -> 10.3, M = 24 16.8 -> 13.1; 13B QKV 3-bit M = 8
+    // 15.4 -> 11.8, M = 24 22.3 -> 17.2; in fp16 at 4 bits the two kernels are within 3 % there, and with two per
+    // compute unit (70B O) the teams win.
+    const bool few = per >= 3 && amax <= 4 && M <= 24 && (bits == 3 || bf16);
+    if (bits == 4) take = (per >= 5 && amax <= 8 && M > 8 && (uneven || bf16 || M <= 16)) || (uneven && per >= 2 && amax <= 4 && M <= (bf16 ? 24 : 16)) || few;
+    else if (bits == 3) take = (per >= 5 && amax <= 8 && M > 8 && M <= 16) || few;
     // (only where one pass covers the workgroup's row blocks: a second pass costs more than the teams)
     return take && rows_decomp(bits, bf16, M, N, K, group_size, cus, out) && out->r >= amax;
 }
@@ -181,7 +186,13 @@ bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K
     // (70B QKV: 12.2 -> 11.4 us, bf16 13.3 -> 12.6) and more than four (LLaMA-2-7B gate+up, 5.4 per compute
     // unit: 12.0 -> 11.1 us; 13B gate+up, 6.75: 15.3 us either way).  With 1.5 (8B QKV) or 3.75 (13B QKV) per
     // compute unit, at 3 bits and at M = 4 the team plans are as fast or faster.
-    const bool uneven_preferred = bits == 4 && M <= 2 && ((nb * 2) % cus == 0 ? per >= 2 : per >= 4);
+    // A sweep over the LLaMA-2-7B/13B shapes (not in the benchmark) added: more than four per compute unit also at
+    // M = 3, 4, with twelve waves there (7B gate+up M = 4 12.3 -> 11.4 us, bf16 14.7 -> 12.6; 13B gate+up bf16 18.8 -> 17.3);
+    // three or more in bf16 (13B QKV bf16 M = 1 11.0 -> 10.4-10.6 us, M = 4 11.4 -> 10.9); and between one and two per
+    // compute unit with a short K, where the compute units that get two row blocks deal sixteen or more items to
+    // sixteen waves (13B O M = 1 6.3 -> 6.0 us, bf16 6.75 -> 6.3; 8B QKV 5.82 -> 5.73, bf16 M = 4 6.34 -> 6.10).
+    const bool uneven_one = !even && per == 1 && bits == 4 && kt % 4 == 0 && kt / 4 <= 16;
+    const bool uneven_preferred = bits == 4 && (((nb * 2) % cus == 0 ? per >= 2 && M <= 2 : per >= 4) || (bf16 && per >= 3) || uneven_one);
     // One row block per compute unit with a short K (4-bit, at most eight items of four tiles: 8B O 4.52 -> 4.38
     // us at M = 1, 4.72 -> 4.57 at M = 4): one item per wave, so the queue is never used, but the short set-up
     // of this kernel shows.  A longer K (8B down) is faster with the teams' even static split.
@@ -208,7 +219,8 @@ bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K
     if (kt % it != 0) return false;
     int64_t items = amax * (kt / it);
     while (queue_lds_bytes(bits, 16, (int)items, r) > 160 * 1024 && kt % (it * 2) == 0) { it *= 2; items = amax * (kt / it); }
-    int nw = items >= 16 ? ((amax <= 3 && !even) || few_bits_mid || few_bits_two ? 12 : 16) : (int)(items < 4 ? 4 : items);
+    int nw = items >= 16 ? ((amax <= 3 && !even && !uneven_one) || few_bits_mid || few_bits_two || (!even && per >= 4 && M > 2) ? 12 : 16)
+                         : (int)(items < 4 ? 4 : items);
     if (queue_lds_bytes(bits, nw, (int)items, r) > 160 * 1024) return false;
     out->r = r; out->grid = cus; out->nw = nw; out->stages = 2; out->rs = (int)a; out->queue = 1; out->it = it;
     return true;

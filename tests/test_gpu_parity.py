@@ -553,7 +553,7 @@ FULL_SIZE = [
     ("8192^2 W2 g32", 8192, 8192, 2, 32, "f16", 4),
     # one case per branch of the default work decomposition
     ("8B o W4 g128 M1 (work queue, one item per wave)", 4096, 4096, 4, 128, "f16", 1),
-    ("8B qkv W4 g128 M1 (one workgroup per row group)", 6144, 4096, 4, 128, "f16", 1),
+    ("8B qkv W4 g128 M1 (work queue, shares of one and two row blocks)", 6144, 4096, 4, 128, "f16", 1),
     ("70B qkv W4 g64 bf16 M1 (work queue, uneven shares of 2 and 3 row blocks)", 10240, 8192, 4, 64, "bf16", 1),
     ("70B o W4 g64 bf16 M1 (R = 2)", 8192, 8192, 4, 64, "bf16", 1),
     ("8B gate_up W3 g128 M1 (work queue, twelve waves)", 28672, 4096, 3, 128, "f16", 1),
@@ -585,6 +585,9 @@ FULL_SIZE = [
     ("22016x4096 W4 M24 (row streaming, shares of 5 and 6 row blocks)", 22016, 4096, 4, 128, "f16", 24),
     ("8B gate_up W4 g128 M16 (row streaming, twelve waves, eight side by side)", 28672, 4096, 4, 128, "f16", 16),
     ("22016x4096 W4 M32 (row streaming, two tiles' activations in registers)", 22016, 4096, 4, 128, "f16", 32),
+    ("12288x4096 W3 bf16 M24 (row streaming, three row blocks per compute unit, more than 16 rows at 3 bits)", 12288, 4096, 3, 128, "bf16", 24),
+    ("15360x5120 W4 bf16 M4 (work queue, shares of 3 and 4 row blocks)", 15360, 5120, 4, 128, "bf16", 4),
+    ("22016x4096 W4 M4 (work queue, twelve waves, shares of 5 and 6)", 22016, 4096, 4, 128, "f16", 4),
 ]
 
 
