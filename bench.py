@@ -283,8 +283,8 @@ def main():
                      "frac": roof_achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes(),
                      "traffic_source": "profiles/" + os.path.basename(TRAFFIC_SUMMARY) + " (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE "
                                        "runs of this workload, scaled by a copy kernel of known size; not re-measured by this run)",
-                     "kernel": "all 128 launches of the step: lutq::decode_kernel<4,128,1,F16,2,false,false> (o and gate_up: 64 launches, 55 % of "
-                               "the time) and lutq::matmul_kernel<4,128,1,1,F16,2,true,4,true,0,false,false> (qkv and down: 64 launches)",
+                     "kernel": "all 128 launches of the step: lutq::decode_kernel<4,128,1,F16,2,false,false> (o, qkv and gate_up: 96 launches, 74 % "
+                               "of the time) and lutq::matmul_kernel<4,128,1,1,F16,2,true,4,true,0,false,false> (down: 32 launches)",
                      "bytes_per_launch": step_bytes / launches, "us_per_launch": per_launch_s * 1e6},
     }
 
