@@ -96,13 +96,18 @@ def trace_shape(lutq, torch, name, N, K, group, tdt, out):
     out.append(f"first wave start to last wave end: median {np.median(end - base):.2f} us; "
                f"previous launch's last end to this launch's first start: median {np.median(gaps):.2f} us")
     rel = h[1:] - base[1:, None, None, None]                               # launches 1..: us since the launch's first start
+    rel[h[1:] == 0] = np.nan                                               # a point a wave never reached (a wave that got no work)
+
+    def med(col):
+        col = col[~np.isnan(col)]
+        return f"{np.median(col):12.2f}" if col.size else f"{'-':>12s}"
     out.append("us since the launch's first wave started, median over workgroups (last column: 90 % quantile of the end)")
     out.append("wave   " + " ".join(f"{n[:12]:>12s}" for n in names) + "      end p90")
     for w in range(NW):
         v = rel[:, :, w, :].reshape(-1, 8)
-        out.append(f"{w:4d}   " + " ".join(f"{np.median(v[:, i]):12.2f}" for i in range(8)) + f" {q(v[:, 7], 0.9):12.2f}")
+        out.append(f"{w:4d}   " + " ".join(med(v[:, i]) for i in range(8)) + f" {q(v[:, 7], 0.9):12.2f}")
     v = rel.reshape(-1, 8)
-    out.append(" all   " + " ".join(f"{np.median(v[:, i]):12.2f}" for i in range(8)) + f" {q(v[:, 7], 0.9):12.2f}")
+    out.append(" all   " + " ".join(med(v[:, i]) for i in range(8)) + f" {q(v[:, 7], 0.9):12.2f}")
     out.append("")
 
 
