@@ -192,7 +192,10 @@ bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K
     // compute unit with a short K, where the compute units that get two row blocks deal sixteen or more items to
     // sixteen waves (13B O M = 1 6.3 -> 6.0 us, bf16 6.75 -> 6.3; 8B QKV 5.82 -> 5.73, bf16 M = 4 6.34 -> 6.10).
     const bool uneven_one = !even && per == 1 && bits == 4 && kt % 4 == 0 && kt / 4 <= 16;
-    const bool uneven_preferred = bits == 4 && (((nb * 2) % cus == 0 ? per >= 2 && M <= 2 : per >= 4) || (bf16 && per >= 3) || uneven_one);
+    // (with eight or more per compute unit the M = 3, 4 cases stay with the teams: a 128256-row output head and Qwen-72B
+    // gate+up, 31 and 14 per unit, are 6 % faster there)
+    const bool uneven_preferred = bits == 4 && (((nb * 2) % cus == 0 ? per >= 2 && M <= 2 : per >= 4 && (M <= 2 || per < 8)) ||
+                                                (bf16 && per >= 3 && (M <= 2 || per < 8)) || uneven_one);
     // One row block per compute unit with a short K (4-bit, at most eight items of four tiles: 8B O 4.52 -> 4.38
     // us at M = 1, 4.72 -> 4.57 at M = 4): one item per wave, so the queue is never used, but the short set-up
     // of this kernel shows.  A longer K (8B down) is faster with the teams' even static split.
