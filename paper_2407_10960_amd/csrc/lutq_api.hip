@@ -154,7 +154,9 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
     // compute unit (70B O) the teams win.
     const bool few = per >= 3 && amax <= 4 && M <= 24 && (bits == 3 || bf16);
     if (bits == 4) take = (per >= 5 && amax <= 8 && M > 8 && (uneven || bf16 || M <= 16)) || (uneven && per >= 2 && amax <= 4 && M <= (bf16 ? 24 : 16)) || few;
-    else if (bits == 3) take = (per >= 5 && amax <= 8 && M > 8 && M <= 16) || few;
+    // (3 bits from six row blocks per compute unit: from five rows up -- 13B gate+up M = 6 / 8 24.8 / 25.3 -> 16.5 / 17.1 us,
+    // 8B gate+up M = 8 15.6 -> 15.2; with five to six per unit, 7B gate+up, the teams are faster up to eight rows)
+    else if (bits == 3) take = (per >= 5 && amax <= 8 && M > 8 && M <= 16) || (per >= 6 && amax <= 8 && M <= 16) || few;
     // (only where one pass covers the workgroup's row blocks: a second pass costs more than the teams)
     return take && rows_decomp(bits, bf16, M, N, K, group_size, cus, out) && out->r >= amax;
 }
@@ -471,7 +473,9 @@ Decomp default_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64
             if (!c.exact && np >= 8 && c.r == 2 && 2 * c.rs <= 16) { c.r = 1; c.rs *= 2; }
             const bool deep = c.r == 1 && np >= 8 && bits != 3;
             const int xpw = x_pieces_per_wave(bits, mb, (int)c.rs);
-            int ks_first = deep ? 1 : (c.rs >= 8 ? (c.exact ? 2 : 1) : 2);
+            // (3 bits up to sixteen rows: two waves per team also where K is cut across workgroups -- 70B down M = 12 / 16
+            // 30.1 / 30.7 -> 28.7 / 29.5 us, bf16 34.0 / 34.1 -> 31.8 / 32.4; at 2 bits one wave per team is faster)
+            int ks_first = deep ? 1 : (c.rs >= 8 ? ((c.exact || (bits == 3 && mb == 1)) ? 2 : 1) : 2);
             while (ks_first > 1 && c.rs * ks_first > 16) --ks_first;
             int nw = 0, stages = 2;
             for (int ks = ks_first; ks >= 1 && !nw; --ks) {          // fewer waves per team if the first choice does not fit
