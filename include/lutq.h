@@ -21,8 +21,10 @@
  * round16 is one round-to-nearest-even to the 16-bit type `dtype`.
  *
  * Supported domain: bits in {2,3,4}; group_size in {32,64,128,256}; 1 <= M <= 128
- * (the kernel works on up to 32 activation rows; more are served in slices of 32, one launch
- * each, so the weights are streamed once per slice);
+ * (a launch works on up to 32 activation rows, at 4 bits with K / group_size a multiple of 8 on up
+ * to 64; more are served in slices of that many rows, one launch each on the caller's stream, so the
+ * weights are streamed once per slice; a 33..64-row launch is preceded by a small launch that copies
+ * the slice's activations into the workspace in the order the matrix instruction reads them);
  * N a multiple of 16; K a multiple of the K-tile of the bit width (128 for
  * 4-bit, 256 for 2- and 3-bit) and of group_size; device pointers 16-byte aligned.
  *
@@ -158,14 +160,19 @@ typedef struct {
                                  row_groups_per_workgroup is 0 or that quotient) or row_groups_per_workgroup
                                  (a divisor of the row groups); R is 1 or 2, waves_per_workgroup 4..16 with
                                  no relation to the row groups, tiles_in_flight 2 */
-                              /* LUTQ_SCHED_ROWS (3) = activation-stationary (5 <= M <= 32): `grid` workgroups own
+                              /* LUTQ_SCHED_ROWS (3) = activation-stationary (M >= 5): `grid` workgroups own
                                  whole 16-row blocks over the whole of K, dealt as evenly as whole row blocks
                                  allow (row_groups_per_workgroup = the whole part of N / 16 / grid, 0 or that
                                  value; at most 64); the wavefronts (waves_per_workgroup 4..16, as many as the
                                  instance's registers allow) split K, hold a K tile's activations in registers
                                  and stream the weights of row_blocks_per_wave (4 or 8) row blocks past them
                                  side by side, in as many passes as the workgroup's row blocks need;
-                                 tiles_in_flight 2 */
+                                 tiles_in_flight 2.  For M > 32 this scheduling asks for slices of 64 rows
+                                 (4 bits, K / group_size a multiple of 8; LUTQ_ERR_PLAN where no such
+                                 instance exists); that launch has one decomposition (4 row blocks side by
+                                 side, one workgroup per compute unit, 8 waves at most), so every other
+                                 field is 0 or the value lutq_plan_default reports; any other plan, and
+                                 the default where 64-row slices are not faster, means slices of 32 rows */
     int tiles_per_item;       /* LUTQ_SCHED_QUEUE: K tiles (128 columns at 4 bits, 256 at 2 and 3) per item:
                                  0, or a multiple of tiles_in_flight that divides the K tiles of a row */
 } lutq_plan;
@@ -192,7 +199,8 @@ lutq_status lutq_plan_check(int bits, int group_size, int64_t M, int64_t N, int6
 /* Plans chosen by measurement (lutq_tune; Section 4.1 picks the kernel configuration per shape offline and
  * dispatches on it): a process-wide table that lutq_matmul and lutq_matmul_static consult, when no plan
  * is passed, before their own choice.  An entry applies to calls with its bits, group_size, dtype, N,
- * K and m_min <= M <= m_max (for M > 32 the M of each 32-row slice counts); the first match wins; an
+ * K and m_min <= M <= m_max (for M > 32 the M of each slice of up to 32 rows counts; slices of 33..64
+ * rows have a single decomposition and do not consult the table); the first match wins; an
  * entry whose plan the kernels cannot run for a call is skipped (the library's own choice is used). */
 typedef struct {
     int bits, group_size;

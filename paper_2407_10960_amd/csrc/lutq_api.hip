@@ -18,7 +18,7 @@ namespace {
 using namespace lutq;
 
 constexpr int kMaxGrid = 4096;
-constexpr int64_t kMaxRows = 128;                  // activation rows of one call (slices of 32 per launch)
+constexpr int64_t kMaxRows = 128;                  // activation rows of one call (slices of 32 or 64 per launch)
 constexpr size_t kCounterBytes = 64 * 1024;                                   // 16384 row groups
 constexpr size_t kSlotBytes = (size_t)kSlotFloats * sizeof(float);            // 8 KiB
 constexpr size_t kWorkspaceBytes = kCounterBytes + (size_t)kMaxGrid * 2 * kSlotBytes;
@@ -30,6 +30,20 @@ constexpr size_t kWorkspaceBytes = kCounterBytes + (size_t)kMaxGrid * 2 * kSlotB
 // counters are zero whenever a launch starts; the slots are overwritten before they are read.
 constexpr size_t kStaticSlotBytes = LUTQ_STATIC_SCRATCH_BYTES - kCounterBytes;
 static __device__ __align__(256) unsigned char scratch[LUTQ_STATIC_SCRATCH_BYTES];
+
+// the operand-order copy of the activations for row-streaming launches beyond 32 rows (XopParams)
+__global__ __launch_bounds__(256) void rows_xop_kernel(const XopParams p) {
+    const int kt = (int)blockIdx.x;
+    const int chunks = p.STEPS * 4;                       // 16-byte chunks per row of a tile
+    for (int i = (int)threadIdx.x; i < p.MB * 16 * chunks; i += 256) {
+        const int m = i / chunks, c = i - m * chunks;
+        u32x4 v = u32x4{0u, 0u, 0u, 0u};
+        if (m < p.M) v = *reinterpret_cast<const u32x4*>(p.X + (size_t)m * p.K + (size_t)kt * (chunks * 8) + 8 * c);
+        const int s = c >> 2, lo = c & 3, mb = m >> 4, li = m & 15;
+        *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(p.Xop) + ((size_t)((kt * p.STEPS + s) * p.MB + mb) * 64 + (lo * 16 + li)) * 16) = v;
+    }
+}
+
 
 using layout::super_block;
 using layout::tile_k;
@@ -159,6 +173,28 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
     else if (bits == 3) take = (per >= 5 && amax <= 8 && M > 8 && M <= 16) || (per >= 6 && amax <= 8 && M <= 16) || few;
     // (only where one pass covers the workgroup's row blocks: a second pass costs more than the teams)
     return take && rows_decomp(bits, bf16, M, N, K, group_size, cus, out) && out->r >= amax;
+}
+
+// 33..64 activation rows in one pass over the weights: the row-streaming kernel with three or four M blocks
+// (4 bits, scale rows of whole 16-byte units, four row blocks side by side, activations from their
+// operand-order copy).  `take`: whether that is also the default (against two launches of 32 rows).
+bool wide_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int group_size, int cus, Decomp* out, bool* take) {
+    if (M <= 32 || M > 64 || ((K / group_size) * 2) % 16 != 0) return false;
+    const int64_t nb = N / 16, kt = K / tile_k(bits);
+    const int mb = (int)((M + 15) / 16);
+    const int grid = (int)(nb < cus ? nb : cus);
+    const int64_t per = nb / grid;
+    if (per > 64) return false;
+    int nw = rows_instance_waves(bits, bf16, mb, 4);
+    if (nw == 0) return false;
+    if (nw > kt) nw = (int)(kt < 4 ? 4 : kt);
+    if (rows_blocks_per_round(bits, 4, (int)(K / group_size) * 2, mb, nw) < 1) return false;
+    out->r = 4; out->grid = grid; out->nw = nw; out->stages = 2; out->rs = (int)per; out->queue = 0; out->it = 0; out->rows = 1;
+    // Measured against two launches of 32 rows (MI355X, M = 64, us): 8B QKV 23.6 -> 16.6, O 21.5 -> 14.9, gate+up 42.3 ->
+    // 32.1 (bf16 46.4 -> 32.7), down 40.4 -> 33.9; 70B QKV bf16 46.7 -> 28.1, O 37.6 -> 25.9, gate+up 135.7 -> 102.3, down
+    // 83.0 -> 71.7; N = K = 8192 group 32 36.5 -> 26.3.  Below one row block per compute unit it was not measured.
+    *take = nb >= (int64_t)cus;
+    return true;
 }
 
 // LDS bytes of a work-queue launch
@@ -673,11 +709,16 @@ extern "C" lutq_status lutq_plan_default_for(int bits, int group_size, int64_t M
     lutq_status st = check_problem(bits, group_size, N, K);
     if (st != LUTQ_OK) return st;
     if (M < 1 || M > kMaxRows || compute_units < 1 || compute_units > 4096) return LUTQ_ERR_SHAPE;
-    if (M > 32) M = 32;                                   // the plan of the 32-row slices
     if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
     const bool sch = (K / group_size) % 8 == 0;
     Decomp d;
-    if (!default_queue_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, &d) &&
+    bool wide = false;
+    // beyond 32 rows: the plan of the 64-row slices where those are the default, else that of the 32-row slices
+    if (M > 32 && !(wide_rows_decomp(bits, dtype == LUTQ_BF16, M < 64 ? M : 64, N, K, group_size, compute_units, &d, &wide) && wide)) {
+        wide = false;
+        M = 32;
+    }
+    if (!wide && !default_queue_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, &d) &&
         !default_rows_decomp(bits, dtype == LUTQ_BF16, M, N, K, group_size, compute_units, &d))
         d = default_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, 0, group_size);
     plan->row_blocks_per_wave = d.r;
@@ -752,15 +793,20 @@ struct Prepared {
     bool rows_rowlut;         // ... with one table per output row
     RowsParams rp;
     int rows_lds;
+    XopParams xp;             // ... beyond 32 rows: the operand-order copy of X made first (xp.Xop != nullptr)
 };
 
 // Validates a row-streaming launch and fills out->rp.  `d`: r = row blocks side by side (4 or 8), grid,
 // nw, rs = row blocks per workgroup (the whole part of row blocks / grid).
 lutq_status prepare_rows(const void* X, const void* packed, const void* scales, const void* lut, int bits,
                          int group_size, int64_t M, int64_t N, int64_t K, bool bf16, void* Y, const Decomp& d, Prepared* out,
-                         bool rowlut = false) {
+                         bool rowlut = false, void* xop = nullptr, size_t xop_room = 0, bool dry = false) {
     const int64_t nb = N / 16, kt = K / tile_k(bits);
-    const int mb = M > 16 ? 2 : 1;
+    if (M < 1 || M > 64) return LUTQ_ERR_SHAPE;
+    const int mb = M > 32 ? (int)((M + 15) / 16) : M > 16 ? 2 : 1;
+    // beyond 32 rows the kernel reads the activations from their operand-order copy in the scratch
+    const size_t xop_bytes = mb > 2 ? (size_t)(K / 32) * mb * 1024 : 0;
+    if (mb > 2 && (rowlut || (!dry && (!xop || xop_bytes > xop_room)))) return LUTQ_ERR_PLAN;
     const int max_waves = rows_instance_waves(bits, bf16, mb, d.r);
     if (max_waves == 0 || d.nw < 4 || d.nw > max_waves || d.stages != 2) return LUTQ_ERR_PLAN;
     if (d.grid < 1 || d.grid > kMaxGrid || d.grid > nb || d.rs < 1 || d.rs > 64 || d.rs != nb / d.grid) return LUTQ_ERR_PLAN;
@@ -788,6 +834,12 @@ lutq_status prepare_rows(const void* X, const void* packed, const void* scales, 
     q.packed_bytes = (uint32_t)(N * K * bits / 8);
     q.scale_bytes = (uint32_t)(N * (K / group_size) * 2);
     q.x_bytes = (uint32_t)(M * K * 2);
+    out->xp = XopParams{};
+    if (mb > 2) {
+        out->xp = XopParams{static_cast<const uint16_t*>(X), static_cast<uint16_t*>(xop), (int)M, (int)K, mb, tile_k(bits) / 32};
+        q.X = static_cast<const uint16_t*>(xop);
+        q.x_bytes = (uint32_t)xop_bytes;
+    }
     q.M = (int)M; q.N = (int)N; q.K = (int)K; q.KT = (int)kt;
     q.SG2 = (int)(K / group_size) * 2;
     q.SBL = ilog2(super_block(nb));
@@ -1150,6 +1202,10 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
 
 lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dtype dtype, void* stream) {
     if (q.rows) {
+        if (q.xp.Xop) {
+            hipLaunchKernelGGL(rows_xop_kernel, dim3((unsigned)q.rp.KT), dim3(256), 0, static_cast<hipStream_t>(stream), q.xp);
+            if (hipGetLastError() != hipSuccess) return LUTQ_ERR_DEVICE;
+        }
         const hipError_t e = pick_rows(bits, dtype)(group_size, q.mb, q.r, q.rows_rowlut, q.rp, q.rows_lds, static_cast<hipStream_t>(stream));
         return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
     }
@@ -1169,33 +1225,89 @@ lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dt
 
 namespace {
 
+// How a call's activation rows are cut into launches: slices of 64 rows through the row-streaming kernel where
+// that exists and is the default (or the plan asks for it: scheduling = LUTQ_SCHED_ROWS), else slices of 32.
+// Returns the slice height; *d holds the 64-row decomposition (its waves are those of a full slice).
+int slice_rows(int bits, int group_size, int64_t M, int64_t N, int64_t K, bool bf16, const lutq_plan* user_plan, bool rowlut,
+               int cus, lutq_status* st) {
+    *st = LUTQ_OK;
+    if (M <= 32 || rowlut) return 32;
+    const bool plan_is_empty = !user_plan || (user_plan->row_blocks_per_wave == 0 && user_plan->grid == 0 &&
+                                              user_plan->waves_per_workgroup == 0 && user_plan->tiles_in_flight == 0 &&
+                                              user_plan->row_groups_per_workgroup == 0 && user_plan->tiles_per_item == 0);
+    const int sched = user_plan ? user_plan->scheduling : 0;
+    if (sched != LUTQ_SCHED_ROWS && !(sched == 0 && plan_is_empty)) return 32;
+    Decomp d;
+    bool take = false;
+    const bool have = wide_rows_decomp(bits, bf16, M < 64 ? M : 64, N, K, group_size, cus, &d, &take);
+    if (sched == LUTQ_SCHED_ROWS) {
+        // beyond 32 rows the row-streaming plan has no free fields: each is zero or the one value there is
+        auto fixed = [](int given, int only) { return given == 0 || given == only; };
+        if (!have || !fixed(user_plan->row_blocks_per_wave, d.r) || !fixed(user_plan->grid, d.grid) ||
+            !fixed(user_plan->waves_per_workgroup, d.nw) || !fixed(user_plan->tiles_in_flight, d.stages) ||
+            !fixed(user_plan->row_groups_per_workgroup, d.rs) || user_plan->tiles_per_item != 0)
+            *st = LUTQ_ERR_PLAN;
+        return 64;
+    }
+    return have && take ? 64 : 32;
+}
+
 lutq_status matmul_sliced(const void* X, const void* packed, const void* scales, const void* lut,
                           int bits, int group_size, int64_t M, int64_t N, int64_t K,
                           lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
                           void* stream, const lutq_plan* user_plan, bool rowlut, bool fitted_workspace = false) {
     if (!X || !Y) return LUTQ_ERR_NULL;
     if (M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
-    // More than 32 activation rows: slices of 32 rows, one launch each on the same stream (the
-    // weights are streamed once per slice).  Every slice is validated before the first launch.
-    const int64_t full = M / 32, rest = M % 32;
+    // More than 32 activation rows: slices of 32 rows (64 where the row-streaming kernel takes them in one pass
+    // over the weights), one launch each on the same stream (the weights are streamed once per slice).  Every
+    // slice is validated before the first launch.
+    int64_t step = 32;
+    if (M > 32) {
+        lutq_status st = check_problem(bits, group_size, N, K);
+        if (st != LUTQ_OK) return st;
+        if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
+        const DeviceInfo di = device_info();
+        if (!di.ok) return LUTQ_ERR_DEVICE;
+        step = slice_rows(bits, group_size, M, N, K, dtype == LUTQ_BF16, user_plan, rowlut, di.cus, &st);
+        if (st != LUTQ_OK) return st;
+    }
+    const int64_t full = M / step, rest = M % step;
     Prepared body{}, tail{};
     const size_t xrow = (size_t)K * 2, yrow = (size_t)N * 2;
+    // one slice of m rows (m <= step) starting at row m0
+    auto prepare = [&](int64_t m0, int64_t m, Prepared* out) -> lutq_status {
+        const void* Xs = static_cast<const char*>(X) + (size_t)m0 * xrow;
+        void* Ys = static_cast<char*>(Y) + (size_t)m0 * yrow;
+        if (m <= 32)
+            return prepare_matmul(Xs, packed, scales, lut, bits, group_size, m, N, K, dtype, Ys, workspace, workspace_bytes,
+                                  step == 64 ? nullptr : user_plan, rowlut, 0, out, fitted_workspace);
+        if (!packed || !scales || !lut) return LUTQ_ERR_NULL;
+        if (!aligned16(X) || !aligned16(packed) || !aligned16(scales) || !aligned16(Y) || !aligned16(workspace) ||
+            (reinterpret_cast<uintptr_t>(lut) & 1u) != 0)
+            return LUTQ_ERR_ALIGN;
+        if (!workspace || workspace_bytes < (fitted_workspace ? kCounterBytes : kWorkspaceBytes)) return LUTQ_ERR_WORKSPACE;
+        Decomp d;
+        bool take = false;
+        if (!wide_rows_decomp(bits, dtype == LUTQ_BF16, m, N, K, group_size, device_info().cus, &d, &take)) return LUTQ_ERR_PLAN;
+        // the operand-order copy of the slice's activations lives where other launches keep their partial sums
+        const lutq_status st = prepare_rows(Xs, packed, scales, lut, bits, group_size, m, N, K, dtype == LUTQ_BF16, Ys, d, out, false,
+                                            static_cast<char*>(workspace) + kCounterBytes, workspace_bytes - kCounterBytes);
+        return st == LUTQ_ERR_PLAN && fitted_workspace ? LUTQ_ERR_SCRATCH : st;
+    };
     if (full > 0) {
-        lutq_status st = prepare_matmul(X, packed, scales, lut, bits, group_size, 32, N, K, dtype, Y, workspace,
-                                        workspace_bytes, user_plan, rowlut, 0, &body, fitted_workspace);
+        const lutq_status st = prepare(0, step, &body);
         if (st != LUTQ_OK) return st;
     }
     if (rest > 0) {
-        lutq_status st = prepare_matmul(static_cast<const char*>(X) + (size_t)full * 32 * xrow, packed, scales, lut, bits,
-                                        group_size, rest, N, K, dtype, static_cast<char*>(Y) + (size_t)full * 32 * yrow,
-                                        workspace, workspace_bytes, user_plan, rowlut, 0, &tail, fitted_workspace);
+        const lutq_status st = prepare(full * step, rest, &tail);
         if (st != LUTQ_OK) return st;
     }
     for (int64_t i = 0; i < full; ++i) {
         Prepared q = body;
-        q.p.X = reinterpret_cast<const uint16_t*>(static_cast<const char*>(X) + (size_t)i * 32 * xrow);
-        q.p.Y = reinterpret_cast<uint16_t*>(static_cast<char*>(Y) + (size_t)i * 32 * yrow);
-        q.rp.X = q.p.X;
+        q.p.X = reinterpret_cast<const uint16_t*>(static_cast<const char*>(X) + (size_t)i * step * xrow);
+        q.p.Y = reinterpret_cast<uint16_t*>(static_cast<char*>(Y) + (size_t)i * step * yrow);
+        if (q.xp.Xop) q.xp.X = q.p.X;       // the kernel reads the copy, which is made from this slice's rows
+        else q.rp.X = q.p.X;
         q.rp.Y = q.p.Y;
         lutq_status st = launch_prepared(q, bits, group_size, dtype, stream);
         if (st != LUTQ_OK) return st;
@@ -1209,10 +1321,27 @@ extern "C" lutq_status lutq_plan_check(int bits, int group_size, int64_t M, int6
                                        int compute_units, const lutq_plan* plan) {
     if (compute_units < 1 || compute_units > 4096 || M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
     Prepared q{};
-    for (int64_t m : {M >= 32 ? (int64_t)32 : (int64_t)0, M % 32}) {      // the 32-row slices, then the rest
+    int64_t step = 32;
+    if (M > 32) {
+        lutq_status st = check_problem(bits, group_size, N, K);
+        if (st != LUTQ_OK) return st;
+        if (dtype != LUTQ_F16 && dtype != LUTQ_BF16) return LUTQ_ERR_DTYPE;
+        step = slice_rows(bits, group_size, M, N, K, dtype == LUTQ_BF16, plan, false, compute_units, &st);
+        if (st != LUTQ_OK) return st;
+    }
+    for (int64_t m : {M >= step ? step : (int64_t)0, M % step}) {      // the full slices, then the rest
         if (m == 0) continue;
-        lutq_status st = prepare_matmul(nullptr, nullptr, nullptr, nullptr, bits, group_size, m, N, K, dtype, nullptr,
-                                        nullptr, 0, plan, false, compute_units, &q);
+        lutq_status st;
+        if (m <= 32) {
+            st = prepare_matmul(nullptr, nullptr, nullptr, nullptr, bits, group_size, m, N, K, dtype, nullptr,
+                                nullptr, 0, step == 64 ? nullptr : plan, false, compute_units, &q);
+        } else {
+            Decomp d;
+            bool take = false;
+            if (!wide_rows_decomp(bits, dtype == LUTQ_BF16, m, N, K, group_size, compute_units, &d, &take)) return LUTQ_ERR_PLAN;
+            st = prepare_rows(nullptr, nullptr, nullptr, nullptr, bits, group_size, m, N, K, dtype == LUTQ_BF16, nullptr, d, &q,
+                              false, nullptr, 0, true);
+        }
         if (st != LUTQ_OK) return st;
     }
     return LUTQ_OK;

@@ -140,7 +140,7 @@ hipError_t launch_decode_group(int r, bool rowlut, const DecodeParams& p, int ld
     return hipErrorInvalidValue;
 }
 
-// Row-streaming kernel for 5..32 activation rows: MB halves of M, AMAX = 4 or 8 row blocks side by side.
+// Row-streaming kernel for 5..64 activation rows: MB blocks of sixteen rows, AMAX = 4 or 8 row blocks side by side.
 template <int GROUP, int MB, int AMAX, bool RLUT = false>
 hipError_t launch_rows_one(const RowsParams& p, int lds_bytes, hipStream_t stream) {
     constexpr int max_waves = rows_max_waves(LUTQ_INST_BITS, MB, AMAX, Tab<LUTQ_INST_BITS, LUTQ_INST_DT>::WIDE);
@@ -170,6 +170,8 @@ hipError_t launch_rows_group(int mb, int amax, bool rowlut, const RowsParams& p,
     if (mb == 1 && amax == 8) return launch_rows_one<GROUP, 1, 8>(p, lds_bytes, stream);
     if (mb == 2 && amax == 4) return launch_rows_one<GROUP, 2, 4>(p, lds_bytes, stream);
     if (mb == 2 && amax == 8) return launch_rows_one<GROUP, 2, 8>(p, lds_bytes, stream);
+    if (mb == 3 && amax == 4) return launch_rows_one<GROUP, 3, 4>(p, lds_bytes, stream);   // 33..64 rows (4 bits)
+    if (mb == 4 && amax == 4) return launch_rows_one<GROUP, 4, 4>(p, lds_bytes, stream);
     return hipErrorInvalidValue;
 }
 

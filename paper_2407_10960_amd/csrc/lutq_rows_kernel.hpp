@@ -31,7 +31,7 @@
 namespace lutq {
 
 struct RowsParams {
-    const uint16_t* X;        // [M, K]
+    const uint16_t* X;        // [M, K]; MB > 2: the operand-order copy (rows_xop_kernel), KT x STEPS x MB fragments of 1 KiB
     const uint8_t* packed;
     const uint16_t* scales;   // [N, SG]
     const uint16_t* lut;
@@ -73,6 +73,7 @@ __host__ __device__ constexpr int rows_tiles_in_flight(int, int) { return 4; }  
 __host__ __device__ constexpr bool rows_x_double(int bits, int mb, bool wide_table) { return bits == 4 && mb == 2 && !wide_table; }
 __host__ __device__ constexpr int rows_max_waves(int bits, int mb, int amax, bool wide_table) {
     const int steps = bits == 4 ? 4 : 8;
+    if (mb > 2 && (bits != 4 || amax != 4)) return 0;   // 33..64 rows: 4 bits, four row blocks side by side
     const int regs = amax * mb * 4 + steps * mb * 4 + (bits == 4 ? 84 : bits == 3 ? 116 : 108) + (wide_table ? 28 : 0)
                    + (bits == 4 && amax == 8 ? 20 : 0) + (rows_x_double(bits, mb, wide_table) ? steps * mb * 4 + 8 : 0);
     return regs <= 128 ? 16 : regs <= 168 ? 12 : regs <= 240 ? 8 : 0;
@@ -95,6 +96,10 @@ void rows_kernel(const RowsParams p) {
     static_assert(STEPS % D == 0, "the ring of table reads runs on from one tile into the next");
     constexpr int NST = rows_tiles_in_flight(BITS, AMAX);   // weight tiles (and their scales) in flight per wave
     constexpr bool XDB = rows_x_double(BITS, MB, Tab<BITS, DT>::WIDE);
+    // More than 32 rows: the activations come from a copy in operand order (fragment (kt, s, mb) = the 1 KiB the
+    // wave's 64 lanes hold for K step s of tile kt and rows 16 mb .. 16 mb + 15, rows beyond M zero), written by
+    // rows_xop_kernel just before this launch: every load is one contiguous KiB instead of sixteen rows' 64 bytes.
+    constexpr bool XOP = MB > 2;
     static_assert(AMAX % NST == 0, "the row blocks of a pass are walked in rounds of the pipeline's stages");
 
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.packed_bytes), "s"(p.scale_bytes),
@@ -142,7 +147,7 @@ void rows_kernel(const RowsParams p) {
     for (int mb = 0; mb < MB; ++mb) {
         const int m = li + 16 * mb;
         valid[mb] = m < p.M;
-        xlane[mb] = ((uint32_t)m * (uint32_t)p.K + 8u * (uint32_t)lo) * 2u;
+        xlane[mb] = XOP ? (uint32_t)mb * 1024u + 16u * (uint32_t)lane : ((uint32_t)m * (uint32_t)p.K + 8u * (uint32_t)lo) * 2u;
     }
     const uint32_t wlane = 16u * lane;
     (void)wlane;
@@ -195,10 +200,11 @@ void rows_kernel(const RowsParams p) {
         // load covers sixteen rows 2K bytes apart -- sixteen requests to one L2 channel -- and takes its time.)
         u32x4 bx[XDB ? 2 : 1][STEPS][MB];
         auto load_x_step = [&](auto buf, int kt, int s) {
-            const uint32_t tx = kt < kb ? (uint32_t)kt * (TK * 2) : kOutOfRange;
+            const uint32_t tx = kt < kb ? (uint32_t)kt * (XOP ? STEPS * MB * 1024 : TK * 2) : kOutOfRange;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
-                bx[decltype(buf)::value][s][mb] = __builtin_amdgcn_raw_buffer_load_b128(rX, tx + xlane[mb] + 64u * s, 0, kAuxNone);
+                bx[decltype(buf)::value][s][mb] =
+                    __builtin_amdgcn_raw_buffer_load_b128(rX, tx + xlane[mb] + (XOP ? MB * 1024u : 64u) * s, 0, kAuxNone);
         };
         auto load_x = [&](auto buf, int kt) {
 #pragma unroll
@@ -345,5 +351,14 @@ void rows_kernel(const RowsParams p) {
         (void)valid;
     }
 }
+
+// The operand-order copy of X for rows_kernel's instances beyond 32 rows (the kernel sits beside the C ABI).  One workgroup per K tile; thread
+// (row m, 16-byte chunk c of the tile's row) reads X[m, kt * TK + 8 c .. + 7] (zero for m >= M) and stores it where
+// lane 16 (c mod 4) + m mod 16 of fragment (kt, c / 4, m / 16) expects it.
+struct XopParams {
+    const uint16_t* X;        // [M, K]
+    uint16_t* Xop;            // KT x STEPS x MB x 1 KiB
+    int M, K, MB, STEPS;      // STEPS = TK / 32
+};
 
 }  // namespace lutq

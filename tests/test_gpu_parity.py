@@ -180,6 +180,78 @@ def test_more_than_32_rows(lutq, bits, dtype):
     assert not d.ws[:65536].any().item()
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_64_row_slices(lutq, dtype):
+    """33..64 activation rows in one pass over the weights (4 bits: the row-streaming kernel with three or four
+    blocks of sixteen rows, activations from their operand-order copy): every row count around the block
+    boundaries, one to six row blocks per workgroup (short and second passes, uneven shares), every group size,
+    65..128 rows as a 64-row slice plus the rest; against the oracle and bit-reproducible.  Where no such
+    instance exists the row-streaming plan is refused and the default stays with 32-row slices."""
+    import torch
+    ROWS = lutq.Plan(scheduling=3)
+    dt = 0 if dtype == "f16" else 1
+    rng = np.random.default_rng(11)
+    for (N, K, group, lut, Ms) in [(208, 1024, 64, "nf", (33, 40, 47, 48, 49, 63, 64)),
+                                   (16 * (256 * 5 + 37), 512, 32, "learned", (36, 64)),
+                                   (16 * 300, 2048, 128, "random_index", (50, 64, 65, 100, 128)),
+                                   (64, 4096, 256, "nf", (33, 64, 96))]:
+        base = gen.make_case(70 + group, 32, N, K, 4, group, dtype, lut)
+        d = DeviceCase(lutq, base)
+        for M in Ms:
+            X = gen.encode16(rng.standard_normal((M, K)), dtype)
+            c = gen.Case(M, N, K, 4, group, dtype, X, base.Q, base.S, base.T)
+            assert lutq.lutq_plan_check(4, group, M, N, K, dt, 256, ROWS) == 0
+            Xd = to_dev(X, dtype)
+            Y = to_bits(d.matmul(lutq, X=Xd, plan=ROWS))
+            check_y(Y, c, f"{dtype} g{group} N{N} M{M} 64-row slices")
+            assert np.array_equal(Y, to_bits(d.matmul(lutq, X=Xd, plan=ROWS))), "not reproducible"
+            Yd = to_bits(d.matmul(lutq, X=Xd))              # the library's own choice
+            check_y(Yd, c, f"{dtype} g{group} N{N} M{M} default")
+        assert not d.ws[:65536].any().item()
+    # a plan with fields: only the values of the one decomposition there is
+    base = gen.make_case(75, 32, 208, 1024, 4, 64, dtype, "nf")
+    d = DeviceCase(lutq, base)
+    Xd = to_dev(gen.encode16(rng.standard_normal((40, 1024)), dtype), dtype)
+    d.matmul(lutq, X=Xd, plan=lutq.Plan(4, 13, 8, 2, 1, 3))
+    for bad in (lutq.Plan(8, 0, 0, 0, 0, 3), lutq.Plan(0, 7, 0, 0, 0, 3), lutq.Plan(0, 0, 12, 0, 0, 3)):
+        Y = torch.full((40, 208), 7.0, dtype=Xd.dtype, device="cuda")
+        with pytest.raises(lutq.LutqError) as e:
+            lutq.lutq_matmul(Xd, d.packed, d.S, d.T, 4, 64, Y, d.ws, plan=bad)
+        assert e.value.code == 10
+        torch.cuda.synchronize()
+        assert (Y == 7.0).all().item()
+    # 3 bits, and scale rows that are not whole 16-byte units, have no such instance
+    assert lutq.lutq_plan_check(3, 64, 64, 208, 2048, dt, 256, ROWS) == 10
+    assert lutq.lutq_plan_check(4, 128, 64, 208, 512, dt, 256, ROWS) == 10
+    assert lutq.lutq_plan_check(3, 64, 64, 208, 2048, dt, 256, None) == 0
+
+
+WIDE_FULL_SIZE = [
+    # (name, N, K, group, dtype, M): shapes with two or more row blocks per compute unit, default launch configuration
+    ("8B gate_up W4 g128 M64 (shares of seven row blocks: passes of four and three)", 28672, 4096, 128, "f16", 64),
+    ("8B gate_up W4 g128 bf16 M40", 28672, 4096, 128, "bf16", 40),
+    ("70B down W4 g64 bf16 M64 (two row blocks per workgroup, K = 28672)", 8192, 28672, 64, "bf16", 64),
+    ("70B qkv W4 g64 M100 (a 64-row slice and 36 rows; shares of 2 and 3)", 10240, 8192, 64, "f16", 100),
+    ("70B gate_up W4 g64 bf16 M128 (fourteen row blocks per workgroup)", 57344, 8192, 64, "bf16", 128),
+]
+
+
+@pytest.mark.parametrize("name,N,K,group,dtype,M", WIDE_FULL_SIZE)
+def test_64_row_slices_full_size(lutq, name, N, K, group, dtype, M):
+    """Full layer sizes beyond 32 rows in the default launch configuration (64-row slices); the oracle recomputes
+    all M rows of 176 sampled weight rows, first and last row blocks included."""
+    assert lutq.lutq_plan_default(4, group, M, N, K, 0 if dtype == "f16" else 1).scheduling == 3
+    c = gen.make_case(31, M, N, K, 4, group, dtype, "random_index")
+    d = DeviceCase(lutq, c)
+    Y = to_bits(d.matmul(lutq))
+    assert not d.ws[:65536].any().item()
+    rng = np.random.default_rng(2)
+    rows = np.unique(np.concatenate([np.arange(16), np.arange(N - 16, N), rng.choice(N, 144, replace=False)]))
+    sub = gen.Case(M, len(rows), K, 4, group, dtype, c.X, c.Q[rows], c.S[rows], c.T)
+    check_y(Y[:, rows], sub, name)
+    assert np.isfinite(orc.to_f64(Y, dtype)).all()
+
+
 @pytest.mark.parametrize("bits", BITS)
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_group_256(lutq, bits, dtype):

@@ -205,7 +205,13 @@ def test_default_plans_of_the_llama3_shapes():
         p = lutq.lutq_plan_default_for(4, g, 1, N, K, 0, 256)
         assert (p.row_blocks_per_wave, p.grid, p.waves_per_workgroup, p.tiles_in_flight, p.row_groups_per_workgroup,
                 p.scheduling, p.tiles_per_item) == plan, (N, K, p)
-    assert lutq.lutq_plan_default_for(4, 128, 100, 4096, 4096, 0, 256) == lutq.lutq_plan_default_for(4, 128, 32, 4096, 4096, 0, 256)
+    # beyond 32 rows: the one decomposition of the 64-row slices (4 bits, whole 16-byte units of scales per row, at
+    # least one row block per compute unit), else the plan of the 32-row slices
+    assert lutq.lutq_plan_default_for(4, 128, 100, 4096, 4096, 0, 256) == lutq.Plan(4, 256, 8, 2, 1, 3, 0)
+    assert lutq.lutq_plan_default_for(4, 128, 40, 28672, 4096, 1, 256) == lutq.Plan(4, 256, 8, 2, 7, 3, 0)
+    for (b, N, K) in [(3, 4096, 4096), (4, 2048, 4096), (4, 4096, 512)]:
+        assert lutq.lutq_plan_default_for(b, 128, 100, N, K, 0, 256) == lutq.lutq_plan_default_for(b, 128, 32, N, K, 0, 256)
+        assert lutq.lutq_plan_check(b, 128, 100, N, K, 0, 256, None) == 0
     with pytest.raises(lutq.LutqError):
         lutq.lutq_plan_default_for(4, 128, 1, 4096, 4096, 0, 0)
 

@@ -34,7 +34,10 @@ def test_static_scratch_matches_workspace_call(lutq):
              (17, 192, 1024, 3, "bf16", lutq.Plan(2, 5, 8, 2, 2)),
              (32, 128, 1024, 2, "f16", lutq.Plan(1, 3, 8, 2, 8)),
              (1, 4096, 4096, 4, "f16", None),
-             (40, 208, 2048, 4, "bf16", lutq.Plan(1, 5, 8, 2, 1))]
+             (40, 208, 2048, 4, "bf16", lutq.Plan(1, 5, 8, 2, 1)),
+             # 64-row slices: the operand-order copy of the activations lives in the same array
+             (64, 4800, 1024, 4, "f16", None),
+             (100, 208, 2048, 4, "bf16", lutq.Plan(scheduling=3))]
     for rnd in range(2):
         for i, (M, N, K, bits, dtype, plan) in enumerate(specs):
             c = gen.make_case(900 + i, M, N, K, bits, 64, dtype, "nf")
