@@ -1,4 +1,5 @@
-// The fused kernel for 5 to 32 activation rows on matrices with several row blocks per compute unit.
+// The fused kernel for 5 to 32 activation rows on matrices with several row blocks per compute unit, and for 33 to 64
+// rows at 4 bits (three or four blocks of sixteen rows; the activations then come from an operand-order copy).
 //
 // What is computed is that of matmul_kernel (Algorithm 1 of the paper).  The loop nest is turned round:
 // from five rows up the activations are as large a stream as the weights (M x 128 x 2 bytes per 1 KiB
