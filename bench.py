@@ -391,7 +391,7 @@ def main():
         del X16, Y16
         # 33..128 activation rows
         dense = Dense(torch, N, K, torch.float16)
-        for m2 in (64, 128):
+        for m2 in (48, 64, 96, 128):
             X2 = torch.randn((m2, K), device="cuda").to(torch.float16)
             Y2 = torch.empty((m2, N), dtype=torch.float16, device="cuda")
             t = timer.per_call(lambda X2=X2, Y2=Y2: [lutq.lutq_matmul(X2, layers[li]["gate_up"]["packed"], layers[li]["gate_up"]["S"], g["T"],

@@ -33,17 +33,17 @@ static __device__ __align__(256) unsigned char scratch[LUTQ_STATIC_SCRATCH_BYTES
 
 // the operand-order copy of the activations for row-streaming launches beyond 32 rows (XopParams)
 __global__ __launch_bounds__(256) void rows_xop_kernel(const XopParams p) {
-    const int kt = (int)blockIdx.x;
+    const int kt = (int)blockIdx.x, mb = (int)blockIdx.y;   // one workgroup per (K tile, block of sixteen rows)
     const int chunks = p.STEPS * 4;                       // 16-byte chunks per row of a tile
-    for (int i = (int)threadIdx.x; i < p.MB * 16 * chunks; i += 256) {
-        const int m = i / chunks, c = i - m * chunks;
+    for (int i = (int)threadIdx.x; i < 16 * chunks; i += 256) {
+        const int li = i / chunks, c = i - li * chunks;
+        const int m = 16 * mb + li;
         u32x4 v = u32x4{0u, 0u, 0u, 0u};
         if (m < p.M) v = *reinterpret_cast<const u32x4*>(p.X + (size_t)m * p.K + (size_t)kt * (chunks * 8) + 8 * c);
-        const int s = c >> 2, lo = c & 3, mb = m >> 4, li = m & 15;
+        const int s = c >> 2, lo = c & 3;
         *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(p.Xop) + ((size_t)((kt * p.STEPS + s) * p.MB + mb) * 64 + (lo * 16 + li)) * 16) = v;
     }
 }
-
 
 using layout::super_block;
 using layout::tile_k;
@@ -1203,7 +1203,7 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
 lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dtype dtype, void* stream) {
     if (q.rows) {
         if (q.xp.Xop) {
-            hipLaunchKernelGGL(rows_xop_kernel, dim3((unsigned)q.rp.KT), dim3(256), 0, static_cast<hipStream_t>(stream), q.xp);
+            hipLaunchKernelGGL(rows_xop_kernel, dim3((unsigned)q.rp.KT, (unsigned)q.xp.MB), dim3(256), 0, static_cast<hipStream_t>(stream), q.xp);
             if (hipGetLastError() != hipSuccess) return LUTQ_ERR_DEVICE;
         }
         const hipError_t e = pick_rows(bits, dtype)(group_size, q.mb, q.r, q.rows_rowlut, q.rp, q.rows_lds, static_cast<hipStream_t>(stream));
