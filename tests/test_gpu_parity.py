@@ -226,6 +226,41 @@ def test_64_row_slices(lutq, dtype):
     assert lutq.lutq_plan_check(3, 64, 64, 208, 2048, dt, 256, None) == 0
 
 
+def test_64_row_slices_over_seeded_random_shapes(lutq):
+    """The 64-row launch (asked for by plan) over shapes it was not written around: one to a thousand row blocks
+    (fewer than compute units, uneven shares, up to four passes), one to sixty-four K tiles (fewer tiles than
+    waves), every group size, 33..128 rows, both dtypes; refused exactly where K / group is not a multiple of 8."""
+    ROWS = lutq.Plan(scheduling=3)
+    rng = np.random.default_rng(4242)
+    nbs = [1, 2, 3, 7, 13, 64, 255, 256, 257, 300, 511, 512, 700, 1023]
+    workspace = None
+    for i in range(40):
+        dtype = str(rng.choice(["f16", "bf16"]))
+        group = int(rng.choice([32, 64, 128, 256]))
+        M = int(rng.choice([33, 37, 48, 49, 57, 64, 65, 80, 97, 127, 128]))
+        nb = int(rng.choice(nbs))
+        kt = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 32, 64]))
+        if nb * kt > 4096:
+            kt = max(1, 4096 // nb)
+        if group == 256 and kt % 2:
+            kt += 1
+        N, K = 16 * nb, 128 * kt
+        ok = (K // group) % 8 == 0
+        what = f"case {i}: {dtype} g{group} M{M} N{N} K{K}"
+        assert (lutq.lutq_plan_check(4, group, M, N, K, 0 if dtype == "f16" else 1, 256, ROWS) == 0) == ok, what
+        if not ok:
+            continue
+        c = gen.make_case(3000 + i, M, N, K, 4, group, dtype, "random_index")
+        d = DeviceCase(lutq, c)
+        if workspace is None:
+            workspace = d.ws
+        d.ws = workspace
+        Y = to_bits(d.matmul(lutq, plan=ROWS))
+        check_y(Y, c, what)
+        assert np.array_equal(Y, to_bits(d.matmul(lutq, plan=ROWS))), what
+    assert not workspace[:65536].any().item()
+
+
 WIDE_FULL_SIZE = [
     # (name, N, K, group, dtype, M): shapes with two or more row blocks per compute unit, default launch configuration
     ("8B gate_up W4 g128 M64 (shares of seven row blocks: passes of four and three)", 28672, 4096, 128, "f16", 64),
