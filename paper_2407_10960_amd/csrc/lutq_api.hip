@@ -257,10 +257,14 @@ bool queue_decomp(int bits, bool bf16, bool sch, int64_t M, int64_t N, int64_t K
     // every wave about four items, so that an item's fold and hand-over stay a small part of its work
     int it = kt % 4 == 0 ? 4 : 2;
     if (kt % 8 == 0 && a * (kt / 8) >= 64 && !few_bits_two) it = 8;
+    // Uneven shares of two and three row blocks (70B QKV): items of eight tiles, and sixteen waves in bf16 (M = 1 fp16 11.3 ->
+    // 11.0 us, bf16 12.4 -> 11.7; M = 2 11.45 -> 11.3, bf16 12.55 -> 12.0; sixteen waves in fp16: 11.25)
+    const bool shares_2_3 = !even && per == 2 && !uneven_one && kt % 8 == 0 && kt / 8 >= 8;
+    if (shares_2_3) it = 8;
     if (kt % it != 0) return false;
     int64_t items = amax * (kt / it);
     while (queue_lds_bytes(bits, 16, (int)items, r) > 160 * 1024 && kt % (it * 2) == 0) { it *= 2; items = amax * (kt / it); }
-    int nw = items >= 16 ? ((amax <= 3 && !even && !uneven_one) || few_bits_mid || few_bits_two || (!even && per >= 4 && M > 2) ? 12 : 16)
+    int nw = items >= 16 ? (((amax <= 3 && !even && !uneven_one) && !(shares_2_3 && bf16)) || few_bits_mid || few_bits_two || (!even && per >= 4 && M > 2) ? 12 : 16)
                          : (int)(items < 4 ? 4 : items);
     if (queue_lds_bytes(bits, nw, (int)items, r) > 160 * 1024) return false;
     out->r = r; out->grid = cus; out->nw = nw; out->stages = 2; out->rs = (int)a; out->queue = 1; out->it = it;
