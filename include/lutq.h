@@ -172,9 +172,19 @@ typedef struct {
                                  instance exists); that launch has one decomposition (4 row blocks side by
                                  side, one workgroup per compute unit, 8 waves at most), so every other
                                  field is 0 or the value lutq_plan_default reports; any other plan, and
-                                 the default where 64-row slices are not faster, means slices of 32 rows */
+                                 the default where 64-row slices are not faster, means slices of 32 rows.
+                                 With tiles_per_item > 0 (M <= 32) K is cut into slices of that many K tiles
+                                 across workgroups: `grid` (required, a multiple of the number of slices) =
+                                 shares x slices, a share being at most row_blocks_per_wave row blocks (one
+                                 pass: row_groups_per_workgroup = the whole part of N / 16 / shares), so a
+                                 workgroup reads only its slice of the activations; every workgroup leaves
+                                 its slice's sums in the scratch and the last of a share to finish adds them
+                                 in slice order (shares <= 1024; shares x slices x row_blocks_per_wave x
+                                 ceil(M / 16) KiB of scratch) */
     int tiles_per_item;       /* LUTQ_SCHED_QUEUE: K tiles (128 columns at 4 bits, 256 at 2 and 3) per item:
-                                 0, or a multiple of tiles_in_flight that divides the K tiles of a row */
+                                 0, or a multiple of tiles_in_flight that divides the K tiles of a row.
+                                 LUTQ_SCHED_ROWS: 0 = K is not cut across workgroups, else the K tiles per
+                                 slice, a divisor of the K tiles of a row that leaves at least two slices */
 } lutq_plan;
 
 #define LUTQ_SCHED_TEAMS 1

@@ -102,6 +102,7 @@ struct Decomp {
     int queue = 0;                    // work-queue kernel (M <= 4): rs = row groups per workgroup, it = tiles per item
     int it = 0;
     int rows = 0;                     // row-streaming kernel: r = row blocks side by side, rs = row blocks per workgroup
+    int ks = 0;                       // ... K slices across workgroups (0, 1: none): grid = shares x ks, it = K tiles per slice
 };
 
 int rows_table_bytes(int bits) { return bits == 2 ? lut_row_table_bytes<2>() : bits == 3 ? lut_row_table_bytes<3>() : lut_row_table_bytes<4>(); }
@@ -173,6 +174,33 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
     else if (bits == 3) take = (per >= 5 && amax <= 8 && M > 8 && M <= 16) || (per >= 6 && amax <= 8 && M <= 16) || few;
     // (only where one pass covers the workgroup's row blocks: a second pass costs more than the teams)
     return take && rows_decomp(bits, bf16, M, N, K, group_size, cus, out) && out->r >= amax;
+}
+
+// K slices on the row-streaming kernel (17..32 rows, 3 and 4 bits): for matrices with at most one row block per compute
+// unit and a long K, four row blocks per share of workgroups and as many K slices as keep the grid within the compute
+// units, at least four slices of at least fourteen K tiles each; every workgroup then reads only its slice of the activations, and
+// a share's slices are added by whichever of its workgroups finishes last.  Measured against the team plans (MI355X, us,
+// HBM-cold weights): 8B down (4096 x 14336) M = 17 / 24 / 32 20.1 / 20.1 / 20.5 -> 14.5 / 15.4 / 16.8, bf16 M = 32 21.3 -> 16.9,
+// 3-bit 21.2 -> 17.9, group 32 20.5 -> 17.9; 4096 x 8192 M = 20 / 32 13.2 / 15.2 -> 11.3 / 12.5; 4096 x 28672 31.8 -> 26.4;
+// 2048 x 14336 18.9 -> 13.0; 3072 x 12288 24.0 -> 15.9.  Not taken: up to sixteen rows (0-6 %), slices of eight tiles
+// (8B O: 10.8 -> 10.2 at M = 32 but 9.3 -> 10.0 at M = 24), grids below half the compute units (1024 x 8192: 11.0 -> 12.3),
+// fewer than four slices (8B O in two slices of sixteen tiles: M = 20 8.6 -> 9.7), more than one row block per compute unit
+// (8B QKV, 70B O and down, N = K = 8192: within 3 % either way).
+bool sliced_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int group_size, int cus, Decomp* out) {
+    if (M < 17 || M > 32 || bits == 2 || ((K / group_size) * 2) % 16 != 0) return false;
+    const int64_t nb = N / 16, kt = K / tile_k(bits);
+    if (nb > cus || nb % 4 != 0) return false;
+    const int64_t shares = nb / 4;
+    int ks = 0;
+    for (int64_t k = cus / shares; k >= 4 && !ks; --k)
+        if (kt % k == 0 && kt / k >= 14) ks = (int)k;
+    if (!ks || shares * ks * 2 < cus || shares * 64 > (int64_t)kCounterBytes) return false;
+    int nw = rows_instance_waves(bits, bf16, 2, 4);
+    if (nw > 8) nw = 8;
+    if (nw < 4 || rows_blocks_per_round(bits, 4, (int)(K / group_size) * 2, 2, nw) < 1) return false;
+    out->r = 4; out->grid = (int)(shares * ks); out->nw = nw; out->stages = 2; out->rs = 4; out->queue = 0;
+    out->it = (int)(kt / ks); out->ks = ks; out->rows = 1;
+    return true;
 }
 
 // 33..64 activation rows in one pass over the weights: the row-streaming kernel with three or four M blocks
@@ -723,6 +751,7 @@ extern "C" lutq_status lutq_plan_default_for(int bits, int group_size, int64_t M
         M = 32;
     }
     if (!wide && !default_queue_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, &d) &&
+        !sliced_rows_decomp(bits, dtype == LUTQ_BF16, M, N, K, group_size, compute_units, &d) &&
         !default_rows_decomp(bits, dtype == LUTQ_BF16, M, N, K, group_size, compute_units, &d))
         d = default_decomp(bits, dtype == LUTQ_BF16, sch, M, N, K, compute_units, 0, group_size);
     plan->row_blocks_per_wave = d.r;
@@ -801,21 +830,32 @@ struct Prepared {
 };
 
 // Validates a row-streaming launch and fills out->rp.  `d`: r = row blocks side by side (4 or 8), grid,
-// nw, rs = row blocks per workgroup (the whole part of row blocks / grid).
+// nw, rs = row blocks per workgroup (the whole part of row blocks / (grid / K slices)), ks = K slices.
+// `scratch`: the partial-sum area of the workspace (behind the counters): K-sliced launches keep their slots there,
+// launches beyond 32 rows the operand-order copy of the activations.
 lutq_status prepare_rows(const void* X, const void* packed, const void* scales, const void* lut, int bits,
                          int group_size, int64_t M, int64_t N, int64_t K, bool bf16, void* Y, const Decomp& d, Prepared* out,
-                         bool rowlut = false, void* xop = nullptr, size_t xop_room = 0, bool dry = false) {
+                         bool rowlut = false, void* scratch = nullptr, size_t scratch_room = 0, bool dry = false) {
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     if (M < 1 || M > 64) return LUTQ_ERR_SHAPE;
     const int mb = M > 32 ? (int)((M + 15) / 16) : M > 16 ? 2 : 1;
+    const int ks = d.ks > 1 ? d.ks : 1;
     // beyond 32 rows the kernel reads the activations from their operand-order copy in the scratch
     const size_t xop_bytes = mb > 2 ? (size_t)(K / 32) * mb * 1024 : 0;
-    if (mb > 2 && (rowlut || (!dry && (!xop || xop_bytes > xop_room)))) return LUTQ_ERR_PLAN;
+    if (mb > 2 && (rowlut || (!dry && (!scratch || xop_bytes > scratch_room)))) return LUTQ_ERR_PLAN;
     const int max_waves = rows_instance_waves(bits, bf16, mb, d.r);
     if (max_waves == 0 || d.nw < 4 || d.nw > max_waves || d.stages != 2) return LUTQ_ERR_PLAN;
-    if (d.grid < 1 || d.grid > kMaxGrid || d.grid > nb || d.rs < 1 || d.rs > 64 || d.rs != nb / d.grid) return LUTQ_ERR_PLAN;
-    const int extra = (int)(nb - (int64_t)d.rs * d.grid);
+    // K slices: grid = shares x ks workgroups; a share's row blocks in one pass; partial sums and counters in the scratch
+    if (d.grid < 1 || d.grid > kMaxGrid || d.grid % ks != 0) return LUTQ_ERR_PLAN;
+    const int shares = d.grid / ks;
+    if (shares > nb || d.rs < 1 || d.rs > 64 || d.rs != nb / shares) return LUTQ_ERR_PLAN;
+    const int extra = (int)(nb - (int64_t)d.rs * shares);
     const int amax = d.rs + (extra ? 1 : 0);
+    if (ks > 1) {
+        if (rowlut || mb > 2 || kt % ks != 0 || amax > d.r || (int64_t)shares * 64 > (int64_t)kCounterBytes) return LUTQ_ERR_PLAN;
+        if (!dry && (!scratch || (size_t)d.grid * d.r * mb * 1024 > scratch_room)) return scratch ? LUTQ_ERR_SCRATCH : LUTQ_ERR_PLAN;
+    }
+    const int64_t ts = kt / ks;                               // K tiles per slice
     // the scales of a pass's row blocks are staged in LDS in 16-byte units
     const int sg2 = (int)(K / group_size) * 2;
     if (sg2 % 16 != 0) return LUTQ_ERR_PLAN;
@@ -840,8 +880,8 @@ lutq_status prepare_rows(const void* X, const void* packed, const void* scales, 
     q.x_bytes = (uint32_t)(M * K * 2);
     out->xp = XopParams{};
     if (mb > 2) {
-        out->xp = XopParams{static_cast<const uint16_t*>(X), static_cast<uint16_t*>(xop), (int)M, (int)K, mb, tile_k(bits) / 32};
-        q.X = static_cast<const uint16_t*>(xop);
+        out->xp = XopParams{static_cast<const uint16_t*>(X), static_cast<uint16_t*>(scratch), (int)M, (int)K, mb, tile_k(bits) / 32};
+        q.X = static_cast<const uint16_t*>(scratch);
         q.x_bytes = (uint32_t)xop_bytes;
     }
     q.M = (int)M; q.N = (int)N; q.K = (int)K; q.KT = (int)kt;
@@ -851,7 +891,10 @@ lutq_status prepare_rows(const void* X, const void* packed, const void* scales, 
     q.tile_stride = tile_bytes << q.SBL;
     q.sblock_bytes = (uint32_t)kt * q.tile_stride;
     q.A = d.rs; q.extra = extra; q.NW = d.nw; q.G = d.grid;
-    q.TQ = (int)(kt / d.nw); q.TR = (int)(kt % d.nw);
+    q.TQ = (int)(ts / d.nw); q.TR = (int)(ts % d.nw);
+    q.KS = ks; q.TS = (int)ts;
+    q.slots = ks > 1 ? static_cast<float*>(scratch) : nullptr;
+    q.counters = ks > 1 && scratch ? reinterpret_cast<uint32_t*>(static_cast<char*>(scratch) - kCounterBytes) : nullptr;   // the scratch begins with the counters
     q.RPR = rpr;
     q.s_units = sg2 / 16;
     q.s_magic = (uint32_t)((1ull << 32) / (uint64_t)q.s_units + 1);
@@ -861,8 +904,8 @@ lutq_status prepare_rows(const void* X, const void* packed, const void* scales, 
     q.lut_ltpe = bits == 2 ? lut_log2_threads_per_row<2>(d.nw * 64)
                : bits == 3 ? lut_log2_threads_per_row<3>(d.nw * 64) : lut_log2_threads_per_row<4>(d.nw * 64);
     if (env_switches().verbose)
-        std::fprintf(stderr, "lutq_matmul: row streaming, %d row blocks side by side, grid=%d waves=%d row blocks per workgroup=%d (+1 in %d) reduce %d per round lds=%d\n",
-                     d.r, d.grid, d.nw, d.rs, extra, rpr, lds);
+        std::fprintf(stderr, "lutq_matmul: row streaming, %d row blocks side by side, grid=%d (%d K slices) waves=%d row blocks per workgroup=%d (+1 in %d) reduce %d per round lds=%d\n",
+                     d.r, d.grid, ks, d.nw, d.rs, extra, rpr, lds);
     out->queue = false;
     out->rows = true;
     out->rows_rowlut = rowlut;
@@ -1040,7 +1083,13 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         if (sched < 0 || sched > LUTQ_SCHED_ROWS) return LUTQ_ERR_PLAN;
         Decomp q;
         if (sched == LUTQ_SCHED_ROWS) {
-            if (user_plan->tiles_per_item != 0) return LUTQ_ERR_PLAN;
+            // tiles_per_item: K tiles per slice where K is cut across workgroups (grid = shares x slices)
+            int ks = 1;
+            if (user_plan->tiles_per_item != 0) {
+                if (user_plan->tiles_per_item < 1 || kt % user_plan->tiles_per_item != 0 || !user_plan->grid) return LUTQ_ERR_PLAN;
+                ks = (int)(kt / user_plan->tiles_per_item);
+                if (ks < 2 || user_plan->grid % ks != 0) return LUTQ_ERR_PLAN;
+            }
             const bool have_default = rows_decomp(bits, bf16, M, N, K, group_size, di.cus, &q);
             if (!have_default) { q.r = 4; q.grid = (int)(nb < di.cus ? nb : di.cus); q.nw = 8; q.stages = 2; }
             if (user_plan->row_blocks_per_wave) {
@@ -1053,11 +1102,19 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
                 if (nb % user_plan->row_groups_per_workgroup != 0) return LUTQ_ERR_PLAN;
                 q.grid = (int)(nb / user_plan->row_groups_per_workgroup);
             }
-            if (q.grid < 1 || q.grid > nb) return LUTQ_ERR_PLAN;
-            q.rs = (int)(nb / q.grid);
+            if (q.grid < 1 || q.grid / ks > nb) return LUTQ_ERR_PLAN;
+            q.rs = (int)(nb / (q.grid / ks));
+            q.ks = ks;
+            q.it = ks > 1 ? user_plan->tiles_per_item : 0;
             if (user_plan->row_groups_per_workgroup && user_plan->row_groups_per_workgroup != q.rs) return LUTQ_ERR_PLAN;
             if (user_plan->waves_per_workgroup) q.nw = user_plan->waves_per_workgroup;
             if (user_plan->tiles_in_flight) q.stages = user_plan->tiles_in_flight;
+            if (ks > 1) {
+                const lutq_status rs = prepare_rows(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out, false,
+                                                    dry ? nullptr : static_cast<char*>(workspace) + kCounterBytes,
+                                                    dry ? 0 : workspace_bytes - kCounterBytes, dry);
+                return rs;
+            }
             return prepare_rows(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out);
         }
         if (sched == LUTQ_SCHED_QUEUE) {
@@ -1090,6 +1147,15 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         }
         if (sched == 0 && plan_is_empty && default_queue_decomp(bits, bf16, sch, M, N, K, di.cus, &q))
             return prepare_queue(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out);
+        if (sched == 0 && plan_is_empty && sliced_rows_decomp(bits, bf16, M, N, K, group_size, di.cus, &q)) {
+            // (a scratch too small for the slices' sums -- the built-in one of lutq_matmul_static -- leaves it to the others)
+            const lutq_status rs = prepare_rows(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out, false,
+                                                dry ? nullptr : static_cast<char*>(workspace) + kCounterBytes,
+                                                dry ? 0 : workspace_bytes - kCounterBytes, dry);
+            if (rs == LUTQ_OK) return rs;
+            out->rows = false;
+            q = Decomp{};
+        }
         if (sched == 0 && plan_is_empty && default_rows_decomp(bits, bf16, M, N, K, group_size, di.cus, &q))
             return prepare_rows(X, packed, scales, lut, bits, group_size, M, N, K, bf16, Y, q, out);
     }
@@ -1275,7 +1341,7 @@ lutq_status matmul_sliced(const void* X, const void* packed, const void* scales,
         step = slice_rows(bits, group_size, M, N, K, dtype == LUTQ_BF16, user_plan, rowlut, di.cus, &st);
         if (st != LUTQ_OK) return st;
     }
-    const int64_t full = M / step, rest = M % step;
+    int64_t full = M / step, rest = M % step;
     Prepared body{}, tail{};
     const size_t xrow = (size_t)K * 2, yrow = (size_t)N * 2;
     // one slice of m rows (m <= step) starting at row m0
@@ -1298,13 +1364,18 @@ lutq_status matmul_sliced(const void* X, const void* packed, const void* scales,
                                             static_cast<char*>(workspace) + kCounterBytes, workspace_bytes - kCounterBytes);
         return st == LUTQ_ERR_PLAN && fitted_workspace ? LUTQ_ERR_SCRATCH : st;
     };
-    if (full > 0) {
-        const lutq_status st = prepare(0, step, &body);
-        if (st != LUTQ_OK) return st;
-    }
-    if (rest > 0) {
-        const lutq_status st = prepare(full * step, rest, &tail);
-        if (st != LUTQ_OK) return st;
+    for (;;) {
+        lutq_status st = full > 0 ? prepare(0, step, &body) : LUTQ_OK;
+        if (st == LUTQ_OK && rest > 0) st = prepare(full * step, rest, &tail);
+        if (st == LUTQ_OK) break;
+        // the library's own choice of 64-row slices does not fit (the copy of the activations is larger than the scratch):
+        // slices of 32 rows instead
+        if (step == 64 && !user_plan && (st == LUTQ_ERR_PLAN || st == LUTQ_ERR_SCRATCH)) {
+            step = 32; full = M / step; rest = M % step;
+            body = Prepared{}; tail = Prepared{};
+            continue;
+        }
+        return st;
     }
     for (int64_t i = 0; i < full; ++i) {
         Prepared q = body;
@@ -1493,6 +1564,24 @@ std::vector<lutq_plan> tune_candidates(int bits, int group_size, int64_t M, int6
                 if (w == 0) continue;
                 for (int nw : {w, 8})
                     if (nw <= w) push_unique(lutq_plan{side, g, nw, 2, (int)(nb / g), LUTQ_SCHED_ROWS, 0});
+            }
+        }
+    }
+    if (M > 4 && ((K / group_size) * 2) % 16 == 0 && nb <= 2 * (int64_t)cus) {
+        // the same with K cut into slices across workgroups: one pass per share of four or eight row blocks, grids of one
+        // workgroup per compute unit, half and twice that
+        const int mbh = M > 16 ? 2 : 1;
+        for (int side : {4, 8}) {
+            const int w = rows_instance_waves(bits, dtype == LUTQ_BF16, mbh, side);
+            if (w == 0) continue;
+            const int64_t shares = (nb + side - 1) / side;
+            if (shares * 64 > (int64_t)kCounterBytes) continue;
+            for (int64_t ks = 2; ks <= kt && shares * ks <= 2 * (int64_t)cus; ++ks) {
+                if (kt % ks != 0 || shares * ks > kMaxGrid) continue;
+                // (small problems, whose grids stay below half the compute units, keep the two extremes)
+                if (shares * ks * 2 < cus && ks != 2 && ks != kt) continue;
+                for (int nw : {w, 8})
+                    if (nw <= w) push_unique(lutq_plan{side, (int)(shares * ks), nw, 2, (int)(nb / shares), LUTQ_SCHED_ROWS, (int)(kt / ks)});
             }
         }
     }

@@ -19,6 +19,15 @@
 //   * After a pass the waves' accumulators are added in wave order through LDS, a few row blocks per
 //     round, and written out: bit-reproducible.
 //
+//   * K slices (matrices with fewer row blocks than would keep every compute unit busy): KS workgroups share a
+//     workgroup's row blocks (at most AMAX: one pass) and take a slice of K each, so that a compute unit reads only
+//     its slice of the activations.  Each writes its sums (fp32, per row block and block of sixteen rows of M) to its
+//     own slot in global memory and, when all of them are stored, bumps the share's arrival counter once; whichever
+//     workgroup arrives last adds the KS slots in slice order, its own included, and writes Y: nobody waits for anybody, and the result does not
+//     depend on who was last.  (Moved with agent-scope atomic loads and stores, ordered by completion: the stores are
+//     acknowledged before the counter is bumped, and the loads are issued after the counter value that proves the
+//     workgroup is last has come back -- the protocol of matmul_kernel's fix-up.)
+//
 //   * The scales of a pass's row blocks (consecutive rows: one contiguous range) are copied into LDS when
 //     the pass begins, 16 bytes per lane, and read from there per (tile, row block): a 2- to 16-byte read
 //     per lane from global memory would touch sixteen cache lines per instruction for one line's worth of
@@ -55,6 +64,10 @@ struct RowsParams {
     int tab_total;            // RLUT: LDS bytes of the pass's per-row tables (AMAX x sixteen copies); the scales follow
     int lut_ltpe;             // log2 of the threads that build one table row together
     int G;                    // workgroups
+    int KS;                   // K slices: workgroup b works on slice b % KS of the row blocks of share b / KS (1: the whole of K)
+    int TS;                   // K tiles per slice (KT / KS)
+    float* slots;             // KS > 1: partial sums, one slot of AMAX x MB KiB per workgroup
+    uint32_t* counters;       // KS > 1: arrivals per share, one counter per 64 bytes; zero between launches
 };
 
 // LDS of one launch: [table, 256-byte entry stride][scales of AMAX x 16 rows, SROW bytes each][RPR x MB x NW slots of 1 KiB]
@@ -106,7 +119,7 @@ void rows_kernel(const RowsParams p) {
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.packed_bytes), "s"(p.scale_bytes),
                  "s"(p.x_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.KT), "s"(p.SG2), "s"(p.SBL), "s"(p.tile_stride),
                  "s"(p.sblock_bytes), "s"(p.A), "s"(p.extra), "s"(p.NW), "s"(p.TQ), "s"(p.TR), "s"(p.RPR), "s"(p.lut_ltpe),
-                 "s"(p.s_units), "s"(p.s_magic), "s"(p.SROW), "s"(p.red_off), "s"(p.tab_total));
+                 "s"(p.s_units), "s"(p.s_magic), "s"(p.SROW), "s"(p.red_off), "s"(p.tab_total), "s"(p.KS), "s"(p.TS));
 
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
@@ -135,10 +148,15 @@ void rows_kernel(const RowsParams p) {
     const rsrc_t rX = make_rsrc(p.X, p.x_bytes);
 
     // this workgroup's row blocks and this wave's K tiles
-    const bool big = (int)blockIdx.x < p.extra;
+    int share = (int)blockIdx.x, slice = 0;
+    if (p.KS > 1) {
+        share = (int)blockIdx.x / p.KS;
+        slice = (int)blockIdx.x - share * p.KS;
+    }
+    const bool big = share < p.extra;
     const int nrb = p.A + (big ? 1 : 0);
-    const int rb_first = (int)blockIdx.x * p.A + ((int)blockIdx.x < p.extra ? (int)blockIdx.x : p.extra);
-    const int ka = wave * p.TQ + (wave < p.TR ? wave : p.TR);
+    const int rb_first = share * p.A + (share < p.extra ? share : p.extra);
+    const int ka = slice * p.TS + wave * p.TQ + (wave < p.TR ? wave : p.TR);     // TQ, TR: the slice's tiles over the waves
     const int kb = ka + p.TQ + (wave < p.TR ? 1 : 0);
 
     // activation rows m >= M lie beyond the X buffer and read as zero
@@ -342,9 +360,57 @@ void rows_kernel(const RowsParams p) {
                 const char* src = red + ((size_t)(task * p.NW) * 64 + lane) * 16;
 #pragma unroll 4
                 for (int w = 0; w < p.NW; ++w) sum += *reinterpret_cast<const f32x4*>(src + (size_t)w * 1024);
+                if (p.KS > 1) {
+                    // this workgroup's sums over its K slice go to its slot (output tile = row block of the share x block
+                    // of sixteen rows of M; one pass: p0 = 0); nobody waits for the stores here
+                    const int tile = (a0 + al) * MB + mb;
+                    float* slot = p.slots + ((size_t)blockIdx.x * (AMAX * MB) + tile) * 256 + lane;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) __hip_atomic_store(slot + i * 64, sum[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    continue;
+                }
                 const int m = li + 16 * mb;
                 if (m < p.M) {
                     const int n = (rb_first + p0 + a0 + al) * 16 + 4 * lo;
+                    *reinterpret_cast<u32x2*>(p.Y + (size_t)m * p.N + n) = pack4<DT>(sum);
+                }
+            }
+        }
+        if (p.KS > 1) {
+            // One arrival per workgroup, once all its stores are acknowledged; whichever of the share's KS workgroups
+            // arrives last adds the slots of all of them in slice order, its own included, and writes Y.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            uint32_t* counter = p.counters + (size_t)share * 16;               // one 64-byte line per share
+            uint32_t* flag = reinterpret_cast<uint32_t*>(red);
+            if (tid == 0) *flag = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            const uint32_t old = *flag;
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            if (old != (uint32_t)(p.KS - 1)) return;
+            if (tid == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int tile = wave; tile < na * MB; tile += p.NW) {
+                const int al = tile / MB, mb = tile - al * MB;
+                f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+                const float* src = p.slots + ((size_t)(share * p.KS) * (AMAX * MB) + tile) * 256 + lane;
+                for (int s0 = 0; s0 < p.KS; s0 += 4) {
+                    // four slices' loads in flight together; a slice beyond the last reads the last one's and adds nothing
+                    f32x4 v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int s = s0 + j < p.KS ? s0 + j : p.KS - 1;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            v[j][i] = __hip_atomic_load(src + (size_t)s * (AMAX * MB * 256) + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (s0 + j < p.KS) sum += v[j];
+                }
+                const int m = li + 16 * mb;
+                if (m < p.M) {
+                    const int n = (rb_first + al) * 16 + 4 * lo;
                     *reinterpret_cast<u32x2*>(p.Y + (size_t)m * p.N + n) = pack4<DT>(sum);
                 }
             }

@@ -671,7 +671,7 @@ FULL_SIZE = [
     # deeper cuts) and the plain plan with four waves
     ("8B gate_up W4 g128 M32 (4 teams of R = 2, one set per workgroup)", 28672, 4096, 4, 128, "f16", 32),
     ("70B qkv W4 g64 M32 (5 teams of R = 2, K cut in four)", 10240, 8192, 4, 64, "f16", 32),
-    ("8B down W3 g128 bf16 M32 (8 teams, K cut in eight)", 4096, 14336, 3, 128, "bf16", 32),
+    ("8B down W2 g128 bf16 M32 (8 teams, K cut in eight)", 4096, 14336, 2, 128, "bf16", 32),
     ("70B o W2 g64 M24 (8 teams)", 8192, 8192, 2, 64, "f16", 24),
     ("70B qkv W3 g64 M12 (3-bit team plan from 12 rows)", 10240, 8192, 3, 64, "f16", 12),
     ("8B qkv W4 g256 M16 (plain, four waves)", 6144, 4096, 4, 256, "f16", 16),
@@ -693,6 +693,12 @@ FULL_SIZE = [
     ("8B gate_up W4 g128 M16 (row streaming, twelve waves, eight side by side)", 28672, 4096, 4, 128, "f16", 16),
     ("22016x4096 W4 M32 (row streaming, two tiles' activations in registers)", 22016, 4096, 4, 128, "f16", 32),
     ("12288x4096 W3 bf16 M24 (row streaming, three row blocks per compute unit, more than 16 rows at 3 bits)", 12288, 4096, 3, 128, "bf16", 24),
+    # row streaming with K slices: at most one row block per compute unit, a long K, 17..32 rows
+    ("8B down W4 g128 M17 (row streaming, 64 shares x 4 K slices)", 4096, 14336, 4, 128, "f16", 17),
+    ("8B down W4 g32 bf16 M32 (row streaming, K slices, group 32)", 4096, 14336, 4, 32, "bf16", 32),
+    ("8B down W3 g128 bf16 M32 (row streaming, K slices, 3 bits)", 4096, 14336, 3, 128, "bf16", 32),
+    ("3072x12288 W4 M24 (row streaming, 48 shares x 4 K slices on 192 of 256 units)", 3072, 12288, 4, 128, "f16", 24),
+    ("2048x14336 W4 M32 (row streaming, 32 shares x 8 K slices)", 2048, 14336, 4, 128, "f16", 32),
     ("15360x5120 W4 bf16 M4 (work queue, shares of 3 and 4 row blocks)", 15360, 5120, 4, 128, "bf16", 4),
     ("22016x4096 W4 M4 (work queue, twelve waves, shares of 5 and 6)", 22016, 4096, 4, 128, "f16", 4),
 ]
@@ -848,6 +854,49 @@ def test_row_streaming_plans_match_oracle(lutq, bits, dtype):
     with pytest.raises(lutq.LutqError) as e:
         DeviceCase(lutq, c).matmul(lutq, plan=lutq.Plan(4, 0, 4, 2, 0, RW, 0))
     assert e.value.code == 10
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_k_sliced_row_streaming_plans_match_oracle(lutq, bits, dtype):
+    """Row-streaming plans with K cut into slices across workgroups (tiles_per_item = K tiles per slice, grid =
+    shares x slices): each workgroup stores its slice's sums, the share's last arrival adds them in slice order.
+    One to many shares, uneven shares, two to twenty slices, more waves than tiles of a slice, M on both sides
+    of 16; against the oracle, bit-reproducible, arrival counters left at zero; malformed cuts refused."""
+    RW = 3                                                  # LUTQ_SCHED_ROWS
+    n = 0
+    for (N, K, group, lut, cuts) in [(64, 8 * tk(bits), 128, "nf", {4: [(1, 2), (1, 8)], 8: [(1, 4)]}),
+                                     (336, 20 * tk(bits), 64, "learned", {4: [(6, 2), (7, 5), (21, 10)], 8: [(3, 4), (4, 20)]}),
+                                     (96, 4 * tk(bits), 32, "random_index", {4: [(2, 2), (3, 4)], 8: [(1, 2)]}),
+                                     (208, 16 * tk(bits), 256, "nf", {4: [(4, 8), (13, 16)], 8: [(2, 2)]})]:
+        nb, kt = N // 16, K // tk(bits)
+        for M in (1, 5, 16, 17, 32):
+            c = gen.make_case(900 + M, M, N, K, bits, group, dtype, lut)
+            d = DeviceCase(lutq, c)
+            for side in (4, 8):
+                w = rows_waves(lutq, bits, dtype, M, N, K, group, side)
+                if w == 0:
+                    continue
+                for shares, ks in cuts[side]:
+                    for nw in (4, w):
+                        plan = lutq.Plan(side, shares * ks, nw, 2, nb // shares, RW, kt // ks)
+                        Y1 = to_bits(d.matmul(lutq, plan=plan))
+                        Y2 = to_bits(d.matmul(lutq, plan=plan))
+                        assert np.array_equal(Y1, Y2), f"{plan} is not reproducible"
+                        check_y(Y1, c, f"b{bits} {dtype} g{group} M{M} N{N} K{K} {plan}")
+                        assert int(d.ws[:65536].count_nonzero()) == 0, f"{plan} left counters behind"
+                        n += 1
+                # slices that do not divide K, a grid that is no multiple of the slices, no grid, a single slice,
+                # more than one pass per share
+                bad = [lutq.Plan(side, 2, 4, 2, 0, RW, kt - 1), lutq.Plan(side, 3, 4, 2, 0, RW, kt // 2),
+                       lutq.Plan(side, 0, 4, 2, 0, RW, kt // 2), lutq.Plan(side, 1, 4, 2, 0, RW, kt)]
+                if nb > side:
+                    bad.append(lutq.Plan(side, 2, 4, 2, 0, RW, kt // 2))
+                for b in bad:
+                    with pytest.raises(lutq.LutqError) as e:
+                        d.matmul(lutq, plan=b)
+                    assert e.value.code == 10, b
+    assert n > 0 or bits != 4
 
 
 @pytest.mark.parametrize("bits", BITS)

@@ -167,8 +167,14 @@ def test_default_plans_are_valid_for_random_problems():
         what = f"b{bits} g{group} M{M} N{N} K{K} cus{cus} dt{dt}: {p}"
         assert 4 <= p.waves_per_workgroup <= 16 and p.tiles_in_flight in (2, 4), what
         if p.scheduling == 3:                       # row streaming: M >= 5, whole row blocks per workgroup
-            assert M >= 5 and p.row_blocks_per_wave in (4, 8) and p.tiles_in_flight == 2 and p.tiles_per_item == 0, what
-            assert 1 <= p.grid <= nb and p.row_groups_per_workgroup == nb // p.grid <= 64, what
+            assert M >= 5 and p.row_blocks_per_wave in (4, 8) and p.tiles_in_flight == 2, what
+            slices = 1
+            if p.tiles_per_item:                    # K cut into slices across workgroups: one pass per share of row blocks
+                assert M >= 17 and bits != 2 and (K // tkb) % p.tiles_per_item == 0 and p.tiles_per_item >= 14, what
+                slices = K // tkb // p.tiles_per_item
+                assert slices >= 4 and p.grid % slices == 0 and cus // 2 <= p.grid <= cus, what
+                assert p.row_groups_per_workgroup <= p.row_blocks_per_wave, what
+            assert 1 <= p.grid // slices <= nb and p.row_groups_per_workgroup == nb // (p.grid // slices) <= 64, what
             assert (K // group * 2) % 16 == 0, what
             assert lutq.lutq_plan_check(bits, group, M, N, K, dt, cus) == 0, what
             if M <= 32:
@@ -240,7 +246,13 @@ def test_default_plans_fitted_by_measurement():
         (4, 128, 16, 22016, 4096, 0): (8, 256, 12, 2, 5, 3),
         (3, 128, 16, 28672, 4096, 1): (8, 256, 8, 2, 7, 3),
         (3, 128, 24, 28672, 4096, 0): (1, 224, 16, 2, 8, 1),
-        (4, 128, 20, 4096, 14336, 1): (2, 256, 4, 2, 1),
+        # K slices on the row-streaming kernel: at most one row block per compute unit, a long K, 17..32 rows
+        (4, 128, 20, 4096, 14336, 1): (4, 256, 8, 2, 4, 3),
+        (3, 128, 32, 4096, 14336, 0): (4, 256, 8, 2, 4, 3),
+        (4, 128, 32, 2048, 14336, 0): (4, 256, 8, 2, 4, 3),
+        (4, 128, 24, 3072, 12288, 0): (4, 192, 8, 2, 4, 3),
+        (4, 128, 16, 4096, 14336, 0): (2, 256, 7, 2, 1),           # ... not up to sixteen rows
+        (4, 128, 32, 4096, 4096, 0): (1, 256, 4, 2, 1),            # ... nor with fewer than four slices of fourteen tiles
         (4, 128, 8, 28672, 4096, 0): (4, 448, 4, 2, 1),
         (4, 128, 32, 28672, 4096, 0): (2, 224, 8, 2, 4),
         # work queue with twelve waves: seven row blocks per compute unit at 2 and 3 bits

@@ -37,7 +37,10 @@ def test_static_scratch_matches_workspace_call(lutq):
              (40, 208, 2048, 4, "bf16", lutq.Plan(1, 5, 8, 2, 1)),
              # 64-row slices: the operand-order copy of the activations lives in the same array
              (64, 4800, 1024, 4, "f16", None),
-             (100, 208, 2048, 4, "bf16", lutq.Plan(scheduling=3))]
+             (100, 208, 2048, 4, "bf16", lutq.Plan(scheduling=3)),
+             # K slices on the row-streaming kernel: the slices' sums and the arrival counters live there too
+             (20, 208, 2048, 4, "f16", lutq.Plan(4, 16, 8, 2, 3, 3, 4)),
+             (32, 4096, 14336, 4, "bf16", None)]
     for rnd in range(2):
         for i, (M, N, K, bits, dtype, plan) in enumerate(specs):
             c = gen.make_case(900 + i, M, N, K, bits, 64, dtype, "nf")
