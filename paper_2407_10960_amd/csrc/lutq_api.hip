@@ -176,28 +176,34 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
     return take && rows_decomp(bits, bf16, M, N, K, group_size, cus, out) && out->r >= amax;
 }
 
-// K slices on the row-streaming kernel (17..32 rows, 3 and 4 bits): for matrices with at most one row block per compute
+// K slices on the row-streaming kernel (12..32 rows, 3 and 4 bits): for matrices with at most one row block per compute
 // unit and a long K, four row blocks per share of workgroups and as many K slices as keep the grid within the compute
 // units, at least four slices of at least fourteen K tiles each; every workgroup then reads only its slice of the activations, and
 // a share's slices are added by whichever of its workgroups finishes last.  Measured against the team plans (MI355X, us,
 // HBM-cold weights): 8B down (4096 x 14336) M = 17 / 24 / 32 20.1 / 20.1 / 20.5 -> 14.5 / 15.4 / 16.8, bf16 M = 32 21.3 -> 16.9,
 // 3-bit 21.2 -> 17.9, group 32 20.5 -> 17.9; 4096 x 8192 M = 20 / 32 13.2 / 15.2 -> 11.3 / 12.5; 4096 x 28672 31.8 -> 26.4;
-// 2048 x 14336 18.9 -> 13.0; 3072 x 12288 24.0 -> 15.9.  Not taken: up to sixteen rows (0-6 %), slices of eight tiles
+// 2048 x 14336 18.9 -> 13.0; 3072 x 12288 24.0 -> 15.9; M = 12 / 16: 8B down 12.3 / 13.4 -> 12.1 / 12.6 (bf16 M = 16 14.3 -> 13.0, 3-bit
+// 14.6 -> 13.7), 4096 x 28672 19.8 / 21.8 -> 17.5 / 18.5, 3072 x 12288 14.5 / 15.3 -> 10.7 / 11.3, 2048 x 14336 10.5 / 11.6 -> 10.2 / 10.6.
+// Not taken: below twelve rows (M = 9 level, M = 8 5-11 % slower), slices of eight tiles
 // (8B O: 10.8 -> 10.2 at M = 32 but 9.3 -> 10.0 at M = 24), grids below half the compute units (1024 x 8192: 11.0 -> 12.3),
 // fewer than four slices (8B O in two slices of sixteen tiles: M = 20 8.6 -> 9.7), more than one row block per compute unit
 // (8B QKV, 70B O and down, N = K = 8192: within 3 % either way).
 bool sliced_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int group_size, int cus, Decomp* out) {
-    if (M < 17 || M > 32 || bits == 2 || ((K / group_size) * 2) % 16 != 0) return false;
+    if (M < 12 || M > 32 || bits == 2 || ((K / group_size) * 2) % 16 != 0) return false;
     const int64_t nb = N / 16, kt = K / tile_k(bits);
+    const int mb = M > 16 ? 2 : 1;
     if (nb > cus || nb % 4 != 0) return false;
     const int64_t shares = nb / 4;
     int ks = 0;
     for (int64_t k = cus / shares; k >= 4 && !ks; --k)
         if (kt % k == 0 && kt / k >= 14) ks = (int)k;
-    if (!ks || shares * ks * 2 < cus || shares * 64 > (int64_t)kCounterBytes) return false;
-    int nw = rows_instance_waves(bits, bf16, 2, 4);
-    if (nw > 8) nw = 8;
-    if (nw < 4 || rows_blocks_per_round(bits, 4, (int)(K / group_size) * 2, 2, nw) < 1) return false;
+    // (grids from half the compute units up beyond sixteen rows, from three quarters up to there: 2048 x 8192 on 128
+    // workgroups M = 24 11.9 -> 11.0 us, but bf16 M = 16 9.1 -> 10.0)
+    if (!ks || shares * ks * (mb == 2 ? 2 : 4) < cus * (mb == 2 ? 1 : 3) || shares * 64 > (int64_t)kCounterBytes) return false;
+    // (eight waves beyond sixteen rows, twelve up to there: 8B down M = 16 13.1 / 12.5 / 12.8 us with 8 / 12 / 16)
+    int nw = rows_instance_waves(bits, bf16, mb, 4);
+    if (nw > (mb == 2 ? 8 : 12)) nw = mb == 2 ? 8 : 12;
+    if (nw < 4 || rows_blocks_per_round(bits, 4, (int)(K / group_size) * 2, mb, nw) < 1) return false;
     out->r = 4; out->grid = (int)(shares * ks); out->nw = nw; out->stages = 2; out->rs = 4; out->queue = 0;
     out->it = (int)(kt / ks); out->ks = ks; out->rows = 1;
     return true;
@@ -1341,7 +1347,7 @@ lutq_status matmul_sliced(const void* X, const void* packed, const void* scales,
         step = slice_rows(bits, group_size, M, N, K, dtype == LUTQ_BF16, user_plan, rowlut, di.cus, &st);
         if (st != LUTQ_OK) return st;
     }
-    int64_t full = M / step, rest = M % step;
+    const int64_t full = M / step, rest = M % step;
     Prepared body{}, tail{};
     const size_t xrow = (size_t)K * 2, yrow = (size_t)N * 2;
     // one slice of m rows (m <= step) starting at row m0
@@ -1364,18 +1370,13 @@ lutq_status matmul_sliced(const void* X, const void* packed, const void* scales,
                                             static_cast<char*>(workspace) + kCounterBytes, workspace_bytes - kCounterBytes);
         return st == LUTQ_ERR_PLAN && fitted_workspace ? LUTQ_ERR_SCRATCH : st;
     };
-    for (;;) {
-        lutq_status st = full > 0 ? prepare(0, step, &body) : LUTQ_OK;
-        if (st == LUTQ_OK && rest > 0) st = prepare(full * step, rest, &tail);
-        if (st == LUTQ_OK) break;
-        // the library's own choice of 64-row slices does not fit (the copy of the activations is larger than the scratch):
-        // slices of 32 rows instead
-        if (step == 64 && !user_plan && (st == LUTQ_ERR_PLAN || st == LUTQ_ERR_SCRATCH)) {
-            step = 32; full = M / step; rest = M % step;
-            body = Prepared{}; tail = Prepared{};
-            continue;
-        }
-        return st;
+    if (full > 0) {
+        const lutq_status st = prepare(0, step, &body);
+        if (st != LUTQ_OK) return st;
+    }
+    if (rest > 0) {
+        const lutq_status st = prepare(full * step, rest, &tail);
+        if (st != LUTQ_OK) return st;
     }
     for (int64_t i = 0; i < full; ++i) {
         Prepared q = body;

@@ -654,7 +654,7 @@ def test_graph_replay_matches_eager(lutq):
 FULL_SIZE = [
     # (name, N, K, bits, group, dtype, M) -- the LLaMA-3 layer shapes at full size, default launch configuration
     ("8B gate_up W4 g128", 28672, 4096, 4, 128, "f16", 1),
-    ("8B down W4 g128", 4096, 14336, 4, 128, "f16", 16),
+    ("8B down W4 g128 M16 (row streaming, K slices, twelve waves)", 4096, 14336, 4, 128, "f16", 16),
     ("8B qkv W3 g64", 6144, 4096, 3, 64, "f16", 32),
     ("70B o W3 g64 bf16", 8192, 8192, 3, 64, "bf16", 16),
     ("8192^2 W2 g32", 8192, 8192, 2, 32, "f16", 4),
@@ -694,6 +694,7 @@ FULL_SIZE = [
     ("22016x4096 W4 M32 (row streaming, two tiles' activations in registers)", 22016, 4096, 4, 128, "f16", 32),
     ("12288x4096 W3 bf16 M24 (row streaming, three row blocks per compute unit, more than 16 rows at 3 bits)", 12288, 4096, 3, 128, "bf16", 24),
     # row streaming with K slices: at most one row block per compute unit, a long K, 17..32 rows
+    ("8B down W3 g64 bf16 M12 (row streaming, K slices, up to sixteen rows at 3 bits)", 4096, 14336, 3, 64, "bf16", 12),
     ("8B down W4 g128 M17 (row streaming, 64 shares x 4 K slices)", 4096, 14336, 4, 128, "f16", 17),
     ("8B down W4 g32 bf16 M32 (row streaming, K slices, group 32)", 4096, 14336, 4, 32, "bf16", 32),
     ("8B down W3 g128 bf16 M32 (row streaming, K slices, 3 bits)", 4096, 14336, 3, 128, "bf16", 32),

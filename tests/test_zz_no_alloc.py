@@ -93,3 +93,4 @@ def test_static_scratch_falls_back_to_a_default_that_fits(lutq):
     with pytest.raises(lutq.LutqError) as e:
         lutq.lutq_matmul_static(d.X, d.packed, d.S, d.T, bits, group, Y, plan=lutq.Plan(2, 256, 14, 2, 14))
     assert e.value.code == 11
+
