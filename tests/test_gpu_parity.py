@@ -923,16 +923,18 @@ def test_table_pointer_in_the_upper_half_of_a_word(lutq, bits, dtype):
 
 def test_fixup_protocol_soak(lutq):
     """The cross-workgroup fix-up (Algorithm 2: partial sums to global scratch, an arrival counter per
-    row group, the last arriver adds all partials in workgroup order) under a heavily split plan, a few
-    thousand launches back to back with two alternating problems on one workspace: every result equals,
+    row group -- per share of row blocks in the K-sliced row-streaming launches --, the last arriver adds all
+    partials in workgroup order) under heavily split plans, a few
+    thousand launches back to back with three alternating problems on one workspace: every result equals,
     bit for bit, the first result of its problem, and the arrival counters end at zero.  Stops at the
     first mismatch."""
     import torch
     bits, group, dtype, N, K = 4, 64, "f16", 256, 8192
-    cases = [gen.make_case(70 + i, M, N, K, bits, group, dtype, "random_index") for i, M in enumerate((1, 16))]
+    cases = [gen.make_case(70 + i, M, N, K, bits, group, dtype, "random_index") for i, M in enumerate((1, 16, 24))]
     devs = [DeviceCase(lutq, c) for c in cases]
     ws = devs[0].ws
-    plans = [lutq.Plan(1, 2048, 8, 2, 2), lutq.Plan(1, 1000, 4, 2, 1)]       # every tile cut across many workgroups
+    # every tile cut across many workgroups; and the row-streaming kernel's K slices (4 shares x 64 slices of one tile)
+    plans = [lutq.Plan(1, 2048, 8, 2, 2), lutq.Plan(1, 1000, 4, 2, 1), lutq.Plan(4, 256, 4, 2, 4, 3, 1)]
     outs = [torch.empty((c.M, N), dtype=torch.float16, device="cuda") for c in cases]
     first = []
     for d, c, y, plan in zip(devs, cases, outs, plans):
