@@ -173,7 +173,8 @@ typedef struct {
                                  side, one workgroup per compute unit, 8 waves at most), so every other
                                  field is 0 or the value lutq_plan_default reports; any other plan, and
                                  the default where 64-row slices are not faster, means slices of 32 rows.
-                                 With tiles_per_item > 0 (M <= 32) K is cut into slices of that many K tiles
+                                 With tiles_per_item > 0 (launches of up to 32 rows; more rows go in slices
+                                 of 32) K is cut into slices of that many K tiles
                                  across workgroups: `grid` (required, a multiple of the number of slices) =
                                  shares x slices, a share being at most row_blocks_per_wave row blocks (one
                                  pass: row_groups_per_workgroup = the whole part of N / 16 / shares), so a

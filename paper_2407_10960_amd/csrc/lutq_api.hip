@@ -176,21 +176,23 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
     return take && rows_decomp(bits, bf16, M, N, K, group_size, cus, out) && out->r >= amax;
 }
 
-// K slices on the row-streaming kernel (9..32 rows, 3 and 4 bits): for matrices with at most one row block per compute
+// K slices on the row-streaming kernel (9..32 rows): for matrices with at most one row block per compute
 // unit (two up to 24 rows) and a long K, four row blocks per share of workgroups and as many K slices as keep the grid within the compute
-// units, at least four slices of at least fourteen K tiles each; every workgroup then reads only its slice of the activations, and
+// units, at least four slices of at least 1792 columns (fourteen 4-bit K tiles) each; every workgroup then reads only its slice of the activations, and
 // a share's slices are added by whichever of its workgroups finishes last.  Measured against the team plans (MI355X, us,
 // HBM-cold weights): 8B down (4096 x 14336) M = 17 / 24 / 32 20.1 / 20.1 / 20.5 -> 14.5 / 15.4 / 16.8, bf16 M = 32 21.3 -> 16.9,
 // 3-bit 21.2 -> 17.9, group 32 20.5 -> 17.9; 4096 x 8192 M = 20 / 32 13.2 / 15.2 -> 11.3 / 12.5; 4096 x 28672 31.8 -> 26.4;
 // 2048 x 14336 18.9 -> 13.0; 3072 x 12288 24.0 -> 15.9; M = 12 / 16: 8B down 12.3 / 13.4 -> 12.1 / 12.6 (bf16 M = 16 14.3 -> 13.0, 3-bit
 // 14.6 -> 13.7), 4096 x 28672 19.8 / 21.8 -> 17.5 / 18.5, 3072 x 12288 14.5 / 15.3 -> 10.7 / 11.3, 2048 x 14336 10.5 / 11.6 -> 10.2 / 10.6.
 // M = 9..11: 70B down bf16 35.0-37.1 -> 29.5-30.0, 3072 x 12288 M = 10 13.6 -> 10.4, 4096 x 28672 M = 9 17.9 -> 17.0, 8B down level to 5 %.
+// 2 bits: 8B down M = 16 / 24 / 32 12.9 / 20.2 / 20.7 -> 11.9 / 15.2 / 16.6 (bf16 M = 32 22.8 -> 17.9), 4096 x 28672 M = 16 / 32 22.5 / 26.7 -> 16.2 / 24.9,
+// 3072 x 12288 M = 20 19.2 -> 13.2, 2048 x 14336 M = 32 19.2 -> 15.7.
 // Not taken: below nine rows (M = 8: 2 % faster to 11 % slower), slices of eight tiles
 // (8B O: 10.8 -> 10.2 at M = 32 but 9.3 -> 10.0 at M = 24), grids below half the compute units (1024 x 8192: 11.0 -> 12.3),
 // fewer than four slices (8B O in two slices of sixteen tiles: M = 20 8.6 -> 9.7), more than one row block per compute unit
 // (8B QKV, 70B O and down, N = K = 8192: within 3 % either way).
 bool sliced_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int group_size, int cus, Decomp* out) {
-    if (M < 9 || M > 32 || bits == 2 || ((K / group_size) * 2) % 16 != 0) return false;
+    if (M < 9 || M > 32 || ((K / group_size) * 2) % 16 != 0) return false;
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1;
     if (nb > 2 * (int64_t)cus || nb % 4 != 0) return false;
@@ -201,7 +203,7 @@ bool sliced_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, in
     // way, and at 3 bits the teams are 1-5 % faster)
     int ks = 0;
     for (int64_t k = cus / shares; k >= 2 && !ks; --k)
-        if (kt % k == 0 && (k >= 4 ? kt / k >= 14 : kt / k >= 56 && bits == 4 && M <= 24)) ks = (int)k;
+        if (kt % k == 0 && (k >= 4 ? kt / k * tile_k(bits) >= 14 * 128 : kt / k >= 56 && bits == 4 && M <= 24)) ks = (int)k;
     // (grids from half the compute units up beyond sixteen rows, from three quarters up to there: 2048 x 8192 on 128
     // workgroups M = 24 11.9 -> 11.0 us, but bf16 M = 16 9.1 -> 10.0)
     if (!ks || shares * ks * (mb == 2 ? 2 : 4) < cus * (mb == 2 ? 1 : 3) || shares * 64 > (int64_t)kCounterBytes) return false;
@@ -1318,6 +1320,8 @@ int slice_rows(int bits, int group_size, int64_t M, int64_t N, int64_t K, bool b
                                               user_plan->row_groups_per_workgroup == 0 && user_plan->tiles_per_item == 0);
     const int sched = user_plan ? user_plan->scheduling : 0;
     if (sched != LUTQ_SCHED_ROWS && !(sched == 0 && plan_is_empty)) return 32;
+    // a row-streaming plan with K slices describes launches of up to 32 rows
+    if (sched == LUTQ_SCHED_ROWS && user_plan->tiles_per_item != 0) return 32;
     Decomp d;
     bool take = false;
     const bool have = wide_rows_decomp(bits, bf16, M < 64 ? M : 64, N, K, group_size, cus, &d, &take);

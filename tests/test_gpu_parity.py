@@ -671,7 +671,7 @@ FULL_SIZE = [
     # deeper cuts) and the plain plan with four waves
     ("8B gate_up W4 g128 M32 (4 teams of R = 2, one set per workgroup)", 28672, 4096, 4, 128, "f16", 32),
     ("70B qkv W4 g64 M32 (5 teams of R = 2, K cut in four)", 10240, 8192, 4, 64, "f16", 32),
-    ("8B down W2 g128 bf16 M32 (8 teams, K cut in eight)", 4096, 14336, 2, 128, "bf16", 32),
+    ("70B o W3 g64 bf16 M32 (8 teams, K cut in eight)", 8192, 8192, 3, 64, "bf16", 32),
     ("70B o W2 g64 M24 (8 teams)", 8192, 8192, 2, 64, "f16", 24),
     ("70B qkv W3 g64 M12 (3-bit team plan from 12 rows)", 10240, 8192, 3, 64, "f16", 12),
     ("8B qkv W4 g256 M16 (plain, four waves)", 6144, 4096, 4, 256, "f16", 16),
@@ -695,6 +695,8 @@ FULL_SIZE = [
     ("12288x4096 W3 bf16 M24 (row streaming, three row blocks per compute unit, more than 16 rows at 3 bits)", 12288, 4096, 3, 128, "bf16", 24),
     # row streaming with K slices: at most one row block per compute unit, a long K, 17..32 rows
     ("8B down W3 g64 bf16 M12 (row streaming, K slices, up to sixteen rows at 3 bits)", 4096, 14336, 3, 64, "bf16", 12),
+    ("8B down W2 g128 bf16 M32 (row streaming, K slices, 2 bits)", 4096, 14336, 2, 128, "bf16", 32),
+    ("4096x8192 W2 g64 M20 (row streaming, four K slices of eight tiles)", 4096, 8192, 2, 64, "f16", 20),
     ("8B down W4 g128 M17 (row streaming, 64 shares x 4 K slices)", 4096, 14336, 4, 128, "f16", 17),
     ("8B down W4 g32 bf16 M32 (row streaming, K slices, group 32)", 4096, 14336, 4, 32, "bf16", 32),
     ("8B down W3 g128 bf16 M32 (row streaming, K slices, 3 bits)", 4096, 14336, 3, 128, "bf16", 32),

@@ -170,9 +170,9 @@ def test_default_plans_are_valid_for_random_problems():
             assert M >= 5 and p.row_blocks_per_wave in (4, 8) and p.tiles_in_flight == 2, what
             slices = 1
             if p.tiles_per_item:                    # K cut into slices across workgroups: one pass per share of row blocks
-                assert M >= 9 and bits != 2 and (K // tkb) % p.tiles_per_item == 0 and p.tiles_per_item >= 14, what
+                assert M >= 9 and (K // tkb) % p.tiles_per_item == 0 and p.tiles_per_item * tkb >= 1792, what
                 slices = K // tkb // p.tiles_per_item
-                assert slices >= (4 if M > 24 or bits == 3 else 2) and p.grid % slices == 0 and cus // 2 <= p.grid <= cus, what
+                assert slices >= (4 if M > 24 or bits != 4 else 2) and p.grid % slices == 0 and cus // 2 <= p.grid <= cus, what
                 assert p.row_groups_per_workgroup <= p.row_blocks_per_wave, what
             assert 1 <= p.grid // slices <= nb and p.row_groups_per_workgroup == nb // (p.grid // slices) <= 64, what
             assert (K // group * 2) % 16 == 0, what
@@ -254,6 +254,7 @@ def test_default_plans_fitted_by_measurement():
         (4, 128, 16, 4096, 14336, 0): (4, 256, 12, 2, 4, 3),       # ... twelve waves up to sixteen rows
         (3, 128, 12, 4096, 14336, 1): (4, 256, 8, 2, 4, 3),        # (the 3-bit bf16 instance holds eight waves)
         (4, 128, 9, 4096, 14336, 0): (4, 256, 12, 2, 4, 3),
+        (2, 128, 24, 4096, 14336, 1): (4, 256, 8, 2, 4, 3),
         (4, 64, 20, 8192, 28672, 1): (4, 256, 8, 2, 4, 3),         # ... two slices up to 24 rows
         (4, 64, 32, 8192, 28672, 1): (1, 256, 8, 4, 8),
         (4, 64, 16, 2048, 8192, 1): (1, 256, 4, 2, 1),             # ... nor on half the compute units up to sixteen rows
