@@ -178,8 +178,8 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
 
 // K slices on the row-streaming kernel (9..32 rows): for matrices with at most one row block per compute
 // unit (two up to 24 rows) and a long K, four row blocks per share of workgroups and as many K slices as keep the grid within the compute
-// units, at least four slices of at least 1792 columns (fourteen 4-bit K tiles) each; every workgroup then reads only its slice of the activations, and
-// a share's slices are added by whichever of its workgroups finishes last.  Measured against the team plans (MI355X, us,
+// units, at least four slices of at least 1792 columns (fourteen 4-bit K tiles) each; every workgroup then reads only its slice of the activations with eight (twelve) waves
+// that hold them in registers, and a share's slices are added by whichever of its workgroups finishes last.  Measured against the team plans (MI355X, us,
 // HBM-cold weights): 8B down (4096 x 14336) M = 17 / 24 / 32 20.1 / 20.1 / 20.5 -> 14.5 / 15.4 / 16.8, bf16 M = 32 21.3 -> 16.9,
 // 3-bit 21.2 -> 17.9, group 32 20.5 -> 17.9; 4096 x 8192 M = 20 / 32 13.2 / 15.2 -> 11.3 / 12.5; 4096 x 28672 31.8 -> 26.4;
 // 2048 x 14336 18.9 -> 13.0; 3072 x 12288 24.0 -> 15.9; M = 12 / 16: 8B down 12.3 / 13.4 -> 12.1 / 12.6 (bf16 M = 16 14.3 -> 13.0, 3-bit
