@@ -381,6 +381,12 @@ def main():
         by = gen.algorithmic_bytes(M, N, K, BITS, GROUP) + Tn.numel() * 2
         more["per_row_tables_m1"] = {"us": r2(t * 1e6), "frac_of_8TBps": round(by / t * 1e-9 / HBM_PEAK_GBS, 3),
                                      "over_shared_table": r2(t * 1e6 / per_shape["gate_up"]["us"])}
+        # a codebook of 256 pairs of adjacent weights (Section 5: vector codebooks), M = 1: the same kernels, the same bytes + 1 KiB
+        Cb = torch.randn((256, 2), device="cuda").to(torch.float16)
+        t = timer.per_call(lambda: [lutq.lutq_matmul_pairs(g["X"], layers[li]["gate_up"]["packed"], layers[li]["gate_up"]["S"], Cb,
+                                                           GROUP, Y["gate_up"], ws) for li in range(LAYERS)], LAYERS)
+        more["pair_codebook_m1"] = {"us": r2(t * 1e6), "frac_of_8TBps": round((gen.algorithmic_bytes(M, N, K, BITS, GROUP) + 1024) / t * 1e-9 / HBM_PEAK_GBS, 3),
+                                    "over_scalar_table": r2(t * 1e6 / per_shape["gate_up"]["us"])}
         # ... and at M = 16 (the row-streaming kernel with four row blocks' tables per pass)
         X16 = torch.randn((16, K), device="cuda").to(torch.float16)
         Y16 = torch.empty((16, N), dtype=torch.float16, device="cuda")

@@ -294,6 +294,22 @@ lutq_status lutq_matmul_channel(const void* X, const void* packed, const void* s
                                 lutq_dtype dtype, void* Y,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* Vector codebooks (Section 5 names them, beside finer-grained tables, as what a flexible lookup kernel is
+ * for): one 8-bit index selects a PAIR of adjacent weights from a codebook of 256 pairs, 4 bits per weight.
+ *        W^[n, 2j + c] = round16( C[V[n, j]][c] * S[n, 2j / group_size] ),  c = 0, 1
+ *   codebook  device, [256][2] values of dtype (1 KiB), 4-byte aligned
+ *   packed    the 4-bit layout of lutq_pack applied to the indices Q[n, 2j] = V[n, j] & 15,
+ *             Q[n, 2j + 1] = V[n, j] >> 4 (one byte of the 4-bit layout is one codebook index)
+ *   every other argument as in lutq_matmul with bits = 4.
+ * The kernels are those of lutq_matmul: their on-chip table at 4 bits already is a table of 256 pairs
+ * (built from sixteen scalars there, copied from the codebook here), so the cost is the same.  A codebook
+ * with C[e] = (T[e & 15], T[e >> 4]) gives lutq_matmul's result bit for bit.  The work decomposition is the
+ * library's.  Errors: those of lutq_matmul; LUTQ_ERR_ALIGN also for a codebook that is not 4-byte aligned. */
+lutq_status lutq_matmul_pairs(const void* X, const void* packed, const void* scales, const void* codebook,
+                              int group_size, int64_t M, int64_t N, int64_t K,
+                              lutq_dtype dtype, void* Y,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* Instance selection by measurement (Section 4.1: the fastest kernel configuration is picked per
  * shape; Section 3.3: how the K range is cut across workgroups is part of that choice).  Times the
  * default plan and the candidate plans that lutq_tune_candidates lists, first with a few launches

@@ -107,10 +107,13 @@ __host__ __device__ constexpr int lut_log2_threads_per_row(int nthreads) {
 }
 
 // The table indices (up to four) that entry e of the vectorised table is made of.
+// pairs (4 bits only): the caller's table IS the vectorised one -- a codebook of 256 pairs, entry e = values 2e and
+// 2e + 1 of the flat array -- instead of sixteen scalars that every pair of nibbles is looked up in.
+constexpr int kLutPairsFlag = 256;      // set in the `ltpe` argument of lut_fetch / lut_build: the table is a codebook of pairs
 template <int BITS>
-__device__ __forceinline__ void entry_indices(int e, int q[4]) {
+__device__ __forceinline__ void entry_indices(int e, int q[4], bool pairs = false) {
     if constexpr (BITS == 4) {
-        q[0] = e & 15; q[1] = (e >> 4) & 15; q[2] = 0; q[3] = 0;
+        q[0] = pairs ? 2 * e : e & 15; q[1] = pairs ? 2 * e + 1 : (e >> 4) & 15; q[2] = 0; q[3] = 0;
     } else if constexpr (BITS == 3) {
         q[0] = (e & 3) | (((e >> 4) & 1) << 2);
         q[1] = ((e >> 2) & 3) | (((e >> 5) & 1) << 2);
@@ -127,13 +130,15 @@ __device__ __forceinline__ void entry_indices(int e, int q[4]) {
 // upper half of a word; lut_build picks the half.
 template <int BITS>
 __device__ __forceinline__ LutSeed lut_fetch(const uint16_t* __restrict__ T, int tid, int ltpe) {
+    const bool pairs = (ltpe & kLutPairsFlag) != 0;
+    ltpe &= kLutPairsFlag - 1;
     const int e = (tid >> ltpe) & (Geo<BITS>::ENTRIES - 1);
     const uintptr_t addr = reinterpret_cast<uintptr_t>(T);
     typedef __attribute__((address_space(1))) const uint32_t global_cu32;
     global_cu32* words = reinterpret_cast<global_cu32*>(addr & ~(uintptr_t)3);
     const int mis = (int)(addr >> 1) & 1;
     int q[4];
-    entry_indices<BITS>(e, q);
+    entry_indices<BITS>(e, q, pairs);
     LutSeed s;
 #pragma unroll
     for (int i = 0; i < 4; ++i) s.w[i] = (BITS == 2 || i < 2) ? words[(q[i] + mis) >> 1] : 0u;
@@ -145,6 +150,8 @@ template <int BITS, typename DT>
 __device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int mis, int log2c, int tid, int ltpe) {
     using Gm = Geo<BITS>;
     constexpr int ESH = Tab<BITS, DT>::ENTRY_BYTES == 8 ? 3 : 2;
+    const bool pairs = (ltpe & kLutPairsFlag) != 0;
+    ltpe &= kLutPairsFlag - 1;
     const int stride = 1 << (log2c + ESH);                        // bytes of one row
     const int chunks = stride >> 4;                               // 16-byte chunks of one row (power of two)
     const int tpe = 1 << ltpe;                                    // threads per row
@@ -152,7 +159,7 @@ __device__ __forceinline__ void lut_build(char* lds, const LutSeed& seed, int mi
     const int per = chunks / tpe > 0 ? chunks / tpe : 1;          // chunks written by this thread
     if (e >= Gm::ENTRIES || part * per >= chunks) return;
     int q[4];
-    entry_indices<BITS>(e, q);
+    entry_indices<BITS>(e, q, pairs);
     uint32_t val[4];                                              // the 16-bit table values of this row
 #pragma unroll
     for (int i = 0; i < 4; ++i) val[i] = ((q[i] + mis) & 1) ? (seed.w[i] >> 16) : (seed.w[i] & 0xffffu);

@@ -26,8 +26,9 @@ def tk(bits):
     return 128 if bits == 4 else 256
 
 
-def check_y(Y_bits, case, what=""):
-    What = orc.dequant(case.Q, case.T, case.S, case.group_size, case.dtype)
+def check_y(Y_bits, case, what="", What=None):
+    if What is None:
+        What = orc.dequant(case.Q, case.T, case.S, case.group_size, case.dtype)
     Yref = orc.matmul_f64(case.X, What, case.dtype)
     Y = orc.to_f64(Y_bits, case.dtype)
     assert np.isfinite(Y).all(), what
@@ -605,6 +606,58 @@ def test_one_table_per_output_row(lutq, bits, dtype):
     lutq.lutq_matmul_channel(d.X, d.packed, d.S, to_dev(np.tile(c.T, (128, 1)), dtype), bits, 64, Y1, d.ws)
     Y2 = d.matmul(lutq, plan=lutq.Plan(1, 8, 8, 2, 1))
     assert np.array_equal(to_bits(Y1), to_bits(Y2))
+
+
+def pair_codebook_case(seed, M, N, K, group, dtype):
+    """A 4-bit case read as 8-bit indices into a codebook of 256 random pairs: V[n, j] = Q[n, 2j] | Q[n, 2j + 1] << 4."""
+    c = gen.make_case(seed, M, N, K, 4, group, dtype, "random_index")
+    rng = np.random.default_rng(seed + 1)
+    C = gen.encode16(rng.standard_normal((256, 2), dtype=np.float32), dtype)
+    V = (c.Q[:, 0::2] | (c.Q[:, 1::2] << 4)).astype(np.uint8)
+    return c, C, V
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_pair_codebook_matches_oracle(lutq, dtype):
+    """lutq_matmul_pairs (Section 5: vector codebooks; here 256 pairs of adjacent weights, one byte of the 4-bit
+    layout = one index): one-hot activations read the dequantised pairs back bit for bit, products match the
+    oracle on every kernel the default plans reach (work queue, teams, row streaming, K slices, slices of 32 and
+    64 rows), a codebook made of a scalar table gives lutq_matmul's bits, and a misaligned codebook is refused."""
+    import torch
+    # weights read back through the kernel: X = one-hot rows
+    N, K, group = 64, 512, 64
+    c, C, V = pair_codebook_case(40, 16, N, K, group, dtype)
+    d = DeviceCase(lutq, c)
+    Cd = to_dev(C, dtype)
+    What = orc.dequant_pairs(V, C, c.S, group, dtype)
+    one = np.zeros((16, K), dtype=np.float32)
+    for k0 in range(0, K, 16):
+        one[:] = 0
+        one[np.arange(16), k0 + np.arange(16)] = 1.0
+        X = to_dev(gen.encode16(one, dtype), dtype)
+        Y = torch.full((16, N), float("nan"), dtype=X.dtype, device="cuda")
+        lutq.lutq_matmul_pairs(X, d.packed, d.S, Cd, group, Y, d.ws)
+        assert np.array_equal(to_bits(Y), What[:, k0:k0 + 16].T), f"columns {k0}.."
+    for (M, N, K, group) in [(1, 4096, 1024, 128), (3, 336, 2560, 64), (8, 96, 512, 32), (16, 22016, 1024, 128),
+                             (24, 4096, 7168, 128), (32, 208, 2048, 64), (48, 4112, 1024, 64), (100, 96, 1024, 32)]:
+        c, C, V = pair_codebook_case(41 + M, M, N, K, group, dtype)
+        d = DeviceCase(lutq, c)
+        Cd = to_dev(C, dtype)
+        Y = torch.full((M, N), float("nan"), dtype=d.X.dtype, device="cuda")
+        lutq.lutq_matmul_pairs(d.X, d.packed, d.S, Cd, group, Y, d.ws)
+        torch.cuda.synchronize()
+        check_y(to_bits(Y), c, f"pairs {dtype} M{M} N{N} K{K} g{group}", What=orc.dequant_pairs(V, C, c.S, group, dtype))
+        assert not d.ws[:65536].any().item()
+        # sixteen scalars as a codebook of pairs: the same bits as the scalar call
+        e = np.arange(256)
+        Cs = to_dev(np.stack([c.T[e & 15], c.T[e >> 4]], axis=1), dtype)
+        lutq.lutq_matmul_pairs(d.X, d.packed, d.S, Cs, group, Y, d.ws)
+        assert np.array_equal(to_bits(Y), to_bits(d.matmul(lutq))), f"scalar table as pairs: M{M} N{N} K{K}"
+    # the codebook is read as aligned 32-bit words
+    buf = torch.zeros(514, dtype=Cd.dtype, device="cuda")
+    with pytest.raises(lutq.LutqError) as e:
+        lutq.lutq_matmul_pairs(d.X, d.packed, d.S, buf[1:513].view(256, 2), group, Y, d.ws)
+    assert e.value.code == 5
 
 
 def test_graph_replay_matches_eager(lutq):
