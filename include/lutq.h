@@ -304,8 +304,20 @@ lutq_status lutq_matmul_channel(const void* X, const void* packed, const void* s
  * The kernels are those of lutq_matmul: their on-chip table at 4 bits already is a table of 256 pairs
  * (built from sixteen scalars there, copied from the codebook here), so the cost is the same.  A codebook
  * with C[e] = (T[e & 15], T[e >> 4]) gives lutq_matmul's result bit for bit.  The work decomposition is the
- * library's.  Errors: those of lutq_matmul; LUTQ_ERR_ALIGN also for a codebook that is not 4-byte aligned. */
+ * library's.  Errors: those of lutq_matmul; LUTQ_ERR_ALIGN also for a codebook that is not 4-byte aligned.
+ *
+ * lutq_matmul_quads is the same at 2 bits per weight: one 8-bit index selects FOUR adjacent weights,
+ *        W^[n, 4j + c] = round16( C[V[n, j]][c] * S[n, 4j / group_size] ),  c = 0 .. 3
+ *   codebook  device, [256][4] values of dtype (2 KiB), 4-byte aligned
+ *   packed    the 2-bit layout of lutq_pack applied to Q[n, 4j + c] = (V[n, j] >> 2c) & 3
+ * (the 2-bit kernels' on-chip table is a table of 256 quads); a codebook with C[e][c] = T[(e >> 2c) & 3]
+ * gives lutq_matmul's 2-bit result bit for bit. */
 lutq_status lutq_matmul_pairs(const void* X, const void* packed, const void* scales, const void* codebook,
+                              int group_size, int64_t M, int64_t N, int64_t K,
+                              lutq_dtype dtype, void* Y,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+lutq_status lutq_matmul_quads(const void* X, const void* packed, const void* scales, const void* codebook,
                               int group_size, int64_t M, int64_t N, int64_t K,
                               lutq_dtype dtype, void* Y,
                               void* workspace, size_t workspace_bytes, void* stream);

@@ -289,20 +289,23 @@ def dequant_channel(Q, Tn_bits, S_bits, group_size: int, dtype: str) -> np.ndarr
     return from_f64(W * np.repeat(S, group_size, axis=1), dtype)
 
 
-def dequant_pairs(V, C_bits, S_bits, group_size: int, dtype: str) -> np.ndarray:
-    """Vector codebook of pairs (Section 5: vector codebooks as a further use of a lookup kernel): index V[n, j]
-    selects the pair of adjacent weights (2j, 2j + 1) from C, a table of pairs of shape [E, 2]:
-    W^[n, 2j + c] = round16( C[V[n, j], c] * S[n, 2j // B] ), c = 0, 1 (B even: a pair lies in one group)."""
+def dequant_vectors(V, C_bits, S_bits, group_size: int, dtype: str) -> np.ndarray:
+    """Vector codebook (Section 5: vector codebooks as a further use of a lookup kernel): index V[n, j] selects the
+    d adjacent weights d*j .. d*j + d - 1 from C, a table of vectors of shape [E, d]:
+    W^[n, d*j + c] = round16( C[V[n, j], c] * S[n, d*j // B] ), c = 0 .. d-1 (d divides B: a vector lies in one group)."""
     V = np.asarray(V)
-    N, K2 = V.shape
-    K = 2 * K2
+    N, Kd = V.shape
     C = to_f64(C_bits, dtype)
     S = to_f64(S_bits, dtype)
-    if C.ndim != 2 or C.shape[1] != 2 or group_size % 2 or S.shape != (N, K // group_size):
-        raise ValueError("codebook shape must be [E, 2], the group even, and the scale shape [N, K / group_size]")
+    if C.ndim != 2:
+        raise ValueError("codebook shape must be [E, d]")
+    d = C.shape[1]
+    K = d * Kd
+    if group_size % d or S.shape != (N, K // group_size):
+        raise ValueError("d must divide the group, and the scale shape must be [N, K / group_size]")
     if V.min() < 0 or V.max() >= C.shape[0]:
         raise ValueError("codebook index out of range")
-    W = C[V].reshape(N, K)                      # [N, K/2, 2] -> [N, K]: the pair's values side by side
+    W = C[V].reshape(N, K)                      # [N, K/d, d] -> [N, K]: a vector's values side by side
     return from_f64(W * np.repeat(S, group_size, axis=1), dtype)
 
 

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     lutq_matmul,
     lutq_matmul_channel,
     lutq_matmul_pairs,
+    lutq_matmul_quads,
     lutq_matmul_static,
     STATIC_SCRATCH_BYTES,
     lutq_pack,

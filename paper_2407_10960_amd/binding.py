@@ -12,7 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "lutq_status_string", "lutq_packed_bytes", "lutq_pack", "lutq_unpack", "lutq_workspace_bytes",
-    "lutq_plan_default", "lutq_plan_default_for", "lutq_plan_check", "lutq_pack_layout", "lutq_plan_table_set", "lutq_plan_table_lookup", "lutq_matmul", "lutq_matmul_plan", "lutq_matmul_static", "lutq_matmul_channel", "lutq_matmul_pairs", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
+    "lutq_plan_default", "lutq_plan_default_for", "lutq_plan_check", "lutq_pack_layout", "lutq_plan_table_set", "lutq_plan_table_lookup", "lutq_matmul", "lutq_matmul_plan", "lutq_matmul_static", "lutq_matmul_channel", "lutq_matmul_pairs", "lutq_matmul_quads", "lutq_tune", "lutq_tune_candidates", "lutq_quantize", "lutq_dequant",
     "lutq_calib_stream_read", "lutq_calib_copy", "lutq_calib_matmul_trace",
 )
 
@@ -106,6 +106,8 @@ def load_library():
     lib.lutq_matmul_static.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, ctypes.POINTER(_CPlan)]
     lib.lutq_matmul_pairs.restype = ci
     lib.lutq_matmul_pairs.argtypes = [vp, vp, vp, vp, ci, i64, i64, i64, ci, vp, vp, sz, vp]
+    lib.lutq_matmul_quads.restype = ci
+    lib.lutq_matmul_quads.argtypes = [vp, vp, vp, vp, ci, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.lutq_matmul_channel.restype = ci
     lib.lutq_matmul_channel.argtypes = [vp, vp, vp, vp, ci, ci, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.lutq_tune.restype = ci
@@ -309,25 +311,34 @@ def lutq_matmul_static(X, packed, scales, lut, bits: int, group_size: int, Y, st
     return Y
 
 
-def lutq_matmul_pairs(X, packed, scales, codebook, group_size: int, Y, workspace, stream=None):
-    """lutq_matmul with a codebook of 256 pairs of adjacent weights (one byte of the 4-bit layout = one index)."""
+def _matmul_codebook(name, dim, bits, X, packed, scales, codebook, group_size, Y, workspace, stream):
     lib = load_library()
     for t in (X, packed, scales, codebook, Y, workspace):
         if not (t.is_cuda and t.is_contiguous()):
-            raise ValueError("lutq_matmul_pairs needs contiguous CUDA (HIP) tensors")
+            raise ValueError(f"{name} needs contiguous CUDA (HIP) tensors")
     code = _dtype_code(X)
     if not (_dtype_code(scales) == code and _dtype_code(codebook) == code and _dtype_code(Y) == code):
         raise TypeError("X, scales, codebook and Y must share one dtype")
     M, K = X.shape
     N = scales.shape[0]
-    if scales.shape[1] * group_size != K or tuple(Y.shape) != (M, N) or tuple(codebook.shape) != (256, 2):
+    if scales.shape[1] * group_size != K or tuple(Y.shape) != (M, N) or tuple(codebook.shape) != (256, dim):
         raise ValueError("inconsistent shapes")
-    if packed.numel() != lib.lutq_packed_bytes(N, K, 4, group_size):
+    if packed.numel() != lib.lutq_packed_bytes(N, K, bits, group_size):
         raise ValueError("packed buffer has the wrong size for (N, K)")
-    _check(lib.lutq_matmul_pairs(X.data_ptr(), packed.data_ptr(), scales.data_ptr(), codebook.data_ptr(), group_size,
-                                 M, N, K, code, Y.data_ptr(), workspace.data_ptr(),
-                                 workspace.numel() * workspace.element_size(), _stream_ptr(stream)), "lutq_matmul_pairs")
+    _check(getattr(lib, name)(X.data_ptr(), packed.data_ptr(), scales.data_ptr(), codebook.data_ptr(), group_size,
+                              M, N, K, code, Y.data_ptr(), workspace.data_ptr(),
+                              workspace.numel() * workspace.element_size(), _stream_ptr(stream)), name)
     return Y
+
+
+def lutq_matmul_pairs(X, packed, scales, codebook, group_size: int, Y, workspace, stream=None):
+    """lutq_matmul with a codebook of 256 pairs of adjacent weights (one byte of the 4-bit layout = one index)."""
+    return _matmul_codebook("lutq_matmul_pairs", 2, 4, X, packed, scales, codebook, group_size, Y, workspace, stream)
+
+
+def lutq_matmul_quads(X, packed, scales, codebook, group_size: int, Y, workspace, stream=None):
+    """lutq_matmul with a codebook of 256 quads of adjacent weights (one byte of the 2-bit layout = one index)."""
+    return _matmul_codebook("lutq_matmul_quads", 4, 2, X, packed, scales, codebook, group_size, Y, workspace, stream)
 
 
 def lutq_matmul_channel(X, packed, scales, luts, bits: int, group_size: int, Y, workspace, stream=None):

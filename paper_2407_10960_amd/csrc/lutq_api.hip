@@ -1342,8 +1342,8 @@ lutq_status matmul_sliced(const void* X, const void* packed, const void* scales,
                           lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
                           void* stream, const lutq_plan* user_plan, bool rowlut, bool fitted_workspace = false, bool pairs = false) {
     if (!X || !Y) return LUTQ_ERR_NULL;
-    // a codebook of pairs: 4-bit layout only (one byte = one codebook index), entries read as aligned 32-bit words
-    if (pairs && bits != 4) return LUTQ_ERR_BITS;
+    // a codebook of pairs (4-bit layout) or quads (2-bit layout): one byte = one codebook index, entries read as aligned 32-bit words
+    if (pairs && bits != 4 && bits != 2) return LUTQ_ERR_BITS;
     if (pairs && (reinterpret_cast<uintptr_t>(lut) & 3u) != 0) return LUTQ_ERR_ALIGN;
     if (M < 1 || M > kMaxRows) return LUTQ_ERR_SHAPE;
     // More than 32 activation rows: slices of 32 rows (64 where the row-streaming kernel takes them in one pass
@@ -1391,7 +1391,7 @@ lutq_status matmul_sliced(const void* X, const void* packed, const void* scales,
         if (st != LUTQ_OK) return st;
     }
     if (pairs) {
-        // the kernels' table build takes the caller's 256 pairs as the vectorised table itself
+        // the kernels' table build takes the caller's 256 pairs or quads as the vectorised table itself
         for (Prepared* q : {&body, &tail}) {
             q->p.lut_ltpe |= kLutPairsFlag;
             q->dp.lut_ltpe |= kLutPairsFlag;
@@ -1464,6 +1464,14 @@ extern "C" lutq_status lutq_matmul_pairs(const void* X, const void* packed, cons
                                          lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
                                          void* stream) {
     return matmul_sliced(X, packed, scales, codebook, 4, group_size, M, N, K, dtype, Y, workspace, workspace_bytes,
+                         stream, nullptr, false, false, true);
+}
+
+extern "C" lutq_status lutq_matmul_quads(const void* X, const void* packed, const void* scales, const void* codebook,
+                                         int group_size, int64_t M, int64_t N, int64_t K,
+                                         lutq_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
+                                         void* stream) {
+    return matmul_sliced(X, packed, scales, codebook, 2, group_size, M, N, K, dtype, Y, workspace, workspace_bytes,
                          stream, nullptr, false, false, true);
 }
 

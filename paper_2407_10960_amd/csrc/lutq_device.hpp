@@ -107,9 +107,10 @@ __host__ __device__ constexpr int lut_log2_threads_per_row(int nthreads) {
 }
 
 // The table indices (up to four) that entry e of the vectorised table is made of.
-// pairs (4 bits only): the caller's table IS the vectorised one -- a codebook of 256 pairs, entry e = values 2e and
-// 2e + 1 of the flat array -- instead of sixteen scalars that every pair of nibbles is looked up in.
-constexpr int kLutPairsFlag = 256;      // set in the `ltpe` argument of lut_fetch / lut_build: the table is a codebook of pairs
+// pairs (4 and 2 bits): the caller's table IS the vectorised one -- a codebook of 256 pairs (4 bits: entry e = values 2e
+// and 2e + 1 of the flat array) or 256 quads (2 bits: values 4e .. 4e + 3) -- instead of sixteen or four scalars that
+// every nibble or bit pair of the byte is looked up in.
+constexpr int kLutPairsFlag = 256;      // set in the `ltpe` argument of lut_fetch / lut_build: the table is a codebook of pairs or quads
 template <int BITS>
 __device__ __forceinline__ void entry_indices(int e, int q[4], bool pairs = false) {
     if constexpr (BITS == 4) {
@@ -119,7 +120,8 @@ __device__ __forceinline__ void entry_indices(int e, int q[4], bool pairs = fals
         q[1] = ((e >> 2) & 3) | (((e >> 5) & 1) << 2);
         q[2] = 0; q[3] = 0;
     } else {
-        q[0] = e & 3; q[1] = (e >> 2) & 3; q[2] = (e >> 4) & 3; q[3] = (e >> 6) & 3;
+        q[0] = pairs ? 4 * e : e & 3; q[1] = pairs ? 4 * e + 1 : (e >> 2) & 3;
+        q[2] = pairs ? 4 * e + 2 : (e >> 4) & 3; q[3] = pairs ? 4 * e + 3 : (e >> 6) & 3;
     }
 }
 

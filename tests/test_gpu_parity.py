@@ -608,55 +608,63 @@ def test_one_table_per_output_row(lutq, bits, dtype):
     assert np.array_equal(to_bits(Y1), to_bits(Y2))
 
 
-def pair_codebook_case(seed, M, N, K, group, dtype):
-    """A 4-bit case read as 8-bit indices into a codebook of 256 random pairs: V[n, j] = Q[n, 2j] | Q[n, 2j + 1] << 4."""
-    c = gen.make_case(seed, M, N, K, 4, group, dtype, "random_index")
+def codebook_case(seed, d, M, N, K, group, dtype):
+    """A 4-bit (d = 2) or 2-bit (d = 4) case read as 8-bit indices into a codebook of 256 random vectors of d
+    adjacent weights: V[n, j] = the d scalar indices of the vector side by side in a byte, lowest first."""
+    b = 8 // d
+    c = gen.make_case(seed, M, N, K, b, group, dtype, "random_index")
     rng = np.random.default_rng(seed + 1)
-    C = gen.encode16(rng.standard_normal((256, 2), dtype=np.float32), dtype)
-    V = (c.Q[:, 0::2] | (c.Q[:, 1::2] << 4)).astype(np.uint8)
+    C = gen.encode16(rng.standard_normal((256, d), dtype=np.float32), dtype)
+    V = np.zeros((N, K // d), dtype=np.uint8)
+    for i in range(d):
+        V |= (c.Q[:, i::d] << (b * i)).astype(np.uint8)
     return c, C, V
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
-def test_pair_codebook_matches_oracle(lutq, dtype):
-    """lutq_matmul_pairs (Section 5: vector codebooks; here 256 pairs of adjacent weights, one byte of the 4-bit
-    layout = one index): one-hot activations read the dequantised pairs back bit for bit, products match the
-    oracle on every kernel the default plans reach (work queue, teams, row streaming, K slices, slices of 32 and
-    64 rows), a codebook made of a scalar table gives lutq_matmul's bits, and a misaligned codebook is refused."""
+@pytest.mark.parametrize("d", (2, 4))
+def test_vector_codebook_matches_oracle(lutq, dtype, d):
+    """lutq_matmul_pairs / lutq_matmul_quads (Section 5: vector codebooks; 256 vectors of two or four adjacent
+    weights, one byte of the 4- or 2-bit layout = one index): one-hot activations read the dequantised vectors
+    back bit for bit, products match the oracle on every kernel the default plans reach (work queue, teams, row
+    streaming, K slices, slices of 32 and 64 rows), a codebook made of a scalar table gives lutq_matmul's bits,
+    and a misaligned codebook is refused."""
     import torch
+    b = 8 // d
+    call = lutq.lutq_matmul_pairs if d == 2 else lutq.lutq_matmul_quads
     # weights read back through the kernel: X = one-hot rows
     N, K, group = 64, 512, 64
-    c, C, V = pair_codebook_case(40, 16, N, K, group, dtype)
-    d = DeviceCase(lutq, c)
+    c, C, V = codebook_case(40, d, 16, N, K, group, dtype)
+    dev = DeviceCase(lutq, c)
     Cd = to_dev(C, dtype)
-    What = orc.dequant_pairs(V, C, c.S, group, dtype)
+    What = orc.dequant_vectors(V, C, c.S, group, dtype)
     one = np.zeros((16, K), dtype=np.float32)
     for k0 in range(0, K, 16):
         one[:] = 0
         one[np.arange(16), k0 + np.arange(16)] = 1.0
         X = to_dev(gen.encode16(one, dtype), dtype)
         Y = torch.full((16, N), float("nan"), dtype=X.dtype, device="cuda")
-        lutq.lutq_matmul_pairs(X, d.packed, d.S, Cd, group, Y, d.ws)
+        call(X, dev.packed, dev.S, Cd, group, Y, dev.ws)
         assert np.array_equal(to_bits(Y), What[:, k0:k0 + 16].T), f"columns {k0}.."
     for (M, N, K, group) in [(1, 4096, 1024, 128), (3, 336, 2560, 64), (8, 96, 512, 32), (16, 22016, 1024, 128),
                              (24, 4096, 7168, 128), (32, 208, 2048, 64), (48, 4112, 1024, 64), (100, 96, 1024, 32)]:
-        c, C, V = pair_codebook_case(41 + M, M, N, K, group, dtype)
-        d = DeviceCase(lutq, c)
+        c, C, V = codebook_case(41 + M, d, M, N, K, group, dtype)
+        dev = DeviceCase(lutq, c)
         Cd = to_dev(C, dtype)
-        Y = torch.full((M, N), float("nan"), dtype=d.X.dtype, device="cuda")
-        lutq.lutq_matmul_pairs(d.X, d.packed, d.S, Cd, group, Y, d.ws)
+        Y = torch.full((M, N), float("nan"), dtype=dev.X.dtype, device="cuda")
+        call(dev.X, dev.packed, dev.S, Cd, group, Y, dev.ws)
         torch.cuda.synchronize()
-        check_y(to_bits(Y), c, f"pairs {dtype} M{M} N{N} K{K} g{group}", What=orc.dequant_pairs(V, C, c.S, group, dtype))
-        assert not d.ws[:65536].any().item()
-        # sixteen scalars as a codebook of pairs: the same bits as the scalar call
+        check_y(to_bits(Y), c, f"codebook d{d} {dtype} M{M} N{N} K{K} g{group}", What=orc.dequant_vectors(V, C, c.S, group, dtype))
+        assert not dev.ws[:65536].any().item()
+        # the scalar table as a codebook of vectors: the same bits as the scalar call
         e = np.arange(256)
-        Cs = to_dev(np.stack([c.T[e & 15], c.T[e >> 4]], axis=1), dtype)
-        lutq.lutq_matmul_pairs(d.X, d.packed, d.S, Cs, group, Y, d.ws)
-        assert np.array_equal(to_bits(Y), to_bits(d.matmul(lutq))), f"scalar table as pairs: M{M} N{N} K{K}"
+        Cs = to_dev(np.stack([c.T[(e >> (b * i)) & ((1 << b) - 1)] for i in range(d)], axis=1), dtype)
+        call(dev.X, dev.packed, dev.S, Cs, group, Y, dev.ws)
+        assert np.array_equal(to_bits(Y), to_bits(dev.matmul(lutq))), f"scalar table as vectors: M{M} N{N} K{K}"
     # the codebook is read as aligned 32-bit words
-    buf = torch.zeros(514, dtype=Cd.dtype, device="cuda")
+    buf = torch.zeros(256 * d + 2, dtype=Cd.dtype, device="cuda")
     with pytest.raises(lutq.LutqError) as e:
-        lutq.lutq_matmul_pairs(d.X, d.packed, d.S, buf[1:513].view(256, 2), group, Y, d.ws)
+        call(dev.X, dev.packed, dev.S, buf[1:256 * d + 1].view(256, d), group, Y, dev.ws)
     assert e.value.code == 5
 
 

@@ -497,30 +497,34 @@ def test_channel_tables(dtype):
 
 
 @pytest.mark.parametrize("dtype", ("f16", "bf16"))
-def test_pair_codebook(dtype):
-    """dequant_pairs against exact rationals element by element, and its reduction to the scalar table: a codebook
-    whose entry e is (T[e & 15], T[e >> 4]) with V = Q[2j] | Q[2j + 1] << 4 is dequant itself."""
-    rng = np.random.default_rng(12)
+@pytest.mark.parametrize("d", (2, 4))
+def test_vector_codebook(dtype, d):
+    """dequant_vectors against exact rationals element by element, and its reduction to the scalar table: a codebook
+    whose entry e is (T[field 0 of e], T[field 1 of e], ...) with V = the d indices of a vector side by side in a
+    byte (d = 2: nibbles, d = 4: bit pairs) is dequant itself."""
+    rng = np.random.default_rng(12 + d)
     group, N, K = 32, 5, 128
-    V = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    b = 8 // d                                    # bits per scalar index in the reduction
+    V = rng.integers(0, 256, size=(N, K // d), dtype=np.uint8)
     S = rand16(rng, (N, K // group), dtype, 0.05)
-    C = rand16(rng, (256, 2), dtype)
-    W = orc.dequant_pairs(V, C, S, group, dtype)
+    C = rand16(rng, (256, d), dtype)
+    W = orc.dequant_vectors(V, C, S, group, dtype)
     assert W.shape == (N, K)
     for n in range(N):
         for k in range(K):
-            exact = frac_of_bits(int(C[V[n, k // 2], k % 2]), dtype) * frac_of_bits(int(S[n, k // group]), dtype)
+            exact = frac_of_bits(int(C[V[n, k // d], k % d]), dtype) * frac_of_bits(int(S[n, k // group]), dtype)
             assert frac_of_bits(int(W[n, k]), dtype) == round_frac_to_format(exact, dtype), (n, k)
-    T = rand16(rng, (16,), dtype)
-    Q = rng.integers(0, 16, size=(N, K), dtype=np.uint8)
+    T = rand16(rng, (1 << b,), dtype)
+    Q = rng.integers(0, 1 << b, size=(N, K), dtype=np.uint8)
     e = np.arange(256)
-    Cs = np.stack([T[e & 15], T[e >> 4]], axis=1)
-    Vs = (Q[:, 0::2] | (Q[:, 1::2] << 4)).astype(np.uint8)
-    assert np.array_equal(orc.dequant_pairs(Vs, Cs, S, group, dtype), orc.dequant(Q, T, S, group, dtype))
-    # a swapped pair, or the scale of the neighbouring group, is a different matrix
-    assert not np.array_equal(orc.dequant_pairs(Vs, Cs[:, ::-1], S, group, dtype), orc.dequant(Q, T, S, group, dtype))
+    Cs = np.stack([T[(e >> (b * c)) & ((1 << b) - 1)] for c in range(d)], axis=1)
+    Vs = np.zeros((N, K // d), dtype=np.uint8)
+    for c in range(d):
+        Vs |= (Q[:, c::d] << (b * c)).astype(np.uint8)
+    assert np.array_equal(orc.dequant_vectors(Vs, Cs, S, group, dtype), orc.dequant(Q, T, S, group, dtype))
+    # a reversed vector is a different matrix
+    assert not np.array_equal(orc.dequant_vectors(Vs, Cs[:, ::-1], S, group, dtype), orc.dequant(Q, T, S, group, dtype))
     with pytest.raises(ValueError):
-        orc.dequant_pairs(V, C[:, :1], S, group, dtype)
+        orc.dequant_vectors(V, C[:, :d - 1], S, group, dtype)
     with pytest.raises(ValueError):
-        orc.dequant_pairs(V.astype(np.int32) + 1, C[:200], S, group, dtype)
-
+        orc.dequant_vectors(V.astype(np.int32) + 1, C[:200], S, group, dtype)
