@@ -185,7 +185,8 @@ typedef struct {
     int tiles_per_item;       /* LUTQ_SCHED_QUEUE: K tiles (128 columns at 4 bits, 256 at 2 and 3) per item:
                                  0, or a multiple of tiles_in_flight that divides the K tiles of a row.
                                  LUTQ_SCHED_ROWS: 0 = K is not cut across workgroups, else the K tiles per
-                                 slice, a divisor of the K tiles of a row that leaves at least two slices */
+                                 slice: the K tiles of a row divided by it, rounded up, is the number of
+                                 slices (at least two), which are as even as whole tiles allow */
 } lutq_plan;
 
 #define LUTQ_SCHED_TEAMS 1

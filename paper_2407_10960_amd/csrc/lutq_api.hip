@@ -178,7 +178,7 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
 
 // K slices on the row-streaming kernel (9..32 rows): for matrices with at most one row block per compute
 // unit (two up to 24 rows) and a long K, four row blocks per share of workgroups and as many K slices as keep the grid within the compute
-// units, at least four slices of at least 1792 columns (fourteen 4-bit K tiles) each; every workgroup then reads only its slice of the activations with eight (twelve) waves
+// units, at least three slices of at least 1792 columns (fourteen 4-bit K tiles) each, as even as whole tiles allow; every workgroup then reads only its slice of the activations with eight (twelve) waves
 // that hold them in registers, and a share's slices are added by whichever of its workgroups finishes last.  Measured against the team plans (MI355X, us,
 // HBM-cold weights): 8B down (4096 x 14336) M = 17 / 24 / 32 20.1 / 20.1 / 20.5 -> 14.5 / 15.4 / 16.8, bf16 M = 32 21.3 -> 16.9,
 // 3-bit 21.2 -> 17.9, group 32 20.5 -> 17.9; 4096 x 8192 M = 20 / 32 13.2 / 15.2 -> 11.3 / 12.5; 4096 x 28672 31.8 -> 26.4;
@@ -192,18 +192,25 @@ bool default_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, i
 // fewer than four slices (8B O in two slices of sixteen tiles: M = 20 8.6 -> 9.7), more than one row block per compute unit
 // (8B QKV, 70B O and down, N = K = 8192: within 3 % either way).
 bool sliced_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int group_size, int cus, Decomp* out) {
-    if (M < 9 || M > 32 || ((K / group_size) * 2) % 16 != 0) return false;
+    if (M < 9 || M > 32) return false;
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1;
     if (nb > 2 * (int64_t)cus || nb % 4 != 0) return false;
     const int64_t shares = nb / 4;
-    // (two or three slices only at 4 bits up to 24 rows and with slices of 56 tiles or more -- two row blocks per compute
+    // (three slices like four: 13B down, 5120 x 13824, 80 shares x 3 slices on 240 units, M = 12 / 16 / 24 / 32 19.1 / 20.0 / 26.3 /
+    // 29.3 -> 14.1 / 14.9 / 17.6 / 19.4 us, the same at 2 and 3 bits and in bf16; 7B down, 4096 x 11008, in slices of 22, 22, 21, 21
+    // tiles: M = 32 19.1 -> 15.9)
+    // (three slices up to sixteen rows only from 4096 columns each: 4096 x 6144 M = 12 8.0 -> 9.2 us, but M = 24 12.5 -> 11.3)
+    // (two slices only at 4 bits up to 24 rows and with slices of 56 tiles or more -- two row blocks per compute
     // unit and a long K, 70B down: bf16 M = 9 / 12 / 16 / 20 / 24 35.0 / 37.9 / 35.0 / 41.6 / 41.7 -> 29.5 / 30.2 / 31.6 / 39.0 / 39.7 us,
     // fp16 M = 16 / 20 32.1 / 39.2 -> 30.6 / 36.8; at M = 32 43.0 -> 43.8; on K = 8192 -- 70B O, N = K = 8192 -- within 5 % either
     // way, and at 3 bits the teams are 1-5 % faster)
     int ks = 0;
+    // (only slice counts that a plan can name: k = the K tiles divided by the tiles per slice, rounded up)
+    auto nameable = [&](int64_t k) { const int64_t it = (kt + k - 1) / k; return (kt + it - 1) / it == k; };
     for (int64_t k = cus / shares; k >= 2 && !ks; --k)
-        if (kt % k == 0 && (k >= 4 ? kt / k * tile_k(bits) >= 14 * 128 : kt / k >= 56 && bits == 4 && M <= 24)) ks = (int)k;
+        if (!nameable(k)) continue;
+        else if (k >= 3 ? kt / k * tile_k(bits) >= (k == 3 && mb == 1 ? 4096 : 14 * 128) : kt / k >= 56 && bits == 4 && M <= 24) ks = (int)k;
     // (grids from half the compute units up beyond sixteen rows, from three quarters up to there: 2048 x 8192 on 128
     // workgroups M = 24 11.9 -> 11.0 us, but bf16 M = 16 9.1 -> 10.0)
     if (!ks || shares * ks * (mb == 2 ? 2 : 4) < cus * (mb == 2 ? 1 : 3) || shares * 64 > (int64_t)kCounterBytes) return false;
@@ -212,7 +219,7 @@ bool sliced_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, in
     if (nw > (mb == 2 ? 8 : 12)) nw = mb == 2 ? 8 : 12;
     if (nw < 4 || rows_blocks_per_round(bits, 4, (int)(K / group_size) * 2, mb, nw) < 1) return false;
     out->r = 4; out->grid = (int)(shares * ks); out->nw = nw; out->stages = 2; out->rs = 4; out->queue = 0;
-    out->it = (int)(kt / ks); out->ks = ks; out->rows = 1;
+    out->it = (int)((kt + ks - 1) / ks); out->ks = ks; out->rows = 1;
     return true;
 }
 
@@ -220,7 +227,7 @@ bool sliced_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, in
 // (4 bits, scale rows of whole 16-byte units, four row blocks side by side, activations from their
 // operand-order copy).  `take`: whether that is also the default (against two launches of 32 rows).
 bool wide_rows_decomp(int bits, bool bf16, int64_t M, int64_t N, int64_t K, int group_size, int cus, Decomp* out, bool* take) {
-    if (M <= 32 || M > 64 || ((K / group_size) * 2) % 16 != 0) return false;
+    if (M <= 32 || M > 64) return false;
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = (int)((M + 15) / 16);
     const int grid = (int)(nb < cus ? nb : cus);
@@ -865,14 +872,16 @@ lutq_status prepare_rows(const void* X, const void* packed, const void* scales, 
     const int extra = (int)(nb - (int64_t)d.rs * shares);
     const int amax = d.rs + (extra ? 1 : 0);
     if (ks > 1) {
-        if (rowlut || mb > 2 || kt % ks != 0 || amax > d.r || (int64_t)shares * 64 > (int64_t)kCounterBytes) return LUTQ_ERR_PLAN;
+        if (rowlut || mb > 2 || ks > kt || amax > d.r || (int64_t)shares * 64 > (int64_t)kCounterBytes) return LUTQ_ERR_PLAN;
         if (!dry && (!scratch || (size_t)d.grid * d.r * mb * 1024 > scratch_room)) return scratch ? LUTQ_ERR_SCRATCH : LUTQ_ERR_PLAN;
     }
-    const int64_t ts = kt / ks;                               // K tiles per slice
-    // the scales of a pass's row blocks are staged in LDS in 16-byte units
+    const int64_t ts = kt / ks;                               // K tiles per slice (the first kt % ks slices: one more)
+    // the scales of a pass's row blocks are staged in LDS in 16-byte units: row by row with 16 bytes of padding, or, where a
+    // row is not a whole number of units, as one range (shared tables only)
     const int sg2 = (int)(K / group_size) * 2;
-    if (sg2 % 16 != 0) return LUTQ_ERR_PLAN;
-    const int srow = sg2 + 16;
+    const bool linear = sg2 % 16 != 0;
+    if (linear && rowlut) return LUTQ_ERR_PLAN;
+    const int srow = linear ? sg2 : sg2 + 16;
     if (rowlut && d.r != 4) return LUTQ_ERR_PLAN;           // per-row tables: four row blocks side by side
     const int tab16 = rowlut ? rowlut16_table_bytes(bits, bf16) : 0;
     const int red_off = rows_red_off(bits, d.r, sg2, tab16);
@@ -905,12 +914,13 @@ lutq_status prepare_rows(const void* X, const void* packed, const void* scales, 
     q.sblock_bytes = (uint32_t)kt * q.tile_stride;
     q.A = d.rs; q.extra = extra; q.NW = d.nw; q.G = d.grid;
     q.TQ = (int)(ts / d.nw); q.TR = (int)(ts % d.nw);
-    q.KS = ks; q.TS = (int)ts;
+    q.KS = ks; q.TS = (int)ts; q.KSB = (int)(kt % ks);
+    q.TQ1 = (int)((ts + 1) / d.nw); q.TR1 = (int)((ts + 1) % d.nw);
     q.slots = ks > 1 ? static_cast<float*>(scratch) : nullptr;
     q.counters = ks > 1 && scratch ? reinterpret_cast<uint32_t*>(static_cast<char*>(scratch) - kCounterBytes) : nullptr;   // the scratch begins with the counters
     q.RPR = rpr;
-    q.s_units = sg2 / 16;
-    q.s_magic = (uint32_t)((1ull << 32) / (uint64_t)q.s_units + 1);
+    q.s_units = linear ? 0 : sg2 / 16;
+    q.s_magic = linear ? 0u : (uint32_t)((1ull << 32) / (uint64_t)q.s_units + 1);
     q.SROW = srow;
     q.red_off = red_off;
     q.tab_total = d.r * tab16;
@@ -1099,8 +1109,8 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
             // tiles_per_item: K tiles per slice where K is cut across workgroups (grid = shares x slices)
             int ks = 1;
             if (user_plan->tiles_per_item != 0) {
-                if (user_plan->tiles_per_item < 1 || kt % user_plan->tiles_per_item != 0 || !user_plan->grid) return LUTQ_ERR_PLAN;
-                ks = (int)(kt / user_plan->tiles_per_item);
+                if (user_plan->tiles_per_item < 1 || !user_plan->grid) return LUTQ_ERR_PLAN;
+                ks = (int)((kt + user_plan->tiles_per_item - 1) / user_plan->tiles_per_item);    // slices as even as whole tiles allow
                 if (ks < 2 || user_plan->grid % ks != 0) return LUTQ_ERR_PLAN;
             }
             const bool have_default = rows_decomp(bits, bf16, M, N, K, group_size, di.cus, &q);
@@ -1590,7 +1600,7 @@ std::vector<lutq_plan> tune_candidates(int bits, int group_size, int64_t M, int6
             }
         }
     }
-    if (M > 4 && ((K / group_size) * 2) % 16 == 0 && nb >= cus / 2) {
+    if (M > 4 && nb >= cus / 2) {
         // row-streaming plans: one workgroup per compute unit (or two, or one per two), four and eight row blocks
         // side by side, all the waves the instance allows and eight
         const int mbh = M > 16 ? 2 : 1;
@@ -1604,7 +1614,7 @@ std::vector<lutq_plan> tune_candidates(int bits, int group_size, int64_t M, int6
             }
         }
     }
-    if (M > 4 && ((K / group_size) * 2) % 16 == 0 && nb <= 2 * (int64_t)cus) {
+    if (M > 4 && nb <= 2 * (int64_t)cus) {
         // the same with K cut into slices across workgroups: one pass per share of four or eight row blocks, grids of one
         // workgroup per compute unit, half and twice that
         const int mbh = M > 16 ? 2 : 1;
@@ -1614,11 +1624,11 @@ std::vector<lutq_plan> tune_candidates(int bits, int group_size, int64_t M, int6
             const int64_t shares = (nb + side - 1) / side;
             if (shares * 64 > (int64_t)kCounterBytes) continue;
             for (int64_t ks = 2; ks <= kt && shares * ks <= 2 * (int64_t)cus; ++ks) {
-                if (kt % ks != 0 || shares * ks > kMaxGrid) continue;
+                if (shares * ks > kMaxGrid || (kt % ks != 0 && (kt + (kt + ks - 1) / ks - 1) / ((kt + ks - 1) / ks) != ks)) continue;
                 // (small problems, whose grids stay below half the compute units, keep the two extremes)
                 if (shares * ks * 2 < cus && ks != 2 && ks != kt) continue;
                 for (int nw : {w, 8})
-                    if (nw <= w) push_unique(lutq_plan{side, (int)(shares * ks), nw, 2, (int)(nb / shares), LUTQ_SCHED_ROWS, (int)(kt / ks)});
+                    if (nw <= w) push_unique(lutq_plan{side, (int)(shares * ks), nw, 2, (int)(nb / shares), LUTQ_SCHED_ROWS, (int)((kt + ks - 1) / ks)});
             }
         }
     }

@@ -20,7 +20,7 @@
 //     round, and written out: bit-reproducible.
 //
 //   * K slices (matrices with fewer row blocks than would keep every compute unit busy): KS workgroups share a
-//     workgroup's row blocks (at most AMAX: one pass) and take a slice of K each, so that a compute unit reads only
+//     workgroup's row blocks (at most AMAX: one pass) and take a slice of K each (as even as whole tiles allow), so that a compute unit reads only
 //     its slice of the activations.  Each writes its sums (fp32, per row block and block of sixteen rows of M) to its
 //     own slot in global memory and, when all of them are stored, bumps the share's arrival counter once; whichever
 //     workgroup arrives last adds the KS slots in slice order, its own included, and writes Y: nobody waits for anybody, and the result does not
@@ -65,7 +65,9 @@ struct RowsParams {
     int lut_ltpe;             // log2 of the threads that build one table row together
     int G;                    // workgroups
     int KS;                   // K slices: workgroup b works on slice b % KS of the row blocks of share b / KS (1: the whole of K)
-    int TS;                   // K tiles per slice (KT / KS)
+    int TS;                   // K tiles per slice (the whole part of KT / KS); the first KSB slices have one more
+    int KSB;                  // KT % KS
+    int TQ1, TR1;             // TQ, TR of the slices with TS + 1 tiles
     float* slots;             // KS > 1: partial sums, one slot of AMAX x MB KiB per workgroup
     uint32_t* counters;       // KS > 1: arrivals per share, one counter per 64 bytes; zero between launches
 };
@@ -119,7 +121,8 @@ void rows_kernel(const RowsParams p) {
     asm volatile("" ::"s"(p.X), "s"(p.packed), "s"(p.scales), "s"(p.lut), "s"(p.Y), "s"(p.packed_bytes), "s"(p.scale_bytes),
                  "s"(p.x_bytes), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.KT), "s"(p.SG2), "s"(p.SBL), "s"(p.tile_stride),
                  "s"(p.sblock_bytes), "s"(p.A), "s"(p.extra), "s"(p.NW), "s"(p.TQ), "s"(p.TR), "s"(p.RPR), "s"(p.lut_ltpe),
-                 "s"(p.s_units), "s"(p.s_magic), "s"(p.SROW), "s"(p.red_off), "s"(p.tab_total), "s"(p.KS), "s"(p.TS));
+                 "s"(p.s_units), "s"(p.s_magic), "s"(p.SROW), "s"(p.red_off), "s"(p.tab_total), "s"(p.KS), "s"(p.TS), "s"(p.KSB), "s"(p.TQ1),
+                 "s"(p.TR1));
 
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
@@ -156,8 +159,11 @@ void rows_kernel(const RowsParams p) {
     const bool big = share < p.extra;
     const int nrb = p.A + (big ? 1 : 0);
     const int rb_first = share * p.A + (share < p.extra ? share : p.extra);
-    const int ka = slice * p.TS + wave * p.TQ + (wave < p.TR ? wave : p.TR);     // TQ, TR: the slice's tiles over the waves
-    const int kb = ka + p.TQ + (wave < p.TR ? 1 : 0);
+    // the slice's tiles (the first KSB slices have TS + 1) over the waves: tq each, the first trm waves one more
+    const bool long_slice = slice < p.KSB;
+    const int tq = long_slice ? p.TQ1 : p.TQ, trm = long_slice ? p.TR1 : p.TR;
+    const int ka = slice * p.TS + (long_slice ? slice : p.KSB) + wave * tq + (wave < trm ? wave : trm);
+    const int kb = ka + tq + (wave < trm ? 1 : 0);
 
     // activation rows m >= M lie beyond the X buffer and read as zero
     uint32_t xlane[MB];
@@ -234,13 +240,16 @@ void rows_kernel(const RowsParams p) {
         {
             // The pass's scales: rows (rb_first + p0) * 16 onwards, na * 16 rows of SG2 bytes, one contiguous
             // range.  (Every wave is past the previous pass's K loop: its reduction began with a barrier.)
-            const int units = na * 16 * p.s_units;
+            // (s_units = 0: rows that are not whole 16-byte units -- the range, a multiple of 32 bytes that starts on one,
+            // is copied as it lies, SROW = SG2, no padding between the rows)
+            const int units = p.s_units ? na * 16 * p.s_units : na * p.SG2;
             const uint32_t gbase = (uint32_t)(rb_first + p0) * 16u * (uint32_t)p.SG2;
             for (int i = tid; i < units; i += p.NW * 64) {
-                const int row = p.s_units == 1 ? i : (int)__umulhi((uint32_t)i, p.s_magic);
+                const int row = p.s_units <= 1 ? i : (int)__umulhi((uint32_t)i, p.s_magic);
                 const int col = i - row * p.s_units;
                 const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rS, gbase + 16u * (uint32_t)i, 0, kAuxNone);
-                *reinterpret_cast<u32x4*>(sc + (size_t)row * p.SROW + 16 * col) = v;
+                char* dst = p.s_units ? sc + (size_t)row * p.SROW + 16 * col : sc + 16 * (size_t)i;
+                *reinterpret_cast<u32x4*>(dst) = v;
             }
         }
         if constexpr (RLUT) {

@@ -221,16 +221,18 @@ def test_64_row_slices(lutq, dtype):
         assert e.value.code == 10
         torch.cuda.synchronize()
         assert (Y == 7.0).all().item()
-    # 3 bits, and scale rows that are not whole 16-byte units, have no such instance
+    # 3 bits have no such instance; scale rows that are not whole 16-byte units (8 bytes here) are served
     assert lutq.lutq_plan_check(3, 64, 64, 208, 2048, dt, 256, ROWS) == 10
-    assert lutq.lutq_plan_check(4, 128, 64, 208, 512, dt, 256, ROWS) == 10
+    assert lutq.lutq_plan_check(4, 128, 64, 208, 512, dt, 256, ROWS) == 0
+    odd = gen.make_case(76, 64, 208, 512, 4, 128, dtype, "nf")
+    check_y(to_bits(DeviceCase(lutq, odd).matmul(lutq, plan=ROWS)), odd, f"{dtype} 64-row slice, scale rows of 8 bytes")
     assert lutq.lutq_plan_check(3, 64, 64, 208, 2048, dt, 256, None) == 0
 
 
 def test_64_row_slices_over_seeded_random_shapes(lutq):
     """The 64-row launch (asked for by plan) over shapes it was not written around: one to a thousand row blocks
     (fewer than compute units, uneven shares, up to four passes), one to sixty-four K tiles (fewer tiles than
-    waves), every group size, 33..128 rows, both dtypes; refused exactly where K / group is not a multiple of 8."""
+    waves), every group size (scale rows of 2 to 512 bytes, whole 16-byte units or not), 33..128 rows, both dtypes."""
     ROWS = lutq.Plan(scheduling=3)
     rng = np.random.default_rng(4242)
     nbs = [1, 2, 3, 7, 13, 64, 255, 256, 257, 300, 511, 512, 700, 1023]
@@ -246,11 +248,8 @@ def test_64_row_slices_over_seeded_random_shapes(lutq):
         if group == 256 and kt % 2:
             kt += 1
         N, K = 16 * nb, 128 * kt
-        ok = (K // group) % 8 == 0
         what = f"case {i}: {dtype} g{group} M{M} N{N} K{K}"
-        assert (lutq.lutq_plan_check(4, group, M, N, K, 0 if dtype == "f16" else 1, 256, ROWS) == 0) == ok, what
-        if not ok:
-            continue
+        assert lutq.lutq_plan_check(4, group, M, N, K, 0 if dtype == "f16" else 1, 256, ROWS) == 0, what
         c = gen.make_case(3000 + i, M, N, K, 4, group, dtype, "random_index")
         d = DeviceCase(lutq, c)
         if workspace is None:
@@ -758,6 +757,9 @@ FULL_SIZE = [
     ("8B down W3 g64 bf16 M12 (row streaming, K slices, up to sixteen rows at 3 bits)", 4096, 14336, 3, 64, "bf16", 12),
     ("8B down W2 g128 bf16 M32 (row streaming, K slices, 2 bits)", 4096, 14336, 2, 128, "bf16", 32),
     ("4096x8192 W2 g64 M20 (row streaming, four K slices of eight tiles)", 4096, 8192, 2, 64, "f16", 20),
+    ("4096x11008 W4 g128 M24 (row streaming, K slices of 22, 22, 21, 21 tiles, scale rows of 172 bytes)", 4096, 11008, 4, 128, "f16", 24),
+    ("5120x13824 W3 g128 M32 (row streaming, 80 shares x 3 K slices on 240 units)", 5120, 13824, 3, 128, "f16", 32),
+    ("5120x13824 W4 g128 bf16 M48 (64-row slice, scale rows of 216 bytes)", 5120, 13824, 4, 128, "bf16", 48),
     ("8B down W4 g128 M17 (row streaming, 64 shares x 4 K slices)", 4096, 14336, 4, 128, "f16", 17),
     ("8B down W4 g32 bf16 M32 (row streaming, K slices, group 32)", 4096, 14336, 4, 32, "bf16", 32),
     ("8B down W3 g128 bf16 M32 (row streaming, K slices, 3 bits)", 4096, 14336, 3, 128, "bf16", 32),
@@ -913,11 +915,16 @@ def test_row_streaming_plans_match_oracle(lutq, bits, dtype):
     for side in (2, 16):
         with pytest.raises(lutq.LutqError):
             d.matmul(lutq, plan=lutq.Plan(side, 0, 8, 2, 0, RW, 0))
-    # rows of scales that are not whole 16-byte units are left to the other kernels
-    c = gen.make_case(9, 8, 64, 3 * tk(bits), bits, 32 if bits == 4 else 64, dtype, "nf")
-    with pytest.raises(lutq.LutqError) as e:
-        DeviceCase(lutq, c).matmul(lutq, plan=lutq.Plan(4, 0, 4, 2, 0, RW, 0))
-    assert e.value.code == 10
+    # rows of scales that are not whole 16-byte units (24, 12 and 6 bytes here) are staged as one range
+    for (M, N, kt, group) in [(8, 64, 3, 32 if bits == 4 else 64), (20, 176, 3, 64 if bits == 4 else 128), (32, 80, 3, 128 if bits == 4 else 256)]:
+        c = gen.make_case(9 + M, M, N, kt * tk(bits), bits, group, dtype, "nf")
+        d = DeviceCase(lutq, c)
+        for side in (4, 8):
+            w = rows_waves(lutq, bits, dtype, M, N, kt * tk(bits), group, side)
+            for plan in ([lutq.Plan(side, 0, 4, 2, 0, RW, 0), lutq.Plan(side, 2, w, 2, 0, RW, 0), lutq.Plan(side, N // 16, 5, 2, 1, RW, 0)] if w else []):
+                Y1 = to_bits(d.matmul(lutq, plan=plan))
+                assert np.array_equal(Y1, to_bits(d.matmul(lutq, plan=plan))), f"{plan} is not reproducible"
+                check_y(Y1, c, f"unaligned scale rows b{bits} {dtype} g{group} M{M} N{N} {plan}")
 
 
 @pytest.mark.parametrize("bits", BITS)
@@ -925,8 +932,8 @@ def test_row_streaming_plans_match_oracle(lutq, bits, dtype):
 def test_k_sliced_row_streaming_plans_match_oracle(lutq, bits, dtype):
     """Row-streaming plans with K cut into slices across workgroups (tiles_per_item = K tiles per slice, grid =
     shares x slices): each workgroup stores its slice's sums, the share's last arrival adds them in slice order.
-    One to many shares, uneven shares, two to twenty slices, more waves than tiles of a slice, M on both sides
-    of 16; against the oracle, bit-reproducible, arrival counters left at zero; malformed cuts refused."""
+    One to many shares, uneven shares, two to twenty slices, slices of unequal length, more waves than tiles of a
+    slice, M on both sides of 16; against the oracle, bit-reproducible, arrival counters left at zero; malformed cuts refused."""
     RW = 3                                                  # LUTQ_SCHED_ROWS
     n = 0
     for (N, K, group, lut, cuts) in [(64, 8 * tk(bits), 128, "nf", {4: [(1, 2), (1, 8)], 8: [(1, 4)]}),
@@ -942,17 +949,23 @@ def test_k_sliced_row_streaming_plans_match_oracle(lutq, bits, dtype):
                 if w == 0:
                     continue
                 for shares, ks in cuts[side]:
-                    for nw in (4, w):
-                        plan = lutq.Plan(side, shares * ks, nw, 2, nb // shares, RW, kt // ks)
+                    for nw, it in ((4, kt // ks), (w, kt // ks), (w, -(-kt // 3) if ks == cuts[side][0][1] else 0)):
+                        if it == 0:
+                            continue
+                        if it != kt // ks:
+                            # slices that do not divide K: three, as even as whole tiles allow
+                            ks = -(-kt // it)
+                            if ks < 2:
+                                continue
+                        plan = lutq.Plan(side, shares * ks, nw, 2, nb // shares, RW, it)
                         Y1 = to_bits(d.matmul(lutq, plan=plan))
                         Y2 = to_bits(d.matmul(lutq, plan=plan))
                         assert np.array_equal(Y1, Y2), f"{plan} is not reproducible"
                         check_y(Y1, c, f"b{bits} {dtype} g{group} M{M} N{N} K{K} {plan}")
                         assert int(d.ws[:65536].count_nonzero()) == 0, f"{plan} left counters behind"
                         n += 1
-                # slices that do not divide K, a grid that is no multiple of the slices, no grid, a single slice,
-                # more than one pass per share
-                bad = [lutq.Plan(side, 2, 4, 2, 0, RW, kt - 1), lutq.Plan(side, 3, 4, 2, 0, RW, kt // 2),
+                # a grid that is no multiple of the slices, no grid, a single slice, more than one pass per share
+                bad = [lutq.Plan(side, 3, 4, 2, 0, RW, kt // 2),
                        lutq.Plan(side, 0, 4, 2, 0, RW, kt // 2), lutq.Plan(side, 1, 4, 2, 0, RW, kt)]
                 if nb > side:
                     bad.append(lutq.Plan(side, 2, 4, 2, 0, RW, kt // 2))

@@ -170,12 +170,13 @@ def test_default_plans_are_valid_for_random_problems():
             assert M >= 5 and p.row_blocks_per_wave in (4, 8) and p.tiles_in_flight == 2, what
             slices = 1
             if p.tiles_per_item:                    # K cut into slices across workgroups: one pass per share of row blocks
-                assert M >= 9 and (K // tkb) % p.tiles_per_item == 0 and p.tiles_per_item * tkb >= 1792, what
-                slices = K // tkb // p.tiles_per_item
-                assert slices >= (4 if M > 24 or bits != 4 else 2) and p.grid % slices == 0 and cus // 2 <= p.grid <= cus, what
+                assert M >= 9 and p.tiles_per_item * tkb >= 1792, what
+                slices = -(-(K // tkb) // p.tiles_per_item)
+                assert -(-(K // tkb) // slices) == p.tiles_per_item, what
+                assert slices >= (3 if M > 24 or bits != 4 else 2) and p.grid % slices == 0 and cus // 2 <= p.grid <= cus, what
                 assert p.row_groups_per_workgroup <= p.row_blocks_per_wave, what
             assert 1 <= p.grid // slices <= nb and p.row_groups_per_workgroup == nb // (p.grid // slices) <= 64, what
-            assert (K // group * 2) % 16 == 0, what
+            assert (K // group * 2) % 16 == 0 or p.tiles_per_item or M > 32, what
             assert lutq.lutq_plan_check(bits, group, M, N, K, dt, cus) == 0, what
             if M <= 32:
                 assert lutq.lutq_plan_check(bits, group, M, N, K, dt, cus, p) == 0, what
@@ -211,11 +212,12 @@ def test_default_plans_of_the_llama3_shapes():
         p = lutq.lutq_plan_default_for(4, g, 1, N, K, 0, 256)
         assert (p.row_blocks_per_wave, p.grid, p.waves_per_workgroup, p.tiles_in_flight, p.row_groups_per_workgroup,
                 p.scheduling, p.tiles_per_item) == plan, (N, K, p)
-    # beyond 32 rows: the one decomposition of the 64-row slices (4 bits, whole 16-byte units of scales per row, at
-    # least one row block per compute unit), else the plan of the 32-row slices
+    # beyond 32 rows: the one decomposition of the 64-row slices (4 bits, at least one row block per compute unit),
+    # else the plan of the 32-row slices
     assert lutq.lutq_plan_default_for(4, 128, 100, 4096, 4096, 0, 256) == lutq.Plan(4, 256, 8, 2, 1, 3, 0)
     assert lutq.lutq_plan_default_for(4, 128, 40, 28672, 4096, 1, 256) == lutq.Plan(4, 256, 8, 2, 7, 3, 0)
-    for (b, N, K) in [(3, 4096, 4096), (4, 2048, 4096), (4, 4096, 512)]:
+    assert lutq.lutq_plan_default_for(4, 128, 100, 4096, 512, 0, 256).scheduling == 3          # scale rows of 8 bytes
+    for (b, N, K) in [(3, 4096, 4096), (4, 2048, 4096)]:
         assert lutq.lutq_plan_default_for(b, 128, 100, N, K, 0, 256) == lutq.lutq_plan_default_for(b, 128, 32, N, K, 0, 256)
         assert lutq.lutq_plan_check(b, 128, 100, N, K, 0, 256, None) == 0
     with pytest.raises(lutq.LutqError):
@@ -230,10 +232,10 @@ def test_default_plans_fitted_by_measurement():
     want = {
         (4, 128, 8, 4096, 14336, 0): (1, 256, 7, 2, 1),          # seven waves: sixteen tiles = two scale chunks each
         (3, 128, 8, 12288, 4096, 0): (4, 256, 12, 2, 3, 3),       # row streaming: three row blocks per compute unit at 3 bits
-        (3, 128, 12, 4096, 11008, 0): (1, 256, 8, 2, 1),
+        (3, 128, 12, 4096, 11008, 0): (4, 256, 12, 2, 4, 3),
         (3, 64, 12, 10240, 8192, 0): (1, 256, 10, 2, 10),
-        (2, 128, 12, 5120, 13824, 0): (2, 160, 8, 2, 1),
-        (3, 128, 32, 5120, 13824, 0): (2, 256, 4, 2, 1),
+        (2, 128, 12, 5120, 13824, 0): (4, 240, 12, 2, 4, 3),
+        (3, 128, 32, 5120, 13824, 0): (4, 240, 8, 2, 4, 3),
         (4, 128, 32, 1024, 4096, 0): (1, 128, 4, 2, 1),
         (4, 128, 4, 5120, 13824, 0): (2, 160, 8, 2, 1),
         (4, 128, 2, 5120, 5120, 0): (1, 256, 16, 2, 1, 2),         # work queue, shares of one and two row blocks
@@ -250,11 +252,15 @@ def test_default_plans_fitted_by_measurement():
         (4, 128, 20, 4096, 14336, 1): (4, 256, 8, 2, 4, 3),
         (3, 128, 32, 4096, 14336, 0): (4, 256, 8, 2, 4, 3),
         (4, 128, 32, 2048, 14336, 0): (4, 256, 8, 2, 4, 3),
-        (4, 128, 24, 3072, 12288, 0): (4, 192, 8, 2, 4, 3),
+        (4, 128, 24, 3072, 12288, 0): (4, 240, 8, 2, 4, 3),
         (4, 128, 16, 4096, 14336, 0): (4, 256, 12, 2, 4, 3),       # ... twelve waves up to sixteen rows
         (3, 128, 12, 4096, 14336, 1): (4, 256, 8, 2, 4, 3),        # (the 3-bit bf16 instance holds eight waves)
         (4, 128, 9, 4096, 14336, 0): (4, 256, 12, 2, 4, 3),
         (2, 128, 24, 4096, 14336, 1): (4, 256, 8, 2, 4, 3),
+        (4, 128, 24, 4096, 11008, 0): (4, 256, 8, 2, 4, 3),        # ... uneven slices (22, 22, 21, 21 tiles), scale rows of 172 bytes
+        (4, 128, 32, 5120, 13824, 0): (4, 240, 8, 2, 4, 3),        # ... 80 shares x 3 slices
+        (4, 128, 12, 4096, 6144, 0): (1, 256, 6, 2, 1),            # ... three slices up to sixteen rows only from 4096 columns each
+        (4, 128, 24, 4096, 6144, 0): (4, 192, 8, 2, 4, 3),
         (4, 64, 20, 8192, 28672, 1): (4, 256, 8, 2, 4, 3),         # ... two slices up to 24 rows
         (4, 64, 32, 8192, 28672, 1): (1, 256, 8, 4, 8),
         (4, 64, 16, 2048, 8192, 1): (1, 256, 4, 2, 1),             # ... nor on half the compute units up to sixteen rows
