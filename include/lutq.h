@@ -21,7 +21,7 @@
  * round16 is one round-to-nearest-even to the 16-bit type `dtype`.
  *
  * Supported domain: bits in {2,3,4}; group_size in {32,64,128,256}; 1 <= M <= 128
- * (a launch works on up to 32 activation rows, at 4 bits with K / group_size a multiple of 8 on up
+ * (a launch works on up to 32 activation rows, at 4 bits on up
  * to 64; more are served in slices of that many rows, one launch each on the caller's stream, so the
  * weights are streamed once per slice; a 33..64-row launch is preceded by a small launch that copies
  * the slice's activations into the workspace in the order the matrix instruction reads them);
@@ -168,7 +168,7 @@ typedef struct {
                                  and stream the weights of row_blocks_per_wave (4 or 8) row blocks past them
                                  side by side, in as many passes as the workgroup's row blocks need;
                                  tiles_in_flight 2.  For M > 32 this scheduling asks for slices of 64 rows
-                                 (4 bits, K / group_size a multiple of 8; LUTQ_ERR_PLAN where no such
+                                 (4 bits; LUTQ_ERR_PLAN where no such
                                  instance exists); that launch has one decomposition (4 row blocks side by
                                  side, one workgroup per compute unit, 8 waves at most), so every other
                                  field is 0 or the value lutq_plan_default reports; any other plan, and
