@@ -675,7 +675,9 @@ def test_graph_replay_matches_eager(lutq):
     import torch
     specs = [(1, 256, 2048, 4, "f16", None), (1, 256, 2048, 4, "f16", lutq.Plan(1, 7, 8, 2, 1)),
              (16, 192, 4096, 3, "f16", lutq.Plan(2, 5, 8, 2, 2)), (32, 128, 1024, 2, "f16", lutq.Plan(1, 3, 8, 2, 8)),
-             (3, 320, 1024, 4, "f16", lutq.Plan(1, 9, 10, 2, 5))]
+             (3, 320, 1024, 4, "f16", lutq.Plan(1, 9, 10, 2, 5)),
+             # the row-streaming kernel's K slices (4 shares x 3 uneven slices) and a 64-row slice with its operand-order copy
+             (24, 208, 2048, 4, "f16", lutq.Plan(4, 12, 8, 2, 3, 3, 6)), (50, 272, 1024, 4, "f16", lutq.Plan(scheduling=3))]
     cases = [gen.make_case(500 + i, M, N, K, bits, 64, dtype, "nf") for i, (M, N, K, bits, dtype, _) in enumerate(specs)]
     devs = [DeviceCase(lutq, c) for c in cases]
     ws = devs[0].ws
