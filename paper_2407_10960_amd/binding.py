@@ -73,6 +73,10 @@ def load_library():
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is missing: build it with `python -m paper_2407_10960_amd.build` "
                            "(there is no CPU or PyTorch fallback)")
+    # PyTorch ships its own HIP runtime and owns the device memory and streams this library works on: it has to be in
+    # the process first, so that liblutq.so binds to that runtime and not to a second copy of its own (a library loaded
+    # before torch would query and launch through a runtime that torch's allocations do not belong to).
+    import torch  # noqa: F401
     lib = ctypes.CDLL(path)
     vp, i64, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
     lib.lutq_status_string.restype = ctypes.c_char_p

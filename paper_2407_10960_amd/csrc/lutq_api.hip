@@ -1044,7 +1044,10 @@ lutq_status prepare_matmul(const void* X, const void* packed, const void* scales
         // fitted_workspace: the scratch is checked further down against what this launch really uses
         if (!workspace || workspace_bytes < (fitted_workspace ? kCounterBytes : kWorkspaceBytes)) return LUTQ_ERR_WORKSPACE;
         di = device_info();
-        if (!di.ok) return LUTQ_ERR_DEVICE;
+        if (!di.ok) {
+            if (env_switches().verbose) std::fprintf(stderr, "lutq_matmul: device query failed: %s\n", hipGetErrorString(hipGetLastError()));
+            return LUTQ_ERR_DEVICE;
+        }
     }
     const int64_t nb = N / 16, kt = K / tile_k(bits);
     const int mb = M > 16 ? 2 : 1;
@@ -1300,6 +1303,8 @@ lutq_status launch_prepared(const Prepared& q, int bits, int group_size, lutq_dt
             if (hipGetLastError() != hipSuccess) return LUTQ_ERR_DEVICE;
         }
         const hipError_t e = pick_rows(bits, dtype)(group_size, q.mb, q.r, q.rows_rowlut, q.rp, q.rows_lds, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess && env_switches().verbose)
+            std::fprintf(stderr, "lutq_matmul: launch failed: %s (grid %d, block %d, lds %d)\n", hipGetErrorString(e), q.rp.G, q.rp.NW * 64, q.rows_lds);
         return e == hipSuccess ? LUTQ_OK : LUTQ_ERR_DEVICE;
     }
     if (q.queue) {

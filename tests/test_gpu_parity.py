@@ -978,6 +978,57 @@ def test_k_sliced_row_streaming_plans_match_oracle(lutq, bits, dtype):
     assert n > 0 or bits != 4
 
 
+def test_k_sliced_plans_over_seeded_random_shapes(lutq):
+    """K-sliced row-streaming plans over shapes they were not written around: one to six hundred row blocks in shares
+    of one to eight (uneven shares), two to sixty-four K tiles in two to sixteen slices that need not divide them,
+    four waves up to what the instance allows, every group size (scale rows of whole 16-byte units or not), all bit
+    widths, both dtypes, 1..32 rows; against the oracle, bit-reproducible, arrival counters left at zero."""
+    RW = 3
+    rng = np.random.default_rng(777)
+    workspace = None
+    done = 0
+    for i in range(90):
+        bits = int(rng.choice([2, 3, 4]))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        group = int(rng.choice([32, 64, 128, 256]))
+        M = int(rng.choice([1, 4, 7, 9, 12, 16, 17, 20, 24, 31, 32]))
+        nb = int(rng.choice([1, 2, 3, 5, 8, 13, 31, 64, 100, 255, 256, 257, 320, 600]))
+        kt = int(rng.choice([2, 3, 4, 5, 7, 8, 11, 16, 24, 43, 64]))
+        if nb * kt > 4096:
+            kt = max(2, 4096 // nb)
+        if group == 256 and bits == 4 and kt % 2:
+            kt += 1
+        side = int(rng.choice([4, 8]))
+        N, K = 16 * nb, tk(bits) * kt
+        w = rows_waves(lutq, bits, dtype, M, N, K, group, side)
+        if w == 0:
+            continue
+        lo = -(-nb // side)                                   # fewest shares that take their row blocks in one pass
+        shares = int(rng.integers(lo, min(nb, 2 * lo) + 1))
+        if nb // shares + (1 if nb % shares else 0) > side:
+            shares = lo
+        it = int(rng.integers(1, kt))                         # tiles per slice: 1 .. kt - 1, so at least two slices
+        ks = -(-kt // it)
+        if shares * ks > 4096 or shares > 1024:
+            continue
+        nw = int(rng.integers(4, w + 1))
+        plan = lutq.Plan(side, shares * ks, nw, 2, nb // shares, RW, it)
+        what = f"case {i}: b{bits} {dtype} g{group} M{M} N{N} K{K} {plan}"
+        assert lutq.lutq_plan_check(bits, group, M, N, K, 0 if dtype == "f16" else 1, 256, plan) == 0, what
+        print(what, flush=True)
+        c = gen.make_case(5000 + i, M, N, K, bits, group, dtype, "random_index")
+        d = DeviceCase(lutq, c)
+        if workspace is None:
+            workspace = d.ws
+        d.ws = workspace
+        Y1 = to_bits(d.matmul(lutq, plan=plan))
+        assert np.array_equal(Y1, to_bits(d.matmul(lutq, plan=plan))), what
+        check_y(Y1, c, what)
+        done += 1
+    assert done >= 40
+    assert not workspace[:65536].any().item()
+
+
 @pytest.mark.parametrize("bits", BITS)
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_table_pointer_in_the_upper_half_of_a_word(lutq, bits, dtype):
